@@ -1,0 +1,137 @@
+"""Python face of the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Thin ctypes marshalling around oracle/liboracle.so; all arithmetic is in xp_oracle.c.
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this package;
+the GPU library never does.
+
+bf16 operands are numpy uint16 arrays of bit patterns; fp32 operands are float32 arrays;
+int8 operands are int8 arrays.  Matrices are described the way the C-ABI describes them:
+a flat buffer, a layout ("row" or "col") of the logical matrix, and a leading dimension.
+"""
+from __future__ import annotations
+
+import ctypes as C
+
+import numpy as np
+
+from .build import LIB, build
+
+_lib = None
+
+_LAYOUT = {"row": 0, "col": 1}
+_FILTER = {"krsc": 0, "rsck": 1}
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = C.CDLL(str(LIB))
+        i64, dbl, vp, i = C.c_int64, C.c_double, C.c_void_p, C.c_int
+        L.oracle_gemm_float.argtypes = [i64, i64, i64, dbl, vp, i, i, i64, vp, i, i, i64,
+                                        dbl, vp, i, i64, vp]
+        L.oracle_gemm_i8.argtypes = [i64, i64, i64, vp, i, i64, vp, i, i64, vp]
+        L.oracle_gemm_float_batched.argtypes = [i64, i64, i64, i64, dbl,
+                                                vp, i, i, i64, i64, vp, i, i, i64, i64,
+                                                dbl, vp, i, i64, i64, vp]
+        L.oracle_conv2d_nhwc.argtypes = [i64] * 11 + [vp, i, vp, i, i, vp]
+        for f in (L.oracle_gemm_float, L.oracle_gemm_i8, L.oracle_gemm_float_batched,
+                  L.oracle_conv2d_nhwc, L.oracle_num_threads):
+            f.restype = i
+        _lib = L
+    return _lib
+
+
+def num_threads() -> int:
+    return lib().oracle_num_threads()
+
+
+def _ftype(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return 0
+    if a.dtype == np.uint16:
+        return 1
+    raise TypeError(f"float operand must be float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def _ptr(a):
+    if a is None:
+        return None
+    assert a.flags["C_CONTIGUOUS"], "oracle operands are flat contiguous buffers"
+    return a.ctypes.data
+
+
+def _min_ld(layout: str, rows: int, cols: int) -> int:
+    return cols if layout == "row" else rows
+
+
+def gemm_float(M, N, K, A, a_layout, B, b_layout, *, lda=None, ldb=None, alpha=1.0, beta=0.0,
+               C0=None, c_layout="row", ldc=None) -> np.ndarray:
+    """fp64 reference of alpha*A.B + beta*C0 as a dense row-major M x N float64 array."""
+    lda = _min_ld(a_layout, M, K) if lda is None else lda
+    ldb = _min_ld(b_layout, K, N) if ldb is None else ldb
+    ldc = _min_ld(c_layout, M, N) if ldc is None else ldc
+    ref = np.empty((M, N), dtype=np.float64)
+    if C0 is not None:
+        assert C0.dtype == np.float32
+    rc = lib().oracle_gemm_float(M, N, K, float(alpha), _ptr(A), _ftype(A), _LAYOUT[a_layout], lda,
+                                 _ptr(B), _ftype(B), _LAYOUT[b_layout], ldb,
+                                 float(beta), _ptr(C0), _LAYOUT[c_layout], ldc, _ptr(ref))
+    if rc:
+        raise ValueError(f"oracle_gemm_float failed with code {rc}")
+    return ref
+
+
+def gemm_i8(M, N, K, A, a_layout, B, b_layout, *, lda=None, ldb=None) -> np.ndarray:
+    """Exact int32 reference of A.B for int8 operands (raises if a sum leaves int32)."""
+    lda = _min_ld(a_layout, M, K) if lda is None else lda
+    ldb = _min_ld(b_layout, K, N) if ldb is None else ldb
+    assert A.dtype == np.int8 and B.dtype == np.int8
+    ref = np.empty((M, N), dtype=np.int32)
+    rc = lib().oracle_gemm_i8(M, N, K, _ptr(A), _LAYOUT[a_layout], lda,
+                              _ptr(B), _LAYOUT[b_layout], ldb, _ptr(ref))
+    if rc == 100:
+        raise OverflowError("int8 GEMM sum outside the int32 range")
+    if rc:
+        raise ValueError(f"oracle_gemm_i8 failed with code {rc}")
+    return ref
+
+
+def gemm_float_batched(batch, M, N, K, A, a_layout, B, b_layout, *, lda=None, ldb=None,
+                       strideA=None, strideB=None, alpha=1.0, beta=0.0, C0=None,
+                       c_layout="row", ldc=None, strideC=None) -> np.ndarray:
+    """fp64 reference of the strided-batched GEMM, dense batch x M x N."""
+    lda = _min_ld(a_layout, M, K) if lda is None else lda
+    ldb = _min_ld(b_layout, K, N) if ldb is None else ldb
+    ldc = _min_ld(c_layout, M, N) if ldc is None else ldc
+    strideA = M * K if strideA is None else strideA
+    strideB = K * N if strideB is None else strideB
+    strideC = M * N if strideC is None else strideC
+    ref = np.empty((batch, M, N), dtype=np.float64)
+    rc = lib().oracle_gemm_float_batched(batch, M, N, K, float(alpha),
+                                         _ptr(A), _ftype(A), _LAYOUT[a_layout], lda, strideA,
+                                         _ptr(B), _ftype(B), _LAYOUT[b_layout], ldb, strideB,
+                                         float(beta), _ptr(C0), _LAYOUT[c_layout], ldc, strideC,
+                                         _ptr(ref))
+    if rc:
+        raise ValueError(f"oracle_gemm_float_batched failed with code {rc}")
+    return ref
+
+
+def conv_out_hw(H, W, R, S, stride, pad):
+    P = (H + 2 * pad[0] - R) // stride[0] + 1 if H + 2 * pad[0] >= R else 0
+    Q = (W + 2 * pad[1] - S) // stride[1] + 1 if W + 2 * pad[1] >= S else 0
+    return P, Q
+
+
+def conv2d_nhwc(x, w, *, N, H, W, Cin, Cout, R, S, stride=(1, 1), pad=(0, 0),
+                filter_layout="krsc") -> np.ndarray:
+    """fp64 reference of the NHWC cross-correlation, dense N x P x Q x Cout."""
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    ref = np.empty((N, P, Q, Cout), dtype=np.float64)
+    rc = lib().oracle_conv2d_nhwc(N, H, W, Cin, Cout, R, S, stride[0], stride[1], pad[0], pad[1],
+                                  _ptr(x), _ftype(x), _ptr(w), _ftype(w), _FILTER[filter_layout],
+                                  _ptr(ref))
+    if rc:
+        raise ValueError(f"oracle_conv2d_nhwc failed with code {rc}")
+    return ref

@@ -1,0 +1,23 @@
+"""Compile the CPU oracle (plain C, OpenMP) into oracle/liboracle.so with gcc."""
+from __future__ import annotations
+
+import pathlib
+import subprocess
+
+HERE = pathlib.Path(__file__).resolve().parent
+LIB = HERE / "liboracle.so"
+
+
+def build(force: bool = True) -> pathlib.Path:
+    src = HERE / "xp_oracle.c"
+    hdr = HERE / "xp_oracle.h"
+    if not force and LIB.exists() and LIB.stat().st_mtime >= max(src.stat().st_mtime, hdr.stat().st_mtime):
+        return LIB
+    cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+           "-o", str(LIB), str(src)]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())

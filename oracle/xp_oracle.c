@@ -1,0 +1,165 @@
+/*
+ * CPU oracle: see xp_oracle.h.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Each function is the operator's definition written as scalar loops.  Floating-point inputs
+ * are widened to double before the multiply, products and sums are formed in double, k ascending.
+ */
+#include "xp_oracle.h"
+
+#include <stddef.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static inline double widen(const void *base, int type, int64_t idx)
+{
+    if (type == ORACLE_F32) {
+        return (double)((const float *)base)[idx];
+    } else {
+        /* bf16 is the upper half of an fp32: shift the bits up, the lower 16 are zero */
+        uint32_t u = (uint32_t)((const uint16_t *)base)[idx] << 16;
+        float f;
+        memcpy(&f, &u, sizeof f);
+        return (double)f;
+    }
+}
+
+static inline int64_t at(int layout, int64_t i, int64_t j, int64_t ld)
+{
+    return layout == ORACLE_ROW ? i * ld + j : i + j * ld;
+}
+
+static int bad_type(int t) { return t != ORACLE_F32 && t != ORACLE_BF16; }
+static int bad_layout(int l) { return l != ORACLE_ROW && l != ORACLE_COL; }
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+int oracle_gemm_float(int64_t M, int64_t N, int64_t K, double alpha,
+                      const void *A, int a_type, int a_layout, int64_t lda,
+                      const void *B, int b_type, int b_layout, int64_t ldb,
+                      double beta, const float *C0, int c_layout, int64_t ldc,
+                      double *ref)
+{
+    if (M < 0 || N < 0 || K < 0) return 1;
+    if (bad_type(a_type) || bad_type(b_type)) return 2;
+    if (bad_layout(a_layout) || bad_layout(b_layout) || bad_layout(c_layout)) return 3;
+    if (M == 0 || N == 0) return 0;
+    if (!ref || (K > 0 && (!A || !B)) || (beta != 0.0 && !C0)) return 4;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                double a = widen(A, a_type, at(a_layout, i, k, lda));
+                double b = widen(B, b_type, at(b_layout, k, j, ldb));
+                acc += a * b;
+            }
+            double r = alpha * acc;
+            if (beta != 0.0) r += beta * (double)C0[at(c_layout, i, j, ldc)];
+            ref[i * N + j] = r;
+        }
+    }
+    return 0;
+}
+
+int oracle_gemm_i8(int64_t M, int64_t N, int64_t K,
+                   const int8_t *A, int a_layout, int64_t lda,
+                   const int8_t *B, int b_layout, int64_t ldb,
+                   int32_t *ref)
+{
+    if (M < 0 || N < 0 || K < 0) return 1;
+    if (bad_layout(a_layout) || bad_layout(b_layout)) return 3;
+    if (M == 0 || N == 0) return 0;
+    if (!ref || (K > 0 && (!A || !B))) return 4;
+
+    int overflow = 0;
+#pragma omp parallel for schedule(static) reduction(| : overflow)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t acc = 0;
+            for (int64_t k = 0; k < K; ++k) {
+                acc += (int64_t)A[at(a_layout, i, k, lda)] * (int64_t)B[at(b_layout, k, j, ldb)];
+            }
+            if (acc > INT32_MAX || acc < INT32_MIN) overflow |= 1;
+            ref[i * N + j] = (int32_t)acc;
+        }
+    }
+    return overflow ? 100 : 0;
+}
+
+int oracle_gemm_float_batched(int64_t batch, int64_t M, int64_t N, int64_t K, double alpha,
+                              const void *A, int a_type, int a_layout, int64_t lda, int64_t strideA,
+                              const void *B, int b_type, int b_layout, int64_t ldb, int64_t strideB,
+                              double beta, const float *C0, int c_layout, int64_t ldc, int64_t strideC,
+                              double *ref)
+{
+    if (batch < 0) return 1;
+    if (bad_type(a_type) || bad_type(b_type)) return 2;
+    const int64_t a_sz = a_type == ORACLE_F32 ? 4 : 2;
+    const int64_t b_sz = b_type == ORACLE_F32 ? 4 : 2;
+    for (int64_t b = 0; b < batch; ++b) {
+        const char *Ab = A ? (const char *)A + b * strideA * a_sz : NULL;
+        const char *Bb = B ? (const char *)B + b * strideB * b_sz : NULL;
+        const float *Cb = C0 ? C0 + b * strideC : NULL;
+        int rc = oracle_gemm_float(M, N, K, alpha, Ab, a_type, a_layout, lda,
+                                   Bb, b_type, b_layout, ldb, beta, Cb, c_layout, ldc,
+                                   ref ? ref + b * M * N : NULL);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+int oracle_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                       int64_t R, int64_t S, int64_t stride_h, int64_t stride_w,
+                       int64_t pad_h, int64_t pad_w,
+                       const void *input, int in_type,
+                       const void *filter, int w_type, int w_layout,
+                       double *ref)
+{
+    if (N < 0 || H < 0 || W < 0 || Cin < 0 || Cout < 0 || R <= 0 || S <= 0) return 1;
+    if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return 1;
+    if (bad_type(in_type) || bad_type(w_type)) return 2;
+    if (w_layout != ORACLE_KRSC && w_layout != ORACLE_RSCK) return 3;
+    if (H + 2 * pad_h < R || W + 2 * pad_w < S) return 0;      /* empty output */
+    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1;
+    const int64_t Q = (W + 2 * pad_w - S) / stride_w + 1;
+    if (N == 0 || Cout == 0) return 0;
+    if (!ref || (Cin > 0 && (!input || !filter))) return 4;
+
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t p = 0; p < P; ++p) {
+            for (int64_t q = 0; q < Q; ++q) {
+                for (int64_t k = 0; k < Cout; ++k) {
+                    double acc = 0.0;
+                    for (int64_t r = 0; r < R; ++r) {
+                        const int64_t h = p * stride_h + r - pad_h;
+                        if (h < 0 || h >= H) continue;          /* zero padding: term is 0 */
+                        for (int64_t s = 0; s < S; ++s) {
+                            const int64_t w = q * stride_w + s - pad_w;
+                            if (w < 0 || w >= W) continue;
+                            for (int64_t c = 0; c < Cin; ++c) {
+                                const int64_t wi = w_layout == ORACLE_KRSC
+                                    ? ((k * R + r) * S + s) * Cin + c
+                                    : ((r * S + s) * Cin + c) * Cout + k;
+                                acc += widen(input, in_type, ((n * H + h) * W + w) * Cin + c)
+                                     * widen(filter, w_type, wi);
+                            }
+                        }
+                    }
+                    ref[((n * P + p) * Q + q) * Cout + k] = acc;
+                }
+            }
+        }
+    }
+    return 0;
+}

@@ -1,0 +1,83 @@
+/*
+ * CPU oracle for the dense tensor operators of the MatMul and Convolution groups of the
+ * paper's benchmark (Table 5: GEMM, Batch GEMM, Conv2D NHWC).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT A PRODUCT PATH.  It exists so that the GPU library can be
+ * checked against something that is obviously right.  It is plain, slow, scalar C: the
+ * textbook definition of each operator written out, with fp64 accumulation for floating-point
+ * inputs and int64 accumulation for int8 inputs.  No blocking, no intrinsics, no BLAS, and no
+ * code, header, table or helper shared with the GPU library.  OpenMP is used only to run
+ * independent output rows in parallel; the summation order inside one output element is always
+ * k ascending (for convolution: r, then s, then c ascending).
+ *
+ * The paper names the operators (Table 5) but prints no definition of them; the definitions
+ * used are the standard ones:
+ *   GEMM        ref(i,j) = alpha * sum_k A(i,k) B(k,j) + beta * C0(i,j)      (beta == 0: C0 unread)
+ *   batched     the same for every batch index on pointers advanced by the batch strides
+ *   conv NHWC   ref[n,p,q,k] = sum_{r,s,c} in[n, p*sh + r - ph, q*sw + s - pw, c] * w(k,r,s,c)
+ *               (cross-correlation, zero padding, dilation 1, groups 1, no bias)
+ *
+ * All pointers are host pointers.  Reference outputs are dense and row-major
+ * (M x N, batch x M x N, N x P x Q x Cout) regardless of the layout of the operands.
+ * Every function returns 0 on success and a positive code on a bad argument.
+ */
+#ifndef XP_ORACLE_H
+#define XP_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* element types of floating-point operands */
+#define ORACLE_F32  0
+#define ORACLE_BF16 1   /* uint16 bit pattern, widened exactly */
+
+/* layouts of the logical matrices */
+#define ORACLE_ROW 0    /* X(i,j) = X[i*ld + j] */
+#define ORACLE_COL 1    /* X(i,j) = X[i + j*ld] */
+
+/* filter layouts */
+#define ORACLE_KRSC 0   /* w(k,r,s,c) = w[((k*R + r)*S + s)*Cin + c]  */
+#define ORACLE_RSCK 1   /* w(k,r,s,c) = w[((r*S + s)*Cin + c)*Cout + k] */
+
+/* Floating-point GEMM.  A is M x K, B is K x N, C0 (fp32, may be NULL when beta == 0) is M x N.
+ * ref receives M*N doubles, row-major. */
+int oracle_gemm_float(int64_t M, int64_t N, int64_t K, double alpha,
+                      const void *A, int a_type, int a_layout, int64_t lda,
+                      const void *B, int b_type, int b_layout, int64_t ldb,
+                      double beta, const float *C0, int c_layout, int64_t ldc,
+                      double *ref);
+
+/* int8 x int8 -> int32 GEMM with int64 accumulation.  Returns 0, or 100 if any exact sum
+ * falls outside the int32 range (ref then holds the truncated value). */
+int oracle_gemm_i8(int64_t M, int64_t N, int64_t K,
+                   const int8_t *A, int a_layout, int64_t lda,
+                   const int8_t *B, int b_layout, int64_t ldb,
+                   int32_t *ref);
+
+/* Strided-batched floating-point GEMM: for every b the single GEMM on A + b*strideA etc.
+ * (strides in elements).  ref receives batch*M*N doubles. */
+int oracle_gemm_float_batched(int64_t batch, int64_t M, int64_t N, int64_t K, double alpha,
+                              const void *A, int a_type, int a_layout, int64_t lda, int64_t strideA,
+                              const void *B, int b_type, int b_layout, int64_t ldb, int64_t strideB,
+                              double beta, const float *C0, int c_layout, int64_t ldc, int64_t strideC,
+                              double *ref);
+
+/* Direct convolution, seven nested loops.  input is N x H x W x Cin contiguous, ref receives
+ * N*P*Q*Cout doubles with P = (H + 2*pad_h - R)/stride_h + 1 (floor), Q likewise. */
+int oracle_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                       int64_t R, int64_t S, int64_t stride_h, int64_t stride_w,
+                       int64_t pad_h, int64_t pad_w,
+                       const void *input, int in_type,
+                       const void *filter, int w_type, int w_layout,
+                       double *ref);
+
+/* Number of OpenMP threads the loops above will use. */
+int oracle_num_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
