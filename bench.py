@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark: bf16 GEMM 4096^3 (A row-major, B column-major, fp32 accumulate and output) on one
+MI355X through the C ABI, with the int8 GEMM, batched-GEMM and convolution workloads timed
+beside it, the MFMA roofline fraction of the dominant kernel, and the CPU oracle timed on the
+host cores as a reported baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only-main] [--no-cpu]
+
+A step is one xp_gemm call on inputs already resident in HBM.  One JSON line is printed.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+PEAK_BF16_TFLOPS = 2516.6     # 256 CU x 4096 FLOP/clk/CU x 2.4 GHz, dense
+PEAK_INT8_TOPS = 5033.2
+PEAK_HBM_GBS = 8000.0
+
+
+def _time_calls(torch, fn, steps, warmup):
+    """Average duration of one call in ms: HIP events on the stream the kernels are launched on."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return start.elapsed_time(stop) / steps, wall_ms / steps
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--only-main", action="store_true", help="skip the int8 / batched / conv side measurements")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2505_02146_amd import inputs, xp          # fails loudly if libxp.so is missing
+    from tests.helpers import dev
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    # ---- main workload: bf16 GEMM 4096^3, NT
+    w = inputs.workload("gemm_bf16_4096")
+    M, N, K = w["M"], w["N"], w["K"]
+    dA, dB = dev(w["A"].reshape(-1)), dev(w["B"].reshape(-1))
+    dC = torch.empty((M, N), dtype=torch.float32, device="cuda")
+
+    def step():
+        xp.xp_gemm(M, N, K, 1.0, dA, "row", K, dB, "col", K, 0.0, dC, "row", N, a_type="bf16", b_type="bf16")
+
+    ev_ms, wall_ms = _time_calls(torch, step, args.steps, args.warmup)
+    flops = 2.0 * M * N * K
+    tflops = flops / (ev_ms * 1e-3) / 1e12
+    variant = xp.xp_describe_config(0, "bf16", xp.xp_last_config(0, "bf16"))
+
+    out = {
+        "metric": "bf16 GEMM TFLOP/s + % MFMA peak at 4096^3; int8 TOPS; conv TFLOP/s",
+        "value": round(flops / (wall_ms * 1e-3) / 1e12, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "gemm_bf16_4096: M=N=K=4096, A row-major, B column-major, N(0,1) entries, "
+                               "fp32 accumulate and output, alpha=1, beta=0", "kernel": variant},
+        "pct_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "roofline": {"bound": "mfma", "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "kernel_ms": round(ev_ms, 5)},
+    }
+
+    # ---- side measurements named by the metric
+    if not args.only_main:
+        side = {}
+        steps2, warm2 = max(20, args.steps // 4), 5
+        del dA, dB, dC
+        w8 = inputs.workload("gemm_i8_4096x4096x8192")
+        a8, b8 = dev(w8["A"].reshape(-1)), dev(w8["B"].reshape(-1))
+        c8 = torch.empty((4096, 4096), dtype=torch.int32, device="cuda")
+        ms, _ = _time_calls(torch, lambda: xp.xp_gemm(4096, 4096, 8192, 1.0, a8, "row", 8192, b8, "col", 8192, 0.0,
+                                                      c8, "row", 4096), steps2, warm2)
+        tops = 2.0 * 4096 * 4096 * 8192 / (ms * 1e-3) / 1e12
+        side["gemm_i8_4096x4096x8192"] = {"ms": round(ms, 5), "TOPS": round(tops, 1),
+                                          "pct_int8_mfma_peak": round(100 * tops / PEAK_INT8_TOPS, 2),
+                                          "kernel": xp.xp_describe_config(0, "i8", xp.xp_last_config(0, "i8"))}
+        del a8, b8, c8
+        wc = inputs.workload("conv_bf16_56")
+        xin, fil = dev(wc["input"].reshape(-1)), dev(wc["filter"].reshape(-1))
+        oc = torch.empty((32, 56, 56, 256), dtype=torch.float32, device="cuda")
+        ms, _ = _time_calls(torch, lambda: xp.xp_conv2d_nhwc(32, 56, 56, 256, 256, 3, 3, 1, 1, 1, 1, xin, fil, "krsc",
+                                                             oc, in_type="bf16", w_type="bf16"), steps2, warm2)
+        tf = 2.0 * 32 * 56 * 56 * 256 * 9 * 256 / (ms * 1e-3) / 1e12
+        side["conv_bf16_56"] = {"ms": round(ms, 5), "TFLOP/s": round(tf, 1),
+                                "pct_bf16_mfma_peak": round(100 * tf / PEAK_BF16_TFLOPS, 2),
+                                "kernel": xp.xp_describe_config(2, "bf16", xp.xp_last_config(2, "bf16"))}
+        del xin, fil, oc
+        for name, alg_bytes in (("bgemm_bf16_qk", 113.2e6), ("bgemm_bf16_pv", 69.2e6)):
+            wb = inputs.workload(name)
+            b, m, n, k = wb["batch"], wb["M"], wb["N"], wb["K"]
+            lb = wb["b_layout"]
+            ldb = n if lb == "row" else k
+            # rotate through buffer sets larger than the 256 MB last-level cache: HBM-cold timing
+            sets = max(2, int(600e6 // alg_bytes) + 1)
+            As = [dev(wb["A"].reshape(-1)) for _ in range(sets)]
+            Bs = [dev(wb["B"].reshape(-1)) for _ in range(sets)]
+            Cs = [torch.empty((b, m, n), dtype=torch.float32, device="cuda") for _ in range(sets)]
+            it = {"i": 0}
+
+            def call():
+                i = it["i"] % sets
+                it["i"] += 1
+                xp.xp_gemm_batched(b, m, n, k, 1.0, As[i], "row", k, m * k, Bs[i], lb, ldb, k * n, 0.0, Cs[i], "row", n,
+                                   m * n, a_type="bf16", b_type="bf16")
+            ms, _ = _time_calls(torch, call, steps2 * 2, warm2)
+            side[name] = {"ms": round(ms, 5), "TFLOP/s": round(2.0 * b * m * n * k / (ms * 1e-3) / 1e12, 1),
+                          "GB/s": round(alg_bytes / (ms * 1e-3) / 1e9, 1),
+                          "pct_hbm_peak": round(100 * alg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 2),
+                          "buffers": f"{sets} rotating sets (HBM-cold)",
+                          "kernel": xp.xp_describe_config(1, "bf16", xp.xp_last_config(1, "bf16"))}
+            del As, Bs, Cs
+        out["other_workloads"] = side
+
+    # ---- CPU oracle on a bounded sample of the main workload (reported baseline, not the target)
+    if not args.no_cpu:
+        import oracle
+        rows = 1536
+        a_sample = np.ascontiguousarray(w["A"][:rows]).reshape(-1)
+        t0 = time.perf_counter()
+        oracle.gemm_float(rows, N, K, a_sample, "row", w["B"].reshape(-1), "col")
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(2.0 * rows * N * K / dt / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"first {rows} of {M} rows of C (all {N} columns, full K), {dt:.1f} s",
+                               "host_cpus": os.cpu_count()}
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,138 @@
+/*
+ * xp -- dense tensor operators for AMD MI355X (gfx950 / CDNA4), C ABI.
+ *
+ * The operators are the MatMul and Convolution rows of the benchmark of the QiMeng-Xpiler
+ * paper (arXiv 2505.02146, Table 5): GEMM, Batch GEMM and Conv2D NHWC.  The paper lists them
+ * by name and prints no definition; the standard definitions below are what the library
+ * computes.  Every entry point launches hand-written HIP kernels (LDS-tiled, matrix-core
+ * MFMA contraction, the kind of instruction Table 1 of the paper names for AMD hardware) on
+ * the caller's stream and returns without synchronising.
+ *
+ * Conventions common to all entry points
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never allocates,
+ *     frees or keeps a pointer; there is no hidden workspace.
+ *   - Inputs are read-only and may alias each other; the output must not overlap an input.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
+ *     on it; the call does not wait for the GPU.
+ *   - Arguments are validated on the host before anything is launched; on error nothing is
+ *     launched and a status code is returned.  The library never aborts, throws or prints.
+ *   - Supported (A, B -> C) element types: (F32, F32 -> F32), (BF16, BF16 -> F32),
+ *     (I8, I8 -> I32).  bf16 is the upper 16 bits of an IEEE fp32; products are accumulated
+ *     in fp32 (int32 for I8; signed x signed, two's complement, no saturation).
+ *     For I8, alpha must be 1 and beta 0.  Any other combination: XP_ERR_UNSUPPORTED.
+ *   - Degenerate sizes: M, N or batch == 0 -> XP_OK, nothing launched.
+ *     K == 0 -> C = beta * C (zero-filled when beta == 0).
+ *   - beta == 0 means C is not read: NaN or Inf already in C never reach the result.
+ *   - Matrices whose layout, alignment or size the tuned kernels do not cover (operands not
+ *     contiguous along K, pointers or leading dimensions not multiples of 16 bytes, extents
+ *     beyond 32-bit byte offsets within a tile) run on a slower general kernel instead of
+ *     failing; the result obeys the same definition.
+ *   - Thread safety: entry points may be called concurrently; xp_force_config changes
+ *     process-wide state and is meant for tuning sweeps and tests only.
+ */
+#ifndef XP_H
+#define XP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    XP_OK = 0,
+    XP_ERR_NULL = 1,         /* NULL pointer for a non-empty operand */
+    XP_ERR_SHAPE = 2,        /* negative extent, zero filter or stride extent */
+    XP_ERR_STRIDE = 3,       /* leading dimension or batch stride smaller than the layout needs */
+    XP_ERR_ALIGN = 4,        /* pointer not aligned to its element size */
+    XP_ERR_UNSUPPORTED = 5,  /* dtype / layout / alpha-beta combination not provided */
+    XP_ERR_CONFIG = 6,       /* forced kernel configuration does not exist or cannot run this call */
+    XP_ERR_LAUNCH = 7        /* the HIP runtime refused the launch */
+} xp_status;
+
+typedef enum { XP_F32 = 0, XP_BF16 = 1, XP_I8 = 2, XP_I32 = 3 } xp_dtype;
+
+/* Layout of a logical matrix X with `rows` x `cols`:
+ *   XP_ROW: X(i,j) = X[i*ld + j], ld >= cols;   XP_COL: X(i,j) = X[i + j*ld], ld >= rows. */
+typedef enum { XP_ROW = 0, XP_COL = 1 } xp_layout;
+
+/* Filter storage: w(k,r,s,c) for output channel k, tap (r,s), input channel c.
+ *   XP_FILTER_KRSC: w[((k*R + r)*S + s)*Cin + c];  XP_FILTER_RSCK: w[((r*S + s)*Cin + c)*Cout + k] */
+typedef enum { XP_FILTER_KRSC = 0, XP_FILTER_RSCK = 1 } xp_filter_layout;
+
+/* Operator families for the tuning surface. */
+typedef enum { XP_OP_GEMM = 0, XP_OP_GEMM_BATCHED = 1, XP_OP_CONV2D = 2 } xp_op;
+
+/*
+ * GEMM (Table 5, "GEMM"):  C(i,j) = alpha * sum_{k<K} A(i,k) * B(k,j) + beta * C(i,j)
+ * for i < M, j < N.  A is the logical M x K matrix, B is K x N, C is M x N, each with its own
+ * layout and leading dimension (in elements).  Device pointers; C is written in place.
+ */
+xp_status xp_gemm(int64_t M, int64_t N, int64_t K, float alpha,
+                  const void *A, xp_dtype a_type, xp_layout a_layout, int64_t lda,
+                  const void *B, xp_dtype b_type, xp_layout b_layout, int64_t ldb,
+                  float beta,
+                  void *C, xp_dtype c_type, xp_layout c_layout, int64_t ldc,
+                  void *stream);
+
+/*
+ * Strided-batched GEMM (Table 5, "Batch GEMM"): for every b < batch the GEMM above on
+ * A + b*strideA, B + b*strideB, C + b*strideC (strides in elements, >= 0).  strideA or strideB
+ * may be 0 to share an operand across the batch; the C slices must not overlap.
+ */
+xp_status xp_gemm_batched(int64_t batch, int64_t M, int64_t N, int64_t K, float alpha,
+                          const void *A, xp_dtype a_type, xp_layout a_layout, int64_t lda, int64_t strideA,
+                          const void *B, xp_dtype b_type, xp_layout b_layout, int64_t ldb, int64_t strideB,
+                          float beta,
+                          void *C, xp_dtype c_type, xp_layout c_layout, int64_t ldc, int64_t strideC,
+                          void *stream);
+
+/*
+ * 2-D convolution, NHWC (Table 5, "Conv2D NHWC"), computed as an implicit GEMM (the im2col
+ * matrix is addressed, never stored):
+ *   out[n,p,q,k] = sum_{r<R, s<S, c<Cin} in[n, p*stride_h + r - pad_h, q*stride_w + s - pad_w, c] * w(k,r,s,c)
+ * with terms outside the image equal to zero; cross-correlation (no filter flip), dilation 1,
+ * one group, no bias.  P = floor((H + 2*pad_h - R)/stride_h) + 1, Q likewise; if the padded image
+ * is smaller than the filter the output is empty and XP_OK is returned.
+ * input is N x H x W x Cin contiguous, output N x P x Q x Cout contiguous (device pointers).
+ * Supported types: (F32, F32 -> F32) and (BF16, BF16 -> F32).
+ */
+xp_status xp_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                         int64_t R, int64_t S, int64_t stride_h, int64_t stride_w,
+                         int64_t pad_h, int64_t pad_w,
+                         const void *input, xp_dtype in_type,
+                         const void *filter, xp_dtype w_type, xp_filter_layout w_layout,
+                         void *output, xp_dtype out_type,
+                         void *stream);
+
+/*
+ * Tuning surface: the stand-in for the tile-size / loop-order / binding knobs that the paper's
+ * intra-pass auto-tuning (Section 5.1) searches by brute force.  Every compiled kernel variant
+ * of an operator family and input type has an index; a sweep forces each in turn, checks the
+ * result and times it, and the winners are recorded in the library's selection table.
+ *
+ *   xp_num_configs      number of variants for (op, in_type); 0 if none.
+ *   xp_describe_config  writes a NUL-terminated description ("bf16 256x256x64 w2x4 st2 ...")
+ *                       into buf (at most n bytes).  XP_ERR_CONFIG for a bad index.
+ *   xp_force_config     idx >= 0: every later call of that (op, in_type) uses variant idx, and
+ *                       returns XP_ERR_CONFIG if the variant cannot run the call's shape or
+ *                       layout.  idx < 0: back to the selection table (the default).
+ *   xp_last_config      index of the variant the most recent call of (op, in_type) used,
+ *                       -1 if none yet.
+ */
+int xp_num_configs(xp_op op, xp_dtype in_type);
+xp_status xp_describe_config(xp_op op, xp_dtype in_type, int idx, char *buf, size_t n);
+xp_status xp_force_config(xp_op op, xp_dtype in_type, int idx);
+int xp_last_config(xp_op op, xp_dtype in_type);
+
+/* Human-readable name of a status code (static storage). */
+const char *xp_status_string(xp_status s);
+
+/* Library version string (static storage). */
+const char *xp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XP_H */

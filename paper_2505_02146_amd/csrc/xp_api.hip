@@ -1,0 +1,288 @@
+// Host side of the C ABI declared in include/xp.h: argument validation, canonicalisation of a
+// call into xp::Problem, selection of a kernel variant, launch.  No device code lives here.
+#include <atomic>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+#include "xp_internal.hpp"
+
+namespace xp {
+
+namespace {
+
+constexpr int kMaxVariants = 64;
+const Variant *g_table[3][kMaxVariants];
+int g_count[3] = {0, 0, 0};
+std::once_flag g_once;
+
+int type_slot(xp_dtype t) { return t == XP_F32 ? 0 : (t == XP_BF16 ? 1 : (t == XP_I8 ? 2 : -1)); }
+
+void build_tables()
+{
+    const xp_dtype types[3] = {XP_F32, XP_BF16, XP_I8};
+    for (int s = 0; s < 3; ++s) {
+        int n = generic_variants(types[s], g_table[s]);
+        if (types[s] == XP_F32) n += f32_mfma_variants(g_table[s] + n);
+        else n += kc_variants(types[s], g_table[s] + n);
+        g_count[s] = n;
+    }
+}
+
+// forced variant per (op, type slot); -1 = use the selection table
+std::atomic<int> g_forced[3][3];
+std::atomic<int> g_last[3][3];
+struct Init {
+    Init()
+    {
+        for (auto &r : g_forced) for (auto &x : r) x.store(-1);
+        for (auto &r : g_last) for (auto &x : r) x.store(-1);
+    }
+} g_init;
+
+}  // namespace
+
+int num_variants(xp_dtype in_type)
+{
+    std::call_once(g_once, build_tables);
+    const int s = type_slot(in_type);
+    return s < 0 ? 0 : g_count[s];
+}
+
+const Variant *variant(xp_dtype in_type, int idx)
+{
+    std::call_once(g_once, build_tables);
+    const int s = type_slot(in_type);
+    if (s < 0 || idx < 0 || idx >= g_count[s]) return nullptr;
+    return g_table[s][idx];
+}
+
+namespace {
+
+// Selection: every variant estimates its run time for the call from its tile shape, the
+// number of workgroup rounds the grid needs on 256 compute units and the efficiency its sweeps
+// measured (the stand-in for the brute-force parameter search of Section 5.1 of the paper);
+// the cheapest variant that can run the call wins.  Variant 0 (general kernel) always can.
+int select_variant(const Problem &q)
+{
+    const int n = num_variants(q.in_type);
+    int best = 0;
+    double best_cost = variant(q.in_type, 0)->cost(q);
+    for (int i = 1; i < n; ++i) {
+        const Variant *v = variant(q.in_type, i);
+        if (!v->can_run(q)) continue;
+        const double c = v->cost(q);
+        if (c < best_cost) { best_cost = c; best = i; }
+    }
+    return best;
+}
+
+xp_status run(const Problem &q)
+{
+    const int slot = type_slot(q.in_type);
+    const int forced = g_forced[q.op][slot].load();
+    int idx;
+    if (forced >= 0) {
+        const Variant *v = variant(q.in_type, forced);
+        if (!v || !v->can_run(q)) return XP_ERR_CONFIG;
+        idx = forced;
+    } else {
+        idx = select_variant(q);
+    }
+    const Variant *v = variant(q.in_type, idx);
+    if (!v || !v->can_run(q)) return XP_ERR_UNSUPPORTED;
+    g_last[q.op][slot].store(idx);
+    return v->launch(q) == hipSuccess ? XP_OK : XP_ERR_LAUNCH;
+}
+
+bool aligned_to(const void *p, int bytes) { return ((uintptr_t)p % (uintptr_t)bytes) == 0; }
+
+xp_status check_types(xp_dtype a, xp_dtype b, xp_dtype c, float alpha, float beta)
+{
+    if (a != b) return XP_ERR_UNSUPPORTED;
+    if (a == XP_F32 || a == XP_BF16) return c == XP_F32 ? XP_OK : XP_ERR_UNSUPPORTED;
+    if (a == XP_I8) {
+        if (c != XP_I32) return XP_ERR_UNSUPPORTED;
+        return (alpha == 1.0f && beta == 0.0f) ? XP_OK : XP_ERR_UNSUPPORTED;
+    }
+    return XP_ERR_UNSUPPORTED;
+}
+
+bool bad_layout(int l) { return l != XP_ROW && l != XP_COL; }
+
+xp_status gemm_common(xp_op op, int64_t batch, int64_t M, int64_t N, int64_t K, float alpha,
+                      const void *A, xp_dtype a_t, xp_layout a_l, int64_t lda, int64_t strideA,
+                      const void *B, xp_dtype b_t, xp_layout b_l, int64_t ldb, int64_t strideB,
+                      float beta, void *C, xp_dtype c_t, xp_layout c_l, int64_t ldc, int64_t strideC,
+                      void *stream)
+{
+    if (batch < 0 || M < 0 || N < 0 || K < 0) return XP_ERR_SHAPE;
+    if (bad_layout(a_l) || bad_layout(b_l) || bad_layout(c_l)) return XP_ERR_UNSUPPORTED;
+    xp_status ts = check_types(a_t, b_t, c_t, alpha, beta);
+    if (ts != XP_OK) return ts;
+    if (batch == 0 || M == 0 || N == 0) return XP_OK;
+    if (!C) return XP_ERR_NULL;
+    if (K > 0 && (!A || !B)) return XP_ERR_NULL;
+    if (K > 0) {
+        if (lda < (a_l == XP_ROW ? K : M)) return XP_ERR_STRIDE;
+        if (ldb < (b_l == XP_ROW ? N : K)) return XP_ERR_STRIDE;
+    }
+    if (ldc < (c_l == XP_ROW ? N : M)) return XP_ERR_STRIDE;
+    if (strideA < 0 || strideB < 0 || strideC < 0) return XP_ERR_STRIDE;
+    if (batch > 1) {
+        const int64_t c_extent = c_l == XP_ROW ? (M - 1) * ldc + N : (N - 1) * ldc + M;
+        if (strideC < c_extent) return XP_ERR_STRIDE;
+    }
+    if (!aligned_to(C, elem_size(c_t)) || (K > 0 && (!aligned_to(A, elem_size(a_t)) || !aligned_to(B, elem_size(b_t)))))
+        return XP_ERR_ALIGN;
+
+    Problem q;
+    memset(&q, 0, sizeof q);
+    q.op = op;
+    q.in_type = a_t;
+    q.batch = batch;
+    q.K = K;
+    q.alpha = alpha;
+    q.beta = beta;
+    q.C = C;
+    q.ldc = ldc;
+    q.strideA = strideA; q.strideB = strideB; q.strideC = strideC;
+    q.conv = false;
+    q.stream = (hipStream_t)stream;
+    const int64_t a_sm = a_l == XP_ROW ? lda : 1, a_sk = a_l == XP_ROW ? 1 : lda;
+    const int64_t b_sk = b_l == XP_ROW ? ldb : 1, b_sn = b_l == XP_ROW ? 1 : ldb;
+    if (c_l == XP_ROW) {
+        q.M = M; q.N = N;
+        q.A = A; q.a_sm = a_sm; q.a_sk = a_sk;
+        q.B = B; q.b_sk = b_sk; q.b_sn = b_sn;
+    } else {
+        // column-major C is the row-major transpose: C^T = B^T . A^T, so the operands trade places
+        q.M = N; q.N = M;
+        q.A = B; q.a_sm = b_sn; q.a_sk = b_sk;
+        q.B = A; q.b_sk = a_sk; q.b_sn = a_sm;
+        q.strideA = strideB; q.strideB = strideA;
+    }
+    return run(q);
+}
+
+}  // namespace
+}  // namespace xp
+
+using namespace xp;
+
+extern "C" {
+
+xp_status xp_gemm(int64_t M, int64_t N, int64_t K, float alpha,
+                  const void *A, xp_dtype a_type, xp_layout a_layout, int64_t lda,
+                  const void *B, xp_dtype b_type, xp_layout b_layout, int64_t ldb,
+                  float beta, void *C, xp_dtype c_type, xp_layout c_layout, int64_t ldc, void *stream)
+{
+    return gemm_common(XP_OP_GEMM, 1, M, N, K, alpha, A, a_type, a_layout, lda, 0, B, b_type, b_layout, ldb, 0,
+                       beta, C, c_type, c_layout, ldc, 0, stream);
+}
+
+xp_status xp_gemm_batched(int64_t batch, int64_t M, int64_t N, int64_t K, float alpha,
+                          const void *A, xp_dtype a_type, xp_layout a_layout, int64_t lda, int64_t strideA,
+                          const void *B, xp_dtype b_type, xp_layout b_layout, int64_t ldb, int64_t strideB,
+                          float beta, void *C, xp_dtype c_type, xp_layout c_layout, int64_t ldc, int64_t strideC,
+                          void *stream)
+{
+    return gemm_common(XP_OP_GEMM_BATCHED, batch, M, N, K, alpha, A, a_type, a_layout, lda, strideA,
+                       B, b_type, b_layout, ldb, strideB, beta, C, c_type, c_layout, ldc, strideC, stream);
+}
+
+xp_status xp_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                         int64_t R, int64_t S, int64_t stride_h, int64_t stride_w,
+                         int64_t pad_h, int64_t pad_w,
+                         const void *input, xp_dtype in_type,
+                         const void *filter, xp_dtype w_type, xp_filter_layout w_layout,
+                         void *output, xp_dtype out_type, void *stream)
+{
+    if (N < 0 || H < 0 || W < 0 || Cin < 0 || Cout < 0) return XP_ERR_SHAPE;
+    if (R <= 0 || S <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return XP_ERR_SHAPE;
+    if (w_layout != XP_FILTER_KRSC && w_layout != XP_FILTER_RSCK) return XP_ERR_UNSUPPORTED;
+    if (in_type != w_type || (in_type != XP_F32 && in_type != XP_BF16) || out_type != XP_F32)
+        return XP_ERR_UNSUPPORTED;
+    if (H + 2 * pad_h < R || W + 2 * pad_w < S) return XP_OK;   // empty output
+    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1;
+    const int64_t Q = (W + 2 * pad_w - S) / stride_w + 1;
+    if (N == 0 || Cout == 0) return XP_OK;
+    if (!output) return XP_ERR_NULL;
+    const int64_t K = R * S * Cin;
+    if (K > 0 && (!input || !filter)) return XP_ERR_NULL;
+    if (!aligned_to(output, 4) || (K > 0 && (!aligned_to(input, elem_size(in_type)) ||
+                                             !aligned_to(filter, elem_size(w_type)))))
+        return XP_ERR_ALIGN;
+
+    Problem q;
+    memset(&q, 0, sizeof q);
+    q.op = XP_OP_CONV2D;
+    q.in_type = in_type;
+    q.batch = 1;
+    q.M = N * P * Q;
+    q.N = Cout;
+    q.K = K;
+    q.A = input;
+    q.B = filter;
+    q.C = output;
+    if (w_layout == XP_FILTER_KRSC) { q.b_sk = 1; q.b_sn = K; }
+    else { q.b_sk = Cout; q.b_sn = 1; }
+    q.ldc = Cout;
+    q.alpha = 1.0f;
+    q.beta = 0.0f;
+    q.conv = true;
+    q.H = H; q.W = W; q.Cin = Cin; q.R = R; q.S = S; q.P = P; q.Q = Q;
+    q.sh = stride_h; q.sw = stride_w; q.ph = pad_h; q.pw = pad_w;
+    q.stream = (hipStream_t)stream;
+    return run(q);
+}
+
+int xp_num_configs(xp_op op, xp_dtype in_type)
+{
+    if (op < 0 || op > 2) return 0;
+    return num_variants(in_type);
+}
+
+xp_status xp_describe_config(xp_op op, xp_dtype in_type, int idx, char *buf, size_t n)
+{
+    if (op < 0 || op > 2 || !buf || n == 0) return XP_ERR_CONFIG;
+    const Variant *v = variant(in_type, idx);
+    if (!v) return XP_ERR_CONFIG;
+    snprintf(buf, n, "%s", v->name);
+    return XP_OK;
+}
+
+xp_status xp_force_config(xp_op op, xp_dtype in_type, int idx)
+{
+    const int slot = in_type == XP_F32 ? 0 : (in_type == XP_BF16 ? 1 : (in_type == XP_I8 ? 2 : -1));
+    if (op < 0 || op > 2 || slot < 0) return XP_ERR_CONFIG;
+    if (idx >= num_variants(in_type)) return XP_ERR_CONFIG;
+    g_forced[op][slot].store(idx < 0 ? -1 : idx);
+    return XP_OK;
+}
+
+int xp_last_config(xp_op op, xp_dtype in_type)
+{
+    const int slot = in_type == XP_F32 ? 0 : (in_type == XP_BF16 ? 1 : (in_type == XP_I8 ? 2 : -1));
+    if (op < 0 || op > 2 || slot < 0) return -1;
+    return g_last[op][slot].load();
+}
+
+const char *xp_status_string(xp_status s)
+{
+    switch (s) {
+    case XP_OK: return "ok";
+    case XP_ERR_NULL: return "null pointer for a non-empty operand";
+    case XP_ERR_SHAPE: return "invalid extent";
+    case XP_ERR_STRIDE: return "leading dimension or batch stride too small";
+    case XP_ERR_ALIGN: return "pointer not aligned to its element size";
+    case XP_ERR_UNSUPPORTED: return "unsupported dtype, layout or scaling combination";
+    case XP_ERR_CONFIG: return "kernel configuration does not exist or cannot run this call";
+    case XP_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+const char *xp_version(void) { return "xp 0.1 (gfx950)"; }
+
+}  // extern "C"

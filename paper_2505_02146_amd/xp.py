@@ -1,0 +1,133 @@
+"""ctypes binding of libxp.so: the same entry points as include/xp.h, marshalling only.
+
+Operands are torch tensors living on the GPU (torch is used for device memory and streams,
+nothing else); every step of the computation runs in the library's HIP kernels.  If the
+shared library has not been built the import of this module fails: there is no fallback.
+
+bf16 operands may be torch.bfloat16 tensors or int16/uint16 tensors holding bf16 bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import pathlib
+
+import torch
+
+_HERE = pathlib.Path(__file__).resolve().parent
+LIB_PATH = _HERE / "libxp.so"
+
+if not LIB_PATH.exists():
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2505_02146_amd.build` "
+                      "(or __graft_entry__.build()); there is no fallback path")
+
+_lib = C.CDLL(str(LIB_PATH))
+
+XP_F32, XP_BF16, XP_I8, XP_I32 = 0, 1, 2, 3
+XP_ROW, XP_COL = 0, 1
+XP_FILTER_KRSC, XP_FILTER_RSCK = 0, 1
+XP_OP_GEMM, XP_OP_GEMM_BATCHED, XP_OP_CONV2D = 0, 1, 2
+XP_OK = 0
+
+_i64, _f, _vp, _i = C.c_int64, C.c_float, C.c_void_p, C.c_int
+_lib.xp_gemm.argtypes = [_i64, _i64, _i64, _f, _vp, _i, _i, _i64, _vp, _i, _i, _i64, _f, _vp, _i, _i, _i64, _vp]
+_lib.xp_gemm_batched.argtypes = [_i64, _i64, _i64, _i64, _f, _vp, _i, _i, _i64, _i64, _vp, _i, _i, _i64, _i64,
+                                 _f, _vp, _i, _i, _i64, _i64, _vp]
+_lib.xp_conv2d_nhwc.argtypes = [_i64] * 11 + [_vp, _i, _vp, _i, _i, _vp, _i, _vp]
+_lib.xp_num_configs.argtypes = [_i, _i]
+_lib.xp_describe_config.argtypes = [_i, _i, _i, C.c_char_p, C.c_size_t]
+_lib.xp_force_config.argtypes = [_i, _i, _i]
+_lib.xp_last_config.argtypes = [_i, _i]
+_lib.xp_status_string.argtypes = [_i]
+_lib.xp_status_string.restype = C.c_char_p
+_lib.xp_version.restype = C.c_char_p
+for _name in ("xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_num_configs", "xp_describe_config",
+              "xp_force_config", "xp_last_config"):
+    getattr(_lib, _name).restype = _i
+
+_LAYOUT = {"row": XP_ROW, "col": XP_COL, XP_ROW: XP_ROW, XP_COL: XP_COL}
+_FILTER = {"krsc": XP_FILTER_KRSC, "rsck": XP_FILTER_RSCK, 0: 0, 1: 1}
+_DTYPE = {torch.float32: XP_F32, torch.bfloat16: XP_BF16, torch.int16: XP_BF16, torch.uint16: XP_BF16,
+          torch.int8: XP_I8, torch.int32: XP_I32}
+DTYPE_BY_NAME = {"f32": XP_F32, "bf16": XP_BF16, "i8": XP_I8, "i32": XP_I32}
+
+
+class XpError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"xp status {status}: {status_string(status)}")
+
+
+def status_string(status: int) -> str:
+    return _lib.xp_status_string(status).decode()
+
+
+def version() -> str:
+    return _lib.xp_version().decode()
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _dt(t, override=None):
+    if override is not None:
+        return DTYPE_BY_NAME.get(override, override)
+    return _DTYPE[t.dtype]
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+
+
+def _check(status: int):
+    if status != XP_OK:
+        raise XpError(status)
+
+
+def xp_gemm(M, N, K, alpha, A, a_layout, lda, B, b_layout, ldb, beta, C_, c_layout, ldc, stream=None,
+            a_type=None, b_type=None, c_type=None):
+    """C = alpha * A.B + beta * C on the GPU (see include/xp.h: xp_gemm)."""
+    _check(_lib.xp_gemm(M, N, K, alpha, _ptr(A), _dt(A, a_type), _LAYOUT[a_layout], lda,
+                        _ptr(B), _dt(B, b_type), _LAYOUT[b_layout], ldb, beta,
+                        _ptr(C_), _dt(C_, c_type), _LAYOUT[c_layout], ldc, _stream(stream)))
+
+
+def xp_gemm_batched(batch, M, N, K, alpha, A, a_layout, lda, strideA, B, b_layout, ldb, strideB, beta,
+                    C_, c_layout, ldc, strideC, stream=None, a_type=None, b_type=None, c_type=None):
+    """Strided-batched GEMM on the GPU (see include/xp.h: xp_gemm_batched)."""
+    _check(_lib.xp_gemm_batched(batch, M, N, K, alpha, _ptr(A), _dt(A, a_type), _LAYOUT[a_layout], lda, strideA,
+                                _ptr(B), _dt(B, b_type), _LAYOUT[b_layout], ldb, strideB, beta,
+                                _ptr(C_), _dt(C_, c_type), _LAYOUT[c_layout], ldc, strideC, _stream(stream)))
+
+
+def xp_conv2d_nhwc(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, x, w, filter_layout, out,
+                   stream=None, in_type=None, w_type=None, out_type=None):
+    """NHWC convolution as an implicit GEMM on the GPU (see include/xp.h: xp_conv2d_nhwc)."""
+    _check(_lib.xp_conv2d_nhwc(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w,
+                               _ptr(x), _dt(x, in_type), _ptr(w), _dt(w, w_type), _FILTER[filter_layout],
+                               _ptr(out), _dt(out, out_type), _stream(stream)))
+
+
+def xp_num_configs(op: int, in_type) -> int:
+    return _lib.xp_num_configs(op, DTYPE_BY_NAME.get(in_type, in_type))
+
+
+def xp_describe_config(op: int, in_type, idx: int) -> str:
+    buf = C.create_string_buffer(256)
+    _check(_lib.xp_describe_config(op, DTYPE_BY_NAME.get(in_type, in_type), idx, buf, 256))
+    return buf.value.decode()
+
+
+def xp_force_config(op: int, in_type, idx: int) -> None:
+    _check(_lib.xp_force_config(op, DTYPE_BY_NAME.get(in_type, in_type), idx))
+
+
+def xp_last_config(op: int, in_type) -> int:
+    return _lib.xp_last_config(op, DTYPE_BY_NAME.get(in_type, in_type))
+
+
+def raw() -> C.CDLL:
+    """The ctypes handle itself, for tests of argument validation with raw pointers."""
+    return _lib

@@ -1,0 +1,125 @@
+"""Host-side checks that need no GPU: the library loads, exports the declared symbols, and
+validates arguments before touching the device."""
+import ctypes
+import pathlib
+import re
+
+import pytest
+
+ROOT = pathlib.Path(__file__).resolve().parent.parent
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2505_02146_amd import xp
+    return xp.raw()
+
+
+def _declared_symbols():
+    text = (ROOT / "include" / "xp.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(xp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_symbols()
+    assert {"xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_num_configs", "xp_describe_config",
+            "xp_force_config", "xp_last_config", "xp_status_string", "xp_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_oracle_and_library_share_no_code():
+    # neither side includes or imports the other
+    for f in (ROOT / "paper_2505_02146_amd").rglob("*"):
+        if f.suffix in (".hip", ".hpp", ".py", ".h"):
+            t = f.read_text()
+            assert "xp_oracle" not in t and "import oracle" not in t and "from oracle" not in t, f
+    for f in (ROOT / "oracle").glob("*"):
+        if f.suffix in (".c", ".h", ".py"):
+            t = f.read_text()
+            assert "paper_2505_02146_amd" not in t and "xp.h" not in t, f
+
+
+def test_variant_tables(lib):
+    from paper_2505_02146_amd import xp
+    for t in ("f32", "bf16", "i8"):
+        n = xp.xp_num_configs(xp.XP_OP_GEMM, t)
+        assert n >= 2
+        names = [xp.xp_describe_config(xp.XP_OP_GEMM, t, i) for i in range(n)]
+        assert len(set(names)) == n
+        assert names[0].startswith("general")
+    assert xp.xp_num_configs(xp.XP_OP_GEMM, xp.XP_I32) == 0
+    buf = ctypes.create_string_buffer(8)
+    assert lib.xp_describe_config(0, xp.XP_BF16, 999, buf, 8) == 6
+    assert lib.xp_describe_config(0, xp.XP_BF16, 1, buf, 8) == 0 and len(buf.value) == 7   # truncated, NUL kept
+    assert lib.xp_force_config(0, xp.XP_BF16, 999) == 6
+    assert lib.xp_force_config(0, xp.XP_BF16, -1) == 0
+    assert lib.xp_last_config(0, xp.XP_I32) == -1
+
+
+def _gemm(lib, M=4, N=4, K=4, alpha=1.0, A=16, at=0, al=0, lda=4, B=16, bt=0, bl=0, ldb=4, beta=0.0,
+          C=16, ct=0, cl=0, ldc=4):
+    return lib.xp_gemm(M, N, K, alpha, A, at, al, lda, B, bt, bl, ldb, beta, C, ct, cl, ldc, None)
+
+
+def test_gemm_validation_returns_before_any_launch(lib):
+    # pointers are fake (never dereferenced on the host, and every call below is rejected)
+    assert _gemm(lib, M=-1) == 2
+    assert _gemm(lib, K=-3) == 2
+    assert _gemm(lib, A=None) == 1
+    assert _gemm(lib, C=None) == 1
+    assert _gemm(lib, lda=3) == 3
+    assert _gemm(lib, ldb=3) == 3
+    assert _gemm(lib, ldc=3) == 3
+    assert _gemm(lib, al=1, lda=3, M=4, K=2) == 3          # column-major A needs ld >= M
+    assert _gemm(lib, at=1, bt=0) == 5                     # mixed input types
+    assert _gemm(lib, at=2, bt=2, ct=0) == 5               # int8 needs int32 output
+    assert _gemm(lib, at=2, bt=2, ct=3, alpha=2.0) == 5    # int8 has no scaling
+    assert _gemm(lib, at=2, bt=2, ct=3, beta=1.0) == 5
+    assert _gemm(lib, at=1, bt=1, ct=1) == 5               # bf16 output not provided
+    assert _gemm(lib, al=7) == 5
+    assert _gemm(lib, A=18) == 4                           # fp32 pointer not 4-byte aligned
+    # empty problems succeed without a launch (and without looking at the pointers)
+    assert _gemm(lib, M=0, A=None, B=None, C=None) == 0
+    assert _gemm(lib, N=0, A=None, B=None, C=None) == 0
+
+
+def test_batched_validation(lib):
+    def call(batch=2, sa=16, sb=16, sc=16, **kw):
+        a = dict(M=4, N=4, K=4, alpha=1.0, A=16, at=0, al=0, lda=4, B=16, bt=0, bl=0, ldb=4, beta=0.0,
+                 C=16, ct=0, cl=0, ldc=4)
+        a.update(kw)
+        return lib.xp_gemm_batched(batch, a["M"], a["N"], a["K"], a["alpha"], a["A"], a["at"], a["al"], a["lda"], sa,
+                                   a["B"], a["bt"], a["bl"], a["ldb"], sb, a["beta"], a["C"], a["ct"], a["cl"],
+                                   a["ldc"], sc, None)
+    assert call(batch=-1) == 2
+    assert call(sc=15) == 3                                # C slices would overlap
+    assert call(sa=-1) == 3
+    assert call(batch=0, A=None, B=None, C=None) == 0
+    assert call(A=None) == 1
+
+
+def test_conv_validation(lib):
+    def call(N=1, H=4, W=4, Cin=2, Cout=2, R=3, S=3, sh=1, sw=1, ph=1, pw=1, x=16, xt=0, w=16, wt=0, wl=0,
+             out=16, ot=0):
+        return lib.xp_conv2d_nhwc(N, H, W, Cin, Cout, R, S, sh, sw, ph, pw, x, xt, w, wt, wl, out, ot, None)
+    assert call(N=-1) == 2
+    assert call(R=0) == 2
+    assert call(sh=0) == 2
+    assert call(ph=-1) == 2
+    assert call(x=None) == 1
+    assert call(out=None) == 1
+    assert call(xt=2, wt=2) == 5                           # int8 convolution not provided
+    assert call(xt=1, wt=0) == 5
+    assert call(ot=1) == 5
+    assert call(wl=3) == 5
+    assert call(H=1, W=1, ph=0, pw=0, x=None, w=None, out=None) == 0   # filter larger than image: empty
+    assert call(N=0, x=None, w=None, out=None) == 0
+
+
+def test_status_strings(lib):
+    from paper_2505_02146_amd import xp
+    seen = {xp.status_string(i) for i in range(8)}
+    assert len(seen) == 8 and "ok" in seen
+    assert "gfx950" in xp.version()

@@ -1,0 +1,294 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Gates: int8 -> int32 results bit-exact; floating point elementwise |err| <= 1e-2 (|ref| + 1) and
+relative Frobenius error <= 5e-3, plus the tighter fp32-accumulation bound in helpers.py, plus
+bit-exactness on integer-valued inputs (every partial sum exactly representable in fp32).
+Every kernel variant is forced in turn, then the library's own selection is checked.
+"""
+import numpy as np
+import pytest
+
+from paper_2505_02146_amd import inputs
+from tests.helpers import check_float, dev, store, unstore
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = [("row", "col"), ("row", "row"), ("col", "row"), ("col", "col")]
+# sizes: single element, below one MFMA block, around tile edges, several 256-tiles with ragged tails
+SHAPES = [(1, 1, 1), (15, 17, 16), (33, 31, 8), (63, 65, 64), (129, 255, 72), (257, 130, 200), (300, 520, 328)]
+
+
+@pytest.fixture(scope="module")
+def xp():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2505_02146_amd import xp as m
+    yield m
+    for op in (0, 1, 2):
+        for t in ("f32", "bf16", "i8"):
+            m.xp_force_config(op, t, -1)
+
+
+def _variants(xp, op, t):
+    return list(range(xp.xp_num_configs(op, t))) + [-1]
+
+
+def _make(kind, shape, seed, tid, integer=False):
+    if kind == "i8":
+        return inputs.int8_uniform(shape, seed, tid)
+    x = inputs.small_integers(shape, seed, tid) if integer else inputs.normal(shape, seed, tid)
+    return x if kind == "f32" else inputs.to_bf16_bits(x)
+
+
+def _run_gemm(xp, oracle, kind, M, N, K, la, lb, lc="row", pads=(0, 0, 0), alpha=1.0, beta=0.0, integer=False,
+              seed=1, variants=None):
+    import torch
+    A = _make(kind, (M, K), seed, 1, integer)
+    B = _make(kind, (K, N), seed, 2, integer)
+    a, lda = store(A, la, pads[0])
+    b, ldb = store(B, lb, pads[1])
+    out_np = np.int32 if kind == "i8" else np.float32
+    C0 = inputs.small_integers((M, N), seed, 3).astype(out_np)
+    c0, ldc = store(C0, lc, pads[2], fill=7)
+    if kind == "i8":
+        ref = oracle.gemm_i8(M, N, K, a, la, b, lb, lda=lda, ldb=ldb)
+    else:
+        ref = oracle.gemm_float(M, N, K, a, la, b, lb, lda=lda, ldb=ldb, alpha=alpha, beta=beta,
+                                C0=c0 if beta != 0 else None, c_layout=lc, ldc=ldc)
+    da, db = dev(a), dev(b)
+    ran = 0
+    for v in (variants if variants is not None else _variants(xp, 0, kind)):
+        xp.xp_force_config(0, kind, v)
+        if beta == 0 and kind != "i8":
+            poison = c0.copy()
+            poison[:] = np.nan                       # beta == 0 must not read C
+            dc = dev(poison)
+        else:
+            dc = dev(c0)
+        try:
+            xp.xp_gemm(M, N, K, alpha, da, la, lda, db, lb, ldb, beta, dc, lc, ldc,
+                       a_type=kind, b_type=kind)
+        except xp.XpError as e:
+            assert e.status == 6 and v > 0, (v, e)   # a forced tuned variant may decline a layout
+            continue
+        torch.cuda.synchronize()
+        got_buf = dc.cpu().numpy()
+        got = unstore(got_buf, lc, M, N, ldc)
+        what = f"{kind} {M}x{N}x{K} {la}/{lb}/{lc} variant {v} ({xp.xp_last_config(0, kind)})"
+        if kind == "i8" or integer:
+            assert np.array_equal(got.astype(np.float64), ref.astype(np.float64)), what
+        else:
+            check_float(got, ref, what)
+        # padding of C (between ld and the extent) must be untouched
+        if pads[2]:
+            full = got_buf.reshape(-1, ldc)
+            ext = N if lc == "row" else M
+            keep = c0.reshape(-1, ldc)[:, ext:] if beta != 0 or kind == "i8" else None
+            if keep is not None:
+                assert np.array_equal(full[:, ext:], keep), what + " wrote into the ld padding"
+            else:
+                assert np.all(np.isnan(full[:, ext:])), what + " wrote into the ld padding"
+        ran += 1
+    xp.xp_force_config(0, kind, -1)
+    assert ran >= 2
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16", "i8"])
+@pytest.mark.parametrize("la,lb", LAYOUTS)
+def test_gemm_shapes_all_variants(xp, oracle, kind, la, lb):
+    for (M, N, K) in SHAPES:
+        _run_gemm(xp, oracle, kind, M, N, K, la, lb, seed=M + N)
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+def test_gemm_integer_inputs_bit_exact(xp, oracle, kind):
+    # every partial sum is an integer below 2^24: any summation order gives the same fp32 bits
+    for (M, N, K) in [(64, 64, 64), (257, 130, 200), (300, 520, 1024)]:
+        for la, lb in LAYOUTS[:2]:
+            _run_gemm(xp, oracle, kind, M, N, K, la, lb, integer=True)
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+def test_gemm_alpha_beta_ld_padding_and_col_major_c(xp, oracle, kind):
+    _run_gemm(xp, oracle, kind, 130, 70, 96, "row", "col", lc="row", pads=(8, 16, 5), alpha=2.0, beta=3.0, integer=True)
+    _run_gemm(xp, oracle, kind, 130, 70, 96, "row", "col", lc="col", pads=(8, 8, 3), alpha=-0.5, beta=0.25)
+    _run_gemm(xp, oracle, kind, 130, 70, 96, "col", "row", lc="col", pads=(8, 8, 2))
+    _run_gemm(xp, oracle, kind, 70, 300, 40, "row", "col", lc="row", pads=(3, 5, 1))       # unaligned ld
+
+
+def test_gemm_int8_padding_and_col_major_c(xp, oracle):
+    _run_gemm(xp, oracle, "i8", 130, 70, 96, "row", "col", lc="col", pads=(16, 32, 3))
+    _run_gemm(xp, oracle, "i8", 70, 300, 40, "row", "col", lc="row", pads=(3, 5, 1))
+
+
+def test_int8_extremes_on_gpu(xp, oracle):
+    import torch
+    M, N, K = 64, 64, 8192
+    for va, vb, want in [(-128, -128, 2 ** 27), (-128, 127, -133169152)]:
+        a = dev(np.full((M, K), va, np.int8))
+        b = dev(np.full((N, K), vb, np.int8))
+        for v in _variants(xp, 0, "i8"):
+            xp.xp_force_config(0, "i8", v)
+            c = torch.zeros((M, N), dtype=torch.int32, device="cuda")
+            xp.xp_gemm(M, N, K, 1.0, a, "row", K, b, "col", K, 0.0, c, "row", N)
+            assert torch.all(c == want), (va, vb, v)
+    xp.xp_force_config(0, "i8", -1)
+
+
+def test_gemm_k_zero_and_closed_forms(xp, oracle):
+    import torch
+    # K == 0: C = beta * C
+    c = torch.full((5, 7), 2.0, device="cuda")
+    a = torch.zeros(1, device="cuda")
+    xp.xp_gemm(5, 7, 0, 1.0, a, "row", 1, a, "row", 7, 3.0, c, "row", 7)
+    assert torch.all(c == 6.0)
+    c = torch.full((5, 7), float("nan"), device="cuda")
+    xp.xp_gemm(5, 7, 0, 1.0, a, "row", 1, a, "row", 7, 0.0, c, "row", 7)
+    assert torch.all(c == 0.0)
+    # identity and all-ones through every bf16 variant
+    n = 288
+    eye = dev(inputs.to_bf16_bits(np.eye(n, dtype=np.float32)))
+    x = inputs.to_bf16_bits(inputs.normal((n, n), 4, 1))
+    dx = dev(x)
+    ones = dev(inputs.to_bf16_bits(np.ones((n, n), np.float32)))
+    for v in _variants(xp, 0, "bf16"):
+        xp.xp_force_config(0, "bf16", v)
+        c = torch.empty((n, n), device="cuda")
+        xp.xp_gemm(n, n, n, 1.0, dx, "row", n, eye, "col", n, 0.0, c, "row", n, a_type="bf16", b_type="bf16")
+        assert np.array_equal(c.cpu().numpy(), inputs.bf16_bits_to_f32(x)), v
+        xp.xp_gemm(n, n, n, 1.0, ones, "row", n, ones, "col", n, 0.0, c, "row", n, a_type="bf16", b_type="bf16")
+        assert torch.all(c == float(n)), v
+    xp.xp_force_config(0, "bf16", -1)
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16", "i8"])
+def test_batched(xp, oracle, kind):
+    import torch
+    for batch, M, N, K, la, lb in [(1, 40, 50, 64, "row", "col"), (3, 129, 70, 80, "row", "col"),
+                                   (3, 70, 64, 144, "row", "row"), (5, 33, 17, 16, "col", "col")]:
+        sA, sB, sC = M * K + 16, K * N + 32, M * N + 8
+        A = np.concatenate([np.concatenate([store(_make(kind, (M, K), 10 + i, 1), la)[0],
+                                            np.zeros(16, _make(kind, (1, 1), 0, 1).dtype)]) for i in range(batch)])
+        B = np.concatenate([np.concatenate([store(_make(kind, (K, N), 10 + i, 2), lb)[0],
+                                            np.zeros(32, A.dtype)]) for i in range(batch)])
+        lda = K if la == "row" else M
+        ldb = N if lb == "row" else K
+        if kind == "i8":
+            ref = np.stack([oracle.gemm_i8(M, N, K, A[i * sA:i * sA + M * K].copy(), la,
+                                           B[i * sB:i * sB + K * N].copy(), lb) for i in range(batch)])
+        else:
+            ref = oracle.gemm_float_batched(batch, M, N, K, A, la, B, lb, strideA=sA, strideB=sB)
+        da, db = dev(A), dev(B)
+        for v in _variants(xp, 1, kind):
+            xp.xp_force_config(1, kind, v)
+            c = torch.full((batch * sC,), 7, dtype=torch.int32 if kind == "i8" else torch.float32, device="cuda")
+            try:
+                xp.xp_gemm_batched(batch, M, N, K, 1.0, da, la, lda, sA, db, lb, ldb, sB, 0.0, c, "row", N, sC,
+                                   a_type=kind, b_type=kind)
+            except xp.XpError as e:
+                assert e.status == 6 and v > 0
+                continue
+            got = c.cpu().numpy().reshape(batch, sC)
+            assert np.all(got[:, M * N:] == 7), "wrote between the C slices"
+            got = got[:, :M * N].reshape(batch, M, N)
+            what = f"batched {kind} {batch}x{M}x{N}x{K} {la}/{lb} variant {v}"
+            if kind == "i8":
+                assert np.array_equal(got, ref), what
+            else:
+                check_float(got, ref, what)
+        xp.xp_force_config(1, kind, -1)
+    # shared B operand (strideB == 0)
+    if kind != "i8":
+        batch, M, N, K = 4, 64, 48, 32
+        A = _make(kind, (batch, M, K), 3, 1)
+        B = _make(kind, (N, K), 3, 2)
+        ref = np.stack([oracle.gemm_float(M, N, K, A[i].reshape(-1), "row", B.reshape(-1), "col") for i in range(batch)])
+        c = torch.empty((batch, M, N), device="cuda")
+        xp.xp_gemm_batched(batch, M, N, K, 1.0, dev(A.reshape(-1)), "row", K, M * K, dev(B.reshape(-1)), "col", K, 0,
+                           0.0, c, "row", N, M * N, a_type=kind, b_type=kind)
+        check_float(c.cpu().numpy(), ref, "shared B")
+
+
+CONV_CASES = [
+    # N, H, W, Cin, Cout, R, S, stride, pad
+    (2, 9, 7, 64, 40, 3, 3, (1, 1), (1, 1)),
+    (1, 12, 12, 128, 96, 3, 3, (2, 2), (1, 1)),
+    (2, 8, 10, 64, 64, 1, 1, (1, 1), (0, 0)),
+    (1, 7, 9, 8, 5, 3, 2, (1, 2), (2, 1)),          # Cin not a multiple of the K step: general kernel
+    (3, 6, 6, 192, 300, 2, 3, (1, 1), (0, 2)),
+    (1, 20, 20, 64, 16, 5, 5, (3, 1), (2, 2)),
+]
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+@pytest.mark.parametrize("fl", ["krsc", "rsck"])
+def test_conv_cases(xp, oracle, kind, fl):
+    import torch
+    for (N, H, W, Cin, Cout, R, S, stride, pad) in CONV_CASES:
+        x = _make(kind, (N, H, W, Cin), 5, 1)
+        w = _make(kind, (Cout, R, S, Cin), 5, 2)
+        wbuf = w if fl == "krsc" else np.ascontiguousarray(w.transpose(1, 2, 3, 0))
+        ref = oracle.conv2d_nhwc(x, wbuf, N=N, H=H, W=W, Cin=Cin, Cout=Cout, R=R, S=S, stride=stride, pad=pad,
+                                 filter_layout=fl)
+        P, Q = ref.shape[1:3]
+        dx, dw = dev(x.reshape(-1)), dev(wbuf.reshape(-1))
+        ran = 0
+        for v in _variants(xp, 2, kind):
+            xp.xp_force_config(2, kind, v)
+            out = torch.full((N, P, Q, Cout), float("nan"), device="cuda")
+            try:
+                xp.xp_conv2d_nhwc(N, H, W, Cin, Cout, R, S, stride[0], stride[1], pad[0], pad[1], dx, dw, fl, out,
+                                  in_type=kind, w_type=kind)
+            except xp.XpError as e:
+                assert e.status == 6 and v > 0
+                continue
+            check_float(out.cpu().numpy(), ref, f"conv {kind} {fl} {(N, H, W, Cin, Cout, R, S, stride, pad)} variant {v}")
+            ran += 1
+        assert ran >= 2
+    xp.xp_force_config(2, kind, -1)
+
+
+def test_conv_closed_forms(xp):
+    import torch
+    # delta filter reproduces the input; shifted delta shifts it; all-ones counts valid taps
+    N, H, W, C = 2, 10, 9, 64
+    x = inputs.to_bf16_bits(inputs.normal((N, H, W, C), 2, 1))
+    xf = inputs.bf16_bits_to_f32(x)
+    w = np.zeros((C, 3, 3, C), np.float32)
+    w[np.arange(C), 1, 1, np.arange(C)] = 1.0
+    ws = np.zeros((C, 3, 3, C), np.float32)
+    ws[np.arange(C), 0, 0, np.arange(C)] = 1.0
+    ones_w = np.ones((C, 3, 3, C), np.float32)
+    dx = dev(x.reshape(-1))
+    for v in _variants(xp, 2, "bf16"):
+        xp.xp_force_config(2, "bf16", v)
+        out = torch.empty((N, H, W, C), device="cuda")
+        xp.xp_conv2d_nhwc(N, H, W, C, C, 3, 3, 1, 1, 1, 1, dx, dev(inputs.to_bf16_bits(w).reshape(-1)), "krsc", out,
+                          in_type="bf16", w_type="bf16")
+        assert np.array_equal(out.cpu().numpy(), xf), v
+        xp.xp_conv2d_nhwc(N, H, W, C, C, 3, 3, 1, 1, 1, 1, dx, dev(inputs.to_bf16_bits(ws).reshape(-1)), "krsc", out,
+                          in_type="bf16", w_type="bf16")
+        want = np.zeros_like(xf)
+        want[:, 1:, 1:] = xf[:, :-1, :-1]
+        assert np.array_equal(out.cpu().numpy(), want), v
+        xp.xp_conv2d_nhwc(N, H, W, C, C, 3, 3, 1, 1, 1, 1, dev(inputs.to_bf16_bits(np.ones_like(xf)).reshape(-1)),
+                          dev(inputs.to_bf16_bits(ones_w).reshape(-1)), "krsc", out, in_type="bf16", w_type="bf16")
+        o = out.cpu().numpy()
+        assert np.all(o[:, 1:-1, 1:-1] == 9 * C) and np.all(o[:, 0, 1:-1] == 6 * C) and np.all(o[:, 0, 0] == 4 * C), v
+    xp.xp_force_config(2, "bf16", -1)
+
+
+def test_stream_argument_is_used(xp, oracle):
+    import torch
+    M = N = K = 128
+    A = inputs.uniform_pm1((M, K), 0, 1)
+    B = inputs.uniform_pm1((K, N), 0, 2)
+    ref = oracle.gemm_float(M, N, K, A.reshape(-1), "row", B.reshape(-1), "row")
+    s = torch.cuda.Stream()
+    da, db = dev(A), dev(B)
+    c = torch.empty((M, N), device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        xp.xp_gemm(M, N, K, 1.0, da, "row", K, db, "row", N, 0.0, c, "row", N)
+    s.synchronize()
+    check_float(c.cpu().numpy(), ref, "side stream")
