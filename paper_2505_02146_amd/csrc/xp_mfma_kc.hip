@@ -64,6 +64,7 @@ struct Tile {
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave sub-tile must be whole MFMA blocks");
     static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0, "staging must divide evenly");
     static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
+    static_assert(NSTAGE == 2, "the pipeline ping-pongs between two LDS buffers");
 };
 
 // chunk swizzle: a per-row XOR of the 16-byte chunk index; distinct for 8 consecutive rows and
@@ -186,12 +187,17 @@ __global__ __launch_bounds__(T::NT) void kc_kernel(KcParams p)
     // conv: the K offset of a step is (tap, c0); it advances without divisions
     int tap_r = 0, tap_s = 0, c0_b = 0;
 
-    auto load_global = [&](int kt) {
+    // One staging slot = one 16-byte chunk per thread: slots [0, LA) belong to A, the rest to B.
+    // Loads past the last K step are redirected out of range (they return zeros without touching
+    // memory), so the pipeline below needs no conditionals.
+    constexpr int NSLOT = T::LA + T::LB;
+    auto kmask_of = [&](int kt) -> unsigned {
         const int kb = kt * ROWB;
-        const bool tail = kb + ROWB > p.Kb;            // only the last step can be partial
-        const unsigned kmask = (tail && kb + (chunk << 4) >= p.Kb) ? OOB : 0u;
-#pragma unroll
-        for (int i = 0; i < T::LA; ++i) {
+        return (kb + (chunk << 4) >= p.Kb) ? OOB : 0u;
+    };
+    auto load_slot = [&](int i, int kt, unsigned kmask) {
+        const int kb = kt * ROWB;
+        if (i < T::LA) {
             unsigned off;
             int soff;
             if constexpr (CONV) {
@@ -204,10 +210,11 @@ __global__ __launch_bounds__(T::NT) void kc_kernel(KcParams p)
                 soff = kb;
             }
             ga[i] = __builtin_amdgcn_raw_buffer_load_b128(ra, off | kmask, soff, 0);
+        } else {
+            gb[i - T::LA] = __builtin_amdgcn_raw_buffer_load_b128(rb, b_off[i - T::LA] | kmask, kb, 0);
         }
-#pragma unroll
-        for (int i = 0; i < T::LB; ++i)
-            gb[i] = __builtin_amdgcn_raw_buffer_load_b128(rb, b_off[i] | kmask, kb, 0);
+    };
+    auto advance_tap = [&]() {
         if constexpr (CONV) {
             c0_b += ROWB;
             if (c0_b >= p.Cin_b) {
@@ -216,46 +223,90 @@ __global__ __launch_bounds__(T::NT) void kc_kernel(KcParams p)
             }
         }
     };
-    auto store_lds = [&](int stage) {
-        char *base = lds + stage * T::STAGE;
-#pragma unroll
-        for (int i = 0; i < T::LA; ++i) *(u32x4 *)(base + a_lds[i]) = ga[i];
-#pragma unroll
-        for (int i = 0; i < T::LB; ++i) *(u32x4 *)(base + b_lds[i]) = gb[i];
+    auto store_slot = [&](int i, int stage_off) {
+        if (i < T::LA) *(u32x4 *)(lds + stage_off + a_lds[i]) = ga[i];
+        else *(u32x4 *)(lds + stage_off + b_lds[i - T::LA]) = gb[i - T::LA];
     };
-    auto compute = [&](int stage) {
-        const char *base = lds + stage * T::STAGE;
+    auto read_frags = [&](int stage_off, int kk, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            u32x4 af[T::MI], bf[T::NI];
+        for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(lds + stage_off + fa[kk] + i * 32 * ROWB);
 #pragma unroll
-            for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(base + fa[kk] + i * 32 * ROWB);
+        for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + stage_off + fb[kk] + j * 32 * ROWB);
+    };
+    auto mma_all = [&](const u32x4 (&af)[T::MI], const u32x4 (&bf)[T::NI]) {
 #pragma unroll
-            for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(base + fb[kk] + j * 32 * ROWB);
+        for (int i = 0; i < T::MI; ++i)
 #pragma unroll
-            for (int i = 0; i < T::MI; ++i)
-#pragma unroll
-                for (int j = 0; j < T::NI; ++j) acc[i][j] = Acc<INT8>::mma(af[i], bf[j], acc[i][j]);
-        }
+            for (int j = 0; j < T::NI; ++j) acc[i][j] = Acc<INT8>::mma(af[i], bf[j], acc[i][j]);
     };
 
-    // ---- pipeline
+    // ---- pipeline.  Per K step (4 MFMA sub-steps kk of 32 bytes of K each):
+    //   sub-steps 0..2: read the fragments of sub-step kk+1, write a third of the staged tile of
+    //                   step kt+1 to the other LDS buffer and re-issue those slots' global loads
+    //                   for step kt+2, then multiply sub-step kk
+    //   sub-step 3:     wait for this wave's LDS traffic, workgroup barrier, read the fragments of
+    //                   sub-step 0 of the next buffer, then multiply sub-step 3 (whose fragments
+    //                   were read before the barrier), so that the barrier is covered by MFMA work
+    // Fragments ping-pong between two register sets (X, Y).
     const int KT = p.KT;
     if (KT > 0) {
-        load_global(0);
-        store_lds(0);
-        if (KT > 1) load_global(1);
+        u32x4 xa[T::MI], xb[T::NI], ya[T::MI], yb[T::NI];
+        {
+            const unsigned km = kmask_of(0);
+#pragma unroll
+            for (int i = 0; i < NSLOT; ++i) load_slot(i, 0, km);
+            advance_tap();
+#pragma unroll
+            for (int i = 0; i < NSLOT; ++i) store_slot(i, 0);
+            const unsigned km1 = kmask_of(1);
+#pragma unroll
+            for (int i = 0; i < NSLOT; ++i) load_slot(i, 1, km1);
+            advance_tap();
+        }
         __builtin_amdgcn_s_waitcnt(0xc07f);     // lgkmcnt(0): this wave's LDS writes have landed
         __builtin_amdgcn_s_barrier();
-        int stage = 0;
+        read_frags(0, 0, xa, xb);
+        int cur = 0;
+        constexpr int S0 = (NSLOT + 2) / 3, S1 = (2 * NSLOT + 2) / 3;
         for (int kt = 0; kt < KT; ++kt) {
-            const int nxt = stage + 1 == T::NSTAGE ? 0 : stage + 1;
-            if (kt + 1 < KT) store_lds(nxt);    // the buffer last read one barrier ago
-            if (kt + 2 < KT) load_global(kt + 2);
-            compute(stage);
+            const int nxt = cur ^ T::STAGE;     // two buffers
+            const unsigned km = kmask_of(kt + 2);
+            // sub-step 0
+            read_frags(cur, 1, ya, yb);
+#pragma unroll
+            for (int i = 0; i < S0; ++i) store_slot(i, nxt);
+#pragma unroll
+            for (int i = 0; i < S0; ++i) load_slot(i, kt + 2, km);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_all(xa, xb);
+            __builtin_amdgcn_sched_barrier(0);
+            // sub-step 1
+            read_frags(cur, 2, xa, xb);
+#pragma unroll
+            for (int i = S0; i < S1; ++i) store_slot(i, nxt);
+#pragma unroll
+            for (int i = S0; i < S1; ++i) load_slot(i, kt + 2, km);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_all(ya, yb);
+            __builtin_amdgcn_sched_barrier(0);
+            // sub-step 2
+            read_frags(cur, 3, ya, yb);
+#pragma unroll
+            for (int i = S1; i < NSLOT; ++i) store_slot(i, nxt);
+#pragma unroll
+            for (int i = S1; i < NSLOT; ++i) load_slot(i, kt + 2, km);
+            advance_tap();
+            __builtin_amdgcn_sched_barrier(0);
+            mma_all(xa, xb);
+            __builtin_amdgcn_sched_barrier(0);
+            // sub-step 3
             __builtin_amdgcn_s_waitcnt(0xc07f);
             __builtin_amdgcn_s_barrier();
-            stage = nxt;
+            read_frags(nxt, 0, xa, xb);          // garbage after the last step, never multiplied
+            __builtin_amdgcn_sched_barrier(0);
+            mma_all(ya, yb);
+            __builtin_amdgcn_sched_barrier(0);
+            cur = nxt;
         }
     }
 
