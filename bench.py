@@ -47,6 +47,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--only-main", action="store_true", help="skip the int8 / batched / conv side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device-to-device copy (a known-size reference for "
+                         "scaling the profiler's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -93,6 +96,13 @@ def main() -> int:
                      "frac": round(tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
                      "kernel_ms": round(ev_ms, 5)},
     }
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- side measurements named by the metric
     if not args.only_main:
@@ -148,14 +158,14 @@ def main() -> int:
     # ---- CPU oracle on a bounded sample of the main workload (reported baseline, not the target)
     if not args.no_cpu:
         import oracle
-        rows = 1536
+        rows = M          # the whole job: about 4-10 s on 16 host cores
         a_sample = np.ascontiguousarray(w["A"][:rows]).reshape(-1)
         t0 = time.perf_counter()
         oracle.gemm_float(rows, N, K, a_sample, "row", w["B"].reshape(-1), "col")
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(2.0 * rows * N * K / dt / 1e12, 5), "unit": "TFLOP/s",
                                "cores": oracle.num_threads(), "kind": "oracle",
-                               "sample": f"first {rows} of {M} rows of C (all {N} columns, full K), {dt:.1f} s",
+                               "sample": f"all {rows} rows of C (the whole 4096^3 workload), {dt:.1f} s",
                                "host_cpus": os.cpu_count()}
 
     print(json.dumps(out))
