@@ -24,7 +24,10 @@ void build_tables()
     for (int s = 0; s < 3; ++s) {
         int n = generic_variants(types[s], g_table[s]);
         if (types[s] == XP_F32) n += f32_mfma_variants(g_table[s] + n);
-        else n += kc_variants(types[s], g_table[s] + n);
+        else {
+            n += kc_variants(types[s], g_table[s] + n);
+            n += dl_variants(types[s], g_table[s] + n);
+        }
         g_count[s] = n;
     }
 }

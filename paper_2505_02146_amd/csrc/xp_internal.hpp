@@ -44,6 +44,7 @@ const Variant *variant(xp_dtype in_type, int idx);
 int generic_variants(xp_dtype in_type, const Variant **out);
 int f32_mfma_variants(const Variant **out);
 int kc_variants(xp_dtype in_type, const Variant **out);
+int dl_variants(xp_dtype in_type, const Variant **out);
 
 inline int elem_size(xp_dtype t) { return t == XP_F32 || t == XP_I32 ? 4 : (t == XP_BF16 ? 2 : 1); }
 

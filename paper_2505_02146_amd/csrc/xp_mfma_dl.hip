@@ -1,0 +1,411 @@
+// MFMA kernels with direct global -> LDS loads ("dl") for operands contiguous along K:
+// bf16 x bf16 -> fp32 and int8 x int8 -> int32 GEMM, strided-batched GEMM and the implicit-GEMM
+// NHWC convolution (Table 5 of the paper: GEMM, Batch GEMM, Conv2D NHWC).
+//
+// Same tile / wave / MFMA structure as the register-staged kernels of xp_mfma_kc.hip, with a
+// different Cache + Pipeline realisation (the passes of Table 4 of the paper that stage data in
+// on-chip memory and overlap the copy with the computation):
+//   * 16-byte buffer loads write straight into LDS (no staging registers, no LDS write
+//     instructions).  One wave-level load fills 1024 contiguous LDS bytes, lane l at l*16, so
+//     the chunk swizzle is applied on the source side: lane l fetches the global chunk whose
+//     swizzled position is l.
+//   * a ring of NS LDS buffers: the loads for K step t+NS-1 are issued at the start of step t,
+//     into the buffer that was read in step t-1.  Before the one workgroup barrier of step t
+//     each wave waits until its own loads for step t+1 have landed (vmcnt), which leaves the
+//     loads NS-1 steps of MFMA work to complete.
+//   * loads past the last K step, rows past the matrix edge and convolution taps in the zero
+//     padding are redirected to an out-of-range buffer offset: the hardware writes zeros into
+//     LDS and touches no memory, so the pipeline needs no conditionals.
+#include "xp_internal.hpp"
+
+#include <type_traits>
+#include <utility>
+
+namespace xp {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void;
+
+constexpr unsigned OOB = 0x80000000u;     // byte offset outside every buffer range used here
+
+struct DlParams {
+    const char *A, *B;
+    char *C;
+    int M, N;
+    int Kb;                               // K in bytes
+    int KT;                               // number of K steps
+    long long lda_b, ldb_b;               // row pitches in bytes
+    long long ldc;                        // elements
+    long long strideA_b, strideB_b, strideC;
+    float alpha, beta;
+    int tiles_m, tiles_n, group_m;
+    unsigned in_bytes;                    // convolution view
+    int H, W, Cin_b, S, PQ, Q, sh, sw, ph, pw;
+};
+
+template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_>
+struct DlTile {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NS = NS_, RB = RB_;
+    static constexpr int NWAVE = WM * WN, NT = NWAVE * 64;
+    static constexpr int WTM = BM / WM, WTN = BN / WN;
+    static constexpr int MI = WTM / 32, NI = WTN / 32;
+    static constexpr int CPR = RB / 16;                 // 16-byte chunks per tile row
+    static constexpr int RPI = 64 / CPR;                // tile rows filled by one wave-level load
+    static constexpr int PH = RB / 32;                  // MFMA sub-steps per K step
+    static constexpr int IA = BM / RPI / NWAVE, IB = BN / RPI / NWAVE;   // loads per wave and step
+    static constexpr int STAGE = (BM + BN) * RB;
+    static constexpr int LDS = NS * STAGE;
+    static_assert(RB == 64 || RB == 128, "row bytes");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave sub-tile must be whole MFMA blocks");
+    static_assert(BM % (RPI * NWAVE) == 0 && BN % (RPI * NWAVE) == 0, "loads must divide evenly");
+    static_assert(NS >= 2 && (NS - 2) * (IA + IB) <= 63, "vmcnt is a 6-bit counter");
+    static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
+};
+
+// Chunk swizzle, a per-row XOR of the chunk index chosen so that 8 lanes (128-byte bank width)
+// and 16 lanes (256-byte bank width) reading the same logical chunk of consecutive rows hit
+// distinct banks.
+template <int RB> __device__ __forceinline__ int swz(int row)
+{
+    if constexpr (RB == 128) return (row & 7) ^ ((row >> 3) & 1);
+    else return ((row >> 1) ^ (row >> 3)) & 3;
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+
+// s_waitcnt immediate for "vmcnt <= n and lgkmcnt == 0" (gfx9 encoding, expcnt left open)
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4); }
+
+template <bool INT8> struct Acc;
+template <> struct Acc<false> {
+    typedef f32x16 type;
+    __device__ static __forceinline__ type mma(u32x4 a, u32x4 b, type c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                       c, 0, 0, 0);
+    }
+};
+template <> struct Acc<true> {
+    typedef i32x16 type;
+    __device__ static __forceinline__ type mma(u32x4 a, u32x4 b, type c)
+    {
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4, a), __builtin_bit_cast(i32x4, b),
+                                                     c, 0, 0, 0);
+    }
+};
+
+template <bool INT8, class T, bool CONV>
+__global__ __launch_bounds__(T::NT) void dl_kernel(DlParams p)
+{
+    using AccT = typename Acc<INT8>::type;
+    constexpr int RB = T::RB;
+    __shared__ __attribute__((aligned(1024))) char lds[T::LDS];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / T::WN, wn = wave % T::WN;
+
+    // workgroup -> tile: one XCD (workgroup id mod 8) owns a run of consecutive tiles, walked in
+    // groups of group_m tile-rows, so that the tiles sharing an L2 share A and B panels
+    int bid = blockIdx.x;
+    const int nb = p.tiles_m * p.tiles_n;
+    if ((nb & 7) == 0) bid = (bid & 7) * (nb >> 3) + (bid >> 3);
+    const int gsz = p.group_m * p.tiles_n;
+    const int g = bid / gsz, first_m = g * p.group_m;
+    const int gm = min(p.tiles_m - first_m, p.group_m);
+    const int tm = first_m + (bid % gsz) % gm, tn = (bid % gsz) / gm;
+    const int m0 = tm * T::BM, n0 = tn * T::BN;
+    const long long batch = blockIdx.y;
+
+    const int rows_a = min(p.M - m0, T::BM), rows_b = min(p.N - n0, T::BN);
+    __amdgpu_buffer_rsrc_t ra, rb;
+    if constexpr (CONV) {
+        ra = make_rsrc(p.A, p.in_bytes);
+    } else {
+        ra = make_rsrc(p.A + batch * p.strideA_b + (long long)m0 * p.lda_b,
+                       (unsigned)((long long)(rows_a - 1) * p.lda_b + p.Kb));
+    }
+    rb = make_rsrc(p.B + batch * p.strideB_b + (long long)n0 * p.ldb_b,
+                   (unsigned)((long long)(rows_b - 1) * p.ldb_b + p.Kb));
+
+    // load slots: slot i of this wave fills the 1024 LDS bytes of row block (wave + i*NWAVE);
+    // lane l lands at row l/CPR, position l%CPR, and fetches the chunk that belongs there
+    unsigned a_off[T::IA], b_off[T::IB];
+    int a_cb[T::IA], b_cb[T::IB];                       // byte offset of the fetched chunk within the row
+    int a_h0[CONV ? T::IA : 1], a_w0[CONV ? T::IA : 1];
+#pragma unroll
+    for (int i = 0; i < T::IA; ++i) {
+        const int row = (wave + i * T::NWAVE) * T::RPI + lane / T::CPR;
+        a_cb[i] = ((lane % T::CPR) ^ swz<RB>(row)) << 4;
+        if constexpr (CONV) {
+            const int m = m0 + row;
+            if (m < p.M) {
+                const int n = m / p.PQ, pq = m % p.PQ;
+                const int op = pq / p.Q, oq = pq % p.Q;
+                a_h0[i] = op * p.sh - p.ph;
+                a_w0[i] = oq * p.sw - p.pw;
+                a_off[i] = (unsigned)n * (unsigned)(p.H * p.W) * (unsigned)p.Cin_b + a_cb[i];
+            } else {
+                a_h0[i] = -0x40000000;                  // never inside the image
+                a_w0[i] = 0;
+                a_off[i] = 0;
+            }
+        } else {
+            a_off[i] = (unsigned)(row * p.lda_b) + a_cb[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < T::IB; ++i) {
+        const int row = (wave + i * T::NWAVE) * T::RPI + lane / T::CPR;
+        b_cb[i] = ((lane % T::CPR) ^ swz<RB>(row)) << 4;
+        b_off[i] = (unsigned)(row * p.ldb_b) + b_cb[i];
+    }
+
+    // fragment reads: lane l reads row (l & 31) of a 32-row block, chunk 2*kk + (l >> 5)
+    const int frow = lane & 31, fhi = lane >> 5;
+    const int fsw = swz<RB>(frow);                      // blocks start at multiples of 32 rows
+    int fa[T::PH], fb[T::PH];
+#pragma unroll
+    for (int kk = 0; kk < T::PH; ++kk) {
+        const int c = ((2 * kk + fhi) ^ fsw) << 4;
+        fa[kk] = (wm * T::WTM + frow) * RB + c;
+        fb[kk] = T::BM * RB + (wn * T::WTN + frow) * RB + c;
+    }
+
+    AccT acc[T::MI][T::NI];
+#pragma unroll
+    for (int i = 0; i < T::MI; ++i)
+#pragma unroll
+        for (int j = 0; j < T::NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    int tap_r = 0, tap_s = 0, c0_b = 0;                 // conv: K offset of the next step to load
+
+    // issue the loads of K step kt into LDS buffer `stage_off`
+    auto issue = [&](int kt, int stage_off) {
+        const int kb = kt * RB;
+#pragma unroll
+        for (int i = 0; i < T::IA; ++i) {
+            unsigned off;
+            int soff;
+            if constexpr (CONV) {
+                const int h = a_h0[i] + tap_r, w = a_w0[i] + tap_s;
+                const bool ok = (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W;
+                off = ok ? a_off[i] + (unsigned)(h * p.W + w) * (unsigned)p.Cin_b : OOB;
+                soff = c0_b;
+            } else {
+                off = a_off[i];
+                soff = kb;
+            }
+            if (kb + a_cb[i] >= p.Kb) off = OOB;
+            lds_void *dst = (lds_void *)(lds + stage_off + (wave + i * T::NWAVE) * 1024);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, dst, 16, off, soff, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < T::IB; ++i) {
+            unsigned off = b_off[i];
+            if (kb + b_cb[i] >= p.Kb) off = OOB;
+            lds_void *dst = (lds_void *)(lds + stage_off + T::BM * RB + (wave + i * T::NWAVE) * 1024);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, dst, 16, off, kb, 0, 0);
+        }
+        if constexpr (CONV) {
+            c0_b += RB;
+            if (c0_b >= p.Cin_b) {
+                c0_b = 0;
+                if (++tap_s == p.S) { tap_s = 0; ++tap_r; }
+            }
+        }
+    };
+    auto read_frags = [&](int stage_off, int kk, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
+#pragma unroll
+        for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(lds + stage_off + fa[kk] + i * 32 * RB);
+#pragma unroll
+        for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + stage_off + fb[kk] + j * 32 * RB);
+    };
+    auto mma_all = [&](const u32x4 (&af)[T::MI], const u32x4 (&bf)[T::NI]) {
+#pragma unroll
+        for (int i = 0; i < T::MI; ++i)
+#pragma unroll
+            for (int j = 0; j < T::NI; ++j) acc[i][j] = Acc<INT8>::mma(af[i], bf[j], acc[i][j]);
+    };
+
+    const int KT = p.KT;
+    constexpr int PENDING = (T::NS - 2) * (T::IA + T::IB);   // loads that may still be in flight at a barrier
+    if (KT > 0) {
+        u32x4 xa[T::MI], xb[T::NI], ya[T::MI], yb[T::NI];     // fragment sets of even / odd sub-steps
+#pragma unroll
+        for (int s = 0; s < T::NS - 1; ++s) issue(s, s * T::STAGE);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
+        __builtin_amdgcn_s_barrier();
+        read_frags(0, 0, xa, xb);
+        int cur = 0, fill = (T::NS - 1) * T::STAGE;
+        for (int kt = 0; kt < KT; ++kt) {
+            const int nxt = cur + T::STAGE == T::LDS ? 0 : cur + T::STAGE;
+            issue(kt + T::NS - 1, fill);                // the buffer read in step kt-1
+            fill = cur;
+#pragma unroll
+            for (int ph = 0; ph < T::PH - 1; ++ph) {
+                if (ph & 1) read_frags(cur, ph + 1, xa, xb);
+                else read_frags(cur, ph + 1, ya, yb);
+                __builtin_amdgcn_sched_barrier(0);
+                if (ph & 1) mma_all(ya, yb);
+                else mma_all(xa, xb);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // last sub-step: its fragments were read before the barrier, the MFMAs run after it
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
+            __builtin_amdgcn_s_barrier();
+            read_frags(nxt, 0, xa, xb);                 // zeros after the last step, never multiplied
+            __builtin_amdgcn_sched_barrier(0);
+            mma_all(ya, yb);
+            __builtin_amdgcn_sched_barrier(0);
+            cur = nxt;
+        }
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
+    }
+
+    // epilogue: accumulator register v of lane l in a 32x32 block is
+    // row (v/4)*8 + (l>>5)*4 + (v&3), column l&31
+    using OutT = typename std::conditional<INT8, int, float>::type;
+    OutT *C = (OutT *)p.C + batch * p.strideC;
+#pragma unroll
+    for (int i = 0; i < T::MI; ++i) {
+#pragma unroll
+        for (int j = 0; j < T::NI; ++j) {
+            const int col = n0 + wn * T::WTN + j * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm * T::WTM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+                if (row < p.M && col < p.N) {
+                    OutT *dst = C + (long long)row * p.ldc + col;
+                    if constexpr (INT8) {
+                        *dst = acc[i][j][v];
+                    } else {
+                        float r = p.alpha * acc[i][j][v];
+                        if (p.beta != 0.0f) r = __builtin_fmaf(p.beta, *dst, r);
+                        *dst = r;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------ host side
+
+template <bool INT8>
+bool dl_can_run_common(const Problem &q, int BM, int BN, int RB)
+{
+    const int64_t esz = INT8 ? 1 : 2;
+    if (q.in_type != (INT8 ? XP_I8 : XP_BF16)) return false;
+    if (q.K <= 0) return false;
+    if ((q.K * esz) % 16 != 0) return false;
+    if (q.M > 0x7fffffffLL || q.N > 0x7fffffffLL || q.K * esz > 0x3fffffffLL) return false;
+    if (q.batch > 65535) return false;
+    if (q.b_sk != 1 || (q.b_sn * esz) % 16 != 0 || ((uintptr_t)q.B % 16) != 0) return false;
+    if ((q.strideB * esz) % 16 != 0) return false;
+    if ((BN - 1) * q.b_sn * esz + q.K * esz >= 0x7fffffffLL) return false;
+    if (q.conv) {
+        if (INT8) return false;
+        const int64_t in_bytes = (q.M / (q.P * q.Q)) * q.H * q.W * q.Cin * esz;
+        if (in_bytes >= 0x7fffffffLL) return false;
+        if ((q.Cin * esz) % RB != 0) return false;         // a K step never straddles a filter tap
+        if (((uintptr_t)q.A % 16) != 0) return false;
+    } else {
+        if (q.a_sk != 1 || (q.a_sm * esz) % 16 != 0 || ((uintptr_t)q.A % 16) != 0) return false;
+        if ((q.strideA * esz) % 16 != 0) return false;
+        if ((BM - 1) * q.a_sm * esz + q.K * esz >= 0x7fffffffLL) return false;
+    }
+    const int64_t tiles = ((q.M + BM - 1) / BM) * ((q.N + BN - 1) / BN);
+    return tiles <= 0x7fffffffLL;
+}
+
+template <bool INT8, class T>
+hipError_t dl_launch(const Problem &q)
+{
+    const int64_t esz = INT8 ? 1 : 2;
+    DlParams p;
+    p.A = (const char *)q.A; p.B = (const char *)q.B; p.C = (char *)q.C;
+    p.M = (int)q.M; p.N = (int)q.N;
+    p.Kb = (int)(q.K * esz);
+    p.KT = (p.Kb + T::RB - 1) / T::RB;
+    p.lda_b = q.a_sm * esz; p.ldb_b = q.b_sn * esz;
+    p.ldc = q.ldc;
+    p.strideA_b = q.strideA * esz; p.strideB_b = q.strideB * esz; p.strideC = q.strideC;
+    p.alpha = q.alpha; p.beta = q.beta;
+    p.tiles_m = (int)((q.M + T::BM - 1) / T::BM);
+    p.tiles_n = (int)((q.N + T::BN - 1) / T::BN);
+    p.group_m = 4;
+    p.in_bytes = 0; p.H = p.W = p.Cin_b = p.S = p.PQ = p.Q = p.sh = p.sw = p.ph = p.pw = 0;
+    if (q.conv) {
+        p.in_bytes = (unsigned)((q.M / (q.P * q.Q)) * q.H * q.W * q.Cin * esz);
+        p.H = (int)q.H; p.W = (int)q.W; p.Cin_b = (int)(q.Cin * esz); p.S = (int)q.S;
+        p.PQ = (int)(q.P * q.Q); p.Q = (int)q.Q;
+        p.sh = (int)q.sh; p.sw = (int)q.sw; p.ph = (int)q.ph; p.pw = (int)q.pw;
+    }
+    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)q.batch);
+    if (q.conv) hipLaunchKernelGGL((dl_kernel<INT8, T, true>), grid, dim3(T::NT), 0, q.stream, p);
+    else hipLaunchKernelGGL((dl_kernel<INT8, T, false>), grid, dim3(T::NT), 0, q.stream, p);
+    return hipGetLastError();
+}
+
+// rounds of workgroups on 256 compute units x work of one tile / swept efficiency of the shape
+template <class T>
+double dl_cost(const Problem &q, double eff)
+{
+    const double tiles = (double)((q.M + T::BM - 1) / T::BM) * (double)((q.N + T::BN - 1) / T::BN) * (double)q.batch;
+    const double per_cu = T::LDS * 2 <= 160 * 1024 ? 2.0 : 1.0;
+    const double rounds = __builtin_ceil(tiles / (256.0 * per_cu));
+    return rounds * per_cu * (double)T::BM * (double)T::BN * (double)(q.K + 64) / eff;
+}
+
+#define XP_DL_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NS, RB, EFF)                                        \
+    bool NAME##_can(const Problem &q) { return dl_can_run_common<INT8>(q, BM, BN, RB); }                       \
+    hipError_t NAME##_launch(const Problem &q) { return dl_launch<INT8, DlTile<BM, BN, WM, WN, NS, RB>>(q); }  \
+    double NAME##_cost(const Problem &q) { return dl_cost<DlTile<BM, BN, WM, WN, NS, RB>>(q, EFF); }           \
+    const Variant NAME = {TYPESTR " " #BM "x" #BN "x" #RB "B waves " #WM "x" #WN " ring " #NS " direct-to-lds mfma32", \
+                          NAME##_can, NAME##_launch, NAME##_cost};
+
+XP_DL_VARIANT(kBfDl256x256r128n2, "bf16", false, 256, 256, 2, 4, 2, 128, 0.52)
+XP_DL_VARIANT(kBfDl256x256r64n4, "bf16", false, 256, 256, 2, 4, 4, 64, 0.52)
+XP_DL_VARIANT(kBfDl256x256r64n3, "bf16", false, 256, 256, 2, 4, 3, 64, 0.51)
+XP_DL_VARIANT(kBfDl256x256r64n4w4, "bf16", false, 256, 256, 2, 2, 4, 64, 0.50)
+XP_DL_VARIANT(kBfDl256x128r128n3, "bf16", false, 256, 128, 2, 2, 3, 128, 0.42)
+XP_DL_VARIANT(kBfDl128x128r128n2, "bf16", false, 128, 128, 2, 2, 2, 128, 0.32)
+
+XP_DL_VARIANT(kI8Dl256x256r128n2, "i8", true, 256, 256, 2, 4, 2, 128, 0.52)
+XP_DL_VARIANT(kI8Dl256x256r64n4, "i8", true, 256, 256, 2, 4, 4, 64, 0.52)
+XP_DL_VARIANT(kI8Dl256x256r64n3, "i8", true, 256, 256, 2, 4, 3, 64, 0.51)
+XP_DL_VARIANT(kI8Dl256x256r64n4w4, "i8", true, 256, 256, 2, 2, 4, 64, 0.50)
+XP_DL_VARIANT(kI8Dl256x128r128n3, "i8", true, 256, 128, 2, 2, 3, 128, 0.42)
+XP_DL_VARIANT(kI8Dl128x128r128n2, "i8", true, 128, 128, 2, 2, 2, 128, 0.32)
+
+}  // namespace
+
+int dl_variants(xp_dtype in_type, const Variant **out)
+{
+    if (in_type == XP_BF16) {
+        const Variant *v[] = {&kBfDl256x256r128n2, &kBfDl256x256r64n4, &kBfDl256x256r64n3, &kBfDl256x256r64n4w4,
+                              &kBfDl256x128r128n3, &kBfDl128x128r128n2};
+        for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
+        return (int)(sizeof v / sizeof *v);
+    }
+    if (in_type == XP_I8) {
+        const Variant *v[] = {&kI8Dl256x256r128n2, &kI8Dl256x256r64n4, &kI8Dl256x256r64n3, &kI8Dl256x256r64n4w4,
+                              &kI8Dl256x128r128n3, &kI8Dl128x128r128n2};
+        for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
+        return (int)(sizeof v / sizeof *v);
+    }
+    return 0;
+}
+
+}  // namespace xp
