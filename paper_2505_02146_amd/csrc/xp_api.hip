@@ -27,6 +27,7 @@ void build_tables()
         else {
             n += kc_variants(types[s], g_table[s] + n);
             n += dl_variants(types[s], g_table[s] + n);
+            n += oc_variants(types[s], g_table[s] + n);
         }
         g_count[s] = n;
     }

@@ -45,6 +45,7 @@ int generic_variants(xp_dtype in_type, const Variant **out);
 int f32_mfma_variants(const Variant **out);
 int kc_variants(xp_dtype in_type, const Variant **out);
 int dl_variants(xp_dtype in_type, const Variant **out);
+int oc_variants(xp_dtype in_type, const Variant **out);
 
 inline int elem_size(xp_dtype t) { return t == XP_F32 || t == XP_I32 ? 4 : (t == XP_BF16 ? 2 : 1); }
 

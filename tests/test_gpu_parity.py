@@ -15,7 +15,8 @@ pytestmark = pytest.mark.gpu
 
 LAYOUTS = [("row", "col"), ("row", "row"), ("col", "row"), ("col", "col")]
 # sizes: single element, below one MFMA block, around tile edges, several 256-tiles with ragged tails
-SHAPES = [(1, 1, 1), (15, 17, 16), (33, 31, 8), (63, 65, 64), (129, 255, 72), (257, 130, 200), (300, 520, 328)]
+SHAPES = [(1, 1, 1), (15, 17, 16), (33, 31, 8), (63, 65, 64), (129, 255, 72), (257, 130, 200), (300, 520, 328),
+          (264, 136, 200), (272, 144, 203), (48, 400, 1040)]
 
 
 @pytest.fixture(scope="module")
@@ -130,7 +131,11 @@ def test_int8_extremes_on_gpu(xp, oracle):
         for v in _variants(xp, 0, "i8"):
             xp.xp_force_config(0, "i8", v)
             c = torch.zeros((M, N), dtype=torch.int32, device="cuda")
-            xp.xp_gemm(M, N, K, 1.0, a, "row", K, b, "col", K, 0.0, c, "row", N)
+            try:
+                xp.xp_gemm(M, N, K, 1.0, a, "row", K, b, "col", K, 0.0, c, "row", N)
+            except xp.XpError as e:
+                assert e.status == 6 and v > 0       # a forced variant may decline this layout
+                continue
             assert torch.all(c == want), (va, vb, v)
     xp.xp_force_config(0, "i8", -1)
 
@@ -154,7 +159,11 @@ def test_gemm_k_zero_and_closed_forms(xp, oracle):
     for v in _variants(xp, 0, "bf16"):
         xp.xp_force_config(0, "bf16", v)
         c = torch.empty((n, n), device="cuda")
-        xp.xp_gemm(n, n, n, 1.0, dx, "row", n, eye, "col", n, 0.0, c, "row", n, a_type="bf16", b_type="bf16")
+        try:
+            xp.xp_gemm(n, n, n, 1.0, dx, "row", n, eye, "col", n, 0.0, c, "row", n, a_type="bf16", b_type="bf16")
+        except xp.XpError as e:
+            assert e.status == 6 and v > 0
+            continue
         assert np.array_equal(c.cpu().numpy(), inputs.bf16_bits_to_f32(x)), v
         xp.xp_gemm(n, n, n, 1.0, ones, "row", n, ones, "col", n, 0.0, c, "row", n, a_type="bf16", b_type="bf16")
         assert torch.all(c == float(n)), v
@@ -263,8 +272,12 @@ def test_conv_closed_forms(xp):
     for v in _variants(xp, 2, "bf16"):
         xp.xp_force_config(2, "bf16", v)
         out = torch.empty((N, H, W, C), device="cuda")
-        xp.xp_conv2d_nhwc(N, H, W, C, C, 3, 3, 1, 1, 1, 1, dx, dev(inputs.to_bf16_bits(w).reshape(-1)), "krsc", out,
-                          in_type="bf16", w_type="bf16")
+        try:
+            xp.xp_conv2d_nhwc(N, H, W, C, C, 3, 3, 1, 1, 1, 1, dx, dev(inputs.to_bf16_bits(w).reshape(-1)), "krsc", out,
+                              in_type="bf16", w_type="bf16")
+        except xp.XpError as e:
+            assert e.status == 6 and v > 0
+            continue
         assert np.array_equal(out.cpu().numpy(), xf), v
         xp.xp_conv2d_nhwc(N, H, W, C, C, 3, 3, 1, 1, 1, 1, dx, dev(inputs.to_bf16_bits(ws).reshape(-1)), "krsc", out,
                           in_type="bf16", w_type="bf16")
