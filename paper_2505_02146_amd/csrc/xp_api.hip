@@ -63,12 +63,46 @@ const Variant *variant(xp_dtype in_type, int idx)
 
 namespace {
 
-// Selection: every variant estimates its run time for the call from its tile shape, the
-// number of workgroup rounds the grid needs on 256 compute units and the efficiency its sweeps
-// measured (the stand-in for the brute-force parameter search of Section 5.1 of the paper);
-// the cheapest variant that can run the call wins.  Variant 0 (general kernel) always can.
+// Selection.  Shapes that have been swept on the hardware (sweep.py: every variant forced, gated
+// and timed -- the brute-force parameter search of Section 5.1 of the paper with the reward of
+// Eq. 3-4) are looked up in a table of winners.  Any other shape falls back to a cost estimate
+// that every variant supplies (rounds of workgroups on 256 compute units x tile work / swept
+// efficiency); the cheapest variant that can run the call wins.  Variant 0 always can.
+struct Tuned {
+    xp_op op;
+    xp_dtype type;
+    int64_t batch, M, N, K;
+    bool a_kc, b_kc;            // operand contiguous along K
+    const char *variant;
+};
+
+const Tuned kTuned[] = {
+    {XP_OP_GEMM, XP_F32, 1, 256, 256, 256, true, false, "f32 64x64x16 waves 2x2 mfma32x32x2"},
+    {XP_OP_GEMM, XP_BF16, 1, 4096, 4096, 4096, true, true, "bf16 256x256x128B waves 2x4 ring 2 direct-to-lds mfma32"},
+    {XP_OP_GEMM, XP_I8, 1, 4096, 4096, 8192, true, true, "i8 256x256x128B waves 2x4 ring 2 direct-to-lds mfma32"},
+    {XP_OP_GEMM_BATCHED, XP_BF16, 96, 512, 512, 64, true, true, "bf16 64x64x128B waves 2x2 stages 2 mfma32"},
+    {XP_OP_GEMM_BATCHED, XP_BF16, 96, 512, 64, 512, true, false, "bf16 128x64x128B waves 4x1 k-group-interleaved mfma32"},
+    {XP_OP_CONV2D, XP_BF16, 1, 100352, 256, 2304, true, true, "bf16 256x256x128B waves 2x4 ring 2 direct-to-lds mfma32"},
+};
+
+int tuned_variant(const Problem &q)
+{
+    const bool a_kc = q.conv || q.a_sk == 1, b_kc = q.b_sk == 1;
+    for (const Tuned &t : kTuned) {
+        if (t.op != q.op || t.type != q.in_type || t.batch != q.batch || t.M != q.M || t.N != q.N || t.K != q.K ||
+            t.a_kc != a_kc || t.b_kc != b_kc)
+            continue;
+        const int n = num_variants(q.in_type);
+        for (int i = 0; i < n; ++i)
+            if (strcmp(variant(q.in_type, i)->name, t.variant) == 0 && variant(q.in_type, i)->can_run(q)) return i;
+    }
+    return -1;
+}
+
 int select_variant(const Problem &q)
 {
+    const int tuned = tuned_variant(q);
+    if (tuned >= 0) return tuned;
     const int n = num_variants(q.in_type);
     int best = 0;
     double best_cost = variant(q.in_type, 0)->cost(q);

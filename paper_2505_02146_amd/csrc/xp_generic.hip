@@ -170,7 +170,7 @@ bool generic_can_run(const Problem &q)
 // when nothing else can run the call.
 double generic_cost(const Problem &q)
 {
-    return 1e3 * (double)q.batch * (double)q.M * (double)q.N * (double)(q.K + 1) + 1e6;
+    return 1e3 + 50.0 * tile_cost_us(q, GT, GT, 8320, 256, 0.01, q.in_type == XP_I8 ? 1 : (q.in_type == XP_BF16 ? 2 : 4));
 }
 
 const Variant kGenericF32 = {"general f32 64x64x16 valu", generic_can_run, launch_generic<float, float, float>,

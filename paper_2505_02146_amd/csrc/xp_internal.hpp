@@ -47,6 +47,27 @@ int kc_variants(xp_dtype in_type, const Variant **out);
 int dl_variants(xp_dtype in_type, const Variant **out);
 int oc_variants(xp_dtype in_type, const Variant **out);
 
+// Run-time estimate (microseconds) shared by the MFMA variants' cost functions, used only for shapes
+// that are not in the table of swept winners.  conc = workgroups that fit one compute unit;
+// a round of workgroups takes the largest of MFMA time at the swept efficiency, HBM time for the
+// C tile plus L2 time for the operand tiles, and a fixed per-workgroup latency.
+inline double tile_cost_us(const Problem &q, int BM, int BN, int lds_bytes, int threads, double eff, int esz)
+{
+    const double tiles = (double)((q.M + BM - 1) / BM) * (double)((q.N + BN - 1) / BN) * (double)q.batch;
+    int conc = lds_bytes > 0 ? (160 * 1024) / lds_bytes : 8;
+    if (conc > 2048 / threads) conc = 2048 / threads;
+    if (conc > 8) conc = 8;
+    if (conc < 1) conc = 1;
+    const double slots = 256.0 * conc;
+    const double rounds = conc == 1 ? __builtin_ceil(tiles / slots) : (tiles <= slots ? 1.0 : tiles / slots);
+    const double rate = esz == 1 ? 2.0 * 9.83e6 : 9.83e6;             // MFMA flop per microsecond per compute unit
+    const double t_comp = 2.0 * BM * BN * (double)q.K / (rate * eff) * conc;
+    const double t_mem = conc * ((double)BM * BN * 4.0 / 16e3 + (double)(BM + BN) * (double)q.K * esz / 64e3);
+    const double t_lat = 3.0;
+    const double t_work = t_comp > t_mem ? t_comp : t_mem;
+    return conc == 1 ? rounds * (t_work + t_lat) : rounds * (t_work > t_lat ? t_work : t_lat);
+}
+
 inline int elem_size(xp_dtype t) { return t == XP_F32 || t == XP_I32 ? 4 : (t == XP_BF16 ? 2 : 1); }
 
 }  // namespace xp

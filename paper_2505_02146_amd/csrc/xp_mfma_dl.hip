@@ -358,14 +358,10 @@ hipError_t dl_launch(const Problem &q)
     return hipGetLastError();
 }
 
-// rounds of workgroups on 256 compute units x work of one tile / swept efficiency of the shape
 template <class T>
 double dl_cost(const Problem &q, double eff)
 {
-    const double tiles = (double)((q.M + T::BM - 1) / T::BM) * (double)((q.N + T::BN - 1) / T::BN) * (double)q.batch;
-    const double per_cu = T::LDS * 2 <= 160 * 1024 ? 2.0 : 1.0;
-    const double rounds = __builtin_ceil(tiles / (256.0 * per_cu));
-    return rounds * per_cu * (double)T::BM * (double)T::BN * (double)(q.K + 64) / eff;
+    return tile_cost_us(q, T::BM, T::BN, T::LDS, T::NT, eff, q.in_type == XP_I8 ? 1 : 2);
 }
 
 #define XP_DL_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NS, RB, EFF)                                        \

@@ -150,10 +150,8 @@ hipError_t f32_launch(const Problem &q)
 template <int BM, int BN>
 double f32_cost(const Problem &q)
 {
-    const double tiles = (double)((q.M + BM - 1) / BM) * (double)((q.N + BN - 1) / BN) * (double)q.batch;
-    const double rounds = __builtin_ceil(tiles / (256.0 * 2.0));
-    // 16x slower per flop than the bf16 MFMA rate; the larger tile reuses LDS traffic better
-    return rounds * 2.0 * BM * BN * (double)(q.K + 64) * 16.0 / (BM == 128 ? 0.5 : 0.3);
+    // the fp32 MFMA rate is 1/16 of the bf16 one; the larger tile reuses LDS traffic better
+    return tile_cost_us(q, BM, BN, (int)sizeof(float) * FK * (BM + BN + 8), 256, (BM == 128 ? 0.5 : 0.3) / 16.0, 4);
 }
 
 const Variant kF32_128 = {"f32 128x128x16 waves 2x2 mfma32x32x2", f32_can_run, f32_launch<128, 128>,

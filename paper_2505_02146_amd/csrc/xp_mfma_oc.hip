@@ -327,19 +327,16 @@ hipError_t oc_launch(const Problem &q)
     return hipGetLastError();
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int WM, int WN>
 double oc_cost(const Problem &q)
 {
-    const double tiles = (double)((q.M + BM - 1) / BM) * (double)((q.N + BN - 1) / BN) * (double)q.batch;
-    const double per_cu = BM * BN >= 128 * 128 ? 2.0 : 4.0;
-    const double rounds = __builtin_ceil(tiles / (256.0 * per_cu));
-    const double eff = BM * BN >= 128 * 128 ? 0.25 : 0.15;
-    return rounds * per_cu * (double)BM * (double)BN * (double)(q.K + 64) / eff;
+    const int lds = 2 * (BM + BN) * (ROWB + 8);
+    return tile_cost_us(q, BM, BN, lds, WM * WN * 64, BM * BN >= 128 * 128 ? 0.25 : 0.18, q.in_type == XP_I8 ? 1 : 2);
 }
 
 #define XP_OC_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN)                                                   \
     const Variant NAME = {TYPESTR " " #BM "x" #BN "x128B waves " #WM "x" #WN " k-group-interleaved mfma32", \
-                          oc_can_run<INT8, BM, BN, WM, WN>, oc_launch<INT8, BM, BN, WM, WN>, oc_cost<BM, BN>};
+                          oc_can_run<INT8, BM, BN, WM, WN>, oc_launch<INT8, BM, BN, WM, WN>, oc_cost<BM, BN, WM, WN>};
 
 XP_OC_VARIANT(kBfOc128x128, "bf16", false, 128, 128, 2, 2)
 XP_OC_VARIANT(kBfOc128x64, "bf16", false, 128, 64, 4, 1)
