@@ -17,6 +17,7 @@
 //     padding are redirected to an out-of-range buffer offset: the hardware writes zeros into
 //     LDS and touches no memory, so the pipeline needs no conditionals.
 #include "xp_internal.hpp"
+#include "xp_epilogue.hpp"
 
 #include <type_traits>
 #include <utility>
@@ -273,31 +274,15 @@ __global__ __launch_bounds__(T::NT) void dl_kernel(DlParams p)
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
     }
 
-    // epilogue: accumulator register v of lane l in a 32x32 block is
-    // row (v/4)*8 + (l>>5)*4 + (v&3), column l&31
+    // epilogue
     using OutT = typename std::conditional<INT8, int, float>::type;
     OutT *C = (OutT *)p.C + batch * p.strideC;
 #pragma unroll
-    for (int i = 0; i < T::MI; ++i) {
+    for (int i = 0; i < T::MI; ++i)
 #pragma unroll
-        for (int j = 0; j < T::NI; ++j) {
-            const int col = n0 + wn * T::WTN + j * 32 + (lane & 31);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * T::WTM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                if (row < p.M && col < p.N) {
-                    OutT *dst = C + (long long)row * p.ldc + col;
-                    if constexpr (INT8) {
-                        *dst = acc[i][j][v];
-                    } else {
-                        float r = p.alpha * acc[i][j][v];
-                        if (p.beta != 0.0f) r = __builtin_fmaf(p.beta, *dst, r);
-                        *dst = r;
-                    }
-                }
-            }
-        }
-    }
+        for (int j = 0; j < T::NI; ++j)
+            store_block32<INT8>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 32, n0 + wn * T::WTN + j * 32, lane, p.M, p.N,
+                                p.alpha, p.beta);
 }
 
 // ------------------------------------------------------------------------------------ host side

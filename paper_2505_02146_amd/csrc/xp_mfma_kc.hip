@@ -20,6 +20,7 @@
 // into a global address: row m = (n, p, q), K offset = (r, s, c); taps that fall into the zero
 // padding are redirected past the end of the buffer range so that the load returns zeros.
 #include "xp_internal.hpp"
+#include "xp_epilogue.hpp"
 
 #include <cstdio>
 #include <type_traits>
@@ -310,31 +311,15 @@ __global__ __launch_bounds__(T::NT) void kc_kernel(KcParams p)
         }
     }
 
-    // ---- epilogue: accumulator register v of lane l in a 32x32 block is
-    // row (v/4)*8 + (l>>5)*4 + (v&3), column l&31
+    // ---- epilogue
     using OutT = typename std::conditional<INT8, int, float>::type;
     OutT *C = (OutT *)p.C + batch * p.strideC;
 #pragma unroll
-    for (int i = 0; i < T::MI; ++i) {
+    for (int i = 0; i < T::MI; ++i)
 #pragma unroll
-        for (int j = 0; j < T::NI; ++j) {
-            const int col = n0 + wn * T::WTN + j * 32 + (lane & 31);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * T::WTM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                if (row < p.M && col < p.N) {
-                    OutT *dst = C + (long long)row * p.ldc + col;
-                    if constexpr (INT8) {
-                        *dst = acc[i][j][v];
-                    } else {
-                        float r = p.alpha * acc[i][j][v];
-                        if (p.beta != 0.0f) r = __builtin_fmaf(p.beta, *dst, r);
-                        *dst = r;
-                    }
-                }
-            }
-        }
-    }
+        for (int j = 0; j < T::NI; ++j)
+            store_block32<INT8>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 32, n0 + wn * T::WTN + j * 32, lane, p.M, p.N,
+                                p.alpha, p.beta);
 }
 
 // ------------------------------------------------------------------------------------ host side

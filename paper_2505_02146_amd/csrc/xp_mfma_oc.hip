@@ -16,6 +16,7 @@
 // is multiplied, one workgroup barrier per step): the shapes this kernel serves are bound by
 // HBM bandwidth or are small, and several workgroups per compute unit hide the latency.
 #include "xp_internal.hpp"
+#include "xp_epilogue.hpp"
 
 #include <type_traits>
 
@@ -244,29 +245,14 @@ __global__ __launch_bounds__(WM *WN * 64) void oc_kernel(OcParams p)
         cur = nxt;
     }
 
-    // accumulator register v of lane l in a 32x32 block: row (v/4)*8 + (l>>5)*4 + (v&3), column l&31
     using OutT = typename std::conditional<INT8, int, float>::type;
     OutT *C = (OutT *)p.C + batch * p.strideC;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int col = n0 + wn * WTN + j * 32 + (lane & 31);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * WTM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                if (row < p.M && col < p.N) {
-                    OutT *dst = C + (long long)row * p.ldc + col;
-                    if constexpr (INT8) {
-                        *dst = acc[i][j][v];
-                    } else {
-                        float r = p.alpha * acc[i][j][v];
-                        if (p.beta != 0.0f) r = __builtin_fmaf(p.beta, *dst, r);
-                        *dst = r;
-                    }
-                }
-            }
-        }
+        for (int j = 0; j < NI; ++j)
+            store_block32<INT8>(acc[i][j], C, p.ldc, m0 + wm * WTM + i * 32, n0 + wn * WTN + j * 32, lane, p.M, p.N,
+                                p.alpha, p.beta);
 }
 
 // ------------------------------------------------------------------------------------ host side
