@@ -53,4 +53,41 @@ __device__ __forceinline__ void store_block32(const AccT &acc, OutT *C, long lon
     }
 }
 
+// 16x16 block computed transposed (B fragment as the first MFMA operand): accumulator register v
+// of lane l holds C(row l&15, column 4*(l>>4) + v), i.e. 4 consecutive columns: one 16-byte store
+// per lane when the address is 16-byte aligned and the block is interior.
+template <bool INT8, typename AccT, typename OutT>
+__device__ __forceinline__ void store_block16t(const AccT &acc, OutT *C, long long ldc, int blk_row0, int blk_col0,
+                                               int lane, int M, int N, float alpha, float beta)
+{
+    const int row = blk_row0 + (lane & 15);
+    const int col0 = blk_col0 + (lane >> 4) * 4;
+    OutT *dst = C + (long long)row * ldc + col0;
+    const bool interior = blk_row0 + 16 <= M && blk_col0 + 16 <= N;
+    const bool vec_ok = interior && (((unsigned long long)C | (unsigned long long)(ldc * (long long)sizeof(OutT))) & 15) == 0 &&
+                        (blk_col0 & 3) == 0;
+    typedef OutT out4 __attribute__((ext_vector_type(4)));
+    if constexpr (INT8) {
+        if (vec_ok) {
+            *(out4 *)dst = out4{acc[0], acc[1], acc[2], acc[3]};
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (row < M && col0 + v < N) dst[v] = acc[v];
+        }
+    } else {
+        if (beta == 0.0f && vec_ok) {
+            *(out4 *)dst = out4{alpha * acc[0], alpha * acc[1], alpha * acc[2], alpha * acc[3]};
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (row < M && col0 + v < N) {
+                    float r = alpha * acc[v];
+                    if (beta != 0.0f) r = __builtin_fmaf(beta, dst[v], r);
+                    dst[v] = r;
+                }
+        }
+    }
+}
+
 }  // namespace xp

@@ -19,6 +19,7 @@
 #include "xp_internal.hpp"
 #include "xp_epilogue.hpp"
 
+#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -49,23 +50,30 @@ struct DlParams {
     int H, W, Cin_b, S, PQ, Q, sh, sw, ph, pw;
 };
 
-template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_>
+template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_, bool SPREAD_ = false, int OCC_ = 1, int MF_ = 32>
 struct DlTile {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NS = NS_, RB = RB_;
+    static constexpr int OCC = OCC_;                     // waves per SIMD the register budget must allow
+    static constexpr bool SPREAD = SPREAD_;             // issue a step's loads a share per MFMA sub-step
     static constexpr int NWAVE = WM * WN, NT = NWAVE * 64;
     static constexpr int WTM = BM / WM, WTN = BN / WN;
-    static constexpr int MI = WTM / 32, NI = WTN / 32;
+    static constexpr int MF = MF_;                       // MFMA block edge: 32 (32x32x16 / x32) or 16 (16x16x32 / x64)
+    static constexpr int MI = WTM / MF, NI = WTN / MF;
     static constexpr int CPR = RB / 16;                 // 16-byte chunks per tile row
     static constexpr int RPI = 64 / CPR;                // tile rows filled by one wave-level load
-    static constexpr int PH = RB / 32;                  // MFMA sub-steps per K step
+    static constexpr int KSUB = 1024 / MF;               // bytes of K one MFMA consumes per row: 64 lanes x 16 B / MF rows
+    static constexpr int PH = RB / KSUB;                 // MFMA sub-steps per K step
     static constexpr int IA = BM / RPI / NWAVE, IB = BN / RPI / NWAVE;   // loads per wave and step
     static constexpr int STAGE = (BM + BN) * RB;
     static constexpr int LDS = NS * STAGE;
     static_assert(RB == 64 || RB == 128, "row bytes");
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave sub-tile must be whole MFMA blocks");
+    static_assert(MF == 32 || MF == 16, "MFMA shape");
+    static_assert(WTM % MF == 0 && WTN % MF == 0, "wave sub-tile must be whole MFMA blocks");
+    static_assert(PH >= 1, "a K step must hold at least one MFMA sub-step");
     static_assert(BM % (RPI * NWAVE) == 0 && BN % (RPI * NWAVE) == 0, "loads must divide evenly");
     static_assert(NS >= 2 && (NS - 2) * (IA + IB) <= 63, "vmcnt is a 6-bit counter");
     static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
+    static_assert(!SPREAD || NS >= 3, "with two buffers the loads of a step must all be issued at its start");
 };
 
 // Chunk swizzle, a per-row XOR of the chunk index chosen so that 8 lanes (128-byte bank width)
@@ -85,8 +93,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, un
 // s_waitcnt immediate for "vmcnt <= n and lgkmcnt == 0" (gfx9 encoding, expcnt left open)
 constexpr int waitcnt_vm_lgkm0(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4); }
 
-template <bool INT8> struct Acc;
-template <> struct Acc<false> {
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <bool INT8, int MF> struct Acc;
+template <> struct Acc<false, 32> {
     typedef f32x16 type;
     __device__ static __forceinline__ type mma(u32x4 a, u32x4 b, type c)
     {
@@ -94,7 +104,7 @@ template <> struct Acc<false> {
                                                        c, 0, 0, 0);
     }
 };
-template <> struct Acc<true> {
+template <> struct Acc<true, 32> {
     typedef i32x16 type;
     __device__ static __forceinline__ type mma(u32x4 a, u32x4 b, type c)
     {
@@ -102,12 +112,29 @@ template <> struct Acc<true> {
                                                      c, 0, 0, 0);
     }
 };
+template <> struct Acc<false, 16> {
+    typedef f32x4 type;
+    __device__ static __forceinline__ type mma(u32x4 a, u32x4 b, type c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                       c, 0, 0, 0);
+    }
+};
+template <> struct Acc<true, 16> {
+    typedef i32x4 type;
+    __device__ static __forceinline__ type mma(u32x4 a, u32x4 b, type c)
+    {
+        return __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, a), __builtin_bit_cast(i32x4, b),
+                                                     c, 0, 0, 0);
+    }
+};
 
 template <bool INT8, class T, bool CONV>
-__global__ __launch_bounds__(T::NT) void dl_kernel(DlParams p)
+__global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
 {
-    using AccT = typename Acc<INT8>::type;
-    constexpr int RB = T::RB;
+    using AccT = typename Acc<INT8, T::MF>::type;
+    constexpr int RB = T::RB, MF = T::MF;
+    constexpr int NACC = MF == 32 ? 16 : 4;           // accumulator registers per lane and block
     __shared__ __attribute__((aligned(1024))) char lds[T::LDS];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -170,13 +197,13 @@ __global__ __launch_bounds__(T::NT) void dl_kernel(DlParams p)
         b_off[i] = (unsigned)(row * p.ldb_b) + b_cb[i];
     }
 
-    // fragment reads: lane l reads row (l & 31) of a 32-row block, chunk 2*kk + (l >> 5)
-    const int frow = lane & 31, fhi = lane >> 5;
-    const int fsw = swz<RB>(frow);                      // blocks start at multiples of 32 rows
+    // fragment reads: lane l reads row l % MF of an MF-row block, chunk (64/MF)*kk + l / MF
+    const int frow = lane & (MF - 1), fch = lane / MF;
+    const int fsw = swz<RB>(frow);                      // blocks start at multiples of 16 rows
     int fa[T::PH], fb[T::PH];
 #pragma unroll
     for (int kk = 0; kk < T::PH; ++kk) {
-        const int c = ((2 * kk + fhi) ^ fsw) << 4;
+        const int c = (((64 / MF) * kk + fch) ^ fsw) << 4;
         fa[kk] = (wm * T::WTM + frow) * RB + c;
         fb[kk] = T::BM * RB + (wn * T::WTN + frow) * RB + c;
     }
@@ -187,15 +214,17 @@ __global__ __launch_bounds__(T::NT) void dl_kernel(DlParams p)
 #pragma unroll
         for (int j = 0; j < T::NI; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+            for (int v = 0; v < NACC; ++v) acc[i][j][v] = 0;
 
     int tap_r = 0, tap_s = 0, c0_b = 0;                 // conv: K offset of the next step to load
 
-    // issue the loads of K step kt into LDS buffer `stage_off`
-    auto issue = [&](int kt, int stage_off) {
+    // issue loads [lo, hi) of K step kt into LDS buffer `stage_off` (A slots first, then B slots)
+    constexpr int IT = T::IA + T::IB;
+    auto issue = [&](int kt, int stage_off, int lo, int hi) {
         const int kb = kt * RB;
 #pragma unroll
         for (int i = 0; i < T::IA; ++i) {
+            if (i < lo || i >= hi) continue;
             unsigned off;
             int soff;
             if constexpr (CONV) {
@@ -213,30 +242,38 @@ __global__ __launch_bounds__(T::NT) void dl_kernel(DlParams p)
         }
 #pragma unroll
         for (int i = 0; i < T::IB; ++i) {
+            if (T::IA + i < lo || T::IA + i >= hi) continue;
             unsigned off = b_off[i];
             if (kb + b_cb[i] >= p.Kb) off = OOB;
             lds_void *dst = (lds_void *)(lds + stage_off + T::BM * RB + (wave + i * T::NWAVE) * 1024);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, dst, 16, off, kb, 0, 0);
         }
         if constexpr (CONV) {
-            c0_b += RB;
-            if (c0_b >= p.Cin_b) {
-                c0_b = 0;
-                if (++tap_s == p.S) { tap_s = 0; ++tap_r; }
+            if (hi == IT) {                             // the step is fully issued: advance (tap, channel offset)
+                c0_b += RB;
+                if (c0_b >= p.Cin_b) {
+                    c0_b = 0;
+                    if (++tap_s == p.S) { tap_s = 0; ++tap_r; }
+                }
             }
         }
     };
     auto read_frags = [&](int stage_off, int kk, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
 #pragma unroll
-        for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(lds + stage_off + fa[kk] + i * 32 * RB);
+        for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(lds + stage_off + fa[kk] + i * MF * RB);
 #pragma unroll
-        for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + stage_off + fb[kk] + j * 32 * RB);
+        for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + stage_off + fb[kk] + j * MF * RB);
     };
     auto mma_all = [&](const u32x4 (&af)[T::MI], const u32x4 (&bf)[T::NI]) {
 #pragma unroll
         for (int i = 0; i < T::MI; ++i)
 #pragma unroll
-            for (int j = 0; j < T::NI; ++j) acc[i][j] = Acc<INT8>::mma(af[i], bf[j], acc[i][j]);
+            for (int j = 0; j < T::NI; ++j) {
+                // 16x16 blocks are computed transposed (B fragment as the first operand) so that a
+                // lane ends up with 4 consecutive columns of C: one 16-byte store per block
+                if constexpr (MF == 32) acc[i][j] = Acc<INT8, 32>::mma(af[i], bf[j], acc[i][j]);
+                else acc[i][j] = Acc<INT8, 16>::mma(bf[j], af[i], acc[i][j]);
+            }
     };
 
     const int KT = p.KT;
@@ -244,32 +281,54 @@ __global__ __launch_bounds__(T::NT) void dl_kernel(DlParams p)
     if (KT > 0) {
         u32x4 xa[T::MI], xb[T::NI], ya[T::MI], yb[T::NI];     // fragment sets of even / odd sub-steps
 #pragma unroll
-        for (int s = 0; s < T::NS - 1; ++s) issue(s, s * T::STAGE);
+        for (int s = 0; s < T::NS - 1; ++s) issue(s, s * T::STAGE, 0, IT);
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
         __builtin_amdgcn_s_barrier();
+        // fragment sets alternate between sub-steps; `odd` says which set holds the sub-step that
+        // is multiplied next (only for PH == 1 does it change from K step to K step)
         read_frags(0, 0, xa, xb);
         int cur = 0, fill = (T::NS - 1) * T::STAGE;
-        for (int kt = 0; kt < KT; ++kt) {
+        auto step = [&](int kt, auto odd_in) {
+            constexpr bool ODD = decltype(odd_in)::value;   // set multiplied in sub-step 0: false = X, true = Y
             const int nxt = cur + T::STAGE == T::LDS ? 0 : cur + T::STAGE;
-            issue(kt + T::NS - 1, fill);                // the buffer read in step kt-1
-            fill = cur;
+            // loads of step kt+NS-1 go into the buffer read in step kt-1
+            if constexpr (!T::SPREAD) issue(kt + T::NS - 1, fill, 0, IT);
 #pragma unroll
             for (int ph = 0; ph < T::PH - 1; ++ph) {
-                if (ph & 1) read_frags(cur, ph + 1, xa, xb);
+                if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill, ph * IT / T::PH, (ph + 1) * IT / T::PH);
+                const bool cur_is_y = ((ph & 1) != 0) != ODD;
+                if (cur_is_y) read_frags(cur, ph + 1, xa, xb);
                 else read_frags(cur, ph + 1, ya, yb);
                 __builtin_amdgcn_sched_barrier(0);
-                if (ph & 1) mma_all(ya, yb);
+                if (cur_is_y) mma_all(ya, yb);
                 else mma_all(xa, xb);
                 __builtin_amdgcn_sched_barrier(0);
             }
             // last sub-step: its fragments were read before the barrier, the MFMAs run after it
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
+            constexpr bool LAST_IS_Y = (((T::PH - 1) & 1) != 0) != ODD;
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(T::SPREAD ? PENDING - (IT - (T::PH - 1) * IT / T::PH) : PENDING));
             __builtin_amdgcn_s_barrier();
-            read_frags(nxt, 0, xa, xb);                 // zeros after the last step, never multiplied
+            if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill, (T::PH - 1) * IT / T::PH, IT);
+            // sub-step 0 of the next buffer (zeros after the last step, never multiplied)
+            if constexpr (LAST_IS_Y) read_frags(nxt, 0, xa, xb);
+            else read_frags(nxt, 0, ya, yb);
             __builtin_amdgcn_sched_barrier(0);
-            mma_all(ya, yb);
+            if constexpr (LAST_IS_Y) mma_all(ya, yb);
+            else mma_all(xa, xb);
             __builtin_amdgcn_sched_barrier(0);
+            fill = cur;
             cur = nxt;
+        };
+        if constexpr (T::PH % 2 == 0) {
+            for (int kt = 0; kt < KT; ++kt) step(kt, std::false_type{});
+        } else {
+            // an odd number of sub-steps per K step: the roles of the two sets swap every step
+            int kt = 0;
+            for (; kt + 1 < KT; kt += 2) {
+                step(kt, std::false_type{});
+                step(kt + 1, std::true_type{});
+            }
+            if (kt < KT) step(kt, std::false_type{});
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
     }
@@ -280,9 +339,14 @@ __global__ __launch_bounds__(T::NT) void dl_kernel(DlParams p)
 #pragma unroll
     for (int i = 0; i < T::MI; ++i)
 #pragma unroll
-        for (int j = 0; j < T::NI; ++j)
-            store_block32<INT8>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 32, n0 + wn * T::WTN + j * 32, lane, p.M, p.N,
-                                p.alpha, p.beta);
+        for (int j = 0; j < T::NI; ++j) {
+            if constexpr (MF == 32)
+                store_block32<INT8>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 32, n0 + wn * T::WTN + j * 32, lane, p.M,
+                                    p.N, p.alpha, p.beta);
+            else
+                store_block16t<INT8>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 16, n0 + wn * T::WTN + j * 16, lane, p.M,
+                                     p.N, p.alpha, p.beta);
+        }
 }
 
 // ------------------------------------------------------------------------------------ host side
@@ -329,7 +393,9 @@ hipError_t dl_launch(const Problem &q)
     p.alpha = q.alpha; p.beta = q.beta;
     p.tiles_m = (int)((q.M + T::BM - 1) / T::BM);
     p.tiles_n = (int)((q.N + T::BN - 1) / T::BN);
-    p.group_m = 4;
+    // tile-rows per raster group; XP_GROUP_M overrides it for tuning experiments
+    static const int env_group_m = [] { const char *e = getenv("XP_GROUP_M"); return e ? atoi(e) : 0; }();
+    p.group_m = env_group_m > 0 ? env_group_m : 4;
     p.in_bytes = 0; p.H = p.W = p.Cin_b = p.S = p.PQ = p.Q = p.sh = p.sw = p.ph = p.pw = 0;
     if (q.conv) {
         p.in_bytes = (unsigned)((q.M / (q.P * q.Q)) * q.H * q.W * q.Cin * esz);
@@ -349,40 +415,54 @@ double dl_cost(const Problem &q, double eff)
     return tile_cost_us(q, T::BM, T::BN, T::LDS, T::NT, eff, q.in_type == XP_I8 ? 1 : 2);
 }
 
-#define XP_DL_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NS, RB, EFF)                                        \
+#define XP_DL_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NS, RB, SPREAD, SPREADSTR, OCC, MF, EFF)                                        \
     bool NAME##_can(const Problem &q) { return dl_can_run_common<INT8>(q, BM, BN, RB); }                       \
-    hipError_t NAME##_launch(const Problem &q) { return dl_launch<INT8, DlTile<BM, BN, WM, WN, NS, RB>>(q); }  \
-    double NAME##_cost(const Problem &q) { return dl_cost<DlTile<BM, BN, WM, WN, NS, RB>>(q, EFF); }           \
-    const Variant NAME = {TYPESTR " " #BM "x" #BN "x" #RB "B waves " #WM "x" #WN " ring " #NS " direct-to-lds mfma32", \
+    hipError_t NAME##_launch(const Problem &q) { return dl_launch<INT8, DlTile<BM, BN, WM, WN, NS, RB, SPREAD, OCC, MF>>(q); }  \
+    double NAME##_cost(const Problem &q) { return dl_cost<DlTile<BM, BN, WM, WN, NS, RB, SPREAD, OCC, MF>>(q, EFF); }           \
+    const Variant NAME = {TYPESTR " " #BM "x" #BN "x" #RB "B waves " #WM "x" #WN " ring " #NS SPREADSTR " direct-to-lds mfma" #MF, \
                           NAME##_can, NAME##_launch, NAME##_cost};
 
-XP_DL_VARIANT(kBfDl256x256r128n2, "bf16", false, 256, 256, 2, 4, 2, 128, 0.52)
-XP_DL_VARIANT(kBfDl256x256r64n4, "bf16", false, 256, 256, 2, 4, 4, 64, 0.52)
-XP_DL_VARIANT(kBfDl256x256r64n3, "bf16", false, 256, 256, 2, 4, 3, 64, 0.51)
-XP_DL_VARIANT(kBfDl256x256r64n4w4, "bf16", false, 256, 256, 2, 2, 4, 64, 0.50)
-XP_DL_VARIANT(kBfDl256x128r128n3, "bf16", false, 256, 128, 2, 2, 3, 128, 0.42)
-XP_DL_VARIANT(kBfDl128x128r128n2, "bf16", false, 128, 128, 2, 2, 2, 128, 0.32)
+XP_DL_VARIANT(kBfDl256x256r128n2, "bf16", false, 256, 256, 2, 4, 2, 128, false, "", 1, 32, 0.52)
+XP_DL_VARIANT(kBfDl256x256r128n2m16, "bf16", false, 256, 256, 2, 4, 2, 128, false, "", 1, 16, 0.55)
+XP_DL_VARIANT(kBfDl256x256r128n2w4m16, "bf16", false, 256, 256, 2, 2, 2, 128, false, "", 1, 16, 0.5)
+XP_DL_VARIANT(kBfDl256x256r64n4m16, "bf16", false, 256, 256, 2, 4, 4, 64, false, "", 1, 16, 0.5)
+XP_DL_VARIANT(kBfDl128x128r128n2m16, "bf16", false, 128, 128, 2, 2, 2, 128, false, "", 2, 16, 0.34)
+XP_DL_VARIANT(kBfDl256x256r64n4, "bf16", false, 256, 256, 2, 4, 4, 64, false, "", 1, 32, 0.5)
+XP_DL_VARIANT(kBfDl256x256r64n4s, "bf16", false, 256, 256, 2, 4, 4, 64, true, " spread", 1, 32, 0.5)
+XP_DL_VARIANT(kBfDl256x256r64n3s, "bf16", false, 256, 256, 2, 4, 3, 64, true, " spread", 1, 32, 0.5)
+XP_DL_VARIANT(kBfDl256x256r128n2w4, "bf16", false, 256, 256, 2, 2, 2, 128, false, "", 1, 32, 0.48)
+XP_DL_VARIANT(kBfDl256x128r64n3, "bf16", false, 256, 128, 2, 2, 3, 64, false, "", 2, 32, 0.45)
+XP_DL_VARIANT(kBfDl256x128r64n3s, "bf16", false, 256, 128, 2, 2, 3, 64, true, " spread", 2, 32, 0.45)
+XP_DL_VARIANT(kBfDl128x256r64n3s, "bf16", false, 128, 256, 2, 2, 3, 64, true, " spread", 2, 32, 0.45)
+XP_DL_VARIANT(kBfDl128x128r128n2, "bf16", false, 128, 128, 2, 2, 2, 128, false, "", 2, 32, 0.32)
+XP_DL_VARIANT(kBfDl128x128r64n4s, "bf16", false, 128, 128, 2, 2, 4, 64, true, " spread", 2, 32, 0.32)
 
-XP_DL_VARIANT(kI8Dl256x256r128n2, "i8", true, 256, 256, 2, 4, 2, 128, 0.52)
-XP_DL_VARIANT(kI8Dl256x256r64n4, "i8", true, 256, 256, 2, 4, 4, 64, 0.52)
-XP_DL_VARIANT(kI8Dl256x256r64n3, "i8", true, 256, 256, 2, 4, 3, 64, 0.51)
-XP_DL_VARIANT(kI8Dl256x256r64n4w4, "i8", true, 256, 256, 2, 2, 4, 64, 0.50)
-XP_DL_VARIANT(kI8Dl256x128r128n3, "i8", true, 256, 128, 2, 2, 3, 128, 0.42)
-XP_DL_VARIANT(kI8Dl128x128r128n2, "i8", true, 128, 128, 2, 2, 2, 128, 0.32)
+XP_DL_VARIANT(kI8Dl256x256r128n2, "i8", true, 256, 256, 2, 4, 2, 128, false, "", 1, 32, 0.52)
+XP_DL_VARIANT(kI8Dl256x256r128n2m16, "i8", true, 256, 256, 2, 4, 2, 128, false, "", 1, 16, 0.55)
+XP_DL_VARIANT(kI8Dl256x256r128n2w4m16, "i8", true, 256, 256, 2, 2, 2, 128, false, "", 1, 16, 0.5)
+XP_DL_VARIANT(kI8Dl256x256r64n4m16, "i8", true, 256, 256, 2, 4, 4, 64, false, "", 1, 16, 0.5)
+XP_DL_VARIANT(kI8Dl128x128r128n2m16, "i8", true, 128, 128, 2, 2, 2, 128, false, "", 2, 16, 0.34)
+XP_DL_VARIANT(kI8Dl256x256r64n4, "i8", true, 256, 256, 2, 4, 4, 64, false, "", 1, 32, 0.5)
+XP_DL_VARIANT(kI8Dl256x256r64n4s, "i8", true, 256, 256, 2, 4, 4, 64, true, " spread", 1, 32, 0.5)
+XP_DL_VARIANT(kI8Dl256x256r64n3s, "i8", true, 256, 256, 2, 4, 3, 64, true, " spread", 1, 32, 0.5)
+XP_DL_VARIANT(kI8Dl256x256r128n2w4, "i8", true, 256, 256, 2, 2, 2, 128, false, "", 1, 32, 0.48)
+XP_DL_VARIANT(kI8Dl256x128r64n3, "i8", true, 256, 128, 2, 2, 3, 64, false, "", 2, 32, 0.45)
+XP_DL_VARIANT(kI8Dl256x128r64n3s, "i8", true, 256, 128, 2, 2, 3, 64, true, " spread", 2, 32, 0.45)
+XP_DL_VARIANT(kI8Dl128x256r64n3s, "i8", true, 128, 256, 2, 2, 3, 64, true, " spread", 2, 32, 0.45)
+XP_DL_VARIANT(kI8Dl128x128r128n2, "i8", true, 128, 128, 2, 2, 2, 128, false, "", 2, 32, 0.32)
+XP_DL_VARIANT(kI8Dl128x128r64n4s, "i8", true, 128, 128, 2, 2, 4, 64, true, " spread", 2, 32, 0.32)
 
 }  // namespace
 
 int dl_variants(xp_dtype in_type, const Variant **out)
 {
     if (in_type == XP_BF16) {
-        const Variant *v[] = {&kBfDl256x256r128n2, &kBfDl256x256r64n4, &kBfDl256x256r64n3, &kBfDl256x256r64n4w4,
-                              &kBfDl256x128r128n3, &kBfDl128x128r128n2};
+        const Variant *v[] = {&kBfDl256x256r128n2, &kBfDl256x256r128n2m16, &kBfDl256x256r128n2w4m16, &kBfDl256x256r64n4m16, &kBfDl128x128r128n2m16, &kBfDl256x256r64n4, &kBfDl256x256r64n4s, &kBfDl256x256r64n3s, &kBfDl256x256r128n2w4, &kBfDl256x128r64n3, &kBfDl256x128r64n3s, &kBfDl128x256r64n3s, &kBfDl128x128r128n2, &kBfDl128x128r64n4s};
         for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
         return (int)(sizeof v / sizeof *v);
     }
     if (in_type == XP_I8) {
-        const Variant *v[] = {&kI8Dl256x256r128n2, &kI8Dl256x256r64n4, &kI8Dl256x256r64n3, &kI8Dl256x256r64n4w4,
-                              &kI8Dl256x128r128n3, &kI8Dl128x128r128n2};
+        const Variant *v[] = {&kI8Dl256x256r128n2, &kI8Dl256x256r128n2m16, &kI8Dl256x256r128n2w4m16, &kI8Dl256x256r64n4m16, &kI8Dl128x128r128n2m16, &kI8Dl256x256r64n4, &kI8Dl256x256r64n4s, &kI8Dl256x256r64n3s, &kI8Dl256x256r128n2w4, &kI8Dl256x128r64n3, &kI8Dl256x128r64n3s, &kI8Dl128x256r64n3s, &kI8Dl128x128r128n2, &kI8Dl128x128r64n4s};
         for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
         return (int)(sizeof v / sizeof *v);
     }

@@ -23,6 +23,7 @@
 #include "xp_epilogue.hpp"
 
 #include <cstdio>
+#include <cstdlib>
 #include <type_traits>
 
 namespace xp {
@@ -367,7 +368,9 @@ hipError_t kc_launch(const Problem &q)
     p.alpha = q.alpha; p.beta = q.beta;
     p.tiles_m = (int)((q.M + T::BM - 1) / T::BM);
     p.tiles_n = (int)((q.N + T::BN - 1) / T::BN);
-    p.group_m = 4;
+    // tile-rows per raster group; XP_GROUP_M overrides it for tuning experiments
+    static const int env_group_m = [] { const char *e = getenv("XP_GROUP_M"); return e ? atoi(e) : 0; }();
+    p.group_m = env_group_m > 0 ? env_group_m : 4;
     p.in_bytes = 0; p.H = p.W = p.Cin_b = p.S = p.PQ = p.Q = p.sh = p.sw = p.ph = p.pw = 0;
     if (q.conv) {
         p.in_bytes = (unsigned)((q.M / (q.P * q.Q)) * q.H * q.W * q.Cin * esz);

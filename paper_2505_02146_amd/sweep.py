@@ -6,7 +6,7 @@ A candidate is valid when the library accepts it for the call and its output agr
 general kernel's output for the same inputs (bit-exact for int8, within fp32 summation-order
 noise otherwise).  Parity against the CPU oracle is the test-suite's job, not the sweep's.
 
-    python -m paper_2505_02146_amd.sweep [--workload NAME ...] [--steps 30] [--json out.json]
+    python -m paper_2505_02146_amd.sweep [--workload NAME ...] [--steps 30] [--rounds 1] [--only IDX ...] [--json out.json]
 """
 from __future__ import annotations
 
@@ -67,7 +67,11 @@ def _prepare(name):
             lambda: torch.zeros((n, p, q, co), dtype=torch.float32, device="cuda"))
 
 
-def sweep(name: str, steps: int = 30, warmup: int = 5) -> list[dict]:
+def sweep(name: str, steps: int = 30, warmup: int = 5, rounds: int = 1, only=None) -> list[dict]:
+    """Force every variant (or the indices in `only`) on workload `name`, gate it, time it.
+
+    With rounds > 1 the valid candidates are timed round-robin `rounds` times and the median
+    is reported, which takes clock drift under the power limit out of the comparison."""
     import torch
     from . import xp
     op, kind, flops, call, make_out = _prepare(name)
@@ -76,15 +80,18 @@ def sweep(name: str, steps: int = 30, warmup: int = 5) -> list[dict]:
     call(ref)
     torch.cuda.synchronize()
     rows = []
+    outs = {}
     for v in range(xp.xp_num_configs(op, kind)):
-        row = {"workload": name, "variant": v, "name": xp.xp_describe_config(op, kind, v)}
+        if only is not None and v not in only:
+            continue
+        row = {"workload": name, "variant": v, "name": xp.xp_describe_config(op, kind, v), "tflops": 0.0}
+        rows.append(row)
         xp.xp_force_config(op, kind, v)
         out = make_out()
         try:
             call(out)
         except xp.XpError:
-            row.update(valid=False, reason="cannot run this call", tflops=0.0)
-            rows.append(row)
+            row.update(valid=False, reason="cannot run this call")
             continue
         torch.cuda.synchronize()
         if kind == "i8":
@@ -93,21 +100,31 @@ def sweep(name: str, steps: int = 30, warmup: int = 5) -> list[dict]:
             d = (out.double() - ref.double()).norm() / ref.double().norm().clamp_min(1e-30)
             ok = bool(torch.isfinite(out).all()) and float(d) < 1e-5
         if not ok:
-            row.update(valid=False, reason="output differs from the general kernel", tflops=0.0)
-            rows.append(row)
+            row.update(valid=False, reason="output differs from the general kernel")
             continue
-        for _ in range(warmup):
-            call(out)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            call(out)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / steps
-        row.update(valid=True, ms=round(ms, 5), tflops=round(flops / (ms * 1e-3) / 1e12, 2))
-        rows.append(row)
+        row.update(valid=True, samples=[])
+        outs[v] = out
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(rounds):
+        for row in rows:
+            if not row["valid"]:
+                continue
+            xp.xp_force_config(op, kind, row["variant"])
+            out = outs[row["variant"]]
+            for _ in range(warmup):
+                call(out)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(steps):
+                call(out)
+            e1.record()
+            torch.cuda.synchronize()
+            row["samples"].append(e0.elapsed_time(e1) / steps)
+    for row in rows:
+        if row["valid"]:
+            ms = sorted(row["samples"])[len(row["samples"]) // 2]
+            row.update(ms=round(ms, 5), tflops=round(flops / (ms * 1e-3) / 1e12, 2),
+                       samples=[round(x, 5) for x in row["samples"]])
     xp.xp_force_config(op, kind, -1)
     out = make_out()
     call(out)
@@ -124,11 +141,13 @@ def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", nargs="*", default=list(inputs.WORKLOADS))
     ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--rounds", type=int, default=1, help="time the candidates round-robin this many times, report medians")
+    ap.add_argument("--only", type=int, nargs="*", default=None, help="variant indices to time (default: all)")
     ap.add_argument("--json", default=None)
     args = ap.parse_args(argv)
     all_rows = []
     for name in args.workload:
-        rows = sweep(name, args.steps)
+        rows = sweep(name, args.steps, rounds=args.rounds, only=args.only)
         all_rows += rows
         print(f"== {name}")
         for r in rows:
