@@ -82,7 +82,7 @@ struct DlTile {
 template <int RB> __device__ __forceinline__ int swz(int row)
 {
     if constexpr (RB == 128) return (row & 7) ^ ((row >> 3) & 1);
-    else return ((row >> 1) ^ (row >> 3)) & 3;
+    else return ((row >> 1) & 3) ^ ((row >> 3) & 1);   // row bits 1..3 only: the same for every 16-row block
 }
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes)
