@@ -47,6 +47,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--only-main", action="store_true", help="skip the int8 / batched / conv side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--force-variant", type=int, default=-1,
+                    help="force this kernel variant index for the main workload (profiling a sweep candidate)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (a known-size reference for "
                          "scaling the profiler's FETCH_SIZE / WRITE_SIZE counters)")
@@ -67,6 +69,9 @@ def main() -> int:
     M, N, K = w["M"], w["N"], w["K"]
     dA, dB = dev(w["A"].reshape(-1)), dev(w["B"].reshape(-1))
     dC = torch.empty((M, N), dtype=torch.float32, device="cuda")
+
+    if args.force_variant >= 0:
+        xp.xp_force_config(xp.XP_OP_GEMM, "bf16", args.force_variant)
 
     def step():
         xp.xp_gemm(M, N, K, 1.0, dA, "row", K, dB, "col", K, 0.0, dC, "row", N, a_type="bf16", b_type="bf16")
@@ -96,6 +101,8 @@ def main() -> int:
                      "frac": round(tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
                      "kernel_ms": round(ev_ms, 5)},
     }
+
+    xp.xp_force_config(xp.XP_OP_GEMM, "bf16", -1)
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)

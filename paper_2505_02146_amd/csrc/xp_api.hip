@@ -29,6 +29,7 @@ void build_tables()
             n += dl_variants(types[s], g_table[s] + n);
             n += oc_variants(types[s], g_table[s] + n);
             n += sk_variants(types[s], g_table[s] + n);
+            n += pp_variants(types[s], g_table[s] + n);
         }
         g_count[s] = n;
     }
