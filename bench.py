@@ -22,6 +22,12 @@ PEAK_BF16_TFLOPS = 2516.6     # 256 CU x 4096 FLOP/clk/CU x 2.4 GHz, dense
 PEAK_INT8_TOPS = 5033.2
 PEAK_HBM_GBS = 8000.0
 
+# Bytes per launch between the L2s and the memory fabric, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs scaled by a plain 256 MiB copy (factors 2.00 and 1.00), see
+# profiles/dl_kernel_bf16_256x256_mfma16_gemm_4096.md.  Keyed by kernel variant: a different
+# kernel than the profiled one reports null.
+TRAFFIC_BYTES = {"bf16 256x256x128B waves 2x4 ring 2 direct-to-lds mfma16": 268.6e6}
+
 
 def _time_calls(torch, fn, steps, warmup):
     """Average duration of one call in ms: HIP events on the stream the kernels are launched on."""
@@ -98,7 +104,7 @@ def main() -> int:
                                "fp32 accumulate and output, alpha=1, beta=0", "kernel": variant},
         "pct_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(tflops / PEAK_BF16_TFLOPS, 4), "traffic": TRAFFIC_BYTES.get(variant),
                      "kernel_ms": round(ev_ms, 5)},
     }
 
