@@ -63,14 +63,17 @@ struct DlTile {
     static constexpr int RPI = 64 / CPR;                // tile rows filled by one wave-level load
     static constexpr int KSUB = 1024 / MF;               // bytes of K one MFMA consumes per row: 64 lanes x 16 B / MF rows
     static constexpr int PH = RB / KSUB;                 // MFMA sub-steps per K step
-    static constexpr int IA = BM / RPI / NWAVE, IB = BN / RPI / NWAVE;   // loads per wave and step
-    static constexpr int STAGE = (BM + BN) * RB;
+    // rows a K step occupies in LDS: the tile height rounded up to what one round of wave-level
+    // loads fills (a tile of 208 rows is loaded as 256; rows past the tile are out of range)
+    static constexpr int BMP = (BM + RPI * NWAVE - 1) / (RPI * NWAVE) * (RPI * NWAVE);
+    static constexpr int BNP = (BN + RPI * NWAVE - 1) / (RPI * NWAVE) * (RPI * NWAVE);
+    static constexpr int IA = BMP / RPI / NWAVE, IB = BNP / RPI / NWAVE;   // loads per wave and step
+    static constexpr int STAGE = (BMP + BNP) * RB;
     static constexpr int LDS = NS * STAGE;
     static_assert(RB == 64 || RB == 128, "row bytes");
     static_assert(MF == 32 || MF == 16, "MFMA shape");
     static_assert(WTM % MF == 0 && WTN % MF == 0, "wave sub-tile must be whole MFMA blocks");
     static_assert(PH >= 1, "a K step must hold at least one MFMA sub-step");
-    static_assert(BM % (RPI * NWAVE) == 0 && BN % (RPI * NWAVE) == 0, "loads must divide evenly");
     static_assert(NS >= 2 && (NS - 2) * (IA + IB) <= 63, "vmcnt is a 6-bit counter");
     static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
     static_assert(!SPREAD || NS >= 3, "with two buffers the loads of a step must all be issued at its start");
@@ -182,7 +185,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
         a_cb[i] = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
         if constexpr (CONV) {
             const int m = m0 + row;
-            if (m < p.M) {
+            if (m < p.M && row < T::BM) {
                 const int n = m / p.PQ, pq = m % p.PQ;
                 const int op = pq / p.Q, oq = pq % p.Q;
                 a_h0[i] = op * p.sh - p.ph;
@@ -212,7 +215,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
     for (int kk = 0; kk < T::PH; ++kk) {
         const int c = (((64 / MF) * kk + fch) ^ fsw) << 4;
         fa[kk] = (wm * T::WTM + frow) * RB + c;
-        fb[kk] = T::BM * RB + (wn * T::WTN + frow) * RB + c;
+        fb[kk] = T::BMP * RB + (wn * T::WTN + frow) * RB + c;
     }
 
     AccT acc[T::MI][T::NI];
@@ -252,7 +255,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
             if (T::IA + i < lo || T::IA + i >= hi) continue;
             unsigned off = b_off[i];
             if (kb + b_cb[i] >= p.Kb) off = OOB;
-            lds_void *dst = (lds_void *)(lds + stage_off + T::BM * RB + (wave + i * T::NWAVE) * 1024);
+            lds_void *dst = (lds_void *)(lds + stage_off + T::BMP * RB + (wave + i * T::NWAVE) * 1024);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, dst, 16, off, kb, 0, 0);
         }
         if constexpr (CONV) {
@@ -431,6 +434,8 @@ double dl_cost(const Problem &q, double eff)
 
 XP_DL_VARIANT(kBfDl256x256r128n2, "bf16", false, 256, 256, 2, 4, 2, 128, false, "", 1, 32, 0.52)
 XP_DL_VARIANT(kBfDl256x256r128n2m16, "bf16", false, 256, 256, 2, 4, 2, 128, false, "", 1, 16, 0.55)
+XP_DL_VARIANT(kBfDl208x256w1x8m16, "bf16", false, 208, 256, 1, 8, 2, 128, false, "", 1, 16, 0.50)
+XP_DL_VARIANT(kBfDl224x256w2x4m16, "bf16", false, 224, 256, 2, 4, 2, 128, false, "", 1, 16, 0.50)
 XP_DL_VARIANT(kBfDl256x256r128n2w4m16, "bf16", false, 256, 256, 2, 2, 2, 128, false, "", 1, 16, 0.5)
 XP_DL_VARIANT(kBfDl256x256r64n4m16, "bf16", false, 256, 256, 2, 4, 4, 64, false, "", 1, 16, 0.5)
 XP_DL_VARIANT(kBfDl128x128r128n2m16, "bf16", false, 128, 128, 2, 2, 2, 128, false, "", 2, 16, 0.34)
@@ -464,7 +469,7 @@ XP_DL_VARIANT(kI8Dl128x128r64n4s, "i8", true, 128, 128, 2, 2, 4, 64, true, " spr
 int dl_variants(xp_dtype in_type, const Variant **out)
 {
     if (in_type == XP_BF16) {
-        const Variant *v[] = {&kBfDl256x256r128n2, &kBfDl256x256r128n2m16, &kBfDl256x256r128n2w4m16, &kBfDl256x256r64n4m16, &kBfDl128x128r128n2m16, &kBfDl256x256r64n4, &kBfDl256x256r64n4s, &kBfDl256x256r64n3s, &kBfDl256x256r128n2w4, &kBfDl256x128r64n3, &kBfDl256x128r64n3s, &kBfDl128x256r64n3s, &kBfDl128x128r128n2, &kBfDl128x128r64n4s};
+        const Variant *v[] = {&kBfDl256x256r128n2, &kBfDl256x256r128n2m16, &kBfDl208x256w1x8m16, &kBfDl224x256w2x4m16, &kBfDl256x256r128n2w4m16, &kBfDl256x256r64n4m16, &kBfDl128x128r128n2m16, &kBfDl256x256r64n4, &kBfDl256x256r64n4s, &kBfDl256x256r64n3s, &kBfDl256x256r128n2w4, &kBfDl256x128r64n3, &kBfDl256x128r64n3s, &kBfDl128x256r64n3s, &kBfDl128x128r128n2, &kBfDl128x128r64n4s};
         for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
         return (int)(sizeof v / sizeof *v);
     }
