@@ -55,6 +55,8 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--force-variant", type=int, default=-1,
                     help="force this kernel variant index for the main workload (profiling a sweep candidate)")
+    ap.add_argument("--force-batched-variant", type=int, default=-1,
+                    help="force this kernel variant index for the two batched side workloads")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (a known-size reference for "
                          "scaling the profiler's FETCH_SIZE / WRITE_SIZE counters)")
@@ -159,7 +161,15 @@ def main() -> int:
                 it["i"] += 1
                 xp.xp_gemm_batched(b, m, n, k, 1.0, As[i], "row", k, m * k, Bs[i], lb, ldb, k * n, 0.0, Cs[i], "row", n,
                                    m * n, a_type="bf16", b_type="bf16")
-            ms, _ = _time_calls(torch, call, steps2 * 2, warm2)
+            if args.force_batched_variant >= 0:
+                xp.xp_force_config(xp.XP_OP_GEMM_BATCHED, "bf16", args.force_batched_variant)
+            try:
+                ms, _ = _time_calls(torch, call, steps2 * 2, warm2)
+            except xp.XpError:                       # the forced variant does not serve this layout
+                xp.xp_force_config(xp.XP_OP_GEMM_BATCHED, "bf16", -1)
+                ms, _ = _time_calls(torch, call, steps2 * 2, warm2)
+            finally:
+                xp.xp_force_config(xp.XP_OP_GEMM_BATCHED, "bf16", -1)
             side[name] = {"ms": round(ms, 5), "TFLOP/s": round(2.0 * b * m * n * k / (ms * 1e-3) / 1e12, 1),
                           "GB/s": round(alg_bytes / (ms * 1e-3) / 1e9, 1),
                           "pct_hbm_peak": round(100 * alg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 2),

@@ -9,7 +9,15 @@
 
 namespace xp {
 
-template <bool INT8, typename AccT, typename OutT>
+// STREAM = true marks the stores non-temporal: for outputs that are written once and not read again
+// by the kernel (the store-bound batched shapes) they should not displace operand lines in the caches.
+template <bool STREAM, typename T> __device__ __forceinline__ void put(T *dst, T v)
+{
+    if constexpr (STREAM) __builtin_nontemporal_store(v, dst);
+    else *dst = v;
+}
+
+template <bool INT8, bool STREAM = false, typename AccT, typename OutT>
 __device__ __forceinline__ void store_block32(const AccT &acc, OutT *C, long long ldc, int blk_row0, int blk_col0,
                                               int lane, int M, int N, float alpha, float beta)
 {
@@ -20,7 +28,7 @@ __device__ __forceinline__ void store_block32(const AccT &acc, OutT *C, long lon
     if constexpr (INT8) {
         if (interior) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) base[(long long)((v >> 2) * 8 + (v & 3)) * ldc] = acc[v];
+            for (int v = 0; v < 16; ++v) put<STREAM>(base + (long long)((v >> 2) * 8 + (v & 3)) * ldc, (OutT)acc[v]);
         } else {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -32,7 +40,7 @@ __device__ __forceinline__ void store_block32(const AccT &acc, OutT *C, long lon
         if (beta == 0.0f) {
             if (interior) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) base[(long long)((v >> 2) * 8 + (v & 3)) * ldc] = alpha * acc[v];
+                for (int v = 0; v < 16; ++v) put<STREAM>(base + (long long)((v >> 2) * 8 + (v & 3)) * ldc, alpha * acc[v]);
             } else {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -56,7 +64,7 @@ __device__ __forceinline__ void store_block32(const AccT &acc, OutT *C, long lon
 // 16x16 block computed transposed (B fragment as the first MFMA operand): accumulator register v
 // of lane l holds C(row l&15, column 4*(l>>4) + v), i.e. 4 consecutive columns: one 16-byte store
 // per lane when the address is 16-byte aligned and the block is interior.
-template <bool INT8, typename AccT, typename OutT>
+template <bool INT8, bool STREAM = false, typename AccT, typename OutT>
 __device__ __forceinline__ void store_block16t(const AccT &acc, OutT *C, long long ldc, int blk_row0, int blk_col0,
                                                int lane, int M, int N, float alpha, float beta)
 {
@@ -69,7 +77,7 @@ __device__ __forceinline__ void store_block16t(const AccT &acc, OutT *C, long lo
     typedef OutT out4 __attribute__((ext_vector_type(4)));
     if constexpr (INT8) {
         if (vec_ok) {
-            *(out4 *)dst = out4{acc[0], acc[1], acc[2], acc[3]};
+            put<STREAM>((out4 *)dst, out4{acc[0], acc[1], acc[2], acc[3]});
         } else {
 #pragma unroll
             for (int v = 0; v < 4; ++v)
@@ -77,7 +85,7 @@ __device__ __forceinline__ void store_block16t(const AccT &acc, OutT *C, long lo
         }
     } else {
         if (beta == 0.0f && vec_ok) {
-            *(out4 *)dst = out4{alpha * acc[0], alpha * acc[1], alpha * acc[2], alpha * acc[3]};
+            put<STREAM>((out4 *)dst, out4{alpha * acc[0], alpha * acc[1], alpha * acc[2], alpha * acc[3]});
         } else {
 #pragma unroll
             for (int v = 0; v < 4; ++v)

@@ -50,9 +50,10 @@ struct DlParams {
     int H, W, Cin_b, S, PQ, Q, sh, sw, ph, pw;
 };
 
-template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_, bool SPREAD_ = false, int OCC_ = 1, int MF_ = 32>
+template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_, bool SPREAD_ = false, int OCC_ = 1, int MF_ = 32, bool NT_ = false>
 struct DlTile {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NS = NS_, RB = RB_;
+    static constexpr bool NTSTORE = NT_;                 // non-temporal stores of C
     static constexpr int OCC = OCC_;                     // waves per SIMD the register budget must allow
     static constexpr bool SPREAD = SPREAD_;             // issue a step's loads a share per MFMA sub-step
     static constexpr int NWAVE = WM * WN, NT = NWAVE * 64;
@@ -351,10 +352,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
 #pragma unroll
         for (int j = 0; j < T::NI; ++j) {
             if constexpr (MF == 32)
-                store_block32<INT8>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 32, n0 + wn * T::WTN + j * 32, lane, p.M,
+                store_block32<INT8, T::NTSTORE>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 32, n0 + wn * T::WTN + j * 32, lane, p.M,
                                     p.N, p.alpha, p.beta);
             else
-                store_block16t<INT8>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 16, n0 + wn * T::WTN + j * 16, lane, p.M,
+                store_block16t<INT8, T::NTSTORE>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 16, n0 + wn * T::WTN + j * 16, lane, p.M,
                                      p.N, p.alpha, p.beta);
         }
 }
@@ -425,44 +426,44 @@ double dl_cost(const Problem &q, double eff)
     return tile_cost_us(q, T::BM, T::BN, T::LDS, T::NT, eff, q.in_type == XP_I8 ? 1 : 2);
 }
 
-#define XP_DL_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NS, RB, SPREAD, SPREADSTR, OCC, MF, EFF)                                        \
+#define XP_DL_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NS, RB, SPREAD, SPREADSTR, OCC, MF, NT, NTSTR, EFF)                                        \
     bool NAME##_can(const Problem &q) { return dl_can_run_common<INT8>(q, BM, BN, RB); }                       \
-    hipError_t NAME##_launch(const Problem &q) { return dl_launch<INT8, DlTile<BM, BN, WM, WN, NS, RB, SPREAD, OCC, MF>>(q); }  \
-    double NAME##_cost(const Problem &q) { return dl_cost<DlTile<BM, BN, WM, WN, NS, RB, SPREAD, OCC, MF>>(q, EFF); }           \
-    const Variant NAME = {TYPESTR " " #BM "x" #BN "x" #RB "B waves " #WM "x" #WN " ring " #NS SPREADSTR " direct-to-lds mfma" #MF, \
+    hipError_t NAME##_launch(const Problem &q) { return dl_launch<INT8, DlTile<BM, BN, WM, WN, NS, RB, SPREAD, OCC, MF, NT>>(q); }  \
+    double NAME##_cost(const Problem &q) { return dl_cost<DlTile<BM, BN, WM, WN, NS, RB, SPREAD, OCC, MF, NT>>(q, EFF); }           \
+    const Variant NAME = {TYPESTR " " #BM "x" #BN "x" #RB "B waves " #WM "x" #WN " ring " #NS SPREADSTR " direct-to-lds" NTSTR " mfma" #MF, \
                           NAME##_can, NAME##_launch, NAME##_cost};
 
-XP_DL_VARIANT(kBfDl256x256r128n2, "bf16", false, 256, 256, 2, 4, 2, 128, false, "", 1, 32, 0.52)
-XP_DL_VARIANT(kBfDl256x256r128n2m16, "bf16", false, 256, 256, 2, 4, 2, 128, false, "", 1, 16, 0.55)
-XP_DL_VARIANT(kBfDl208x256w1x8m16, "bf16", false, 208, 256, 1, 8, 2, 128, false, "", 1, 16, 0.50)
-XP_DL_VARIANT(kBfDl224x256w2x4m16, "bf16", false, 224, 256, 2, 4, 2, 128, false, "", 1, 16, 0.50)
-XP_DL_VARIANT(kBfDl256x256r128n2w4m16, "bf16", false, 256, 256, 2, 2, 2, 128, false, "", 1, 16, 0.5)
-XP_DL_VARIANT(kBfDl256x256r64n4m16, "bf16", false, 256, 256, 2, 4, 4, 64, false, "", 1, 16, 0.5)
-XP_DL_VARIANT(kBfDl128x128r128n2m16, "bf16", false, 128, 128, 2, 2, 2, 128, false, "", 2, 16, 0.34)
-XP_DL_VARIANT(kBfDl256x256r64n4, "bf16", false, 256, 256, 2, 4, 4, 64, false, "", 1, 32, 0.5)
-XP_DL_VARIANT(kBfDl256x256r64n4s, "bf16", false, 256, 256, 2, 4, 4, 64, true, " spread", 1, 32, 0.5)
-XP_DL_VARIANT(kBfDl256x256r64n3s, "bf16", false, 256, 256, 2, 4, 3, 64, true, " spread", 1, 32, 0.5)
-XP_DL_VARIANT(kBfDl256x256r128n2w4, "bf16", false, 256, 256, 2, 2, 2, 128, false, "", 1, 32, 0.48)
-XP_DL_VARIANT(kBfDl256x128r64n3, "bf16", false, 256, 128, 2, 2, 3, 64, false, "", 2, 32, 0.45)
-XP_DL_VARIANT(kBfDl256x128r64n3s, "bf16", false, 256, 128, 2, 2, 3, 64, true, " spread", 2, 32, 0.45)
-XP_DL_VARIANT(kBfDl128x256r64n3s, "bf16", false, 128, 256, 2, 2, 3, 64, true, " spread", 2, 32, 0.45)
-XP_DL_VARIANT(kBfDl128x128r128n2, "bf16", false, 128, 128, 2, 2, 2, 128, false, "", 2, 32, 0.32)
-XP_DL_VARIANT(kBfDl128x128r64n4s, "bf16", false, 128, 128, 2, 2, 4, 64, true, " spread", 2, 32, 0.32)
+XP_DL_VARIANT(kBfDl256x256r128n2, "bf16", false, 256, 256, 2, 4, 2, 128, false, "", 1, 32, false, "", 0.52)
+XP_DL_VARIANT(kBfDl256x256r128n2m16, "bf16", false, 256, 256, 2, 4, 2, 128, false, "", 1, 16, false, "", 0.55)
+XP_DL_VARIANT(kBfDl208x256w1x8m16, "bf16", false, 208, 256, 1, 8, 2, 128, false, "", 1, 16, false, "", 0.50)
+XP_DL_VARIANT(kBfDl224x256w2x4m16, "bf16", false, 224, 256, 2, 4, 2, 128, false, "", 1, 16, false, "", 0.50)
+XP_DL_VARIANT(kBfDl256x256r128n2w4m16, "bf16", false, 256, 256, 2, 2, 2, 128, false, "", 1, 16, false, "", 0.5)
+XP_DL_VARIANT(kBfDl256x256r64n4m16, "bf16", false, 256, 256, 2, 4, 4, 64, false, "", 1, 16, false, "", 0.5)
+XP_DL_VARIANT(kBfDl128x128r128n2m16, "bf16", false, 128, 128, 2, 2, 2, 128, false, "", 2, 16, false, "", 0.34)
+XP_DL_VARIANT(kBfDl256x256r64n4, "bf16", false, 256, 256, 2, 4, 4, 64, false, "", 1, 32, false, "", 0.5)
+XP_DL_VARIANT(kBfDl256x256r64n4s, "bf16", false, 256, 256, 2, 4, 4, 64, true, " spread", 1, 32, false, "", 0.5)
+XP_DL_VARIANT(kBfDl256x256r64n3s, "bf16", false, 256, 256, 2, 4, 3, 64, true, " spread", 1, 32, false, "", 0.5)
+XP_DL_VARIANT(kBfDl256x256r128n2w4, "bf16", false, 256, 256, 2, 2, 2, 128, false, "", 1, 32, false, "", 0.48)
+XP_DL_VARIANT(kBfDl256x128r64n3, "bf16", false, 256, 128, 2, 2, 3, 64, false, "", 2, 32, false, "", 0.45)
+XP_DL_VARIANT(kBfDl256x128r64n3s, "bf16", false, 256, 128, 2, 2, 3, 64, true, " spread", 2, 32, false, "", 0.45)
+XP_DL_VARIANT(kBfDl128x256r64n3s, "bf16", false, 128, 256, 2, 2, 3, 64, true, " spread", 2, 32, false, "", 0.45)
+XP_DL_VARIANT(kBfDl128x128r128n2, "bf16", false, 128, 128, 2, 2, 2, 128, false, "", 2, 32, false, "", 0.32)
+XP_DL_VARIANT(kBfDl128x128r64n4s, "bf16", false, 128, 128, 2, 2, 4, 64, true, " spread", 2, 32, false, "", 0.32)
 
-XP_DL_VARIANT(kI8Dl256x256r128n2, "i8", true, 256, 256, 2, 4, 2, 128, false, "", 1, 32, 0.52)
-XP_DL_VARIANT(kI8Dl256x256r128n2m16, "i8", true, 256, 256, 2, 4, 2, 128, false, "", 1, 16, 0.55)
-XP_DL_VARIANT(kI8Dl256x256r128n2w4m16, "i8", true, 256, 256, 2, 2, 2, 128, false, "", 1, 16, 0.5)
-XP_DL_VARIANT(kI8Dl256x256r64n4m16, "i8", true, 256, 256, 2, 4, 4, 64, false, "", 1, 16, 0.5)
-XP_DL_VARIANT(kI8Dl128x128r128n2m16, "i8", true, 128, 128, 2, 2, 2, 128, false, "", 2, 16, 0.34)
-XP_DL_VARIANT(kI8Dl256x256r64n4, "i8", true, 256, 256, 2, 4, 4, 64, false, "", 1, 32, 0.5)
-XP_DL_VARIANT(kI8Dl256x256r64n4s, "i8", true, 256, 256, 2, 4, 4, 64, true, " spread", 1, 32, 0.5)
-XP_DL_VARIANT(kI8Dl256x256r64n3s, "i8", true, 256, 256, 2, 4, 3, 64, true, " spread", 1, 32, 0.5)
-XP_DL_VARIANT(kI8Dl256x256r128n2w4, "i8", true, 256, 256, 2, 2, 2, 128, false, "", 1, 32, 0.48)
-XP_DL_VARIANT(kI8Dl256x128r64n3, "i8", true, 256, 128, 2, 2, 3, 64, false, "", 2, 32, 0.45)
-XP_DL_VARIANT(kI8Dl256x128r64n3s, "i8", true, 256, 128, 2, 2, 3, 64, true, " spread", 2, 32, 0.45)
-XP_DL_VARIANT(kI8Dl128x256r64n3s, "i8", true, 128, 256, 2, 2, 3, 64, true, " spread", 2, 32, 0.45)
-XP_DL_VARIANT(kI8Dl128x128r128n2, "i8", true, 128, 128, 2, 2, 2, 128, false, "", 2, 32, 0.32)
-XP_DL_VARIANT(kI8Dl128x128r64n4s, "i8", true, 128, 128, 2, 2, 4, 64, true, " spread", 2, 32, 0.32)
+XP_DL_VARIANT(kI8Dl256x256r128n2, "i8", true, 256, 256, 2, 4, 2, 128, false, "", 1, 32, false, "", 0.52)
+XP_DL_VARIANT(kI8Dl256x256r128n2m16, "i8", true, 256, 256, 2, 4, 2, 128, false, "", 1, 16, false, "", 0.55)
+XP_DL_VARIANT(kI8Dl256x256r128n2w4m16, "i8", true, 256, 256, 2, 2, 2, 128, false, "", 1, 16, false, "", 0.5)
+XP_DL_VARIANT(kI8Dl256x256r64n4m16, "i8", true, 256, 256, 2, 4, 4, 64, false, "", 1, 16, false, "", 0.5)
+XP_DL_VARIANT(kI8Dl128x128r128n2m16, "i8", true, 128, 128, 2, 2, 2, 128, false, "", 2, 16, false, "", 0.34)
+XP_DL_VARIANT(kI8Dl256x256r64n4, "i8", true, 256, 256, 2, 4, 4, 64, false, "", 1, 32, false, "", 0.5)
+XP_DL_VARIANT(kI8Dl256x256r64n4s, "i8", true, 256, 256, 2, 4, 4, 64, true, " spread", 1, 32, false, "", 0.5)
+XP_DL_VARIANT(kI8Dl256x256r64n3s, "i8", true, 256, 256, 2, 4, 3, 64, true, " spread", 1, 32, false, "", 0.5)
+XP_DL_VARIANT(kI8Dl256x256r128n2w4, "i8", true, 256, 256, 2, 2, 2, 128, false, "", 1, 32, false, "", 0.48)
+XP_DL_VARIANT(kI8Dl256x128r64n3, "i8", true, 256, 128, 2, 2, 3, 64, false, "", 2, 32, false, "", 0.45)
+XP_DL_VARIANT(kI8Dl256x128r64n3s, "i8", true, 256, 128, 2, 2, 3, 64, true, " spread", 2, 32, false, "", 0.45)
+XP_DL_VARIANT(kI8Dl128x256r64n3s, "i8", true, 128, 256, 2, 2, 3, 64, true, " spread", 2, 32, false, "", 0.45)
+XP_DL_VARIANT(kI8Dl128x128r128n2, "i8", true, 128, 128, 2, 2, 2, 128, false, "", 2, 32, false, "", 0.32)
+XP_DL_VARIANT(kI8Dl128x128r64n4s, "i8", true, 128, 128, 2, 2, 4, 64, true, " spread", 2, 32, false, "", 0.32)
 
 }  // namespace
 

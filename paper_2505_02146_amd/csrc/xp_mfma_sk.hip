@@ -80,7 +80,7 @@ template <> struct Acc<true> {
     }
 };
 
-template <bool INT8, int BN>
+template <bool INT8, int BN, bool STREAM>
 __global__ __launch_bounds__(320) void sk_kernel(SkParams p)
 {
     using AccT = typename Acc<INT8>::type;
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(320) void sk_kernel(SkParams p)
         wg_barrier();
 #pragma unroll
         for (int b = 0; b < NI; ++b)
-            store_block32<INT8>(acc[b], C, p.ldc, m0 + wm * 32, j * BN + wn * (BN / 2) + b * 32, lane, p.M, p.N, p.alpha,
+            store_block32<INT8, STREAM>(acc[b], C, p.ldc, m0 + wm * 32, j * BN + wn * (BN / 2) + b * 32, lane, p.M, p.N, p.alpha,
                                 p.beta);
     }
 }
@@ -196,7 +196,7 @@ bool sk_can_run(const Problem &q)
     return (q.M + BM - 1) / BM <= 0x7fffffffLL;
 }
 
-template <bool INT8, int BN>
+template <bool INT8, int BN, bool STREAM>
 hipError_t sk_launch(const Problem &q)
 {
     const int64_t esz = INT8 ? 1 : 2;
@@ -207,7 +207,7 @@ hipError_t sk_launch(const Problem &q)
     p.strideA_b = q.strideA * esz; p.strideB_b = q.strideB * esz; p.strideC = q.strideC;
     p.alpha = q.alpha; p.beta = q.beta;
     p.tiles_n = (int)((q.N + BN - 1) / BN);
-    hipLaunchKernelGGL((sk_kernel<INT8, BN>), dim3((unsigned)((q.M + BM - 1) / BM), (unsigned)q.batch), dim3(320), 0,
+    hipLaunchKernelGGL((sk_kernel<INT8, BN, STREAM>), dim3((unsigned)((q.M + BM - 1) / BM), (unsigned)q.batch), dim3(320), 0,
                        q.stream, p);
     return hipGetLastError();
 }
@@ -222,21 +222,24 @@ double sk_cost(const Problem &q)
     return 4.0 + fill * bytes / 5e6;
 }
 
-const Variant kBfSk64 = {"bf16 64x64-stream x128B single-k-step producer/consumer mfma32", sk_can_run<false, 64>,
-                         sk_launch<false, 64>, sk_cost<64>};
-const Variant kBfSk128 = {"bf16 64x128-stream x128B single-k-step producer/consumer mfma32", sk_can_run<false, 128>,
-                          sk_launch<false, 128>, sk_cost<128>};
-const Variant kI8Sk64 = {"i8 64x64-stream x128B single-k-step producer/consumer mfma32", sk_can_run<true, 64>,
-                         sk_launch<true, 64>, sk_cost<64>};
-const Variant kI8Sk128 = {"i8 64x128-stream x128B single-k-step producer/consumer mfma32", sk_can_run<true, 128>,
-                          sk_launch<true, 128>, sk_cost<128>};
+#define XP_SK_VARIANT(NAME, TYPESTR, INT8, BN, STREAM, STREAMSTR)                                                      \
+    const Variant NAME = {TYPESTR " 64x" #BN "-stream x128B single-k-step producer/consumer" STREAMSTR " mfma32",      \
+                          sk_can_run<INT8, BN>, sk_launch<INT8, BN, STREAM>, sk_cost<BN>};
+
+XP_SK_VARIANT(kBfSk64, "bf16", false, 64, false, "")
+XP_SK_VARIANT(kBfSk128, "bf16", false, 128, false, "")
+XP_SK_VARIANT(kBfSk64nt, "bf16", false, 64, true, " nt-stores")
+XP_SK_VARIANT(kBfSk128nt, "bf16", false, 128, true, " nt-stores")
+XP_SK_VARIANT(kI8Sk64, "i8", true, 64, false, "")
+XP_SK_VARIANT(kI8Sk128, "i8", true, 128, false, "")
+XP_SK_VARIANT(kI8Sk128nt, "i8", true, 128, true, " nt-stores")
 
 }  // namespace
 
 int sk_variants(xp_dtype in_type, const Variant **out)
 {
-    if (in_type == XP_BF16) { out[0] = &kBfSk64; out[1] = &kBfSk128; return 2; }
-    if (in_type == XP_I8) { out[0] = &kI8Sk64; out[1] = &kI8Sk128; return 2; }
+    if (in_type == XP_BF16) { out[0] = &kBfSk64; out[1] = &kBfSk128; out[2] = &kBfSk64nt; out[3] = &kBfSk128nt; return 4; }
+    if (in_type == XP_I8) { out[0] = &kI8Sk64; out[1] = &kI8Sk128; out[2] = &kI8Sk128nt; return 3; }
     return 0;
 }
 
