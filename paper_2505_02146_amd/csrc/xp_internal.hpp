@@ -62,9 +62,12 @@ inline double tile_cost_us(const Problem &q, int BM, int BN, int lds_bytes, int 
     if (conc < 1) conc = 1;
     const double slots = 256.0 * conc;
     const double rounds = conc == 1 ? __builtin_ceil(tiles / slots) : (tiles <= slots ? 1.0 : tiles / slots);
+    // workgroups that actually share a compute unit: fewer than conc when the grid is small
+    double share = tiles >= slots ? (double)conc : __builtin_ceil(tiles / 256.0);
+    if (share < 1.0) share = 1.0;
     const double rate = esz == 1 ? 2.0 * 9.83e6 : 9.83e6;             // MFMA flop per microsecond per compute unit
-    const double t_comp = 2.0 * BM * BN * (double)q.K / (rate * eff) * conc;
-    const double t_mem = conc * ((double)BM * BN * 4.0 / 16e3 + (double)(BM + BN) * (double)q.K * esz / 64e3);
+    const double t_comp = 2.0 * BM * BN * (double)q.K / (rate * eff) * share;
+    const double t_mem = share * ((double)BM * BN * 4.0 / 16e3 + (double)(BM + BN) * (double)q.K * esz / 64e3);
     const double t_lat = 3.0;
     const double t_work = t_comp > t_mem ? t_comp : t_mem;
     return conc == 1 ? rounds * (t_work + t_lat) : rounds * (t_work > t_lat ? t_work : t_lat);

@@ -448,7 +448,7 @@ XP_DL_VARIANT(kBfDl256x128r64n3, "bf16", false, 256, 128, 2, 2, 3, 64, false, ""
 XP_DL_VARIANT(kBfDl256x128r64n3s, "bf16", false, 256, 128, 2, 2, 3, 64, true, " spread", 2, 32, false, "", 0.45)
 XP_DL_VARIANT(kBfDl128x256r64n3s, "bf16", false, 128, 256, 2, 2, 3, 64, true, " spread", 2, 32, false, "", 0.45)
 XP_DL_VARIANT(kBfDl128x128r128n2, "bf16", false, 128, 128, 2, 2, 2, 128, false, "", 2, 32, false, "", 0.32)
-XP_DL_VARIANT(kBfDl128x128r64n4s, "bf16", false, 128, 128, 2, 2, 4, 64, true, " spread", 2, 32, false, "", 0.32)
+XP_DL_VARIANT(kBfDl128x128r64n4s, "bf16", false, 128, 128, 2, 2, 4, 64, true, " spread", 2, 32, false, "", 0.40)
 
 XP_DL_VARIANT(kI8Dl256x256r128n2, "i8", true, 256, 256, 2, 4, 2, 128, false, "", 1, 32, false, "", 0.52)
 XP_DL_VARIANT(kI8Dl256x256r128n2m16, "i8", true, 256, 256, 2, 4, 2, 128, false, "", 1, 16, false, "", 0.55)
@@ -463,7 +463,7 @@ XP_DL_VARIANT(kI8Dl256x128r64n3, "i8", true, 256, 128, 2, 2, 3, 64, false, "", 2
 XP_DL_VARIANT(kI8Dl256x128r64n3s, "i8", true, 256, 128, 2, 2, 3, 64, true, " spread", 2, 32, false, "", 0.45)
 XP_DL_VARIANT(kI8Dl128x256r64n3s, "i8", true, 128, 256, 2, 2, 3, 64, true, " spread", 2, 32, false, "", 0.45)
 XP_DL_VARIANT(kI8Dl128x128r128n2, "i8", true, 128, 128, 2, 2, 2, 128, false, "", 2, 32, false, "", 0.32)
-XP_DL_VARIANT(kI8Dl128x128r64n4s, "i8", true, 128, 128, 2, 2, 4, 64, true, " spread", 2, 32, false, "", 0.32)
+XP_DL_VARIANT(kI8Dl128x128r64n4s, "i8", true, 128, 128, 2, 2, 4, 64, true, " spread", 2, 32, false, "", 0.40)
 
 }  // namespace
 

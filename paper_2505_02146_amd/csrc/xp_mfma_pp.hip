@@ -298,20 +298,21 @@ hipError_t pp_launch(const Problem &q)
     return hipGetLastError();
 }
 
-template <bool INT8>
+template <bool INT8, int MF>
 double pp_cost(const Problem &q)
 {
-    return tile_cost_us(q, BM, BN, 2 * STAGE, 512, 0.58, INT8 ? 1 : 2);
+    // ahead of the plain direct-to-LDS kernel once the grid is several rounds deep (swept at 8192^3)
+    return tile_cost_us(q, BM, BN, 2 * STAGE, 512, MF == 16 ? 0.565 : 0.525, INT8 ? 1 : 2);
 }
 
 const Variant kBfPp32 = {"bf16 256x256x128B waves 2x4 ring 2 ping-pong direct-to-lds mfma32", pp_can_run<false>,
-                         pp_launch<false, 32>, pp_cost<false>};
+                         pp_launch<false, 32>, pp_cost<false, 32>};
 const Variant kBfPp16 = {"bf16 256x256x128B waves 2x4 ring 2 ping-pong direct-to-lds mfma16", pp_can_run<false>,
-                         pp_launch<false, 16>, pp_cost<false>};
+                         pp_launch<false, 16>, pp_cost<false, 16>};
 const Variant kI8Pp32 = {"i8 256x256x128B waves 2x4 ring 2 ping-pong direct-to-lds mfma32", pp_can_run<true>,
-                         pp_launch<true, 32>, pp_cost<true>};
+                         pp_launch<true, 32>, pp_cost<true, 32>};
 const Variant kI8Pp16 = {"i8 256x256x128B waves 2x4 ring 2 ping-pong direct-to-lds mfma16", pp_can_run<true>,
-                         pp_launch<true, 16>, pp_cost<true>};
+                         pp_launch<true, 16>, pp_cost<true, 16>};
 
 }  // namespace
 
