@@ -73,6 +73,24 @@ inline double tile_cost_us(const Problem &q, int BM, int BN, int lds_bytes, int 
     return conc == 1 ? rounds * (t_work + t_lat) : rounds * (t_work > t_lat ? t_work : t_lat);
 }
 
+// Batched launches with few tiles per problem: the workgroups of one problem have consecutive
+// linear ids and would be dealt round-robin to the 8 XCDs, so each XCD's L2 would fetch that
+// problem's operands again.  This renumbering gives XCD x (linear id mod 8) a contiguous run of
+// (tile, batch) pairs instead, so a problem's tiles share one L2.  Returns the renumbered
+// blockIdx.x in `x` and blockIdx.y in `y`; identity when the grid size is not a multiple of 8.
+__device__ __forceinline__ void xcd_batch_remap(unsigned &x, unsigned &y)
+{
+    const unsigned gx = gridDim.x, total = gx * gridDim.y;
+    x = blockIdx.x;
+    y = blockIdx.y;
+    if ((total & 7) == 0) {
+        const unsigned lin = y * gx + x;
+        const unsigned ren = (lin & 7) * (total >> 3) + (lin >> 3);
+        x = ren % gx;
+        y = ren / gx;
+    }
+}
+
 inline int elem_size(xp_dtype t) { return t == XP_F32 || t == XP_I32 ? 4 : (t == XP_BF16 ? 2 : 1); }
 
 }  // namespace xp

@@ -184,8 +184,10 @@ __global__ __launch_bounds__(WM *WN * 64) void oc_kernel(OcParams p)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int m0 = (blockIdx.x / p.tiles_n) * BM, n0 = (blockIdx.x % p.tiles_n) * BN;
-    const long long batch = blockIdx.y;
+    unsigned bx, by;
+    xcd_batch_remap(bx, by);                          // the tiles of one problem share an L2
+    const int m0 = (bx / p.tiles_n) * BM, n0 = (bx % p.tiles_n) * BN;
+    const long long batch = by;
     const int Kb = p.K * ESZ;
 
     __amdgpu_buffer_rsrc_t ra, rb;

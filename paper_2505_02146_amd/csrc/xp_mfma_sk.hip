@@ -93,8 +93,10 @@ __global__ __launch_bounds__(320) void sk_kernel(SkParams p)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int m0 = blockIdx.x * BM;
-    const long long batch = blockIdx.y;
+    unsigned bx, by;
+    xcd_batch_remap(bx, by);                          // the row tiles of one problem share an L2: B is fetched once
+    const int m0 = bx * BM;
+    const long long batch = by;
 
     if (wave == 4) {
         // ------------------------------------------------------------------ producer wave

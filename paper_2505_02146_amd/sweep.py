@@ -6,7 +6,8 @@ A candidate is valid when the library accepts it for the call and its output agr
 general kernel's output for the same inputs (bit-exact for int8, within fp32 summation-order
 noise otherwise).  Parity against the CPU oracle is the test-suite's job, not the sweep's.
 
-    python -m paper_2505_02146_amd.sweep [--workload NAME ...] [--steps 30] [--rounds 1] [--only IDX ...] [--json out.json]
+    python -m paper_2505_02146_amd.sweep [--workload NAME ...] [--steps 30] [--rounds 1] [--only IDX ...]
+        [--json out.json] [--calibrate-copy]
 """
 from __future__ import annotations
 
@@ -144,7 +145,14 @@ def main(argv=None) -> int:
     ap.add_argument("--rounds", type=int, default=1, help="time the candidates round-robin this many times, report medians")
     ap.add_argument("--only", type=int, nargs="*", default=None, help="variant indices to time (default: all)")
     ap.add_argument("--json", default=None)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device copy: a known traffic for scaling profiler byte counters")
     args = ap.parse_args(argv)
+    if args.calibrate_copy:
+        import torch
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        torch.empty_like(src).copy_(src)
+        torch.cuda.synchronize()
     all_rows = []
     for name in args.workload:
         rows = sweep(name, args.steps, rounds=args.rounds, only=args.only)
