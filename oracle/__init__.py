@@ -35,8 +35,9 @@ def lib() -> C.CDLL:
                                                 vp, i, i, i64, i64, vp, i, i, i64, i64,
                                                 dbl, vp, i, i64, i64, vp]
         L.oracle_conv2d_nhwc.argtypes = [i64] * 11 + [vp, i, vp, i, i, vp]
+        L.oracle_attention.argtypes = [i64] * 5 + [dbl] + [vp, i, i64, i64] * 3 + [vp]
         for f in (L.oracle_gemm_float, L.oracle_gemm_i8, L.oracle_gemm_float_batched,
-                  L.oracle_conv2d_nhwc, L.oracle_num_threads):
+                  L.oracle_conv2d_nhwc, L.oracle_attention, L.oracle_num_threads):
             f.restype = i
         _lib = L
     return _lib
@@ -134,4 +135,22 @@ def conv2d_nhwc(x, w, *, N, H, W, Cin, Cout, R, S, stride=(1, 1), pad=(0, 0),
                                   _ptr(ref))
     if rc:
         raise ValueError(f"oracle_conv2d_nhwc failed with code {rc}")
+    return ref
+
+
+def attention(Q, K, V, *, batch, Lq, Lk, d, dv, scale, ldq=None, ldk=None, ldv=None,
+              strideQ=None, strideK=None, strideV=None) -> np.ndarray:
+    """fp64 reference of softmax(scale * Q.K^T).V per batch index, dense batch x Lq x dv."""
+    ldq = d if ldq is None else ldq
+    ldk = d if ldk is None else ldk
+    ldv = dv if ldv is None else ldv
+    strideQ = Lq * ldq if strideQ is None else strideQ
+    strideK = Lk * ldk if strideK is None else strideK
+    strideV = Lk * ldv if strideV is None else strideV
+    ref = np.empty((batch, Lq, dv), dtype=np.float64)
+    rc = lib().oracle_attention(batch, Lq, Lk, d, dv, float(scale),
+                                _ptr(Q), _ftype(Q), ldq, strideQ, _ptr(K), _ftype(K), ldk, strideK,
+                                _ptr(V), _ftype(V), ldv, strideV, _ptr(ref))
+    if rc:
+        raise ValueError(f"oracle_attention failed with code {rc}")
     return ref

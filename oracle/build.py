@@ -14,7 +14,7 @@ def build(force: bool = True) -> pathlib.Path:
     if not force and LIB.exists() and LIB.stat().st_mtime >= max(src.stat().st_mtime, hdr.stat().st_mtime):
         return LIB
     cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-           "-o", str(LIB), str(src)]
+           "-o", str(LIB), str(src), "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 

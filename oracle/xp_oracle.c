@@ -7,6 +7,8 @@
 #include "xp_oracle.h"
 
 #include <stddef.h>
+#include <math.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -162,4 +164,54 @@ int oracle_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cou
         }
     }
     return 0;
+}
+
+/* Scaled dot-product attention without a mask: the scores of one query against every key, a
+ * softmax over the keys, the weighted sum of the value rows.  The largest score is subtracted
+ * before exponentiation (this does not change the quotient; it keeps exp() in range). */
+int oracle_attention(int64_t batch, int64_t Lq, int64_t Lk, int64_t d, int64_t dv, double scale,
+                     const void *Q, int q_type, int64_t ldq, int64_t strideQ,
+                     const void *K, int k_type, int64_t ldk, int64_t strideK,
+                     const void *V, int v_type, int64_t ldv, int64_t strideV,
+                     double *ref)
+{
+    if (batch < 0 || Lq < 0 || Lk <= 0 || d < 0 || dv < 0) return 1;
+    if (bad_type(q_type) || bad_type(k_type) || bad_type(v_type)) return 2;
+    if (ldq < d || ldk < d || ldv < dv) return 3;
+    if (batch == 0 || Lq == 0 || dv == 0) return 0;
+    if (!ref || !V || (d > 0 && (!Q || !K))) return 4;
+
+    int failed = 0;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t b = 0; b < batch; ++b) {
+        for (int64_t i = 0; i < Lq; ++i) {
+            double *w = (double *)malloc((size_t)Lk * sizeof(double));
+            if (!w) {
+#pragma omp atomic write
+                failed = 1;
+                continue;
+            }
+            double top = -INFINITY;
+            for (int64_t j = 0; j < Lk; ++j) {
+                double dot = 0.0;
+                for (int64_t c = 0; c < d; ++c)
+                    dot += widen(Q, q_type, b * strideQ + i * ldq + c) * widen(K, k_type, b * strideK + j * ldk + c);
+                w[j] = scale * dot;
+                if (w[j] > top) top = w[j];
+            }
+            double total = 0.0;
+            for (int64_t j = 0; j < Lk; ++j) {
+                w[j] = exp(w[j] - top);
+                total += w[j];
+            }
+            for (int64_t x = 0; x < dv; ++x) {
+                double acc = 0.0;
+                for (int64_t j = 0; j < Lk; ++j)
+                    acc += (w[j] / total) * widen(V, v_type, b * strideV + j * ldv + x);
+                ref[(b * Lq + i) * dv + x] = acc;
+            }
+            free(w);
+        }
+    }
+    return failed ? 5 : 0;
 }

@@ -1,6 +1,7 @@
 /*
  * CPU oracle for the dense tensor operators of the MatMul and Convolution groups of the
- * paper's benchmark (Table 5: GEMM, Batch GEMM, Conv2D NHWC).
+ * paper's benchmark (Table 5: GEMM, Batch GEMM, Conv2D NHWC) and for the fused attention operator
+ * of its LLM group (Table 5: Self Attention).
  *
  * THIS IS TEST INFRASTRUCTURE, NOT A PRODUCT PATH.  It exists so that the GPU library can be
  * checked against something that is obviously right.  It is plain, slow, scalar C: the
@@ -16,6 +17,7 @@
  *   batched     the same for every batch index on pointers advanced by the batch strides
  *   conv NHWC   ref[n,p,q,k] = sum_{r,s,c} in[n, p*sh + r - ph, q*sw + s - pw, c] * w(k,r,s,c)
  *               (cross-correlation, zero padding, dilation 1, groups 1, no bias)
+ *   attention   ref = softmax_over_keys(scale * Q K^T) V, no mask, for every batch index
  *
  * All pointers are host pointers.  Reference outputs are dense and row-major
  * (M x N, batch x M x N, N x P x Q x Cout) regardless of the layout of the operands.
@@ -73,6 +75,19 @@ int oracle_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cou
                        const void *input, int in_type,
                        const void *filter, int w_type, int w_layout,
                        double *ref);
+
+/* Scaled dot-product attention without a mask (the "Self Attention" operator of Table 5; the
+ * paper prints no definition, the standard one is used):
+ *   s(i,j) = scale * sum_c Q(i,c) K(j,c),   p(i,j) = exp(s(i,j)) / sum_j' exp(s(i,j')),
+ *   ref(i,x) = sum_j p(i,j) V(j,x)
+ * for every batch index.  Q is batch x Lq x d, K is batch x Lk x d, V is batch x Lk x dv; each
+ * is row-major with a row pitch (ldq, ldk, ldv) and a batch stride, both in elements.  Lk must
+ * be positive.  ref receives batch*Lq*dv doubles, dense.  Everything is computed in fp64. */
+int oracle_attention(int64_t batch, int64_t Lq, int64_t Lk, int64_t d, int64_t dv, double scale,
+                     const void *Q, int q_type, int64_t ldq, int64_t strideQ,
+                     const void *K, int k_type, int64_t ldk, int64_t strideK,
+                     const void *V, int v_type, int64_t ldv, int64_t strideV,
+                     double *ref);
 
 /* Number of OpenMP threads the loops above will use. */
 int oracle_num_threads(void);

@@ -148,8 +148,19 @@ def workload(name: str, seed: int = 0) -> dict:
                     stride=(1, 1), pad=(1, 1), filter_layout="krsc",
                     input=to_bf16_bits(normal((n, h, w, ci), seed, TID_A)),
                     filter=to_bf16_bits(normal((co, r, s, ci), seed, TID_B, 1.0 / 48.0)))
+    if name == "attention_bf16_512":
+        # the two batched stages above with a row softmax between them, as one operator: unit-variance
+        # Q and K with scale 1/sqrt(d) give scores of unit variance, i.e. a softmax that is neither
+        # flat nor one-hot
+        b, L, d = 96, 512, 64
+        return dict(op="attention", dtype="bf16", batch=b, Lq=L, Lk=L, d=d, dv=d, scale=1.0 / 8.0,
+                    Q=to_bf16_bits(normal((b, L, d), seed, TID_A)),
+                    K=to_bf16_bits(normal((b, L, d), seed, TID_B)),
+                    V=to_bf16_bits(normal((b, L, d), seed, TID_C)))
     raise KeyError(name)
 
 
 WORKLOADS = ("gemm_f32_256", "gemm_bf16_4096", "gemm_i8_4096x4096x8192",
              "bgemm_bf16_qk", "bgemm_bf16_pv", "conv_bf16_56")
+# operators beyond the GEMM / convolution set, each served by its own entry point
+EXTRA_WORKLOADS = ("attention_bf16_512",)
