@@ -2,7 +2,8 @@
  * xp -- dense tensor operators for AMD MI355X (gfx950 / CDNA4), C ABI.
  *
  * The operators are the MatMul and Convolution rows of the benchmark of the QiMeng-Xpiler
- * paper (arXiv 2505.02146, Table 5): GEMM, Batch GEMM and Conv2D NHWC.  The paper lists them
+ * paper (arXiv 2505.02146, Table 5): GEMM, Batch GEMM and Conv2D NHWC, plus the fused
+ * Self Attention operator of its LLM rows.  The paper lists them
  * by name and prints no definition; the standard definitions below are what the library
  * computes.  Every entry point launches hand-written HIP kernels (LDS-tiled, matrix-core
  * MFMA contraction, the kind of instruction Table 1 of the paper names for AMD hardware) on
@@ -62,7 +63,7 @@ typedef enum { XP_ROW = 0, XP_COL = 1 } xp_layout;
 typedef enum { XP_FILTER_KRSC = 0, XP_FILTER_RSCK = 1 } xp_filter_layout;
 
 /* Operator families for the tuning surface. */
-typedef enum { XP_OP_GEMM = 0, XP_OP_GEMM_BATCHED = 1, XP_OP_CONV2D = 2 } xp_op;
+typedef enum { XP_OP_GEMM = 0, XP_OP_GEMM_BATCHED = 1, XP_OP_CONV2D = 2, XP_OP_ATTENTION = 3 } xp_op;
 
 /*
  * GEMM (Table 5, "GEMM"):  C(i,j) = alpha * sum_{k<K} A(i,k) * B(k,j) + beta * C(i,j)
@@ -105,6 +106,34 @@ xp_status xp_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t C
                          const void *filter, xp_dtype w_type, xp_filter_layout w_layout,
                          void *output, xp_dtype out_type,
                          void *stream);
+
+/*
+ * Fused scaled dot-product attention without a mask (Table 5, "Self Attention"; the paper names
+ * the operator and prints no definition, the standard one is computed): for every b < batch,
+ *   s(i,j) = scale * sum_{c<d} Q(i,c) K(j,c)            i < Lq, j < Lk
+ *   p(i,j) = exp(s(i,j)) / sum_{j'<Lk} exp(s(i,j'))
+ *   O(i,x) = sum_{j<Lk} p(i,j) V(j,x)                   x < dv
+ * i.e. the two Batch GEMM stages with a row softmax between them, as one kernel that never
+ * writes the Lq x Lk score matrix to memory.
+ *   Q  batch x Lq x d,  K  batch x Lk x d,  V  batch x Lk x dv,  O  batch x Lq x dv (written).
+ * Each is row-major: element (b, i, c) at  base[b*stride + i*ld + c], with the row pitch ld
+ * (>= the row length) and the batch stride in elements (>= 0; 0 shares Q, K or V across the
+ * batch; the O slices must not overlap).  All four are DEVICE pointers owned by the caller.
+ * Supported types: Q, K, V all F32 or all BF16; O is F32.  Products and sums are formed in
+ * fp32; on the matrix-core path (BF16, d == dv == 64, 16-byte aligned pointers, pitches and
+ * strides) the probabilities are rounded to bf16 before they multiply V.  Other shapes and
+ * alignments run on a slower general kernel under the same definition.
+ * scale must be finite (the usual choice is 1/sqrt(d)).
+ * Degenerate sizes: batch, Lq or dv == 0 -> XP_OK, nothing launched; d == 0 -> every score is
+ * 0, O is the mean of the value rows; Lk == 0 with a non-empty output -> XP_ERR_SHAPE (a
+ * softmax over no keys is undefined).
+ */
+xp_status xp_attention(int64_t batch, int64_t Lq, int64_t Lk, int64_t d, int64_t dv, float scale,
+                       const void *Q, xp_dtype q_type, int64_t ldq, int64_t strideQ,
+                       const void *K, xp_dtype k_type, int64_t ldk, int64_t strideK,
+                       const void *V, xp_dtype v_type, int64_t ldv, int64_t strideV,
+                       void *O, xp_dtype o_type, int64_t ldo, int64_t strideO,
+                       void *stream);
 
 /*
  * Tuning surface: the stand-in for the tile-size / loop-order / binding knobs that the paper's

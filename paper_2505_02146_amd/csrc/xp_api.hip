@@ -36,8 +36,8 @@ void build_tables()
 }
 
 // forced variant per (op, type slot); -1 = use the selection table
-std::atomic<int> g_forced[3][3];
-std::atomic<int> g_last[3][3];
+std::atomic<int> g_forced[4][3];
+std::atomic<int> g_last[4][3];
 struct Init {
     Init()
     {
@@ -277,15 +277,69 @@ xp_status xp_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t C
     return run(q);
 }
 
+xp_status xp_attention(int64_t batch, int64_t Lq, int64_t Lk, int64_t d, int64_t dv, float scale,
+                       const void *Q, xp_dtype q_type, int64_t ldq, int64_t strideQ,
+                       const void *K, xp_dtype k_type, int64_t ldk, int64_t strideK,
+                       const void *V, xp_dtype v_type, int64_t ldv, int64_t strideV,
+                       void *O, xp_dtype o_type, int64_t ldo, int64_t strideO,
+                       void *stream)
+{
+    if (batch < 0 || Lq < 0 || Lk < 0 || d < 0 || dv < 0) return XP_ERR_SHAPE;
+    if (q_type != k_type || q_type != v_type || (q_type != XP_F32 && q_type != XP_BF16) || o_type != XP_F32)
+        return XP_ERR_UNSUPPORTED;
+    if (!(scale == scale) || scale - scale != 0.0f) return XP_ERR_UNSUPPORTED;      // NaN or infinite
+    if (batch == 0 || Lq == 0 || dv == 0) return XP_OK;
+    if (Lk == 0) return XP_ERR_SHAPE;
+    if (ldq < d || ldk < d || ldv < dv || ldo < dv) return XP_ERR_STRIDE;
+    if (strideQ < 0 || strideK < 0 || strideV < 0 || strideO < 0) return XP_ERR_STRIDE;
+    if (batch > 1 && strideO < (Lq - 1) * ldo + dv) return XP_ERR_STRIDE;           // O slices must not overlap
+    if (!O || !V || (d > 0 && (!Q || !K))) return XP_ERR_NULL;
+    const int esz = elem_size(q_type);
+    if (!aligned_to(Q, esz) || !aligned_to(K, esz) || !aligned_to(V, esz) || !aligned_to(O, 4)) return XP_ERR_ALIGN;
+
+    AttnProblem q;
+    q.in_type = q_type;
+    q.batch = batch; q.Lq = Lq; q.Lk = Lk; q.d = d; q.dv = dv;
+    q.scale = scale;
+    q.Q = Q; q.K = K; q.V = V; q.O = O;
+    q.ldq = ldq; q.ldk = ldk; q.ldv = ldv; q.ldo = ldo;
+    q.strideQ = strideQ; q.strideK = strideK; q.strideV = strideV; q.strideO = strideO;
+    q.stream = (hipStream_t)stream;
+
+    const int slot = type_slot(q_type);
+    const int forced = g_forced[XP_OP_ATTENTION][slot].load();
+    int idx = 0;
+    if (forced >= 0) {
+        const AttnVariant *v = attn_variant(q_type, forced);
+        if (!v || !v->can_run(q)) return XP_ERR_CONFIG;
+        idx = forced;
+    } else {
+        // the last variant that can run the call: the table is ordered from general to specialised
+        for (int i = attn_num_variants(q_type) - 1; i > 0; --i)
+            if (attn_variant(q_type, i)->can_run(q)) { idx = i; break; }
+    }
+    const AttnVariant *v = attn_variant(q_type, idx);
+    if (!v || !v->can_run(q)) return XP_ERR_UNSUPPORTED;
+    g_last[XP_OP_ATTENTION][slot].store(idx);
+    return v->launch(q) == hipSuccess ? XP_OK : XP_ERR_LAUNCH;
+}
+
 int xp_num_configs(xp_op op, xp_dtype in_type)
 {
+    if (op == XP_OP_ATTENTION) return attn_num_variants(in_type);
     if (op < 0 || op > 2) return 0;
     return num_variants(in_type);
 }
 
 xp_status xp_describe_config(xp_op op, xp_dtype in_type, int idx, char *buf, size_t n)
 {
-    if (op < 0 || op > 2 || !buf || n == 0) return XP_ERR_CONFIG;
+    if (op < 0 || op > 3 || !buf || n == 0) return XP_ERR_CONFIG;
+    if (op == XP_OP_ATTENTION) {
+        const AttnVariant *a = attn_variant(in_type, idx);
+        if (!a) return XP_ERR_CONFIG;
+        snprintf(buf, n, "%s", a->name);
+        return XP_OK;
+    }
     const Variant *v = variant(in_type, idx);
     if (!v) return XP_ERR_CONFIG;
     snprintf(buf, n, "%s", v->name);
@@ -295,8 +349,8 @@ xp_status xp_describe_config(xp_op op, xp_dtype in_type, int idx, char *buf, siz
 xp_status xp_force_config(xp_op op, xp_dtype in_type, int idx)
 {
     const int slot = in_type == XP_F32 ? 0 : (in_type == XP_BF16 ? 1 : (in_type == XP_I8 ? 2 : -1));
-    if (op < 0 || op > 2 || slot < 0) return XP_ERR_CONFIG;
-    if (idx >= num_variants(in_type)) return XP_ERR_CONFIG;
+    if (op < 0 || op > 3 || slot < 0) return XP_ERR_CONFIG;
+    if (idx >= (op == XP_OP_ATTENTION ? attn_num_variants(in_type) : num_variants(in_type))) return XP_ERR_CONFIG;
     g_forced[op][slot].store(idx < 0 ? -1 : idx);
     return XP_OK;
 }
@@ -304,7 +358,7 @@ xp_status xp_force_config(xp_op op, xp_dtype in_type, int idx)
 int xp_last_config(xp_op op, xp_dtype in_type)
 {
     const int slot = in_type == XP_F32 ? 0 : (in_type == XP_BF16 ? 1 : (in_type == XP_I8 ? 2 : -1));
-    if (op < 0 || op > 2 || slot < 0) return -1;
+    if (op < 0 || op > 3 || slot < 0) return -1;
     return g_last[op][slot].load();
 }
 

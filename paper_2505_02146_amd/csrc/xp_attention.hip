@@ -1,0 +1,358 @@
+// Fused scaled dot-product attention (Table 5 of the paper: Self Attention):
+//   O = softmax_over_keys(scale * Q K^T) V      for every batch index, no mask.
+// The score matrix never reaches memory: a workgroup owns 64 queries, walks the keys in tiles of
+// 64 and keeps, per query, a running maximum, a running sum and an unnormalised output row that
+// are rescaled whenever the maximum grows (the usual streaming form of the softmax, which
+// reaches the same quotient as the two-pass definition).
+//
+// Two kernels:
+//   general   one wave per query, fp32 VALU arithmetic, any head size, fp32 or bf16 inputs
+//   mfma      bf16 inputs, head size 64 for Q/K and for V: both contractions on the 16x16x32
+//             matrix-core instruction, laid out so that nothing has to be transposed between them
+#include "xp_internal.hpp"
+
+namespace xp {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void;
+
+constexpr unsigned OOB = 0x80000000u;
+constexpr float LOG2E = 1.4426950408889634f;
+
+struct AttnParams {
+    const char *Q, *K, *V;
+    float *O;
+    int Lq, Lk, d, dv;
+    long long ldq, ldk, ldv, ldo;                 // general kernel: elements; mfma kernel: bytes (ldo: elements)
+    long long strideQ, strideK, strideV, strideO;
+    float scale;
+};
+
+// ---------------------------------------------------------------------------------- general kernel
+
+template <class T> __device__ __forceinline__ float widen(const T *p, long long i);
+template <> __device__ __forceinline__ float widen<float>(const float *p, long long i) { return p[i]; }
+template <> __device__ __forceinline__ float widen<unsigned short>(const unsigned short *p, long long i)
+{
+    return __uint_as_float((unsigned)p[i] << 16);
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+// One wave per (query, batch, block of 64 output columns).  Keys are taken in chunks of CHUNK:
+// the lanes share out the scores of a chunk and park them in LDS, then every lane walks the whole
+// chunk for its own output column.
+constexpr int CHUNK = 1024;
+
+template <class T>
+__global__ __launch_bounds__(64) void attn_general_kernel(AttnParams p)
+{
+    __shared__ float sc[CHUNK];
+    const int lane = threadIdx.x, i = blockIdx.x;
+    const long long b = blockIdx.y;
+    const int x = blockIdx.z * 64 + lane;
+    const T *Q = (const T *)p.Q + b * p.strideQ + (long long)i * p.ldq;
+    const T *K = (const T *)p.K + b * p.strideK;
+    const T *V = (const T *)p.V + b * p.strideV;
+
+    float top = -INFINITY, total = 0.0f, acc = 0.0f;
+    for (int c0 = 0; c0 < p.Lk; c0 += CHUNK) {
+        const int n = min(CHUNK, p.Lk - c0);
+        float mx = -INFINITY;
+        for (int j = lane; j < n; j += 64) {
+            const T *k = K + (long long)(c0 + j) * p.ldk;
+            float dot = 0.0f;
+            for (int c = 0; c < p.d; ++c) dot = fmaf(widen(Q, c), widen(k, c), dot);
+            const float s = p.scale * dot;
+            sc[j] = s;
+            mx = fmaxf(mx, s);
+        }
+        const float new_top = fmaxf(top, wave_max(mx));     // finite: the chunk holds at least one key
+        const float shrink = expf(top - new_top);            // 0 on the first chunk
+        total *= shrink;
+        acc *= shrink;
+        top = new_top;
+        __syncthreads();
+        for (int j = 0; j < n; ++j) {
+            const float w = expf(sc[j] - top);
+            total += w;
+            if (x < p.dv) acc = fmaf(w, widen(V, (long long)(c0 + j) * p.ldv + x), acc);
+        }
+        __syncthreads();
+    }
+    if (x < p.dv) p.O[b * p.strideO + (long long)i * p.ldo + x] = acc / total;
+}
+
+// ------------------------------------------------------------------------------------- mfma kernel
+//
+// Matrix-core instruction used for both contractions (16x16x32, bf16 in, fp32 out):
+//   D[m][n] += sum_k A[m][k] B[k][n];  lane l supplies A[l%16][8*(l/16) .. +8] and
+//   B[8*(l/16) .. +8][l%16] and holds D[4*(l/16) + v][l%16], v = 0..3.
+//
+// Scores are computed transposed, S^T = K Q^T (A = key rows from LDS, B = the wave's 16 queries,
+// resident in registers): lane l then holds, for ITS query l%16, the keys 16*blk + 4*(l/16) + v.
+// A query's softmax statistics are therefore lane-local up to two cross-lane steps (over l/16),
+// and the lane's probabilities of two key blocks are exactly the 8 values the B operand of
+//   O^T = V^T P^T      (A = V^T from LDS, B = P^T from registers)
+// needs, if the 32 keys of one k step are numbered: slot 8*g + e  <->  key 4*g + e (e < 4),
+// key 16 + 4*g + (e - 4) (e >= 4).  V is staged to LDS as words {V[2kp][x], V[2kp+1][x]} (key-pair
+// major), so a lane gathers its 8 keys of column x with four 32-bit reads that follow the same
+// numbering.  O^T comes out with the query in l%16 again, so the running rescale factor applies
+// without any exchange, and a lane ends up with 4 consecutive output columns: one 16-byte store.
+constexpr int HD = 64;                                  // head size (Q/K and V)
+constexpr int BQ = 64, BK = 64;                         // queries per workgroup, keys per step
+constexpr int KROW = HD * 2;                            // bytes per K row in LDS (swizzled 16-byte chunks)
+constexpr int K_TILE = BK * KROW;
+constexpr int VPITCH = HD * 4 + 32;                     // bytes per key-pair row of V: 4 lane groups hit disjoint banks
+constexpr int V_TILE = (BK / 2) * VPITCH;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+
+__device__ __forceinline__ void wg_barrier()
+{
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi)
+{
+    f32x2 f = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));   // round to nearest even
+}
+
+__device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
+{
+    __shared__ __attribute__((aligned(1024))) char lds[2 * K_TILE + 2 * V_TILE];
+    char *const ks = lds, *const vs = lds + 2 * K_TILE;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15, g = lane >> 4;
+    unsigned bx, by;
+    xcd_batch_remap(bx, by);                            // the query tiles of one problem share an L2: K, V fetched once
+    const int q0 = bx * BQ;
+    const long long b = by;
+
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc(p.Q + b * p.strideQ + (long long)q0 * p.ldq,
+                                                (unsigned)((long long)(min(p.Lq - q0, BQ) - 1) * p.ldq + KROW));
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.K + b * p.strideK, (unsigned)((long long)(p.Lk - 1) * p.ldk + KROW));
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.V + b * p.strideV, (unsigned)((long long)(p.Lk - 1) * p.ldv + KROW));
+
+    // the wave's queries: B operand of S^T, two k steps over the head dimension
+    u32x4 qf[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+        qf[s] = __builtin_amdgcn_raw_buffer_load_b128(rq, (unsigned)((wave * 16 + r) * p.ldq) + (32 * s + 8 * g) * 2, 0, 0);
+
+    // K tile: 8 wave-level loads of 8 rows each, two per wave, straight into LDS; lane l lands at
+    // row l/8, position l%8 and fetches the chunk whose swizzled position that is
+    const int krow = lane >> 3;
+    const int kchunk = ((lane & 7) ^ (krow & 6)) << 4;   // rows of a load start at multiples of 8: the swizzle term is the lane's
+    auto issue_k = [&](int j0, int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int blk = wave * 2 + i;
+            const unsigned off = (unsigned)((j0 + blk * 8 + krow) * p.ldk) + kchunk;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void *)(ks + buf * K_TILE + blk * 1024), 16, off, 0, 0, 0);
+        }
+    };
+    // V tile: thread t takes key pair t/8 and output columns 8*(t%8) .. +8
+    const int vkp = tid >> 3, vc = tid & 7;
+    u32x4 v0, v1;
+    auto load_v = [&](int j0) {
+        v0 = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp) * p.ldv) + vc * 16, 0, 0);
+        v1 = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp + 1) * p.ldv) + vc * 16, 0, 0);
+    };
+    auto store_v = [&](int buf) {
+        u32x4 lo, hi;                                    // 8 words {V[2kp][x], V[2kp+1][x]}
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            lo[2 * e] = (v0[e] & 0xffffu) | (v1[e] << 16);
+            lo[2 * e + 1] = (v0[e] >> 16) | (v1[e] & 0xffff0000u);
+            hi[2 * e] = (v0[e + 2] & 0xffffu) | (v1[e + 2] << 16);
+            hi[2 * e + 1] = (v0[e + 2] >> 16) | (v1[e + 2] & 0xffff0000u);
+        }
+        char *dst = vs + buf * V_TILE + vkp * VPITCH + vc * 32;
+        *(u32x4 *)dst = lo;
+        *(u32x4 *)(dst + 16) = hi;
+    };
+
+    const float c = p.scale * LOG2E;                     // scores are kept in units of log2
+    float top = -INFINITY, total = 0.0f;                 // total: this lane's share of the query's sum
+    f32x4 acc[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) acc[x] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    const int NT = (p.Lk + BK - 1) / BK;
+    issue_k(0, 0);
+    load_v(0);
+    store_v(0);
+    __builtin_amdgcn_s_waitcnt(0x0070);                  // vmcnt(0) and lgkmcnt(0)
+    wg_barrier();
+
+    for (int t = 0; t < NT; ++t) {
+        const int buf = t & 1, j0 = t * BK;
+        if (t + 1 < NT) {                                // uniform
+            issue_k(j0 + BK, buf ^ 1);
+            load_v(j0 + BK);
+        }
+        // S^T: 4 blocks of 16 keys
+        f32x4 s[4];
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+            s[kb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            const int row = kb * 16 + r;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const u32x4 kf = *(const u32x4 *)(ks + buf * K_TILE + row * KROW + (((4 * h + g) ^ (row & 6)) << 4));
+                s[kb] = mma(kf, qf[h], s[kb]);
+            }
+        }
+        // scale; keys past the end count as minus infinity (only the last tile can hold any)
+        float mx = -INFINITY;
+        const bool ragged = j0 + BK > p.Lk;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float z = s[kb][v] * c;
+                if (ragged && j0 + kb * 16 + 4 * g + v >= p.Lk) z = -INFINITY;
+                s[kb][v] = z;
+                mx = fmaxf(mx, z);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float new_top = fmaxf(top, mx);            // finite: every tile holds at least one key
+        const float shrink = __builtin_amdgcn_exp2f(top - new_top);
+        top = new_top;
+        total *= shrink;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) acc[x] *= shrink;
+        // probabilities, rounded to bf16 for the second contraction; the sum uses the rounded values
+        u32x4 pf[2];
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+            const unsigned w0 = pack_bf16(__builtin_amdgcn_exp2f(s[kb][0] - top), __builtin_amdgcn_exp2f(s[kb][1] - top));
+            const unsigned w1 = pack_bf16(__builtin_amdgcn_exp2f(s[kb][2] - top), __builtin_amdgcn_exp2f(s[kb][3] - top));
+            total += __uint_as_float(w0 << 16) + __uint_as_float(w0 & 0xffff0000u) + __uint_as_float(w1 << 16) +
+                     __uint_as_float(w1 & 0xffff0000u);
+            pf[kb >> 1][(kb & 1) * 2] = w0;
+            pf[kb >> 1][(kb & 1) * 2 + 1] = w1;
+        }
+        // O^T += V^T P^T: 4 blocks of 16 output columns, 2 k steps of 32 keys
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const char *src = vs + buf * V_TILE + (16 * h + 2 * g) * VPITCH + (x * 16 + r) * 4;
+                u32x4 vf;
+                vf[0] = *(const unsigned *)src;
+                vf[1] = *(const unsigned *)(src + VPITCH);
+                vf[2] = *(const unsigned *)(src + 8 * VPITCH);
+                vf[3] = *(const unsigned *)(src + 9 * VPITCH);
+                acc[x] = mma(vf, pf[h], acc[x]);
+            }
+        if (t + 1 < NT) store_v(buf ^ 1);                // the buffers read one barrier ago
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        wg_barrier();
+    }
+
+    total += __shfl_xor(total, 16);
+    total += __shfl_xor(total, 32);
+    const float inv = 1.0f / total;
+    const int q = q0 + wave * 16 + r;
+    if (q < p.Lq) {
+        float *dst = p.O + b * p.strideO + (long long)q * p.ldo + 4 * g;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) *(f32x4 *)(dst + 16 * x) = acc[x] * inv;
+    }
+}
+
+// ------------------------------------------------------------------------------------ host side
+
+AttnParams params_elements(const AttnProblem &q)
+{
+    AttnParams p;
+    p.Q = (const char *)q.Q; p.K = (const char *)q.K; p.V = (const char *)q.V; p.O = (float *)q.O;
+    p.Lq = (int)q.Lq; p.Lk = (int)q.Lk; p.d = (int)q.d; p.dv = (int)q.dv;
+    p.ldq = q.ldq; p.ldk = q.ldk; p.ldv = q.ldv; p.ldo = q.ldo;
+    p.strideQ = q.strideQ; p.strideK = q.strideK; p.strideV = q.strideV; p.strideO = q.strideO;
+    p.scale = q.scale;
+    return p;
+}
+
+bool general_can_run(const AttnProblem &q)
+{
+    return q.Lq <= 0x7fffffffLL && q.Lk <= 0x7fffffffLL && q.d <= 0x7fffffffLL && q.dv <= 0x7fffffffLL &&
+           q.batch <= 65535 && (q.dv + 63) / 64 <= 65535;
+}
+
+hipError_t general_launch(const AttnProblem &q)
+{
+    const AttnParams p = params_elements(q);
+    const dim3 grid((unsigned)q.Lq, (unsigned)q.batch, (unsigned)((q.dv + 63) / 64));
+    if (q.in_type == XP_F32) hipLaunchKernelGGL(attn_general_kernel<float>, grid, dim3(64), 0, q.stream, p);
+    else hipLaunchKernelGGL(attn_general_kernel<unsigned short>, grid, dim3(64), 0, q.stream, p);
+    return hipGetLastError();
+}
+
+bool mfma_can_run(const AttnProblem &q)
+{
+    if (q.in_type != XP_BF16 || q.d != HD || q.dv != HD) return false;
+    if (q.batch > 65535 || q.Lq > 0x3fffffffLL || q.Lk > 0x3fffffffLL) return false;
+    const void *ptrs[3] = {q.Q, q.K, q.V};
+    const int64_t lds_[3] = {q.ldq, q.ldk, q.ldv}, strides[3] = {q.strideQ, q.strideK, q.strideV};
+    const int64_t rows[3] = {q.Lq, q.Lk, q.Lk};
+    for (int i = 0; i < 3; ++i) {
+        if (((uintptr_t)ptrs[i] % 16) != 0 || (lds_[i] * 2) % 16 != 0 || (strides[i] * 2) % 16 != 0) return false;
+        if ((rows[i] + BK) * lds_[i] * 2 >= 0x7fffffffLL) return false;     // 32-bit byte offsets within one problem
+    }
+    if (((uintptr_t)q.O % 16) != 0 || (q.ldo * 4) % 16 != 0 || (q.strideO * 4) % 16 != 0) return false;
+    return true;
+}
+
+hipError_t mfma_launch(const AttnProblem &q)
+{
+    AttnParams p = params_elements(q);
+    p.ldq *= 2; p.ldk *= 2; p.ldv *= 2;                  // bytes
+    p.strideQ *= 2; p.strideK *= 2; p.strideV *= 2;
+    const dim3 grid((unsigned)((q.Lq + BQ - 1) / BQ), (unsigned)q.batch);
+    hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, q.stream, p);
+    return hipGetLastError();
+}
+
+const AttnVariant kGeneral = {"general attention one wave per query valu", general_can_run, general_launch};
+const AttnVariant kMfma64 = {"bf16 attention head 64, 64 queries x 64-key steps, waves 4x1 mfma16", mfma_can_run, mfma_launch};
+
+}  // namespace
+
+int attn_num_variants(xp_dtype in_type) { return in_type == XP_BF16 ? 2 : (in_type == XP_F32 ? 1 : 0); }
+
+const AttnVariant *attn_variant(xp_dtype in_type, int idx)
+{
+    if (idx < 0 || idx >= attn_num_variants(in_type)) return nullptr;
+    return idx == 0 ? &kGeneral : &kMfma64;
+}
+
+}  // namespace xp

@@ -36,6 +36,25 @@ struct Variant {
     double (*cost)(const Problem &);   // estimated run time, arbitrary units, lower is better
 };
 
+// Fused attention has its own problem description and its own (short) variant table.
+struct AttnProblem {
+    xp_dtype in_type;             // XP_F32 or XP_BF16 (Q, K and V alike); the output is fp32
+    int64_t batch, Lq, Lk, d, dv;
+    float scale;
+    const void *Q, *K, *V;
+    void *O;
+    int64_t ldq, ldk, ldv, ldo;   // row pitches, elements
+    int64_t strideQ, strideK, strideV, strideO;
+    hipStream_t stream;
+};
+struct AttnVariant {
+    const char *name;
+    bool (*can_run)(const AttnProblem &);
+    hipError_t (*launch)(const AttnProblem &);
+};
+int attn_num_variants(xp_dtype in_type);                    // index 0 is the general kernel
+const AttnVariant *attn_variant(xp_dtype in_type, int idx);
+
 // Variant tables, one per input type.  Index 0 is always the general (any layout) kernel.
 int num_variants(xp_dtype in_type);
 const Variant *variant(xp_dtype in_type, int idx);

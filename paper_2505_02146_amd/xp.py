@@ -25,7 +25,7 @@ _lib = C.CDLL(str(LIB_PATH))
 XP_F32, XP_BF16, XP_I8, XP_I32 = 0, 1, 2, 3
 XP_ROW, XP_COL = 0, 1
 XP_FILTER_KRSC, XP_FILTER_RSCK = 0, 1
-XP_OP_GEMM, XP_OP_GEMM_BATCHED, XP_OP_CONV2D = 0, 1, 2
+XP_OP_GEMM, XP_OP_GEMM_BATCHED, XP_OP_CONV2D, XP_OP_ATTENTION = 0, 1, 2, 3
 XP_OK = 0
 
 _i64, _f, _vp, _i = C.c_int64, C.c_float, C.c_void_p, C.c_int
@@ -33,6 +33,7 @@ _lib.xp_gemm.argtypes = [_i64, _i64, _i64, _f, _vp, _i, _i, _i64, _vp, _i, _i, _
 _lib.xp_gemm_batched.argtypes = [_i64, _i64, _i64, _i64, _f, _vp, _i, _i, _i64, _i64, _vp, _i, _i, _i64, _i64,
                                  _f, _vp, _i, _i, _i64, _i64, _vp]
 _lib.xp_conv2d_nhwc.argtypes = [_i64] * 11 + [_vp, _i, _vp, _i, _i, _vp, _i, _vp]
+_lib.xp_attention.argtypes = [_i64] * 5 + [_f] + [_vp, _i, _i64, _i64] * 4 + [_vp]
 _lib.xp_num_configs.argtypes = [_i, _i]
 _lib.xp_describe_config.argtypes = [_i, _i, _i, C.c_char_p, C.c_size_t]
 _lib.xp_force_config.argtypes = [_i, _i, _i]
@@ -40,7 +41,7 @@ _lib.xp_last_config.argtypes = [_i, _i]
 _lib.xp_status_string.argtypes = [_i]
 _lib.xp_status_string.restype = C.c_char_p
 _lib.xp_version.restype = C.c_char_p
-for _name in ("xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_num_configs", "xp_describe_config",
+for _name in ("xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_attention", "xp_num_configs", "xp_describe_config",
               "xp_force_config", "xp_last_config"):
     getattr(_lib, _name).restype = _i
 
@@ -108,6 +109,14 @@ def xp_conv2d_nhwc(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, x
     _check(_lib.xp_conv2d_nhwc(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w,
                                _ptr(x), _dt(x, in_type), _ptr(w), _dt(w, w_type), _FILTER[filter_layout],
                                _ptr(out), _dt(out, out_type), _stream(stream)))
+
+
+def xp_attention(batch, Lq, Lk, d, dv, scale, Q, ldq, strideQ, K, ldk, strideK, V, ldv, strideV, O, ldo, strideO,
+                 stream=None, q_type=None, k_type=None, v_type=None, o_type=None):
+    """O = softmax(scale * Q.K^T).V per batch index, fused on the GPU (see include/xp.h: xp_attention)."""
+    _check(_lib.xp_attention(batch, Lq, Lk, d, dv, scale, _ptr(Q), _dt(Q, q_type), ldq, strideQ,
+                             _ptr(K), _dt(K, k_type), ldk, strideK, _ptr(V), _dt(V, v_type), ldv, strideV,
+                             _ptr(O), _dt(O, o_type), ldo, strideO, _stream(stream)))
 
 
 def xp_num_configs(op: int, in_type) -> int:

@@ -23,7 +23,7 @@ def _declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_symbols()
-    assert {"xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_num_configs", "xp_describe_config",
+    assert {"xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_attention", "xp_num_configs", "xp_describe_config",
             "xp_force_config", "xp_last_config", "xp_status_string", "xp_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -116,6 +116,47 @@ def test_conv_validation(lib):
     assert call(wl=3) == 5
     assert call(H=1, W=1, ph=0, pw=0, x=None, w=None, out=None) == 0   # filter larger than image: empty
     assert call(N=0, x=None, w=None, out=None) == 0
+
+
+def test_attention_validation(lib):
+    # every call here must be turned away (or be empty) on the host: the pointers are fake
+    def call(batch=2, Lq=4, Lk=4, d=8, dv=8, scale=0.5, Q=16, qt=0, ldq=8, sq=32, K=16, kt=0, ldk=8, sk=32,
+             V=16, vt=0, ldv=8, sv=32, O=16, ot=0, ldo=8, so=32):
+        return lib.xp_attention(batch, Lq, Lk, d, dv, scale, Q, qt, ldq, sq, K, kt, ldk, sk, V, vt, ldv, sv,
+                                O, ot, ldo, so, None)
+    assert call(batch=-1) == 2
+    assert call(Lk=-1) == 2
+    assert call(Lk=0) == 2                                 # softmax over no keys
+    assert call(Lk=0, Lq=0) == 0                           # ... unless the output is empty
+    assert call(batch=0, Q=None, K=None, V=None, O=None) == 0
+    assert call(dv=0, V=None, O=None) == 0
+    assert call(ldq=7) == 3
+    assert call(ldk=7) == 3
+    assert call(ldv=7) == 3
+    assert call(ldo=7) == 3
+    assert call(sq=-1) == 3
+    assert call(so=31) == 3                                # O slices would overlap
+    assert call(Q=None) == 1
+    assert call(V=None) == 1
+    assert call(O=None) == 1
+    assert call(qt=1, kt=0) == 5                           # mixed input types
+    assert call(qt=2, kt=2, vt=2) == 5                     # int8 attention not provided
+    assert call(ot=1) == 5
+    assert call(scale=float("nan")) == 5
+    assert call(scale=float("inf")) == 5
+    assert call(Q=17, qt=1, kt=1, vt=1) == 4               # bf16 pointer not 2-byte aligned
+    assert call(O=18) == 4
+
+
+def test_attention_variant_table(lib):
+    from paper_2505_02146_amd import xp
+    assert xp.xp_num_configs(xp.XP_OP_ATTENTION, "bf16") >= 2
+    assert xp.xp_num_configs(xp.XP_OP_ATTENTION, "f32") >= 1
+    assert xp.xp_num_configs(xp.XP_OP_ATTENTION, "i8") == 0
+    assert xp.xp_describe_config(xp.XP_OP_ATTENTION, "bf16", 0).startswith("general")
+    assert lib.xp_force_config(xp.XP_OP_ATTENTION, xp.XP_BF16, 99) == 6
+    assert lib.xp_force_config(xp.XP_OP_ATTENTION, xp.XP_BF16, -1) == 0
+    assert lib.xp_last_config(xp.XP_OP_ATTENTION, xp.XP_I8) == -1
 
 
 def test_status_strings(lib):
