@@ -57,6 +57,8 @@ def main() -> int:
                     help="force this kernel variant index for the main workload (profiling a sweep candidate)")
     ap.add_argument("--force-batched-variant", type=int, default=-1,
                     help="force this kernel variant index for the two batched side workloads")
+    ap.add_argument("--force-attention-variant", type=int, default=-1,
+                    help="time this attention variant instead of the library's choice")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (a known-size reference for "
                          "scaling the profiler's FETCH_SIZE / WRITE_SIZE counters)")
@@ -176,6 +178,33 @@ def main() -> int:
                           "buffers": f"{sets} rotating sets (HBM-cold)",
                           "kernel": xp.xp_describe_config(1, "bf16", xp.xp_last_config(1, "bf16"))}
             del As, Bs, Cs
+        # fused attention: the two batched stages with the row softmax between them, as one launch
+        wa = inputs.workload("attention_bf16_512")
+        b, L, d = wa["batch"], wa["Lq"], wa["d"]
+        alg_bytes = 3 * b * L * d * 2 + b * L * d * 4        # Q, K, V read once, O written once
+        sets = max(2, int(600e6 // alg_bytes) + 1)
+        Qs, Ks, Vs = ([dev(wa[t].reshape(-1)) for _ in range(sets)] for t in ("Q", "K", "V"))
+        Os = [torch.empty((b, L, d), dtype=torch.float32, device="cuda") for _ in range(sets)]
+        it = {"i": 0}
+
+        def call_attention():
+            i = it["i"] % sets
+            it["i"] += 1
+            xp.xp_attention(b, L, L, d, d, wa["scale"], Qs[i], d, L * d, Ks[i], d, L * d, Vs[i], d, L * d, Os[i], d, L * d,
+                            q_type="bf16", k_type="bf16", v_type="bf16")
+        if args.force_attention_variant >= 0:
+            xp.xp_force_config(xp.XP_OP_ATTENTION, "bf16", args.force_attention_variant)
+        try:
+            ms, _ = _time_calls(torch, call_attention, steps2 * 2, warm2)
+        finally:
+            xp.xp_force_config(xp.XP_OP_ATTENTION, "bf16", -1)
+        unfused = side["bgemm_bf16_qk"]["ms"] + side["bgemm_bf16_pv"]["ms"]
+        side["attention_bf16_512"] = {"ms": round(ms, 5), "TFLOP/s": round(4.0 * b * L * L * d / (ms * 1e-3) / 1e12, 1),
+                                      "GB/s": round(alg_bytes / (ms * 1e-3) / 1e9, 1),
+                                      "buffers": f"{sets} rotating sets (HBM-cold)",
+                                      "vs_two_batched_gemm_stages_without_softmax": round(unfused / ms, 2),
+                                      "kernel": xp.xp_describe_config(3, "bf16", xp.xp_last_config(3, "bf16"))}
+        del Qs, Ks, Vs, Os
         out["other_workloads"] = side
 
     # ---- CPU oracle on a bounded sample of the main workload (reported baseline, not the target)

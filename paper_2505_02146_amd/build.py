@@ -14,11 +14,14 @@ OBJ = HERE / "_build"
 SOURCES = ["xp_api.hip", "xp_generic.hip", "xp_mfma_f32.hip", "xp_mfma_kc.hip", "xp_mfma_dl.hip", "xp_mfma_oc.hip", "xp_mfma_sk.hip", "xp_mfma_pp.hip", "xp_attention.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", str(INCLUDE), "-I", str(CSRC),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+# The attention kernel rescales its MFMA accumulators with vector arithmetic in every step: keep
+# them in ordinary vector registers instead of moving them to and from the accumulation registers.
+EXTRA_FLAGS = {"xp_attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _compile(src: str) -> str:
     obj = OBJ / (src + ".o")
-    cmd = ["hipcc", *FLAGS, "-c", str(CSRC / src), "-o", str(obj)]
+    cmd = ["hipcc", *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", str(CSRC / src), "-o", str(obj)]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

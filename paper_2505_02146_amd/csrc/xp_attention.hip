@@ -105,16 +105,24 @@ __global__ __launch_bounds__(64) void attn_general_kernel(AttnParams p)
 // and the lane's probabilities of two key blocks are exactly the 8 values the B operand of
 //   O^T = V^T P^T      (A = V^T from LDS, B = P^T from registers)
 // needs, if the 32 keys of one k step are numbered: slot 8*g + e  <->  key 4*g + e (e < 4),
-// key 16 + 4*g + (e - 4) (e >= 4).  V is staged to LDS as words {V[2kp][x], V[2kp+1][x]} (key-pair
-// major), so a lane gathers its 8 keys of column x with four 32-bit reads that follow the same
-// numbering.  O^T comes out with the query in l%16 again, so the running rescale factor applies
-// without any exchange, and a lane ends up with 4 consecutive output columns: one 16-byte store.
+// key 16 + 4*g + (e - 4) (e >= 4).  V is staged to LDS column-major as words {V[2kp][x], V[2kp+1][x]}
+// (two keys of one output column), the 16 words of a column and k step ordered so that the four
+// words a lane needs (its 8 keys of column x in the numbering above) are one aligned 16-byte group:
+// one 128-bit read per operand.  O^T comes out with the query in l%16 again, so the running
+// rescale factor applies without any exchange, and a lane ends up with 4 consecutive output
+// columns: one 16-byte store.
 constexpr int HD = 64;                                  // head size (Q/K and V)
 constexpr int BQ = 64, BK = 64;                         // queries per workgroup, keys per step
 constexpr int KROW = HD * 2;                            // bytes per K row in LDS (swizzled 16-byte chunks)
 constexpr int K_TILE = BK * KROW;
-constexpr int VPITCH = HD * 4 + 32;                     // bytes per key-pair row of V: 4 lane groups hit disjoint banks
-constexpr int V_TILE = (BK / 2) * VPITCH;
+// V tile in LDS: column x at x*VPITCH, 8 groups of 16 bytes (k step h, lane group g -> group 4h+g),
+// the group index XORed with vswz(x).  Pitch and swizzle were found by exhaustive search against
+// the measured pass grouping of 128-bit LDS reads: fragment reads and staging writes are both
+// free of bank conflicts.
+constexpr int VPITCH = 144;
+constexpr int V_TILE = HD * VPITCH;
+__device__ __forceinline__ int vswz(int x) { return (((x >> 2) ^ (x >> 3)) & 1) | (((x >> 4) & 3) << 1); }
+constexpr float TAU = 8.0f;                             // the reference maximum may lag by this much (log2 units)
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes)
 {
@@ -141,10 +149,20 @@ __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// s_waitcnt immediate for "vmcnt <= n and lgkmcnt == 0" (gfx9 encoding, expcnt left open)
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4); }
+
+// D = prefetch distance in key tiles.  Tile t+D is requested at the top of step t: its K rows go
+// straight into the LDS buffer that step t-1 read (a ring of D+1 buffers), its V rows into one of
+// D register sets, which is interleaved into LDS D-1 steps later, at the end of step t+D-1.  Every
+// wave issues exactly 4 loads per step (tiles past the end are out of range: zeros, no memory
+// touched), so "at most 4*(D-1) loads outstanding" means that tile t+1 has landed.
+template <int D>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
 {
-    __shared__ __attribute__((aligned(1024))) char lds[2 * K_TILE + 2 * V_TILE];
-    char *const ks = lds, *const vs = lds + 2 * K_TILE;
+    constexpr int NS = D + 1;
+    __shared__ __attribute__((aligned(1024))) char lds[NS * (K_TILE + V_TILE)];
+    char *const ks = lds, *const vs = lds + NS * K_TILE;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -169,54 +187,63 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
     // row l/8, position l%8 and fetches the chunk whose swizzled position that is
     const int krow = lane >> 3;
     const int kchunk = ((lane & 7) ^ (krow & 6)) << 4;   // rows of a load start at multiples of 8: the swizzle term is the lane's
-    auto issue_k = [&](int j0, int buf) {
+    auto issue_k = [&](int j0, int koff) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int blk = wave * 2 + i;
             const unsigned off = (unsigned)((j0 + blk * 8 + krow) * p.ldk) + kchunk;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void *)(ks + buf * K_TILE + blk * 1024), 16, off, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void *)(ks + koff + blk * 1024), 16, off, 0, 0, 0);
         }
     };
-    // V tile: thread t takes key pair t/8 and output columns 8*(t%8) .. +8
+    // V tile: thread t takes key pair t/8 (rows 2kp, 2kp+1) and output columns 8*(t%8) .. +8
     const int vkp = tid >> 3, vc = tid & 7;
-    u32x4 v0, v1;
-    auto load_v = [&](int j0) {
-        v0 = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp) * p.ldv) + vc * 16, 0, 0);
-        v1 = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp + 1) * p.ldv) + vc * 16, 0, 0);
+    u32x4 vr[D][2];
+    auto load_v = [&](int j0, u32x4 (&v)[2]) {
+        v[0] = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp) * p.ldv) + vc * 16, 0, 0);
+        v[1] = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp + 1) * p.ldv) + vc * 16, 0, 0);
     };
-    auto store_v = [&](int buf) {
-        u32x4 lo, hi;                                    // 8 words {V[2kp][x], V[2kp+1][x]}
+    // where the pair lands inside a column: group (k step, lane group), word slot
+    const int vk2 = vkp & 15;
+    const int vgrp = (vkp >> 4) * 4 + ((vk2 & 7) >> 1), vslot = (vk2 >> 3) * 2 + (vk2 & 1);
+    // vswz(8*vc + e) is vc for e < 4 and vc ^ 1 for e >= 4
+    const int vw0 = 8 * vc * VPITCH + ((vgrp ^ vc) << 4) + vslot * 4;
+    const int vw1 = 8 * vc * VPITCH + ((vgrp ^ vc ^ 1) << 4) + vslot * 4;
+    auto store_v = [&](int voff, const u32x4 (&v)[2]) {
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            lo[2 * e] = (v0[e] & 0xffffu) | (v1[e] << 16);
-            lo[2 * e + 1] = (v0[e] >> 16) | (v1[e] & 0xffff0000u);
-            hi[2 * e] = (v0[e + 2] & 0xffffu) | (v1[e + 2] << 16);
-            hi[2 * e + 1] = (v0[e + 2] >> 16) | (v1[e + 2] & 0xffff0000u);
+        for (int e = 0; e < 8; ++e) {                    // word {V[2kp][x], V[2kp+1][x]} of column x = 8*vc + e
+            const unsigned w = __builtin_amdgcn_perm(v[1][e >> 1], v[0][e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
+            *(unsigned *)(vs + voff + (e < 4 ? vw0 : vw1) + e * VPITCH) = w;
         }
-        char *dst = vs + buf * V_TILE + vkp * VPITCH + vc * 32;
-        *(u32x4 *)dst = lo;
-        *(u32x4 *)(dst + 16) = hi;
     };
+    // fragment of column block x, k step h: column 16x + r, group (4h + g) ^ vswz(16x + r)
+    const int vsr = ((r >> 2) ^ (r >> 3)) & 1;
+    const int vf0 = r * VPITCH + ((g ^ vsr) << 4), vf1 = r * VPITCH + ((g ^ vsr ^ 2) << 4);   // x even / odd
 
     const float c = p.scale * LOG2E;                     // scores are kept in units of log2
-    float top = -INFINITY, total = 0.0f;                 // total: this lane's share of the query's sum
+    float top = -INFINITY;
+    f32x4 total = {0.0f, 0.0f, 0.0f, 0.0f};              // running sum of the query's probabilities (4 copies)
+    const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};   // bf16 1.0 x 8
     f32x4 acc[4];
 #pragma unroll
     for (int x = 0; x < 4; ++x) acc[x] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     const int NT = (p.Lk + BK - 1) / BK;
-    issue_k(0, 0);
-    load_v(0);
-    store_v(0);
-    __builtin_amdgcn_s_waitcnt(0x0070);                  // vmcnt(0) and lgkmcnt(0)
+#pragma unroll
+    for (int u = 0; u < D; ++u) {
+        issue_k(u * BK, u * K_TILE);
+        load_v(u * BK, vr[u]);
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(4 * (D - 1)));   // tile 0 (and the queries) have landed
+    store_v(0, vr[0]);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(4 * (D - 1)));
     wg_barrier();
 
-    for (int t = 0; t < NT; ++t) {
-        const int buf = t & 1, j0 = t * BK;
-        if (t + 1 < NT) {                                // uniform
-            issue_k(j0 + BK, buf ^ 1);
-            load_v(j0 + BK);
-        }
+    int cur = 0;                                         // ring slot of the tile being multiplied
+    auto step = [&](int t, u32x4 (&v_in)[2], const u32x4 (&v_out)[2]) {
+        const int j0 = t * BK;
+        const int prev = cur == 0 ? NS - 1 : cur - 1, next = cur == NS - 1 ? 0 : cur + 1;
+        issue_k(j0 + D * BK, prev * K_TILE);             // slot read one barrier ago
+        load_v(j0 + D * BK, v_in);
         // S^T: 4 blocks of 16 keys
         f32x4 s[4];
 #pragma unroll
@@ -225,62 +252,80 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
             const int row = kb * 16 + r;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const u32x4 kf = *(const u32x4 *)(ks + buf * K_TILE + row * KROW + (((4 * h + g) ^ (row & 6)) << 4));
+                const u32x4 kf = *(const u32x4 *)(ks + cur * K_TILE + row * KROW + (((4 * h + g) ^ (row & 6)) << 4));
                 s[kb] = mma(kf, qf[h], s[kb]);
             }
         }
-        // scale; keys past the end count as minus infinity (only the last tile can hold any)
-        float mx = -INFINITY;
-        const bool ragged = j0 + BK > p.Lk;
+        // keys past the end count for nothing (only the last tile can hold any): the raw score is set
+        // so that its scaled value is minus infinity
+        if (j0 + BK > p.Lk) {
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb)
+            for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                float z = s[kb][v] * c;
-                if (ragged && j0 + kb * 16 + 4 * g + v >= p.Lk) z = -INFINITY;
-                s[kb][v] = z;
-                mx = fmaxf(mx, z);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float new_top = fmaxf(top, mx);            // finite: every tile holds at least one key
-        const float shrink = __builtin_amdgcn_exp2f(top - new_top);
-        top = new_top;
-        total *= shrink;
+                for (int v = 0; v < 4; ++v)
+                    if (j0 + kb * 16 + 4 * g + v >= p.Lk) s[kb][v] = c < 0.0f ? INFINITY : -INFINITY;
+        }
+        // largest scaled score of the tile: the extreme raw score times c (c may be negative)
+        float mx = s[0][0];
+        if (c >= 0.0f) {
 #pragma unroll
-        for (int x = 0; x < 4; ++x) acc[x] *= shrink;
-        // probabilities, rounded to bf16 for the second contraction; the sum uses the rounded values
+            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i >> 2][i & 3]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+        } else {
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = fminf(mx, s[i >> 2][i & 3]);
+            mx = fminf(mx, __shfl_xor(mx, 16));
+            mx = fminf(mx, __shfl_xor(mx, 32));
+        }
+        // The reference maximum `top` only has to keep exp2() in range, the quotient does not depend
+        // on it: it is moved (and the sums rescaled) only when some query of the wave would otherwise
+        // exceed it by more than TAU, which after the first tile is rare.
+        const float cand = mx * c;                       // finite: every tile holds at least one key
+        if (__builtin_amdgcn_ballot_w64(cand > top + TAU) != 0) {
+            const float new_top = fmaxf(top, cand);
+            const float shrink = __builtin_amdgcn_exp2f(top - new_top);
+            top = new_top;
+            total *= shrink;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) acc[x] *= shrink;
+        }
+        // probabilities exp2(c*s - top), rounded to bf16 for the second contraction
         u32x4 pf[2];
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb) {
-            const unsigned w0 = pack_bf16(__builtin_amdgcn_exp2f(s[kb][0] - top), __builtin_amdgcn_exp2f(s[kb][1] - top));
-            const unsigned w1 = pack_bf16(__builtin_amdgcn_exp2f(s[kb][2] - top), __builtin_amdgcn_exp2f(s[kb][3] - top));
-            total += __uint_as_float(w0 << 16) + __uint_as_float(w0 & 0xffff0000u) + __uint_as_float(w1 << 16) +
-                     __uint_as_float(w1 & 0xffff0000u);
-            pf[kb >> 1][(kb & 1) * 2] = w0;
-            pf[kb >> 1][(kb & 1) * 2 + 1] = w1;
+            pf[kb >> 1][(kb & 1) * 2] = pack_bf16(__builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][0], c, -top)),
+                                                  __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][1], c, -top)));
+            pf[kb >> 1][(kb & 1) * 2 + 1] = pack_bf16(__builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][2], c, -top)),
+                                                      __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][3], c, -top)));
         }
-        // O^T += V^T P^T: 4 blocks of 16 output columns, 2 k steps of 32 keys
+        // O^T += V^T P^T: 4 blocks of 16 output columns, 2 k steps of 32 keys; a block of ones in
+        // place of V^T yields the row sums of the rounded probabilities, for every lane of the query
+#pragma unroll
+        for (int h = 0; h < 2; ++h) total = mma(ones, pf[h], total);
 #pragma unroll
         for (int x = 0; x < 4; ++x)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const char *src = vs + buf * V_TILE + (16 * h + 2 * g) * VPITCH + (x * 16 + r) * 4;
-                u32x4 vf;
-                vf[0] = *(const unsigned *)src;
-                vf[1] = *(const unsigned *)(src + VPITCH);
-                vf[2] = *(const unsigned *)(src + 8 * VPITCH);
-                vf[3] = *(const unsigned *)(src + 9 * VPITCH);
+                const int grp_hi = (4 * h) ^ ((2 * x) & 4);
+                const u32x4 vf = *(const u32x4 *)(vs + cur * V_TILE + ((x & 1) ? vf1 : vf0) + 16 * x * VPITCH + grp_hi * 16);
                 acc[x] = mma(vf, pf[h], acc[x]);
             }
-        if (t + 1 < NT) store_v(buf ^ 1);                // the buffers read one barrier ago
-        __builtin_amdgcn_s_waitcnt(0x0070);
+        store_v(next * V_TILE, v_out);                   // tile t+1, into a slot last read D barriers ago
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(4 * (D - 1)));
         wg_barrier();
+        cur = next;
+    };
+    for (int t0 = 0; t0 < NT; t0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            if (t0 + u >= NT) break;                     // uniform over the workgroup
+            step(t0 + u, vr[u], vr[(u + 1) % D]);
+        }
     }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
 
-    total += __shfl_xor(total, 16);
-    total += __shfl_xor(total, 32);
-    const float inv = 1.0f / total;
+    const float inv = 1.0f / total[0];
     const int q = q0 + wave * 16 + r;
     if (q < p.Lq) {
         float *dst = p.O + b * p.strideO + (long long)q * p.ldo + 4 * g;
@@ -320,39 +365,47 @@ hipError_t general_launch(const AttnProblem &q)
 bool mfma_can_run(const AttnProblem &q)
 {
     if (q.in_type != XP_BF16 || q.d != HD || q.dv != HD) return false;
+    if (q.scale == 0.0f) return false;                   // the kernel masks absent keys by an infinite raw score times the scale
     if (q.batch > 65535 || q.Lq > 0x3fffffffLL || q.Lk > 0x3fffffffLL) return false;
     const void *ptrs[3] = {q.Q, q.K, q.V};
     const int64_t lds_[3] = {q.ldq, q.ldk, q.ldv}, strides[3] = {q.strideQ, q.strideK, q.strideV};
     const int64_t rows[3] = {q.Lq, q.Lk, q.Lk};
     for (int i = 0; i < 3; ++i) {
         if (((uintptr_t)ptrs[i] % 16) != 0 || (lds_[i] * 2) % 16 != 0 || (strides[i] * 2) % 16 != 0) return false;
-        if ((rows[i] + BK) * lds_[i] * 2 >= 0x7fffffffLL) return false;     // 32-bit byte offsets within one problem
+        if ((rows[i] + 4 * BK) * lds_[i] * 2 >= 0x7fffffffLL) return false;  // 32-bit byte offsets, prefetch past the end included
     }
     if (((uintptr_t)q.O % 16) != 0 || (q.ldo * 4) % 16 != 0 || (q.strideO * 4) % 16 != 0) return false;
     return true;
 }
 
+template <int D>
 hipError_t mfma_launch(const AttnProblem &q)
 {
     AttnParams p = params_elements(q);
     p.ldq *= 2; p.ldk *= 2; p.ldv *= 2;                  // bytes
     p.strideQ *= 2; p.strideK *= 2; p.strideV *= 2;
     const dim3 grid((unsigned)((q.Lq + BQ - 1) / BQ), (unsigned)q.batch);
-    hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, q.stream, p);
+    hipLaunchKernelGGL(attn_mfma_kernel<D>, grid, dim3(256), 0, q.stream, p);
     return hipGetLastError();
 }
 
 const AttnVariant kGeneral = {"general attention one wave per query valu", general_can_run, general_launch};
-const AttnVariant kMfma64 = {"bf16 attention head 64, 64 queries x 64-key steps, waves 4x1 mfma16", mfma_can_run, mfma_launch};
+const AttnVariant kMfma64d1 = {"bf16 attention head 64, 64 queries x 64-key steps, prefetch 1, waves 4x1 mfma16", mfma_can_run,
+                               mfma_launch<1>};
+const AttnVariant kMfma64d2 = {"bf16 attention head 64, 64 queries x 64-key steps, prefetch 2, waves 4x1 mfma16", mfma_can_run,
+                               mfma_launch<2>};
+// swept on the 96 x 512 x 512 x 64 workload: a prefetch distance of 1 is as fast as 2 (the step is bound
+// by its own dependency chain, not by load latency) and leaves more LDS free; 3 is slower
+const AttnVariant *const kBf16Table[] = {&kGeneral, &kMfma64d2, &kMfma64d1};   // the last that can run is the default
 
 }  // namespace
 
-int attn_num_variants(xp_dtype in_type) { return in_type == XP_BF16 ? 2 : (in_type == XP_F32 ? 1 : 0); }
+int attn_num_variants(xp_dtype in_type) { return in_type == XP_BF16 ? 3 : (in_type == XP_F32 ? 1 : 0); }
 
 const AttnVariant *attn_variant(xp_dtype in_type, int idx)
 {
     if (idx < 0 || idx >= attn_num_variants(in_type)) return nullptr;
-    return idx == 0 ? &kGeneral : &kMfma64;
+    return in_type == XP_BF16 ? kBf16Table[idx] : &kGeneral;
 }
 
 }  // namespace xp

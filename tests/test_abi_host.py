@@ -159,6 +159,19 @@ def test_attention_variant_table(lib):
     assert lib.xp_last_config(xp.XP_OP_ATTENTION, xp.XP_I8) == -1
 
 
+def test_entry_points_resolve_their_builders():
+    # build() compiles for minutes, so it is not run here; what broke once is the lookup of the
+    # oracle's build module behind the package attribute of the same name
+    import importlib
+    import inspect
+    entry = importlib.import_module("__graft_entry__")
+    assert callable(entry.build) and callable(entry.smoke)
+    assert inspect.ismodule(importlib.import_module("oracle.build"))
+    assert callable(importlib.import_module("oracle.build").build)
+    assert callable(importlib.import_module("paper_2505_02146_amd.build").build)
+    assert 'import_module("oracle.build")' in inspect.getsource(entry.build)
+
+
 def test_status_strings(lib):
     from paper_2505_02146_amd import xp
     seen = {xp.status_string(i) for i in range(8)}
