@@ -205,6 +205,26 @@ def main() -> int:
                                       "vs_two_batched_gemm_stages_without_softmax": round(unfused / ms, 2),
                                       "kernel": xp.xp_describe_config(3, "bf16", xp.xp_last_config(3, "bf16"))}
         del Qs, Ks, Vs, Os
+        # matrix-vector product: one pass over a 134 MB matrix, HBM-cold by rotation
+        wv = inputs.workload("gemv_bf16_8192")
+        mv, kv = wv["M"], wv["K"]
+        alg_bytes = mv * kv * 2 + kv * 2 + mv * 4
+        sets = 5
+        Av = [dev(wv["A"].reshape(-1)) for _ in range(sets)]
+        xv = dev(wv["B"].reshape(-1))
+        yv = torch.empty((mv,), dtype=torch.float32, device="cuda")
+        it = {"i": 0}
+
+        def call_gemv():
+            i = it["i"] % sets
+            it["i"] += 1
+            xp.xp_gemm(mv, 1, kv, 1.0, Av[i], "row", kv, xv, "col", kv, 0.0, yv, "row", 1, a_type="bf16", b_type="bf16")
+        ms, _ = _time_calls(torch, call_gemv, steps2 * 2, warm2)
+        side["gemv_bf16_8192"] = {"ms": round(ms, 5), "GB/s": round(alg_bytes / (ms * 1e-3) / 1e9, 1),
+                                  "pct_hbm_peak": round(100 * alg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 2),
+                                  "buffers": f"{sets} rotating matrices (HBM-cold)",
+                                  "kernel": xp.xp_describe_config(0, "bf16", xp.xp_last_config(0, "bf16"))}
+        del Av, xv, yv
         out["other_workloads"] = side
 
     # ---- CPU oracle on a bounded sample of the main workload (reported baseline, not the target)

@@ -30,7 +30,9 @@ void build_tables()
             n += oc_variants(types[s], g_table[s] + n);
             n += sk_variants(types[s], g_table[s] + n);
             n += pp_variants(types[s], g_table[s] + n);
+            n += dl_asym_variants(types[s], g_table[s] + n);
         }
+        n += gemv_variants(types[s], g_table[s] + n);
         g_count[s] = n;
     }
 }
@@ -201,6 +203,17 @@ xp_status gemm_common(xp_op op, int64_t batch, int64_t M, int64_t N, int64_t K, 
         q.A = B; q.a_sm = b_sn; q.a_sk = b_sk;
         q.B = A; q.b_sk = a_sk; q.b_sn = a_sm;
         q.strideA = strideB; q.strideB = strideA;
+    }
+    if (q.M == 1 && q.N > 1) {
+        // a row vector times a matrix is the transposed matrix-vector product: y^T = B^T x^T, with the
+        // 1 x N row of C seen as an N x 1 column of unit pitch
+        const void *t = q.A; q.A = q.B; q.B = t;
+        const int64_t sm = q.b_sn, sk = q.b_sk;
+        q.b_sk = q.a_sk; q.b_sn = q.a_sm;
+        q.a_sm = sm; q.a_sk = sk;
+        const int64_t st = q.strideA; q.strideA = q.strideB; q.strideB = st;
+        q.M = q.N; q.N = 1;
+        q.ldc = 1;
     }
     return run(q);
 }

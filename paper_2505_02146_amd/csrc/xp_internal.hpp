@@ -67,6 +67,8 @@ int dl_variants(xp_dtype in_type, const Variant **out);
 int oc_variants(xp_dtype in_type, const Variant **out);
 int sk_variants(xp_dtype in_type, const Variant **out);
 int pp_variants(xp_dtype in_type, const Variant **out);
+int dl_asym_variants(xp_dtype in_type, const Variant **out);
+int gemv_variants(xp_dtype in_type, const Variant **out);
 
 // Run-time estimate (microseconds) shared by the MFMA variants' cost functions, used only for shapes
 // that are not in the table of swept winners.  conc = workgroups that fit one compute unit;

@@ -50,9 +50,14 @@ struct DlParams {
     int H, W, Cin_b, S, PQ, Q, sh, sw, ph, pw;
 };
 
-template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_, bool SPREAD_ = false, int OCC_ = 1, int MF_ = 32, bool NT_ = false>
+template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_, bool SPREAD_ = false, int OCC_ = 1, int MF_ = 32, bool NT_ = false,
+          int NSA_ = NS_>
 struct DlTile {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NS = NS_, RB = RB_;
+    // ring depth of the A buffers (NS is that of the B buffers): one more A buffer than B buffers
+    // gives the A loads an extra K step to land where LDS cannot hold a third whole stage
+    static constexpr int NSA = NSA_;
+    static constexpr bool ASYM = NSA_ != NS_;
     static constexpr bool NTSTORE = NT_;                 // non-temporal stores of C
     static constexpr int OCC = OCC_;                     // waves per SIMD the register budget must allow
     static constexpr bool SPREAD = SPREAD_;             // issue a step's loads a share per MFMA sub-step
@@ -69,13 +74,17 @@ struct DlTile {
     static constexpr int BMP = (BM + RPI * NWAVE - 1) / (RPI * NWAVE) * (RPI * NWAVE);
     static constexpr int BNP = (BN + RPI * NWAVE - 1) / (RPI * NWAVE) * (RPI * NWAVE);
     static constexpr int IA = BMP / RPI / NWAVE, IB = BNP / RPI / NWAVE;   // loads per wave and step
-    static constexpr int STAGE = (BMP + BNP) * RB;
-    static constexpr int LDS = NS * STAGE;
+    static constexpr int A_BYTES = BMP * RB, B_BYTES = BNP * RB;   // one buffer of each ring
+    static constexpr int B_BASE = NSA * A_BYTES;                   // the B ring follows the A ring
+    static constexpr int LDS = NSA * A_BYTES + NS * B_BYTES;
+    // loads of this wave that may still be in flight when the loads of the next K step must have landed
+    static constexpr int PENDING = ASYM ? IA + (NS - 2) * (IA + IB) : (NS - 2) * (IA + IB);
     static_assert(RB == 64 || RB == 128, "row bytes");
     static_assert(MF == 32 || MF == 16, "MFMA shape");
     static_assert(WTM % MF == 0 && WTN % MF == 0, "wave sub-tile must be whole MFMA blocks");
     static_assert(PH >= 1, "a K step must hold at least one MFMA sub-step");
-    static_assert(NS >= 2 && (NS - 2) * (IA + IB) <= 63, "vmcnt is a 6-bit counter");
+    static_assert(NS >= 2 && NSA >= NS && NSA <= NS + 1 && PENDING <= 63, "ring depths; vmcnt is a 6-bit counter");
+    static_assert(!ASYM || !SPREAD_, "spread issue is for equal ring depths");
     static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
     static_assert(!SPREAD || NS >= 3, "with two buffers the loads of a step must all be issued at its start");
 };
@@ -177,7 +186,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
 
     // load slots: slot i of this wave fills the 1024 LDS bytes of row block (wave + i*NWAVE);
     // lane l lands at row l/CPR, position l%CPR, and fetches the chunk that belongs there
-    unsigned a_off[T::IA], b_off[T::IB];
+    unsigned a_off_g[T::IA], b_off_g[T::IB];            // byte offsets of this lane's chunks in global memory
     int a_cb[T::IA], b_cb[T::IB];                       // byte offset of the fetched chunk within the row
     int a_h0[CONV ? T::IA : 1], a_w0[CONV ? T::IA : 1];
 #pragma unroll
@@ -191,21 +200,21 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
                 const int op = pq / p.Q, oq = pq % p.Q;
                 a_h0[i] = op * p.sh - p.ph;
                 a_w0[i] = oq * p.sw - p.pw;
-                a_off[i] = (unsigned)n * (unsigned)(p.H * p.W) * (unsigned)p.Cin_b + a_cb[i];
+                a_off_g[i] = (unsigned)n * (unsigned)(p.H * p.W) * (unsigned)p.Cin_b + a_cb[i];
             } else {
                 a_h0[i] = -0x40000000;                  // never inside the image
                 a_w0[i] = 0;
-                a_off[i] = 0;
+                a_off_g[i] = 0;
             }
         } else {
-            a_off[i] = (unsigned)(row * p.lda_b) + a_cb[i];
+            a_off_g[i] = (unsigned)(row * p.lda_b) + a_cb[i];
         }
     }
 #pragma unroll
     for (int i = 0; i < T::IB; ++i) {
         const int row = (wave + i * T::NWAVE) * T::RPI + lane / T::CPR;
         b_cb[i] = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
-        b_off[i] = (unsigned)(row * p.ldb_b) + b_cb[i];
+        b_off_g[i] = (unsigned)(row * p.ldb_b) + b_cb[i];
     }
 
     // fragment reads: lane l reads row l % MF of an MF-row block, chunk (64/MF)*kk + l / MF
@@ -216,7 +225,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
     for (int kk = 0; kk < T::PH; ++kk) {
         const int c = (((64 / MF) * kk + fch) ^ fsw) << 4;
         fa[kk] = (wm * T::WTM + frow) * RB + c;
-        fb[kk] = T::BMP * RB + (wn * T::WTN + frow) * RB + c;
+        fb[kk] = (wn * T::WTN + frow) * RB + c;
     }
 
     AccT acc[T::MI][T::NI];
@@ -229,9 +238,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
 
     int tap_r = 0, tap_s = 0, c0_b = 0;                 // conv: K offset of the next step to load
 
-    // issue loads [lo, hi) of K step kt into LDS buffer `stage_off` (A slots first, then B slots)
+    // issue A loads [lo, hi) of K step kt into the A buffer at byte offset a_off; likewise for B
     constexpr int IT = T::IA + T::IB;
-    auto issue = [&](int kt, int stage_off, int lo, int hi) {
+    auto issue_a = [&](int kt, int a_off, int lo, int hi) {
         const int kb = kt * RB;
 #pragma unroll
         for (int i = 0; i < T::IA; ++i) {
@@ -241,26 +250,18 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
             if constexpr (CONV) {
                 const int h = a_h0[i] + tap_r, w = a_w0[i] + tap_s;
                 const bool ok = (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W;
-                off = ok ? a_off[i] + (unsigned)(h * p.W + w) * (unsigned)p.Cin_b : OOB;
+                off = ok ? a_off_g[i] + (unsigned)(h * p.W + w) * (unsigned)p.Cin_b : OOB;
                 soff = c0_b;
             } else {
-                off = a_off[i];
+                off = a_off_g[i];
                 soff = kb;
             }
             if (kb + a_cb[i] >= p.Kb) off = OOB;
-            lds_void *dst = (lds_void *)(lds + stage_off + (wave + i * T::NWAVE) * 1024);
+            lds_void *dst = (lds_void *)(lds + a_off + (wave + i * T::NWAVE) * 1024);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, dst, 16, off, soff, 0, 0);
         }
-#pragma unroll
-        for (int i = 0; i < T::IB; ++i) {
-            if (T::IA + i < lo || T::IA + i >= hi) continue;
-            unsigned off = b_off[i];
-            if (kb + b_cb[i] >= p.Kb) off = OOB;
-            lds_void *dst = (lds_void *)(lds + stage_off + T::BMP * RB + (wave + i * T::NWAVE) * 1024);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, dst, 16, off, kb, 0, 0);
-        }
         if constexpr (CONV) {
-            if (hi == IT) {                             // the step is fully issued: advance (tap, channel offset)
+            if (hi >= T::IA && lo < T::IA) {            // the step's A loads are all issued: advance (tap, channel offset)
                 c0_b += RB;
                 if (c0_b >= p.Cin_b) {
                     c0_b = 0;
@@ -269,11 +270,27 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
             }
         }
     };
-    auto read_frags = [&](int stage_off, int kk, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
+    auto issue_b = [&](int kt, int b_off, int lo, int hi) {
+        const int kb = kt * RB;
 #pragma unroll
-        for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(lds + stage_off + fa[kk] + i * MF * RB);
+        for (int i = 0; i < T::IB; ++i) {
+            if (i < lo || i >= hi) continue;
+            unsigned off = b_off_g[i];
+            if (kb + b_cb[i] >= p.Kb) off = OOB;
+            lds_void *dst = (lds_void *)(lds + b_off + (wave + i * T::NWAVE) * 1024);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, dst, 16, off, kb, 0, 0);
+        }
+    };
+    // loads [lo, hi) of the IA + IB that one K step issues when both rings have the same depth
+    auto issue = [&](int kt, int a_off, int b_off, int lo, int hi) {
+        issue_a(kt, a_off, lo, hi < T::IA ? hi : T::IA);
+        issue_b(kt, b_off, lo > T::IA ? lo - T::IA : 0, hi - T::IA);
+    };
+    auto read_frags = [&](int a_off, int b_off, int kk, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
 #pragma unroll
-        for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + stage_off + fb[kk] + j * MF * RB);
+        for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(lds + a_off + fa[kk] + i * MF * RB);
+#pragma unroll
+        for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + b_off + fb[kk] + j * MF * RB);
     };
     auto mma_all = [&](const u32x4 (&af)[T::MI], const u32x4 (&bf)[T::NI]) {
 #pragma unroll
@@ -288,28 +305,45 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
     };
 
     const int KT = p.KT;
-    constexpr int PENDING = (T::NS - 2) * (T::IA + T::IB);   // loads that may still be in flight at a barrier
+    constexpr int PENDING = T::PENDING;                  // loads that may still be in flight at a barrier
+    constexpr int A_END = T::NSA * T::A_BYTES, B_END = T::B_BASE + T::NS * T::B_BYTES;
     if (KT > 0) {
         u32x4 xa[T::MI], xb[T::NI], ya[T::MI], yb[T::NI];     // fragment sets of even / odd sub-steps
+        if constexpr (T::ASYM) {
+            // step j issues B(j+NS-1) and then A(j+NSA-1); the steps before the first one do the same
 #pragma unroll
-        for (int s = 0; s < T::NS - 1; ++s) issue(s, s * T::STAGE, 0, IT);
+            for (int j = -(T::NSA - 1); j < 0; ++j) {
+                if (j + T::NS - 1 >= 0) issue_b(j + T::NS - 1, T::B_BASE + (j + T::NS - 1) * T::B_BYTES, 0, T::IB);
+                issue_a(j + T::NSA - 1, (j + T::NSA - 1) * T::A_BYTES, 0, T::IA);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < T::NS - 1; ++s) issue(s, s * T::A_BYTES, T::B_BASE + s * T::B_BYTES, 0, IT);
+        }
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
         __builtin_amdgcn_s_barrier();
         // fragment sets alternate between sub-steps; `odd` says which set holds the sub-step that
         // is multiplied next (only for PH == 1 does it change from K step to K step)
-        read_frags(0, 0, xa, xb);
-        int cur = 0, fill = (T::NS - 1) * T::STAGE;
+        read_frags(0, T::B_BASE, 0, xa, xb);
+        int cur_a = 0, cur_b = T::B_BASE;
+        int fill_a = (T::NSA - 1) * T::A_BYTES, fill_b = T::B_BASE + (T::NS - 1) * T::B_BYTES;
         auto step = [&](int kt, auto odd_in) {
             constexpr bool ODD = decltype(odd_in)::value;   // set multiplied in sub-step 0: false = X, true = Y
-            const int nxt = cur + T::STAGE == T::LDS ? 0 : cur + T::STAGE;
-            // loads of step kt+NS-1 go into the buffer read in step kt-1
-            if constexpr (!T::SPREAD) issue(kt + T::NS - 1, fill, 0, IT);
+            const int nxt_a = cur_a + T::A_BYTES == A_END ? 0 : cur_a + T::A_BYTES;
+            const int nxt_b = cur_b + T::B_BYTES == B_END ? T::B_BASE : cur_b + T::B_BYTES;
+            // loads go into the buffers read in step kt-1
+            if constexpr (T::ASYM) {
+                issue_b(kt + T::NS - 1, fill_b, 0, T::IB);
+                issue_a(kt + T::NSA - 1, fill_a, 0, T::IA);
+            } else if constexpr (!T::SPREAD) {
+                issue(kt + T::NS - 1, fill_a, fill_b, 0, IT);
+            }
 #pragma unroll
             for (int ph = 0; ph < T::PH - 1; ++ph) {
-                if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill, ph * IT / T::PH, (ph + 1) * IT / T::PH);
+                if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill_a, fill_b, ph * IT / T::PH, (ph + 1) * IT / T::PH);
                 const bool cur_is_y = ((ph & 1) != 0) != ODD;
-                if (cur_is_y) read_frags(cur, ph + 1, xa, xb);
-                else read_frags(cur, ph + 1, ya, yb);
+                if (cur_is_y) read_frags(cur_a, cur_b, ph + 1, xa, xb);
+                else read_frags(cur_a, cur_b, ph + 1, ya, yb);
                 __builtin_amdgcn_sched_barrier(0);
                 if (cur_is_y) mma_all(ya, yb);
                 else mma_all(xa, xb);
@@ -319,16 +353,18 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
             constexpr bool LAST_IS_Y = (((T::PH - 1) & 1) != 0) != ODD;
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(T::SPREAD ? PENDING - (IT - (T::PH - 1) * IT / T::PH) : PENDING));
             __builtin_amdgcn_s_barrier();
-            if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill, (T::PH - 1) * IT / T::PH, IT);
-            // sub-step 0 of the next buffer (zeros after the last step, never multiplied)
-            if constexpr (LAST_IS_Y) read_frags(nxt, 0, xa, xb);
-            else read_frags(nxt, 0, ya, yb);
+            if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill_a, fill_b, (T::PH - 1) * IT / T::PH, IT);
+            // sub-step 0 of the next buffers (zeros after the last step, never multiplied)
+            if constexpr (LAST_IS_Y) read_frags(nxt_a, nxt_b, 0, xa, xb);
+            else read_frags(nxt_a, nxt_b, 0, ya, yb);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (LAST_IS_Y) mma_all(ya, yb);
             else mma_all(xa, xb);
             __builtin_amdgcn_sched_barrier(0);
-            fill = cur;
-            cur = nxt;
+            fill_a = cur_a;
+            fill_b = cur_b;
+            cur_a = nxt_a;
+            cur_b = nxt_b;
         };
         if constexpr (T::PH % 2 == 0) {
             for (int kt = 0; kt < KT; ++kt) step(kt, std::false_type{});
@@ -465,7 +501,27 @@ XP_DL_VARIANT(kI8Dl128x256r64n3s, "i8", true, 128, 256, 2, 2, 3, 64, true, " spr
 XP_DL_VARIANT(kI8Dl128x128r128n2, "i8", true, 128, 128, 2, 2, 2, 128, false, "", 2, 32, false, "", 0.32)
 XP_DL_VARIANT(kI8Dl128x128r64n4s, "i8", true, 128, 128, 2, 2, 4, 64, true, " spread", 2, 32, false, "", 0.40)
 
+// one more A buffer than B buffers: three A + two B buffers of 32 KB fill the 160 KB of LDS exactly
+#define XP_DL_ASYM_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, MF, EFF)                                                              \
+    bool NAME##_can(const Problem &q) { return dl_can_run_common<INT8>(q, BM, BN, 128); }                                            \
+    hipError_t NAME##_launch(const Problem &q) { return dl_launch<INT8, DlTile<BM, BN, WM, WN, 2, 128, false, 1, MF, false, 3>>(q); } \
+    double NAME##_cost(const Problem &q) { return dl_cost<DlTile<BM, BN, WM, WN, 2, 128, false, 1, MF, false, 3>>(q, EFF); }          \
+    const Variant NAME = {TYPESTR " " #BM "x" #BN "x128B waves " #WM "x" #WN " ring 3(A)+2(B) direct-to-lds mfma" #MF, NAME##_can, \
+                          NAME##_launch, NAME##_cost};
+
+XP_DL_ASYM_VARIANT(kBfDl256x256a3m16, "bf16", false, 256, 256, 2, 4, 16, 0.54)
+XP_DL_ASYM_VARIANT(kBfDl224x256a3m16, "bf16", false, 224, 256, 2, 4, 16, 0.49)
+XP_DL_ASYM_VARIANT(kI8Dl256x256a3m16, "i8", true, 256, 256, 2, 4, 16, 0.54)
+
 }  // namespace
+
+// Registered after every other family so that the older variants keep their indices.
+int dl_asym_variants(xp_dtype in_type, const Variant **out)
+{
+    if (in_type == XP_BF16) { out[0] = &kBfDl256x256a3m16; out[1] = &kBfDl224x256a3m16; return 2; }
+    if (in_type == XP_I8) { out[0] = &kI8Dl256x256a3m16; return 1; }
+    return 0;
+}
 
 int dl_variants(xp_dtype in_type, const Variant **out)
 {

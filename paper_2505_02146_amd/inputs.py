@@ -157,10 +157,16 @@ def workload(name: str, seed: int = 0) -> dict:
                     Q=to_bf16_bits(normal((b, L, d), seed, TID_A)),
                     K=to_bf16_bits(normal((b, L, d), seed, TID_B)),
                     V=to_bf16_bits(normal((b, L, d), seed, TID_C)))
+    if name == "gemv_bf16_8192":
+        # matrix-vector product: nothing is reused, the 134 MB matrix is read once
+        M = K = 8192
+        return dict(op="gemm", dtype="bf16", M=M, N=1, K=K, a_layout="row", b_layout="col",
+                    A=to_bf16_bits(normal((M, K), seed, TID_A)),
+                    B=to_bf16_bits(normal((1, K), seed, TID_B)))
     raise KeyError(name)
 
 
 WORKLOADS = ("gemm_f32_256", "gemm_bf16_4096", "gemm_i8_4096x4096x8192",
              "bgemm_bf16_qk", "bgemm_bf16_pv", "conv_bf16_56")
 # operators beyond the GEMM / convolution set, each served by its own entry point
-EXTRA_WORKLOADS = ("attention_bf16_512",)
+EXTRA_WORKLOADS = ("attention_bf16_512", "gemv_bf16_8192")
