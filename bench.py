@@ -24,9 +24,11 @@ PEAK_HBM_GBS = 8000.0
 
 # Bytes per launch between the L2s and the memory fabric, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs scaled by a plain 256 MiB copy (factors 2.00 and 1.00), see
-# profiles/dl_kernel_bf16_256x256_mfma16_gemm_4096.md.  Keyed by kernel variant: a different
-# kernel than the profiled one reports null.
-TRAFFIC_BYTES = {"bf16 256x256x128B waves 2x4 ring 2 direct-to-lds mfma16": 268.6e6}
+# profiles/dl_kernel_bf16_256x256_ring3a2b_mfma16_gemm_4096.md (and, for the two-buffer variant,
+# profiles/dl_kernel_bf16_256x256_mfma16_gemm_4096.md).  Keyed by kernel variant: a different
+# kernel than the profiled ones reports null.
+TRAFFIC_BYTES = {"bf16 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds mfma16": 268.7e6,
+                 "bf16 256x256x128B waves 2x4 ring 2 direct-to-lds mfma16": 268.6e6}
 
 
 def _time_calls(torch, fn, steps, warmup):
