@@ -48,6 +48,9 @@ struct DlParams {
     int tiles_m, tiles_n, group_m;
     unsigned in_bytes;                    // convolution view
     int H, W, Cin_b, S, PQ, Q, sh, sw, ph, pw;
+    // two-height launches: workgroups [0, n1) tile rows [0, m_split) with the first tile type,
+    // the rest tile rows [m_split, M) with the second
+    int n1, m_split, tiles_m2;
 };
 
 template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_, bool SPREAD_ = false, int OCC_ = 1, int MF_ = 32, bool NT_ = false,
@@ -149,13 +152,14 @@ template <> struct Acc<true, 16> {
     }
 };
 
+// One tile of C.  `bid` numbers the tiles of the row range [m_base, m_end) of the problem, which is
+// tiles_m tile-rows high; lds points at T::LDS bytes of shared memory.
 template <bool INT8, class T, bool CONV>
-__global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
+__device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, int m_base, int m_end, int tiles_m)
 {
     using AccT = typename Acc<INT8, T::MF>::type;
     constexpr int RB = T::RB, MF = T::MF;
     constexpr int NACC = MF == 32 ? 16 : 4;           // accumulator registers per lane and block
-    __shared__ __attribute__((aligned(1024))) char lds[T::LDS];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -163,17 +167,16 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
 
     // workgroup -> tile: one XCD (workgroup id mod 8) owns a run of consecutive tiles, walked in
     // groups of group_m tile-rows, so that the tiles sharing an L2 share A and B panels
-    int bid = blockIdx.x;
-    const int nb = p.tiles_m * p.tiles_n;
+    const int nb = tiles_m * p.tiles_n;
     if ((nb & 7) == 0) bid = (bid & 7) * (nb >> 3) + (bid >> 3);
     const int gsz = p.group_m * p.tiles_n;
     const int g = bid / gsz, first_m = g * p.group_m;
-    const int gm = min(p.tiles_m - first_m, p.group_m);
+    const int gm = min(tiles_m - first_m, p.group_m);
     const int tm = first_m + (bid % gsz) % gm, tn = (bid % gsz) / gm;
-    const int m0 = tm * T::BM, n0 = tn * T::BN;
+    const int m0 = m_base + tm * T::BM, n0 = tn * T::BN;
     const long long batch = blockIdx.y;
 
-    const int rows_a = min(p.M - m0, T::BM), rows_b = min(p.N - n0, T::BN);
+    const int rows_a = min(m_end - m0, T::BM), rows_b = min(p.N - n0, T::BN);
     __amdgpu_buffer_rsrc_t ra, rb;
     if constexpr (CONV) {
         ra = make_rsrc(p.A, p.in_bytes);
@@ -195,7 +198,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
         a_cb[i] = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
         if constexpr (CONV) {
             const int m = m0 + row;
-            if (m < p.M && row < T::BM) {
+            if (m < m_end && row < T::BM) {
                 const int n = m / p.PQ, pq = m % p.PQ;
                 const int op = pq / p.Q, oq = pq % p.Q;
                 a_h0[i] = op * p.sh - p.ph;
@@ -388,12 +391,31 @@ __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
 #pragma unroll
         for (int j = 0; j < T::NI; ++j) {
             if constexpr (MF == 32)
-                store_block32<INT8, T::NTSTORE>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 32, n0 + wn * T::WTN + j * 32, lane, p.M,
+                store_block32<INT8, T::NTSTORE>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 32, n0 + wn * T::WTN + j * 32, lane, m_end,
                                     p.N, p.alpha, p.beta);
             else
-                store_block16t<INT8, T::NTSTORE>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 16, n0 + wn * T::WTN + j * 16, lane, p.M,
+                store_block16t<INT8, T::NTSTORE>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 16, n0 + wn * T::WTN + j * 16, lane, m_end,
                                      p.N, p.alpha, p.beta);
         }
+}
+
+template <bool INT8, class T, bool CONV>
+__global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
+{
+    __shared__ __attribute__((aligned(1024))) char lds[T::LDS];
+    dl_body<INT8, T, CONV>(p, lds, blockIdx.x, 0, p.M, p.tiles_m);
+}
+
+// Two tile heights in one launch: full rounds of T1 tiles first, then one last round of the lower
+// T2 tiles, so that a grid that does not fill its last round of compute units wastes less of it
+// (workgroups start in index order: the T1 tiles occupy every compute unit before a T2 tile starts).
+template <bool INT8, class T1, class T2, bool CONV>
+__global__ __launch_bounds__(T1::NT, 1) void dl_kernel_two_heights(DlParams p)
+{
+    static_assert(T1::NT == T2::NT && T1::BN == T2::BN, "the two tile types share the workgroup shape and the tile width");
+    __shared__ __attribute__((aligned(1024))) char lds[T1::LDS > T2::LDS ? T1::LDS : T2::LDS];
+    if ((int)blockIdx.x < p.n1) dl_body<INT8, T1, CONV>(p, lds, blockIdx.x, 0, p.m_split, p.tiles_m);
+    else dl_body<INT8, T2, CONV>(p, lds, blockIdx.x - p.n1, p.m_split, p.M, p.tiles_m2);
 }
 
 // ------------------------------------------------------------------------------------ host side
@@ -426,7 +448,7 @@ bool dl_can_run_common(const Problem &q, int BM, int BN, int RB)
 }
 
 template <bool INT8, class T>
-hipError_t dl_launch(const Problem &q)
+DlParams dl_params(const Problem &q)
 {
     const int64_t esz = INT8 ? 1 : 2;
     DlParams p;
@@ -450,9 +472,46 @@ hipError_t dl_launch(const Problem &q)
         p.PQ = (int)(q.P * q.Q); p.Q = (int)q.Q;
         p.sh = (int)q.sh; p.sw = (int)q.sw; p.ph = (int)q.ph; p.pw = (int)q.pw;
     }
+    p.n1 = 0; p.m_split = 0; p.tiles_m2 = 0;
+    return p;
+}
+
+template <bool INT8, class T>
+hipError_t dl_launch(const Problem &q)
+{
+    const DlParams p = dl_params<INT8, T>(q);
     const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)q.batch);
     if (q.conv) hipLaunchKernelGGL((dl_kernel<INT8, T, true>), grid, dim3(T::NT), 0, q.stream, p);
     else hipLaunchKernelGGL((dl_kernel<INT8, T, false>), grid, dim3(T::NT), 0, q.stream, p);
+    return hipGetLastError();
+}
+
+// Rows [0, m_split) in whole rounds of T1 tiles over the 256 compute units, the rest in T2 tiles:
+// as few T1 rounds as leave a remainder that one round of T2 tiles covers.
+template <class T1, class T2>
+int64_t two_heights_split(const Problem &q)
+{
+    const int64_t tiles_n = (q.N + T1::BN - 1) / T1::BN;
+    const int64_t per_round = tiles_n >= 256 ? 1 : 256 / tiles_n;          // tile-rows that one round holds
+    const int64_t rows1 = per_round * T1::BM, cap2 = per_round * T2::BM;
+    if (q.M <= cap2) return 0;
+    const int64_t k = (q.M - cap2 + rows1 - 1) / rows1;
+    return k * rows1 < q.M ? k * rows1 : q.M;
+}
+
+template <bool INT8, class T1, class T2>
+hipError_t dl_launch_two_heights(const Problem &q)
+{
+    DlParams p = dl_params<INT8, T1>(q);
+    const int64_t split = two_heights_split<T1, T2>(q);
+    p.m_split = (int)split;
+    p.tiles_m = (int)(split / T1::BM);                    // split is a multiple of T1::BM or equals M
+    if (split % T1::BM != 0) p.tiles_m += 1;
+    p.tiles_m2 = (int)((q.M - split + T2::BM - 1) / T2::BM);
+    p.n1 = p.tiles_m * p.tiles_n;
+    const dim3 grid((unsigned)(p.n1 + p.tiles_m2 * p.tiles_n), (unsigned)q.batch);
+    if (q.conv) hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, true>), grid, dim3(T1::NT), 0, q.stream, p);
+    else hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, false>), grid, dim3(T1::NT), 0, q.stream, p);
     return hipGetLastError();
 }
 
@@ -513,12 +572,21 @@ XP_DL_ASYM_VARIANT(kBfDl256x256a3m16, "bf16", false, 256, 256, 2, 4, 16, 0.54)
 XP_DL_ASYM_VARIANT(kBfDl224x256a3m16, "bf16", false, 224, 256, 2, 4, 16, 0.49)
 XP_DL_ASYM_VARIANT(kI8Dl256x256a3m16, "i8", true, 256, 256, 2, 4, 16, 0.54)
 
+// 224-row tiles in whole rounds, a last round of 192-row tiles
+typedef DlTile<224, 256, 2, 4, 2, 128, false, 1, 16, false, 3> TwoHi;
+typedef DlTile<192, 256, 2, 4, 2, 128, false, 1, 16, false, 3> TwoLo;
+bool kBfDlTwoHeights_can(const Problem &q) { return dl_can_run_common<false>(q, 224, 256, 128); }
+hipError_t kBfDlTwoHeights_launch(const Problem &q) { return dl_launch_two_heights<false, TwoHi, TwoLo>(q); }
+double kBfDlTwoHeights_cost(const Problem &q) { return dl_cost<TwoHi>(q, 0.49); }
+const Variant kBfDlTwoHeights = {"bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 3(A)+2(B) direct-to-lds mfma16",
+                                 kBfDlTwoHeights_can, kBfDlTwoHeights_launch, kBfDlTwoHeights_cost};
+
 }  // namespace
 
 // Registered after every other family so that the older variants keep their indices.
 int dl_asym_variants(xp_dtype in_type, const Variant **out)
 {
-    if (in_type == XP_BF16) { out[0] = &kBfDl256x256a3m16; out[1] = &kBfDl224x256a3m16; return 2; }
+    if (in_type == XP_BF16) { out[0] = &kBfDl256x256a3m16; out[1] = &kBfDl224x256a3m16; out[2] = &kBfDlTwoHeights; return 3; }
     if (in_type == XP_I8) { out[0] = &kI8Dl256x256a3m16; return 1; }
     return 0;
 }

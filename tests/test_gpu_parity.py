@@ -305,3 +305,41 @@ def test_stream_argument_is_used(xp, oracle):
         xp.xp_gemm(M, N, K, 1.0, da, "row", K, db, "row", N, 0.0, c, "row", N)
     s.synchronize()
     check_float(c.cpu().numpy(), ref, "side stream")
+
+
+def _variant_named(xp, op, kind, fragment):
+    for v in range(xp.xp_num_configs(op, kind)):
+        if fragment in xp.xp_describe_config(op, kind, v):
+            return v
+    raise AssertionError(f"no variant named *{fragment}*")
+
+
+def test_two_tile_heights_in_one_launch(xp, oracle):
+    """Shapes whose rows spill over whole rounds of the tall tiles, so that both tile types of the
+    two-height kernel run in the same launch (GEMM: 2 rounds of 224-row tiles + 208 rows of 192-row
+    tiles with a ragged last tile; convolution: 1 round + 512 rows)."""
+    import torch
+    M, N, K = 2000, 16384, 136
+    A = _make("bf16", (M, K), 9, 1)
+    B = _make("bf16", (N, K), 9, 2)
+    v = _variant_named(xp, 0, "bf16", "then 192x256 in the last round")
+    xp.xp_force_config(0, "bf16", v)
+    c = torch.full((M, N), float("nan"), device="cuda")
+    xp.xp_gemm(M, N, K, 1.0, dev(A.reshape(-1)), "row", K, dev(B.reshape(-1)), "col", K, 0.0, c, "row", N,
+               a_type="bf16", b_type="bf16")
+    assert xp.xp_last_config(0, "bf16") == v
+    xp.xp_force_config(0, "bf16", -1)
+    check_float(c.cpu().numpy(), oracle.gemm_float(M, N, K, A.reshape(-1), "row", B.reshape(-1), "col"), "two heights gemm")
+
+    n, h, w_, ci, co = 4, 32, 32, 64, 4096
+    x = _make("bf16", (n, h, w_, ci), 9, 1)
+    f = _make("bf16", (co, 3, 3, ci), 9, 2)
+    v = _variant_named(xp, 2, "bf16", "then 192x256 in the last round")
+    xp.xp_force_config(2, "bf16", v)
+    out = torch.full((n, h, w_, co), float("nan"), device="cuda")
+    xp.xp_conv2d_nhwc(n, h, w_, ci, co, 3, 3, 1, 1, 1, 1, dev(x.reshape(-1)), dev(f.reshape(-1)), "krsc", out,
+                      in_type="bf16", w_type="bf16")
+    assert xp.xp_last_config(2, "bf16") == v
+    xp.xp_force_config(2, "bf16", -1)
+    check_float(out.cpu().numpy(), oracle.conv2d_nhwc(x, f, N=n, H=h, W=w_, Cin=ci, Cout=co, R=3, S=3, pad=(1, 1)),
+                "two heights conv")
