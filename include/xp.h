@@ -49,7 +49,8 @@ typedef enum {
     XP_ERR_ALIGN = 4,        /* pointer not aligned to its element size */
     XP_ERR_UNSUPPORTED = 5,  /* dtype / layout / alpha-beta combination not provided */
     XP_ERR_CONFIG = 6,       /* forced kernel configuration does not exist or cannot run this call */
-    XP_ERR_LAUNCH = 7        /* the HIP runtime refused the launch */
+    XP_ERR_LAUNCH = 7,       /* the HIP runtime refused the launch */
+    XP_ERR_WORKSPACE = 8     /* tuning workspace missing, not 256-byte aligned or too small; file not readable / writable */
 } xp_status;
 
 typedef enum { XP_F32 = 0, XP_BF16 = 1, XP_I8 = 2, XP_I32 = 3 } xp_dtype;
@@ -154,6 +155,68 @@ int xp_num_configs(xp_op op, xp_dtype in_type);
 xp_status xp_describe_config(xp_op op, xp_dtype in_type, int idx, char *buf, size_t n);
 xp_status xp_force_config(xp_op op, xp_dtype in_type, int idx);
 int xp_last_config(xp_op op, xp_dtype in_type);
+
+/*
+ * Run-time parameter search: the brute-force intra-pass auto-tuning of the paper (Section 5.1) with
+ * its reward (Eq. 3-4), inside the library.  xp_tune_* takes the arguments of the entry point it is
+ * named after plus a workspace, and
+ *   1. computes the call once with the general kernel into the workspace (the reference);
+ *   2. forces every variant that accepts the call in turn, into a second workspace copy of C, and
+ *      compares it with the reference on the device: a candidate is valid if every element is
+ *      finite and the relative Frobenius distance is <= 1e-5 (bit-exact for int8);
+ *   3. times each valid candidate (`reps` back-to-back launches between two events, after two
+ *      warm-up launches) and the three fastest twice more, in turn; reward = 1 / best time if
+ *      valid, else 0; the largest reward wins;
+ *   4. records the winner for the call's shape (operator, type, batch, M, N, K, which operands are
+ *      contiguous along K, and for a convolution its geometry), so that every later call of that
+ *      shape uses it (ahead of the built-in table), and computes C once more with the winner.
+ * The calls synchronise `stream` many times and are meant to be made once per shape, off the
+ * critical path.  C must hold valid input when beta != 0; it ends up holding the result.
+ *   workspace        DEVICE memory owned by the caller, 256-byte aligned, at least
+ *                    xp_tune_workspace_bytes(...) bytes; contents are scratch
+ *   reps             timed launches per candidate (>= 1)
+ *   best, best_us    if not NULL: index of the winning variant (see xp_describe_config) and its
+ *                    time per launch in microseconds (HOST pointers)
+ * Errors: those of the underlying entry point; XP_ERR_WORKSPACE; XP_ERR_SHAPE for reps < 1.
+ * A call with nothing to compute returns XP_OK and records nothing.
+ */
+xp_status xp_tune_gemm(int64_t M, int64_t N, int64_t K, float alpha,
+                       const void *A, xp_dtype a_type, xp_layout a_layout, int64_t lda,
+                       const void *B, xp_dtype b_type, xp_layout b_layout, int64_t ldb,
+                       float beta,
+                       void *C, xp_dtype c_type, xp_layout c_layout, int64_t ldc,
+                       void *workspace, size_t workspace_bytes, int reps, int *best, float *best_us,
+                       void *stream);
+xp_status xp_tune_gemm_batched(int64_t batch, int64_t M, int64_t N, int64_t K, float alpha,
+                               const void *A, xp_dtype a_type, xp_layout a_layout, int64_t lda, int64_t strideA,
+                               const void *B, xp_dtype b_type, xp_layout b_layout, int64_t ldb, int64_t strideB,
+                               float beta,
+                               void *C, xp_dtype c_type, xp_layout c_layout, int64_t ldc, int64_t strideC,
+                               void *workspace, size_t workspace_bytes, int reps, int *best, float *best_us,
+                               void *stream);
+xp_status xp_tune_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                              int64_t R, int64_t S, int64_t stride_h, int64_t stride_w,
+                              int64_t pad_h, int64_t pad_w,
+                              const void *input, xp_dtype in_type,
+                              const void *filter, xp_dtype w_type, xp_filter_layout w_layout,
+                              void *output, xp_dtype out_type,
+                              void *workspace, size_t workspace_bytes, int reps, int *best, float *best_us,
+                              void *stream);
+
+/* Workspace size for tuning a call whose output spans `c_extent` elements, i.e. from the first to
+ * the last element of C including pitch padding and batch gaps:
+ * (batch-1)*strideC + (rows-1)*ldc + cols for the stored orientation; N*P*Q*Cout for a convolution. */
+size_t xp_tune_workspace_bytes(int64_t c_extent);
+
+/* The table of tuned shapes.  xp_tune_save writes it as text (one shape per line, the variant by
+ * name, so that a file survives changes of the variant numbering); xp_tune_load merges a file into
+ * the table (later entries replace earlier ones; lines naming unknown variants are kept but have no
+ * effect until such a variant exists); xp_tune_clear empties it; xp_tune_count returns its size.
+ * Paths are HOST strings.  Thread-safe. */
+xp_status xp_tune_save(const char *path);
+xp_status xp_tune_load(const char *path);
+void xp_tune_clear(void);
+int xp_tune_count(void);
 
 /* Human-readable name of a status code (static storage). */
 const char *xp_status_string(xp_status s);

@@ -105,6 +105,8 @@ int tuned_variant(const Problem &q)
 
 int select_variant(const Problem &q)
 {
+    const int learned = runtime_tuned_variant(q);        // shapes tuned in this process or loaded from a file
+    if (learned >= 0) return learned;
     const int tuned = tuned_variant(q);
     if (tuned >= 0) return tuned;
     const int n = num_variants(q.in_type);
@@ -117,6 +119,15 @@ int select_variant(const Problem &q)
         if (c < best_cost) { best_cost = c; best = i; }
     }
     return best;
+}
+
+}  // namespace
+
+xp_status launch_variant(const Problem &q, int idx)
+{
+    const Variant *v = variant(q.in_type, idx);
+    if (!v || !v->can_run(q)) return XP_ERR_CONFIG;
+    return v->launch(q) == hipSuccess ? XP_OK : XP_ERR_LAUNCH;
 }
 
 xp_status run(const Problem &q)
@@ -137,6 +148,8 @@ xp_status run(const Problem &q)
     return v->launch(q) == hipSuccess ? XP_OK : XP_ERR_LAUNCH;
 }
 
+namespace {
+
 bool aligned_to(const void *p, int bytes) { return ((uintptr_t)p % (uintptr_t)bytes) == 0; }
 
 xp_status check_types(xp_dtype a, xp_dtype b, xp_dtype c, float alpha, float beta)
@@ -152,12 +165,17 @@ xp_status check_types(xp_dtype a, xp_dtype b, xp_dtype c, float alpha, float bet
 
 bool bad_layout(int l) { return l != XP_ROW && l != XP_COL; }
 
-xp_status gemm_common(xp_op op, int64_t batch, int64_t M, int64_t N, int64_t K, float alpha,
-                      const void *A, xp_dtype a_t, xp_layout a_l, int64_t lda, int64_t strideA,
-                      const void *B, xp_dtype b_t, xp_layout b_l, int64_t ldb, int64_t strideB,
-                      float beta, void *C, xp_dtype c_t, xp_layout c_l, int64_t ldc, int64_t strideC,
-                      void *stream)
+}  // namespace
+
+// Validation and canonicalisation of a (batched) GEMM call.  *nothing is set when the call is valid
+// but has no output element to compute.
+xp_status make_gemm_problem(xp_op op, int64_t batch, int64_t M, int64_t N, int64_t K, float alpha,
+                            const void *A, xp_dtype a_t, xp_layout a_l, int64_t lda, int64_t strideA,
+                            const void *B, xp_dtype b_t, xp_layout b_l, int64_t ldb, int64_t strideB,
+                            float beta, void *C, xp_dtype c_t, xp_layout c_l, int64_t ldc, int64_t strideC,
+                            void *stream, Problem *out, bool *nothing)
 {
+    *nothing = true;
     if (batch < 0 || M < 0 || N < 0 || K < 0) return XP_ERR_SHAPE;
     if (bad_layout(a_l) || bad_layout(b_l) || bad_layout(c_l)) return XP_ERR_UNSUPPORTED;
     xp_status ts = check_types(a_t, b_t, c_t, alpha, beta);
@@ -215,42 +233,37 @@ xp_status gemm_common(xp_op op, int64_t batch, int64_t M, int64_t N, int64_t K, 
         q.M = q.N; q.N = 1;
         q.ldc = 1;
     }
+    *out = q;
+    *nothing = false;
+    return XP_OK;
+}
+
+namespace {
+
+xp_status gemm_common(xp_op op, int64_t batch, int64_t M, int64_t N, int64_t K, float alpha,
+                      const void *A, xp_dtype a_t, xp_layout a_l, int64_t lda, int64_t strideA,
+                      const void *B, xp_dtype b_t, xp_layout b_l, int64_t ldb, int64_t strideB,
+                      float beta, void *C, xp_dtype c_t, xp_layout c_l, int64_t ldc, int64_t strideC,
+                      void *stream)
+{
+    Problem q;
+    bool nothing;
+    const xp_status st = make_gemm_problem(op, batch, M, N, K, alpha, A, a_t, a_l, lda, strideA, B, b_t, b_l, ldb, strideB,
+                                           beta, C, c_t, c_l, ldc, strideC, stream, &q, &nothing);
+    if (st != XP_OK || nothing) return st;
     return run(q);
 }
 
 }  // namespace
-}  // namespace xp
 
-using namespace xp;
-
-extern "C" {
-
-xp_status xp_gemm(int64_t M, int64_t N, int64_t K, float alpha,
-                  const void *A, xp_dtype a_type, xp_layout a_layout, int64_t lda,
-                  const void *B, xp_dtype b_type, xp_layout b_layout, int64_t ldb,
-                  float beta, void *C, xp_dtype c_type, xp_layout c_layout, int64_t ldc, void *stream)
+// Validation and canonicalisation of a convolution call (see make_gemm_problem).
+xp_status make_conv_problem(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                            int64_t R, int64_t S, int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                            const void *input, xp_dtype in_type, const void *filter, xp_dtype w_type,
+                            xp_filter_layout w_layout, void *output, xp_dtype out_type, void *stream,
+                            Problem *out, bool *nothing)
 {
-    return gemm_common(XP_OP_GEMM, 1, M, N, K, alpha, A, a_type, a_layout, lda, 0, B, b_type, b_layout, ldb, 0,
-                       beta, C, c_type, c_layout, ldc, 0, stream);
-}
-
-xp_status xp_gemm_batched(int64_t batch, int64_t M, int64_t N, int64_t K, float alpha,
-                          const void *A, xp_dtype a_type, xp_layout a_layout, int64_t lda, int64_t strideA,
-                          const void *B, xp_dtype b_type, xp_layout b_layout, int64_t ldb, int64_t strideB,
-                          float beta, void *C, xp_dtype c_type, xp_layout c_layout, int64_t ldc, int64_t strideC,
-                          void *stream)
-{
-    return gemm_common(XP_OP_GEMM_BATCHED, batch, M, N, K, alpha, A, a_type, a_layout, lda, strideA,
-                       B, b_type, b_layout, ldb, strideB, beta, C, c_type, c_layout, ldc, strideC, stream);
-}
-
-xp_status xp_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
-                         int64_t R, int64_t S, int64_t stride_h, int64_t stride_w,
-                         int64_t pad_h, int64_t pad_w,
-                         const void *input, xp_dtype in_type,
-                         const void *filter, xp_dtype w_type, xp_filter_layout w_layout,
-                         void *output, xp_dtype out_type, void *stream)
-{
+    *nothing = true;
     if (N < 0 || H < 0 || W < 0 || Cin < 0 || Cout < 0) return XP_ERR_SHAPE;
     if (R <= 0 || S <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return XP_ERR_SHAPE;
     if (w_layout != XP_FILTER_KRSC && w_layout != XP_FILTER_RSCK) return XP_ERR_UNSUPPORTED;
@@ -287,6 +300,48 @@ xp_status xp_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t C
     q.H = H; q.W = W; q.Cin = Cin; q.R = R; q.S = S; q.P = P; q.Q = Q;
     q.sh = stride_h; q.sw = stride_w; q.ph = pad_h; q.pw = pad_w;
     q.stream = (hipStream_t)stream;
+    *out = q;
+    *nothing = false;
+    return XP_OK;
+}
+
+}  // namespace xp
+
+using namespace xp;
+
+extern "C" {
+
+xp_status xp_gemm(int64_t M, int64_t N, int64_t K, float alpha,
+                  const void *A, xp_dtype a_type, xp_layout a_layout, int64_t lda,
+                  const void *B, xp_dtype b_type, xp_layout b_layout, int64_t ldb,
+                  float beta, void *C, xp_dtype c_type, xp_layout c_layout, int64_t ldc, void *stream)
+{
+    return gemm_common(XP_OP_GEMM, 1, M, N, K, alpha, A, a_type, a_layout, lda, 0, B, b_type, b_layout, ldb, 0,
+                       beta, C, c_type, c_layout, ldc, 0, stream);
+}
+
+xp_status xp_gemm_batched(int64_t batch, int64_t M, int64_t N, int64_t K, float alpha,
+                          const void *A, xp_dtype a_type, xp_layout a_layout, int64_t lda, int64_t strideA,
+                          const void *B, xp_dtype b_type, xp_layout b_layout, int64_t ldb, int64_t strideB,
+                          float beta, void *C, xp_dtype c_type, xp_layout c_layout, int64_t ldc, int64_t strideC,
+                          void *stream)
+{
+    return gemm_common(XP_OP_GEMM_BATCHED, batch, M, N, K, alpha, A, a_type, a_layout, lda, strideA,
+                       B, b_type, b_layout, ldb, strideB, beta, C, c_type, c_layout, ldc, strideC, stream);
+}
+
+xp_status xp_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                         int64_t R, int64_t S, int64_t stride_h, int64_t stride_w,
+                         int64_t pad_h, int64_t pad_w,
+                         const void *input, xp_dtype in_type,
+                         const void *filter, xp_dtype w_type, xp_filter_layout w_layout,
+                         void *output, xp_dtype out_type, void *stream)
+{
+    Problem q;
+    bool nothing;
+    const xp_status st = make_conv_problem(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, input, in_type,
+                                           filter, w_type, w_layout, output, out_type, stream, &q, &nothing);
+    if (st != XP_OK || nothing) return st;
     return run(q);
 }
 
@@ -386,6 +441,7 @@ const char *xp_status_string(xp_status s)
     case XP_ERR_UNSUPPORTED: return "unsupported dtype, layout or scaling combination";
     case XP_ERR_CONFIG: return "kernel configuration does not exist or cannot run this call";
     case XP_ERR_LAUNCH: return "kernel launch failed";
+    case XP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     }
     return "unknown status";
 }

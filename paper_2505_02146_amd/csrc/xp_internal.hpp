@@ -70,6 +70,23 @@ int pp_variants(xp_dtype in_type, const Variant **out);
 int dl_asym_variants(xp_dtype in_type, const Variant **out);
 int gemv_variants(xp_dtype in_type, const Variant **out);
 
+// Pieces of the dispatcher that the run-time tuner uses (xp_api.hip).
+xp_status make_gemm_problem(xp_op op, int64_t batch, int64_t M, int64_t N, int64_t K, float alpha,
+                            const void *A, xp_dtype a_t, xp_layout a_l, int64_t lda, int64_t strideA,
+                            const void *B, xp_dtype b_t, xp_layout b_l, int64_t ldb, int64_t strideB,
+                            float beta, void *C, xp_dtype c_t, xp_layout c_l, int64_t ldc, int64_t strideC,
+                            void *stream, Problem *out, bool *nothing);
+xp_status make_conv_problem(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                            int64_t R, int64_t S, int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                            const void *input, xp_dtype in_type, const void *filter, xp_dtype w_type,
+                            xp_filter_layout w_layout, void *output, xp_dtype out_type, void *stream,
+                            Problem *out, bool *nothing);
+xp_status launch_variant(const Problem &q, int idx);      // that variant or XP_ERR_CONFIG; no selection
+xp_status run(const Problem &q);                          // forced variant, else selection
+// Table of shapes tuned at run time or loaded from a file (xp_tune.hip): index of the recorded
+// variant if the shape is known and the variant can run the call, else -1.
+int runtime_tuned_variant(const Problem &q);
+
 // Run-time estimate (microseconds) shared by the MFMA variants' cost functions, used only for shapes
 // that are not in the table of swept winners.  conc = workgroups that fit one compute unit;
 // a round of workgroups takes the largest of MFMA time at the swept efficiency, HBM time for the

@@ -34,6 +34,16 @@ _lib.xp_gemm_batched.argtypes = [_i64, _i64, _i64, _i64, _f, _vp, _i, _i, _i64, 
                                  _f, _vp, _i, _i, _i64, _i64, _vp]
 _lib.xp_conv2d_nhwc.argtypes = [_i64] * 11 + [_vp, _i, _vp, _i, _i, _vp, _i, _vp]
 _lib.xp_attention.argtypes = [_i64] * 5 + [_f] + [_vp, _i, _i64, _i64] * 4 + [_vp]
+_ip, _fp = C.POINTER(C.c_int), C.POINTER(C.c_float)
+_tune_tail = [_vp, C.c_size_t, _i, _ip, _fp, _vp]       # workspace, bytes, reps, best, best_us, stream
+_lib.xp_tune_gemm.argtypes = _lib.xp_gemm.argtypes[:-1] + _tune_tail
+_lib.xp_tune_gemm_batched.argtypes = _lib.xp_gemm_batched.argtypes[:-1] + _tune_tail
+_lib.xp_tune_conv2d_nhwc.argtypes = _lib.xp_conv2d_nhwc.argtypes[:-1] + _tune_tail
+_lib.xp_tune_workspace_bytes.argtypes = [_i64]
+_lib.xp_tune_workspace_bytes.restype = C.c_size_t
+_lib.xp_tune_save.argtypes = [C.c_char_p]
+_lib.xp_tune_load.argtypes = [C.c_char_p]
+_lib.xp_tune_clear.restype = None
 _lib.xp_num_configs.argtypes = [_i, _i]
 _lib.xp_describe_config.argtypes = [_i, _i, _i, C.c_char_p, C.c_size_t]
 _lib.xp_force_config.argtypes = [_i, _i, _i]
@@ -41,7 +51,8 @@ _lib.xp_last_config.argtypes = [_i, _i]
 _lib.xp_status_string.argtypes = [_i]
 _lib.xp_status_string.restype = C.c_char_p
 _lib.xp_version.restype = C.c_char_p
-for _name in ("xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_attention", "xp_num_configs", "xp_describe_config",
+for _name in ("xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_attention", "xp_tune_gemm", "xp_tune_gemm_batched",
+              "xp_tune_conv2d_nhwc", "xp_tune_save", "xp_tune_load", "xp_tune_count", "xp_num_configs", "xp_describe_config",
               "xp_force_config", "xp_last_config"):
     getattr(_lib, _name).restype = _i
 
@@ -117,6 +128,57 @@ def xp_attention(batch, Lq, Lk, d, dv, scale, Q, ldq, strideQ, K, ldk, strideK, 
     _check(_lib.xp_attention(batch, Lq, Lk, d, dv, scale, _ptr(Q), _dt(Q, q_type), ldq, strideQ,
                              _ptr(K), _dt(K, k_type), ldk, strideK, _ptr(V), _dt(V, v_type), ldv, strideV,
                              _ptr(O), _dt(O, o_type), ldo, strideO, _stream(stream)))
+
+
+def _tune_call(fn, args, workspace, reps, stream):
+    best, best_us = C.c_int(-1), C.c_float(0.0)
+    _check(fn(*args, _ptr(workspace), workspace.numel() * workspace.element_size(), reps, C.byref(best), C.byref(best_us),
+              _stream(stream)))
+    return best.value, best_us.value
+
+
+def xp_tune_gemm(M, N, K, alpha, A, a_layout, lda, B, b_layout, ldb, beta, C_, c_layout, ldc, workspace, reps=20,
+                 stream=None, a_type=None, b_type=None, c_type=None):
+    """Brute-force search over the variants for this call's shape (see include/xp.h: xp_tune_gemm).
+    Returns (index of the winner, microseconds per launch)."""
+    args = (M, N, K, alpha, _ptr(A), _dt(A, a_type), _LAYOUT[a_layout], lda, _ptr(B), _dt(B, b_type), _LAYOUT[b_layout], ldb,
+            beta, _ptr(C_), _dt(C_, c_type), _LAYOUT[c_layout], ldc)
+    return _tune_call(_lib.xp_tune_gemm, args, workspace, reps, stream)
+
+
+def xp_tune_gemm_batched(batch, M, N, K, alpha, A, a_layout, lda, strideA, B, b_layout, ldb, strideB, beta, C_, c_layout,
+                         ldc, strideC, workspace, reps=20, stream=None, a_type=None, b_type=None, c_type=None):
+    args = (batch, M, N, K, alpha, _ptr(A), _dt(A, a_type), _LAYOUT[a_layout], lda, strideA,
+            _ptr(B), _dt(B, b_type), _LAYOUT[b_layout], ldb, strideB, beta,
+            _ptr(C_), _dt(C_, c_type), _LAYOUT[c_layout], ldc, strideC)
+    return _tune_call(_lib.xp_tune_gemm_batched, args, workspace, reps, stream)
+
+
+def xp_tune_conv2d_nhwc(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, x, w, filter_layout, out, workspace,
+                        reps=20, stream=None, in_type=None, w_type=None, out_type=None):
+    args = (N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, _ptr(x), _dt(x, in_type), _ptr(w), _dt(w, w_type),
+            _FILTER[filter_layout], _ptr(out), _dt(out, out_type))
+    return _tune_call(_lib.xp_tune_conv2d_nhwc, args, workspace, reps, stream)
+
+
+def xp_tune_workspace_bytes(c_extent: int) -> int:
+    return _lib.xp_tune_workspace_bytes(c_extent)
+
+
+def xp_tune_save(path: str) -> None:
+    _check(_lib.xp_tune_save(str(path).encode()))
+
+
+def xp_tune_load(path: str) -> None:
+    _check(_lib.xp_tune_load(str(path).encode()))
+
+
+def xp_tune_clear() -> None:
+    _lib.xp_tune_clear()
+
+
+def xp_tune_count() -> int:
+    return _lib.xp_tune_count()
 
 
 def xp_num_configs(op: int, in_type) -> int:

@@ -159,6 +159,51 @@ def test_attention_variant_table(lib):
     assert lib.xp_last_config(xp.XP_OP_ATTENTION, xp.XP_I8) == -1
 
 
+def test_tuned_shape_table_round_trip(lib, tmp_path):
+    from paper_2505_02146_amd import xp
+    xp.xp_tune_clear()
+    assert xp.xp_tune_count() == 0
+    src = tmp_path / "tuned.txt"
+    src.write_text("# comment\n"
+                   "gemm0 t1 b1 m512 n512 k512 a1 b1 | bf16 128x128x128B waves 2x2 ring 2 direct-to-lds mfma16\n"
+                   "gemm0 t1 b1 m512 n512 k512 a1 b1 | bf16 64x64x128B waves 2x2 stages 2 mfma32\n"      # replaces the line above
+                   "conv t1 n2 h8 w8 c64 k64 r3 s3 sh1 sw1 ph1 pw1 b1 | no such variant\n"
+                   "a line without a separator\n")
+    xp.xp_tune_load(src)
+    assert xp.xp_tune_count() == 2
+    dst = tmp_path / "saved.txt"
+    xp.xp_tune_save(dst)
+    lines = [l for l in dst.read_text().splitlines() if not l.startswith("#")]
+    assert lines == ["conv t1 n2 h8 w8 c64 k64 r3 s3 sh1 sw1 ph1 pw1 b1 | no such variant",
+                     "gemm0 t1 b1 m512 n512 k512 a1 b1 | bf16 64x64x128B waves 2x2 stages 2 mfma32"]
+    xp.xp_tune_clear()
+    xp.xp_tune_load(dst)
+    assert xp.xp_tune_count() == 2
+    xp.xp_tune_clear()
+    assert xp.xp_tune_count() == 0
+    assert lib.xp_tune_load(str(tmp_path / "missing.txt").encode()) == 8
+    assert lib.xp_tune_save(str(tmp_path / "no_such_dir" / "x.txt").encode()) == 8
+    assert lib.xp_tune_load(None) == 1 and lib.xp_tune_save(None) == 1
+    assert xp.xp_tune_workspace_bytes(0) == 256 and xp.xp_tune_workspace_bytes(64) == 768
+    assert xp.xp_tune_workspace_bytes(-1) == 0
+
+
+def test_tune_validation(lib):
+    # every call here must be turned away (or be empty) on the host: the pointers are fake
+    def call(M=64, N=64, K=64, A=256, B=256, C=256, ws=256, ws_bytes=1 << 20, reps=3, at=0, ct=0):
+        return lib.xp_tune_gemm(M, N, K, 1.0, A, at, 0, K, B, at, 1, K, 0.0, C, ct, 0, N, ws, ws_bytes, reps, None, None, None)
+    assert call(M=-1) == 2
+    assert call(A=None) == 1
+    assert call(at=1, ct=1) == 5
+    assert call(reps=0) == 2
+    assert call(ws=None) == 8
+    assert call(ws=260) == 8                                  # not 256-byte aligned
+    assert call(ws_bytes=2 * 64 * 64 * 4 + 255) == 8          # one byte short
+    assert call(M=0, A=None, B=None, C=None, ws=None) == 0    # nothing to compute, nothing recorded
+    from paper_2505_02146_amd import xp
+    assert xp.xp_tune_count() == 0
+
+
 def test_entry_points_resolve_their_builders():
     # build() compiles for minutes, so it is not run here; what broke once is the lookup of the
     # oracle's build module behind the package attribute of the same name
@@ -174,6 +219,6 @@ def test_entry_points_resolve_their_builders():
 
 def test_status_strings(lib):
     from paper_2505_02146_amd import xp
-    seen = {xp.status_string(i) for i in range(8)}
-    assert len(seen) == 8 and "ok" in seen
+    seen = {xp.status_string(i) for i in range(9)}
+    assert len(seen) == 9 and "ok" in seen
     assert "gfx950" in xp.version()
