@@ -36,8 +36,15 @@ def lib() -> C.CDLL:
                                                 dbl, vp, i, i64, i64, vp]
         L.oracle_conv2d_nhwc.argtypes = [i64] * 11 + [vp, i, vp, i, i, vp]
         L.oracle_attention.argtypes = [i64] * 5 + [dbl] + [vp, i, i64, i64] * 3 + [vp]
+        L.oracle_softmax.argtypes = [i64, i64, vp, i, i64, vp]
+        L.oracle_layernorm.argtypes = [i64, i64, vp, i, i64, vp, vp, dbl, vp]
+        L.oracle_rmsnorm.argtypes = [i64, i64, vp, i, i64, vp, dbl, vp]
+        L.oracle_unary.argtypes = [i, i64, vp, i, vp]
+        L.oracle_add.argtypes = [i64, vp, vp, i, vp]
+        L.oracle_pool2d_nhwc.argtypes = [i] + [i64] * 10 + [vp, i, vp]
         for f in (L.oracle_gemm_float, L.oracle_gemm_i8, L.oracle_gemm_float_batched,
-                  L.oracle_conv2d_nhwc, L.oracle_attention, L.oracle_num_threads):
+                  L.oracle_conv2d_nhwc, L.oracle_attention, L.oracle_softmax, L.oracle_layernorm,
+                  L.oracle_rmsnorm, L.oracle_unary, L.oracle_add, L.oracle_pool2d_nhwc, L.oracle_num_threads):
             f.restype = i
         _lib = L
     return _lib
@@ -153,4 +160,58 @@ def attention(Q, K, V, *, batch, Lq, Lk, d, dv, scale, ldq=None, ldk=None, ldv=N
                                 _ptr(V), _ftype(V), ldv, strideV, _ptr(ref))
     if rc:
         raise ValueError(f"oracle_attention failed with code {rc}")
+    return ref
+
+
+UNARY = {"relu": 0, "gelu": 1, "sigmoid": 2, "sign": 3}
+POOL = {"max": 0, "avg": 1, "min": 2, "sum": 3}
+
+
+def _rc(rc, what):
+    if rc:
+        raise ValueError(f"{what} failed with code {rc}")
+
+
+def softmax(x, *, rows, cols, ldx=None) -> np.ndarray:
+    """fp64 softmax over the last dimension of a rows x cols matrix with row pitch ldx."""
+    ref = np.empty((rows, cols), dtype=np.float64)
+    _rc(lib().oracle_softmax(rows, cols, _ptr(x), _ftype(x), cols if ldx is None else ldx, _ptr(ref)), "oracle_softmax")
+    return ref
+
+
+def layernorm(x, *, rows, cols, gamma=None, beta=None, eps=1e-5, ldx=None) -> np.ndarray:
+    ref = np.empty((rows, cols), dtype=np.float64)
+    for v in (gamma, beta):
+        assert v is None or v.dtype == x.dtype
+    _rc(lib().oracle_layernorm(rows, cols, _ptr(x), _ftype(x), cols if ldx is None else ldx, _ptr(gamma), _ptr(beta),
+                               float(eps), _ptr(ref)), "oracle_layernorm")
+    return ref
+
+
+def rmsnorm(x, *, rows, cols, gamma=None, eps=1e-6, ldx=None) -> np.ndarray:
+    ref = np.empty((rows, cols), dtype=np.float64)
+    assert gamma is None or gamma.dtype == x.dtype
+    _rc(lib().oracle_rmsnorm(rows, cols, _ptr(x), _ftype(x), cols if ldx is None else ldx, _ptr(gamma), float(eps),
+                             _ptr(ref)), "oracle_rmsnorm")
+    return ref
+
+
+def unary(op: str, x) -> np.ndarray:
+    ref = np.empty(x.size, dtype=np.float64)
+    _rc(lib().oracle_unary(UNARY[op], x.size, _ptr(x), _ftype(x), _ptr(ref)), "oracle_unary")
+    return ref.reshape(x.shape)
+
+
+def add(a, b) -> np.ndarray:
+    assert a.dtype == b.dtype and a.size == b.size
+    ref = np.empty(a.size, dtype=np.float64)
+    _rc(lib().oracle_add(a.size, _ptr(a), _ptr(b), _ftype(a), _ptr(ref)), "oracle_add")
+    return ref.reshape(a.shape)
+
+
+def pool2d_nhwc(op: str, x, *, N, H, W, C, R, S, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    ref = np.empty((N, P, Q, C), dtype=np.float64)
+    _rc(lib().oracle_pool2d_nhwc(POOL[op], N, H, W, C, R, S, stride[0], stride[1], pad[0], pad[1], _ptr(x), _ftype(x),
+                                 _ptr(ref)), "oracle_pool2d_nhwc")
     return ref

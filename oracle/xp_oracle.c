@@ -215,3 +215,153 @@ int oracle_attention(int64_t batch, int64_t Lq, int64_t Lk, int64_t d, int64_t d
     }
     return failed ? 5 : 0;
 }
+
+/* ---- row-wise operators over the last dimension: x is rows x cols with row pitch ldx ---- */
+
+int oracle_softmax(int64_t rows, int64_t cols, const void *x, int x_type, int64_t ldx, double *ref)
+{
+    if (rows < 0 || cols < 0 || ldx < cols) return 1;
+    if (bad_type(x_type)) return 2;
+    if (rows == 0 || cols == 0) return 0;
+    if (!x || !ref) return 4;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        double top = -INFINITY, total = 0.0;
+        for (int64_t j = 0; j < cols; ++j) {
+            const double v = widen(x, x_type, i * ldx + j);
+            if (v > top) top = v;
+        }
+        for (int64_t j = 0; j < cols; ++j) {
+            ref[i * cols + j] = exp(widen(x, x_type, i * ldx + j) - top);
+            total += ref[i * cols + j];
+        }
+        for (int64_t j = 0; j < cols; ++j) ref[i * cols + j] /= total;
+    }
+    return 0;
+}
+
+/* gamma and beta have the element type of x; NULL stands for all ones / all zeros */
+int oracle_layernorm(int64_t rows, int64_t cols, const void *x, int x_type, int64_t ldx,
+                     const void *gamma, const void *beta, double eps, double *ref)
+{
+    if (rows < 0 || cols < 0 || ldx < cols) return 1;
+    if (bad_type(x_type)) return 2;
+    if (rows == 0 || cols == 0) return 0;
+    if (!x || !ref) return 4;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        double mean = 0.0, var = 0.0;
+        for (int64_t j = 0; j < cols; ++j) mean += widen(x, x_type, i * ldx + j);
+        mean /= (double)cols;
+        for (int64_t j = 0; j < cols; ++j) {
+            const double d = widen(x, x_type, i * ldx + j) - mean;
+            var += d * d;
+        }
+        var /= (double)cols;                                  /* the biased (population) variance */
+        const double rstd = 1.0 / sqrt(var + eps);
+        for (int64_t j = 0; j < cols; ++j) {
+            const double g = gamma ? widen(gamma, x_type, j) : 1.0, b = beta ? widen(beta, x_type, j) : 0.0;
+            ref[i * cols + j] = (widen(x, x_type, i * ldx + j) - mean) * rstd * g + b;
+        }
+    }
+    return 0;
+}
+
+int oracle_rmsnorm(int64_t rows, int64_t cols, const void *x, int x_type, int64_t ldx,
+                   const void *gamma, double eps, double *ref)
+{
+    if (rows < 0 || cols < 0 || ldx < cols) return 1;
+    if (bad_type(x_type)) return 2;
+    if (rows == 0 || cols == 0) return 0;
+    if (!x || !ref) return 4;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        double ms = 0.0;
+        for (int64_t j = 0; j < cols; ++j) {
+            const double v = widen(x, x_type, i * ldx + j);
+            ms += v * v;
+        }
+        ms /= (double)cols;
+        const double r = 1.0 / sqrt(ms + eps);
+        for (int64_t j = 0; j < cols; ++j)
+            ref[i * cols + j] = widen(x, x_type, i * ldx + j) * r * (gamma ? widen(gamma, x_type, j) : 1.0);
+    }
+    return 0;
+}
+
+/* ---- element-wise operators on n elements ---- */
+
+int oracle_unary(int op, int64_t n, const void *x, int x_type, double *ref)
+{
+    if (n < 0) return 1;
+    if (bad_type(x_type)) return 2;
+    if (op < ORACLE_RELU || op > ORACLE_SIGN) return 3;
+    if (n == 0) return 0;
+    if (!x || !ref) return 4;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const double v = widen(x, x_type, i);
+        double y;
+        switch (op) {
+        case ORACLE_RELU: y = v > 0.0 ? v : 0.0; break;
+        case ORACLE_GELU: y = 0.5 * v * (1.0 + erf(v / sqrt(2.0))); break;
+        case ORACLE_SIGMOID: y = 1.0 / (1.0 + exp(-v)); break;
+        default: y = v > 0.0 ? 1.0 : (v < 0.0 ? -1.0 : 0.0); break;
+        }
+        ref[i] = y;
+    }
+    return 0;
+}
+
+int oracle_add(int64_t n, const void *a, const void *b, int type, double *ref)
+{
+    if (n < 0) return 1;
+    if (bad_type(type)) return 2;
+    if (n == 0) return 0;
+    if (!a || !b || !ref) return 4;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) ref[i] = widen(a, type, i) + widen(b, type, i);
+    return 0;
+}
+
+/* ---- 2-D pooling, NHWC.  Window positions outside the image do not take part: the maximum and
+ * minimum are over the positions inside, the sum adds nothing for them, and the average divides by
+ * the number of positions inside.  A window with no position inside gives 0. ---- */
+int oracle_pool2d_nhwc(int op, int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S,
+                       int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                       const void *x, int x_type, double *ref)
+{
+    if (N < 0 || H < 0 || W < 0 || C < 0 || R <= 0 || S <= 0) return 1;
+    if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return 1;
+    if (bad_type(x_type)) return 2;
+    if (op < ORACLE_POOL_MAX || op > ORACLE_POOL_SUM) return 3;
+    if (H + 2 * pad_h < R || W + 2 * pad_w < S) return 0;
+    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1, Q = (W + 2 * pad_w - S) / stride_w + 1;
+    if (N == 0 || C == 0) return 0;
+    if (!x || !ref) return 4;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t p = 0; p < P; ++p)
+            for (int64_t q = 0; q < Q; ++q)
+                for (int64_t c = 0; c < C; ++c) {
+                    double acc = 0.0;
+                    int64_t inside = 0;
+                    for (int64_t r = 0; r < R; ++r) {
+                        const int64_t h = p * stride_h + r - pad_h;
+                        if (h < 0 || h >= H) continue;
+                        for (int64_t s = 0; s < S; ++s) {
+                            const int64_t w = q * stride_w + s - pad_w;
+                            if (w < 0 || w >= W) continue;
+                            const double v = widen(x, x_type, ((n * H + h) * W + w) * C + c);
+                            if (inside == 0) acc = v;
+                            else if (op == ORACLE_POOL_MAX) acc = v > acc ? v : acc;
+                            else if (op == ORACLE_POOL_MIN) acc = v < acc ? v : acc;
+                            else acc += v;
+                            ++inside;
+                        }
+                    }
+                    if (op == ORACLE_POOL_AVG && inside > 0) acc /= (double)inside;
+                    ref[((n * P + p) * Q + q) * C + c] = acc;
+                }
+    return 0;
+}

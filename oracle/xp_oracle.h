@@ -1,7 +1,8 @@
 /*
  * CPU oracle for the dense tensor operators of the MatMul and Convolution groups of the
  * paper's benchmark (Table 5: GEMM, Batch GEMM, Conv2D NHWC) and for the fused attention operator
- * of its LLM group (Table 5: Self Attention).
+ * of its LLM group (Table 5: Self Attention), and for the memory-bound operators of its Activation,
+ * Elementwise, Pooling and LLM groups.
  *
  * THIS IS TEST INFRASTRUCTURE, NOT A PRODUCT PATH.  It exists so that the GPU library can be
  * checked against something that is obviously right.  It is plain, slow, scalar C: the
@@ -88,6 +89,34 @@ int oracle_attention(int64_t batch, int64_t Lq, int64_t Lk, int64_t d, int64_t d
                      const void *K, int k_type, int64_t ldk, int64_t strideK,
                      const void *V, int v_type, int64_t ldv, int64_t strideV,
                      double *ref);
+
+/* Memory-bound operators of Table 5 (Activation: ReLU, Softmax, GeLU, Sigmoid; Elementwise: Add,
+ * Sign; Pooling: MaxPool, AvgPool, MinPool, SumPool; LLM: LayerNorm, RMSNorm), named there without a
+ * definition; the standard ones, in fp64:
+ *   softmax    y(i,j) = exp(x(i,j)) / sum_j' exp(x(i,j'))                     over the last dimension
+ *   layernorm  y(i,j) = (x(i,j) - mean_i) / sqrt(var_i + eps) * gamma(j) + beta(j), var_i = mean of squares of deviations
+ *   rmsnorm    y(i,j) = x(i,j) / sqrt(mean_j x(i,j)^2 + eps) * gamma(j)
+ *   relu max(x,0); gelu x/2 (1 + erf(x/sqrt 2)); sigmoid 1/(1+exp(-x)); sign -1, 0 or +1; add a + b
+ *   pooling    NHWC, window R x S, strides, zero-free padding (positions outside the image do not take part)
+ * x is rows x cols with row pitch ldx (elements); ref is dense.  gamma / beta have x's element type, NULL = 1 / 0. */
+#define ORACLE_RELU 0
+#define ORACLE_GELU 1
+#define ORACLE_SIGMOID 2
+#define ORACLE_SIGN 3
+#define ORACLE_POOL_MAX 0
+#define ORACLE_POOL_AVG 1
+#define ORACLE_POOL_MIN 2
+#define ORACLE_POOL_SUM 3
+int oracle_softmax(int64_t rows, int64_t cols, const void *x, int x_type, int64_t ldx, double *ref);
+int oracle_layernorm(int64_t rows, int64_t cols, const void *x, int x_type, int64_t ldx,
+                     const void *gamma, const void *beta, double eps, double *ref);
+int oracle_rmsnorm(int64_t rows, int64_t cols, const void *x, int x_type, int64_t ldx,
+                   const void *gamma, double eps, double *ref);
+int oracle_unary(int op, int64_t n, const void *x, int x_type, double *ref);
+int oracle_add(int64_t n, const void *a, const void *b, int type, double *ref);
+int oracle_pool2d_nhwc(int op, int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S,
+                       int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                       const void *x, int x_type, double *ref);
 
 /* Number of OpenMP threads the loops above will use. */
 int oracle_num_threads(void);
