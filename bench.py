@@ -227,6 +227,52 @@ def main() -> int:
                                   "buffers": f"{sets} rotating matrices (HBM-cold)",
                                   "kernel": xp.xp_describe_config(0, "bf16", xp.xp_last_config(0, "bf16"))}
         del Av, xv, yv
+        # memory-bound operators: achieved bytes/s against the HBM peak.  Timing inputs come from torch's
+        # seeded generator on the device (the values do not matter here; parity is the tests' job).
+        # Working sets are rotated or larger than the 256 MB last-level cache, so the rates are HBM-cold.
+        torch.manual_seed(0)
+        mem = {}
+
+        def rate(name, nbytes, fn, sets):
+            ms, _ = _time_calls(torch, fn, steps2 * 2, warm2)
+            mem[name] = {"ms": round(ms, 5), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                         "pct_hbm_peak": round(100 * nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 2), "buffers": sets}
+
+        rows, cols = 16384, 4096
+        xs = [torch.randn(rows, cols, device="cuda").bfloat16() for _ in range(3)]
+        ys = [torch.empty(rows, cols, device="cuda", dtype=torch.bfloat16) for _ in range(3)]
+        gam, bet = torch.randn(cols, device="cuda").bfloat16(), torch.randn(cols, device="cuda").bfloat16()
+        it = {"i": 0}
+
+        def nxt():
+            it["i"] += 1
+            return it["i"] % 3
+        nb = 2 * rows * cols * 2
+        rate("layernorm_bf16_16384x4096", nb, lambda: (lambda i: xp.xp_layernorm(rows, cols, xs[i], cols, gam, bet, 1e-5, ys[i], cols))(nxt()), "3 rotating sets of 268 MB")
+        rate("rmsnorm_bf16_16384x4096", nb, lambda: (lambda i: xp.xp_rmsnorm(rows, cols, xs[i], cols, gam, 1e-6, ys[i], cols))(nxt()), "3 rotating sets of 268 MB")
+        n = rows * cols
+        rate("gelu_bf16_64M", nb, lambda: (lambda i: xp.xp_unary("gelu", n, xs[i], ys[i]))(nxt()), "3 rotating sets of 268 MB")
+        rate("add_bf16_64M", 3 * n * 2, lambda: (lambda i: xp.xp_add(n, xs[i], xs[(i + 1) % 3], ys[i]))(nxt()), "3 rotating sets")
+        del xs, ys
+        srows, scols = 96 * 512, 512
+        sx = [torch.randn(srows, scols, device="cuda") for _ in range(4)]
+        sy = [torch.empty(srows, scols, device="cuda") for _ in range(4)]
+        it["i"] = 0
+
+        def nxt4():
+            it["i"] += 1
+            return it["i"] % 4
+        rate("softmax_f32_49152x512", 2 * srows * scols * 4, lambda: (lambda i: xp.xp_softmax(srows, scols, sx[i], scols, sy[i], scols))(nxt4()),
+             "4 rotating sets of 201 MB")
+        del sx, sy
+        pn, ph_, pc = 64, 112, 64
+        px = [torch.randn(pn, ph_, ph_, pc, device="cuda").bfloat16() for _ in range(4)]
+        py = [torch.empty(pn, 56, 56, pc, device="cuda", dtype=torch.bfloat16) for _ in range(4)]
+        rate("maxpool_bf16_64x112x112x64_3x3s2", (pn * ph_ * ph_ * pc + pn * 56 * 56 * pc) * 2,
+             lambda: (lambda i: xp.xp_pool2d_nhwc("max", pn, ph_, ph_, pc, 3, 3, 2, 2, 1, 1, px[i], py[i]))(nxt4()),
+             "4 rotating sets of 128 MB")
+        del px, py
+        side["memory_bound"] = mem
         out["other_workloads"] = side
 
     # ---- CPU oracle on a bounded sample of the main workload (reported baseline, not the target)

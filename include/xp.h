@@ -157,6 +157,50 @@ xp_status xp_force_config(xp_op op, xp_dtype in_type, int idx);
 int xp_last_config(xp_op op, xp_dtype in_type);
 
 /*
+ * Memory-bound operators (Table 5: Activation -- ReLU, Softmax, GeLU, Sigmoid; Elementwise -- Add,
+ * Sign; Pooling -- MaxPool, AvgPool, MinPool, SumPool; LLM -- LayerNorm, RMSNorm; named there without
+ * a definition, the standard ones are computed).  Storage types: XP_F32 or XP_BF16 for inputs and,
+ * independently, for the output (bf16 output is rounded to nearest even); the arithmetic is fp32.
+ * All data pointers are DEVICE pointers; inputs are read-only; in-place use (y == x) is allowed for
+ * xp_unary and xp_add with equal input and output types, and for the row-wise operators when, in
+ * addition, ldy == ldx.  Empty extents return XP_OK without a launch.
+ *
+ * Row-wise operators: x is rows x cols, element (i,j) at x[i*ldx + j] (ldx >= cols), y likewise with ldy.
+ *   xp_softmax    y(i,j) = exp(x(i,j)) / sum_j' exp(x(i,j'))
+ *   xp_layernorm  y(i,j) = (x(i,j) - mean_i) / sqrt(var_i + eps) * gamma(j) + beta(j),
+ *                 var_i = (1/cols) sum_j (x(i,j) - mean_i)^2
+ *   xp_rmsnorm    y(i,j) = x(i,j) / sqrt((1/cols) sum_j x(i,j)^2 + eps) * gamma(j)
+ * gamma and beta are vectors of cols elements of x's type; NULL means all ones / all zeros.
+ * eps must be finite and >= 0.  Rows whose length and alignment allow 16-byte accesses (cols a
+ * multiple of 4 fp32 / 8 bf16 elements, 16-byte aligned rows) are read from memory exactly once;
+ * other rows, and rows longer than 32768 fp32 / 65536 bf16 elements, take a general three-pass kernel.
+ */
+xp_status xp_softmax(int64_t rows, int64_t cols, const void *x, xp_dtype x_type, int64_t ldx,
+                     void *y, xp_dtype y_type, int64_t ldy, void *stream);
+xp_status xp_layernorm(int64_t rows, int64_t cols, const void *x, xp_dtype x_type, int64_t ldx,
+                       const void *gamma, const void *beta, float eps,
+                       void *y, xp_dtype y_type, int64_t ldy, void *stream);
+xp_status xp_rmsnorm(int64_t rows, int64_t cols, const void *x, xp_dtype x_type, int64_t ldx,
+                     const void *gamma, float eps,
+                     void *y, xp_dtype y_type, int64_t ldy, void *stream);
+
+/* Element-wise: relu max(x,0); gelu x/2 (1 + erf(x / sqrt 2)) (the erf form, not the tanh
+ * approximation); sigmoid 1 / (1 + exp(-x)); sign -1, 0 or +1; xp_add y = a + b.  n contiguous elements. */
+typedef enum { XP_RELU = 0, XP_GELU = 1, XP_SIGMOID = 2, XP_SIGN = 3 } xp_unary_op;
+xp_status xp_unary(xp_unary_op op, int64_t n, const void *x, xp_dtype x_type, void *y, xp_dtype y_type, void *stream);
+xp_status xp_add(int64_t n, const void *a, const void *b, xp_dtype type, void *y, xp_dtype y_type, void *stream);
+
+/* 2-D pooling, NHWC: x is N x H x W x C contiguous, y is N x P x Q x C contiguous with
+ * P = floor((H + 2*pad_h - R)/stride_h) + 1, Q likewise (empty, XP_OK, if the padded image is smaller
+ * than the window).  Window positions outside the image do not take part: maximum and minimum are over
+ * the positions inside, the sum adds nothing for them, the average divides by the number of
+ * positions inside; a window with no position inside gives 0. */
+typedef enum { XP_POOL_MAX = 0, XP_POOL_AVG = 1, XP_POOL_MIN = 2, XP_POOL_SUM = 3 } xp_pool_op;
+xp_status xp_pool2d_nhwc(xp_pool_op op, int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S,
+                         int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                         const void *x, xp_dtype x_type, void *y, xp_dtype y_type, void *stream);
+
+/*
  * Run-time parameter search: the brute-force intra-pass auto-tuning of the paper (Section 5.1) with
  * its reward (Eq. 3-4), inside the library.  xp_tune_* takes the arguments of the entry point it is
  * named after plus a workspace, and

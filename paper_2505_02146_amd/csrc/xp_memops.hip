@@ -1,0 +1,502 @@
+// Memory-bound operators of the paper's benchmark (Table 5: Activation -- ReLU, Softmax, GeLU,
+// Sigmoid; Elementwise -- Add, Sign; Pooling -- Max/Avg/Min/SumPool; LLM -- LayerNorm, RMSNorm).
+// Each reads its input once and writes its output once: the bound is HBM bandwidth, the matrix
+// cores have nothing to do.  Common shape of the kernels: 16-byte loads and stores, fp32
+// arithmetic whatever the storage type (fp32 or bf16, output rounded to nearest even), and for the
+// row-wise operators the whole row held in registers between the reduction and the write, so that
+// it is fetched from memory exactly once.
+#include "xp_internal.hpp"
+
+namespace xp {
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi)
+{
+    f32x2 f = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));      // round to nearest even
+}
+__device__ __forceinline__ unsigned short to_bf16(float v) { return (unsigned short)pack_bf16(v, 0.0f); }
+
+// EPC elements per 16-byte input chunk: 4 fp32 or 8 bf16
+template <bool BF16> struct Chunk {
+    static constexpr int EPC = BF16 ? 8 : 4;
+    __device__ static __forceinline__ void load(const void *p, long long chunk, float (&v)[EPC])
+    {
+        const u32x4 w = *((const u32x4 *)p + chunk);
+        if constexpr (BF16) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { v[2 * i] = bf16_lo(w[i]); v[2 * i + 1] = bf16_hi(w[i]); }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = __uint_as_float(w[i]);
+        }
+    }
+};
+// store EPC values starting at element e0 of p (aligned to EPC output elements)
+template <bool OUT_BF16, int EPC> __device__ __forceinline__ void store_chunk(void *p, long long e0, const float (&v)[EPC])
+{
+    if constexpr (OUT_BF16) {
+        unsigned w[EPC / 2];
+#pragma unroll
+        for (int i = 0; i < EPC / 2; ++i) w[i] = pack_bf16(v[2 * i], v[2 * i + 1]);
+        if constexpr (EPC == 8) *(u32x4 *)((unsigned short *)p + e0) = u32x4{w[0], w[1], w[2], w[3]};
+        else *(u32x2 *)((unsigned short *)p + e0) = u32x2{w[0], w[1]};
+    } else {
+#pragma unroll
+        for (int i = 0; i < EPC; i += 4)
+            *(u32x4 *)((float *)p + e0 + i) = u32x4{__float_as_uint(v[i]), __float_as_uint(v[i + 1]), __float_as_uint(v[i + 2]),
+                                                    __float_as_uint(v[i + 3])};
+    }
+}
+template <bool BF16> __device__ __forceinline__ float load1(const void *p, long long i)
+{
+    if constexpr (BF16) return __uint_as_float((unsigned)((const unsigned short *)p)[i] << 16);
+    else return ((const float *)p)[i];
+}
+template <bool BF16> __device__ __forceinline__ void store1(void *p, long long i, float v)
+{
+    if constexpr (BF16) ((unsigned short *)p)[i] = to_bf16(v);
+    else ((float *)p)[i] = v;
+}
+
+// -------------------------------------------------------------------------------- row-wise operators
+enum RowOp { SOFTMAX = 0, LAYERNORM = 1, RMSNORM = 2 };
+
+struct RowParams {
+    const void *x, *gamma, *beta;
+    void *y;
+    long long rows, ldx, ldy;
+    int cols;
+    float eps;
+};
+
+// reduction over the TPR threads that share a row (TPR = 64: one wave; else several waves through LDS)
+template <int TPR, bool MAX>
+__device__ __forceinline__ float row_reduce(float v, float *scratch, int group, int t)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float w = __shfl_xor(v, o);
+        v = MAX ? fmaxf(v, w) : v + w;
+    }
+    if constexpr (TPR > 64) {
+        constexpr int NW = TPR / 64;
+        __syncthreads();                                   // scratch may still be read from the previous reduction
+        if ((t & 63) == 0) scratch[group * NW + (t >> 6)] = v;
+        __syncthreads();
+        v = scratch[group * NW];
+#pragma unroll
+        for (int i = 1; i < NW; ++i) v = MAX ? fmaxf(v, scratch[group * NW + i]) : v + scratch[group * NW + i];
+    }
+    return v;
+}
+
+constexpr int MAXC = 8;                                    // 16-byte chunks of a row that one thread keeps in registers
+
+// TPR threads per row; the workgroup holds BLOCK / TPR rows.  cols is a multiple of EPC, rows start
+// 16-byte aligned, cols / EPC <= TPR * MAXC.
+template <int OP, bool IN_BF16, bool OUT_BF16, int TPR>
+__global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void row_kernel(RowParams p)
+{
+    constexpr int BLOCK = TPR < 256 ? 256 : TPR, RPB = BLOCK / TPR, EPC = Chunk<IN_BF16>::EPC;
+    __shared__ float scratch[BLOCK / 64];
+    const int group = threadIdx.x / TPR, t = threadIdx.x % TPR;
+    const long long row = (long long)blockIdx.x * RPB + group;
+    const bool live = row < p.rows;                        // a dead row group still takes part in the barriers
+    const int nchunks = p.cols / EPC;
+    const char *xr = (const char *)p.x + (live ? row : 0) * p.ldx * (IN_BF16 ? 2 : 4);
+
+    float v[MAXC][EPC];
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int ch = t + c * TPR;
+        if (live && ch < nchunks) Chunk<IN_BF16>::load(xr, ch, v[c]);
+        else {
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) v[c][e] = OP == SOFTMAX ? -INFINITY : 0.0f;
+        }
+    }
+    const float inv_n = 1.0f / (float)p.cols;
+    float shift = 0.0f, scale = 1.0f;                      // y = (x - shift) * scale [* gamma + beta]
+    if constexpr (OP == SOFTMAX) {
+        float m = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) m = fmaxf(m, v[c][e]);
+        m = row_reduce<TPR, true>(m, scratch, group, t);
+        float s = 0.0f;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) {
+                v[c][e] = expf(v[c][e] - m);               // padding lanes hold -inf: exp gives 0
+                s += v[c][e];
+            }
+        s = row_reduce<TPR, false>(s, scratch, group, t);
+        scale = 1.0f / s;
+    } else if constexpr (OP == LAYERNORM) {
+        float s = 0.0f;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) s += v[c][e];
+        shift = row_reduce<TPR, false>(s, scratch, group, t) * inv_n;
+        float q = 0.0f;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const bool in = t + c * TPR < nchunks;         // padding must not count as (0 - mean)^2
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) {
+                const float d = v[c][e] - shift;
+                q += in ? d * d : 0.0f;
+            }
+        }
+        q = row_reduce<TPR, false>(q, scratch, group, t) * inv_n;
+        scale = 1.0f / sqrtf(q + p.eps);
+    } else {
+        float q = 0.0f;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) q += v[c][e] * v[c][e];
+        q = row_reduce<TPR, false>(q, scratch, group, t) * inv_n;
+        scale = 1.0f / sqrtf(q + p.eps);
+    }
+    if (!live) return;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int ch = t + c * TPR;
+        if (ch >= nchunks) continue;
+        float o[EPC];
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) o[e] = (v[c][e] - shift) * scale;
+        if constexpr (OP != SOFTMAX) {
+            if (p.gamma) {
+                float g[EPC];
+                Chunk<IN_BF16>::load(p.gamma, ch, g);
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) o[e] *= g[e];
+            }
+            if (OP == LAYERNORM && p.beta) {
+                float b[EPC];
+                Chunk<IN_BF16>::load(p.beta, ch, b);
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) o[e] += b[e];
+            }
+        }
+        store_chunk<OUT_BF16, EPC>(p.y, row * p.ldy + (long long)ch * EPC, o);
+    }
+}
+
+// any row length and alignment: one workgroup per row, three passes over the row (the second and
+// third come from cache for all but very long rows)
+template <int OP, bool IN_BF16, bool OUT_BF16>
+__global__ __launch_bounds__(256) void row_general_kernel(RowParams p)
+{
+    __shared__ float scratch[4];
+    const int t = threadIdx.x;
+    const long long row = blockIdx.x;
+    const long long x0 = row * p.ldx, y0 = row * p.ldy;
+    const float inv_n = 1.0f / (float)p.cols;
+    float shift = 0.0f, scale = 1.0f;
+    if constexpr (OP == SOFTMAX) {
+        float m = -INFINITY;
+        for (int j = t; j < p.cols; j += 256) m = fmaxf(m, load1<IN_BF16>(p.x, x0 + j));
+        shift = row_reduce<256, true>(m, scratch, 0, t);
+        float s = 0.0f;
+        for (int j = t; j < p.cols; j += 256) s += expf(load1<IN_BF16>(p.x, x0 + j) - shift);
+        scale = 1.0f / row_reduce<256, false>(s, scratch, 0, t);
+        for (int j = t; j < p.cols; j += 256) store1<OUT_BF16>(p.y, y0 + j, expf(load1<IN_BF16>(p.x, x0 + j) - shift) * scale);
+        return;
+    } else if constexpr (OP == LAYERNORM) {
+        float s = 0.0f;
+        for (int j = t; j < p.cols; j += 256) s += load1<IN_BF16>(p.x, x0 + j);
+        shift = row_reduce<256, false>(s, scratch, 0, t) * inv_n;
+        float q = 0.0f;
+        for (int j = t; j < p.cols; j += 256) {
+            const float d = load1<IN_BF16>(p.x, x0 + j) - shift;
+            q += d * d;
+        }
+        scale = 1.0f / sqrtf(row_reduce<256, false>(q, scratch, 0, t) * inv_n + p.eps);
+    } else {
+        float q = 0.0f;
+        for (int j = t; j < p.cols; j += 256) {
+            const float a = load1<IN_BF16>(p.x, x0 + j);
+            q += a * a;
+        }
+        scale = 1.0f / sqrtf(row_reduce<256, false>(q, scratch, 0, t) * inv_n + p.eps);
+    }
+    for (int j = t; j < p.cols; j += 256) {
+        float o = (load1<IN_BF16>(p.x, x0 + j) - shift) * scale;
+        if (p.gamma) o *= load1<IN_BF16>(p.gamma, j);
+        if (OP == LAYERNORM && p.beta) o += load1<IN_BF16>(p.beta, j);
+        store1<OUT_BF16>(p.y, y0 + j, o);
+    }
+}
+
+bool aligned(const void *p, uintptr_t a) { return ((uintptr_t)p % a) == 0; }
+
+template <int OP, bool IB, bool OB>
+hipError_t launch_row(const RowParams &p, hipStream_t stream)
+{
+    constexpr int EPC = Chunk<IB>::EPC;
+    const int isz = IB ? 2 : 4, osz = OB ? 2 : 4;
+    const bool vec = p.cols % EPC == 0 && aligned(p.x, 16) && (p.ldx * isz) % 16 == 0 && aligned(p.y, (uintptr_t)EPC * osz) &&
+                     p.ldy % EPC == 0 && (!p.gamma || aligned(p.gamma, 16)) && (!p.beta || aligned(p.beta, 16)) &&
+                     p.rows <= 0x7fffffffLL;
+    const int nchunks = p.cols / EPC;
+    if (vec && nchunks <= 64 * MAXC)
+        hipLaunchKernelGGL((row_kernel<OP, IB, OB, 64>), dim3((unsigned)((p.rows + 3) / 4)), dim3(256), 0, stream, p);
+    else if (vec && nchunks <= 256 * MAXC)
+        hipLaunchKernelGGL((row_kernel<OP, IB, OB, 256>), dim3((unsigned)p.rows), dim3(256), 0, stream, p);
+    else if (vec && nchunks <= 1024 * MAXC)
+        hipLaunchKernelGGL((row_kernel<OP, IB, OB, 1024>), dim3((unsigned)p.rows), dim3(1024), 0, stream, p);
+    else
+        hipLaunchKernelGGL((row_general_kernel<OP, IB, OB>), dim3((unsigned)p.rows), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+template <int OP>
+xp_status row_entry(int64_t rows, int64_t cols, const void *x, xp_dtype x_type, int64_t ldx, const void *gamma,
+                    const void *beta, float eps, void *y, xp_dtype y_type, int64_t ldy, void *stream)
+{
+    if (rows < 0 || cols < 0) return XP_ERR_SHAPE;
+    if ((x_type != XP_F32 && x_type != XP_BF16) || (y_type != XP_F32 && y_type != XP_BF16)) return XP_ERR_UNSUPPORTED;
+    if (OP != SOFTMAX && (!(eps >= 0.0f) || eps - eps != 0.0f)) return XP_ERR_UNSUPPORTED;     // negative, NaN or infinite
+    if (rows == 0 || cols == 0) return XP_OK;
+    if (ldx < cols || ldy < cols) return XP_ERR_STRIDE;
+    if (!x || !y) return XP_ERR_NULL;
+    if (cols > 0x7fffffffLL || rows > 0x7fffffffLL) return XP_ERR_SHAPE;
+    const int isz = x_type == XP_BF16 ? 2 : 4, osz = y_type == XP_BF16 ? 2 : 4;
+    if (!aligned(x, isz) || !aligned(y, osz) || (gamma && !aligned(gamma, isz)) || (beta && !aligned(beta, isz))) return XP_ERR_ALIGN;
+    RowParams p;
+    p.x = x; p.gamma = gamma; p.beta = beta; p.y = y;
+    p.rows = rows; p.ldx = ldx; p.ldy = ldy; p.cols = (int)cols; p.eps = eps;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if (x_type == XP_BF16) e = y_type == XP_BF16 ? launch_row<OP, true, true>(p, s) : launch_row<OP, true, false>(p, s);
+    else e = y_type == XP_BF16 ? launch_row<OP, false, true>(p, s) : launch_row<OP, false, false>(p, s);
+    return e == hipSuccess ? XP_OK : XP_ERR_LAUNCH;
+}
+
+// ------------------------------------------------------------------------------ element-wise operators
+__device__ __forceinline__ float unary_apply(int op, float v)
+{
+    switch (op) {
+    case XP_RELU: return fmaxf(v, 0.0f);
+    // 1 + erf(z) cancels for z < 0: the complementary error function keeps the relative accuracy there
+    case XP_GELU: return v >= 0.0f ? 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)) : 0.5f * v * erfcf(-v * 0.70710678118654752f);
+    case XP_SIGMOID: return 1.0f / (1.0f + expf(-v));
+    default: return v > 0.0f ? 1.0f : (v < 0.0f ? -1.0f : 0.0f);
+    }
+}
+
+struct PointParams {
+    const void *a, *b;
+    void *y;
+    long long n;
+    int op;                                                 // unary operator, or -1 for a + b
+};
+
+template <bool IB, bool OB, bool VEC>
+__global__ __launch_bounds__(256) void point_kernel(PointParams p)
+{
+    constexpr int EPC = Chunk<IB>::EPC;
+    const long long tid = (long long)blockIdx.x * 256 + threadIdx.x, nthreads = (long long)gridDim.x * 256;
+    if constexpr (VEC) {
+        const long long chunks = p.n / EPC;
+        for (long long c = tid; c < chunks; c += nthreads) {
+            float v[EPC], o[EPC];
+            Chunk<IB>::load(p.a, c, v);
+            if (p.op < 0) {
+                float w[EPC];
+                Chunk<IB>::load(p.b, c, w);
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) o[e] = v[e] + w[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) o[e] = unary_apply(p.op, v[e]);
+            }
+            store_chunk<OB, EPC>(p.y, c * EPC, o);
+        }
+        for (long long i = chunks * EPC + tid; i < p.n; i += nthreads) {
+            const float v = load1<IB>(p.a, i);
+            store1<OB>(p.y, i, p.op < 0 ? v + load1<IB>(p.b, i) : unary_apply(p.op, v));
+        }
+    } else {
+        for (long long i = tid; i < p.n; i += nthreads) {
+            const float v = load1<IB>(p.a, i);
+            store1<OB>(p.y, i, p.op < 0 ? v + load1<IB>(p.b, i) : unary_apply(p.op, v));
+        }
+    }
+}
+
+xp_status point_entry(int op, int64_t n, const void *a, const void *b, xp_dtype x_type, void *y, xp_dtype y_type, void *stream)
+{
+    if (n < 0) return XP_ERR_SHAPE;
+    if ((x_type != XP_F32 && x_type != XP_BF16) || (y_type != XP_F32 && y_type != XP_BF16)) return XP_ERR_UNSUPPORTED;
+    if (op > XP_SIGN) return XP_ERR_UNSUPPORTED;
+    if (n == 0) return XP_OK;
+    if (!a || !y || (op < 0 && !b)) return XP_ERR_NULL;
+    const int isz = x_type == XP_BF16 ? 2 : 4, osz = y_type == XP_BF16 ? 2 : 4;
+    if (!aligned(a, isz) || !aligned(y, osz) || (op < 0 && !aligned(b, isz))) return XP_ERR_ALIGN;
+    PointParams p;
+    p.a = a; p.b = b; p.y = y; p.n = n; p.op = op;
+    const int epc = x_type == XP_BF16 ? 8 : 4;
+    const bool vec = aligned(a, 16) && (op >= 0 || aligned(b, 16)) && aligned(y, (uintptr_t)epc * osz);
+    const long long work = vec ? (n + epc - 1) / epc : n;
+    long long blocks = (work + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;               // grid-stride beyond 32 workgroups per compute unit
+    const dim3 grid((unsigned)blocks), block(256);
+    hipStream_t s = (hipStream_t)stream;
+#define XP_POINT(IB, OB)                                                                              \
+    do {                                                                                              \
+        if (vec) hipLaunchKernelGGL((point_kernel<IB, OB, true>), grid, block, 0, s, p);              \
+        else hipLaunchKernelGGL((point_kernel<IB, OB, false>), grid, block, 0, s, p);                 \
+    } while (0)
+    if (x_type == XP_BF16) { if (y_type == XP_BF16) XP_POINT(true, true); else XP_POINT(true, false); }
+    else { if (y_type == XP_BF16) XP_POINT(false, true); else XP_POINT(false, false); }
+#undef XP_POINT
+    return hipGetLastError() == hipSuccess ? XP_OK : XP_ERR_LAUNCH;
+}
+
+// ---------------------------------------------------------------------------------------- pooling
+struct PoolParams {
+    const void *x;
+    void *y;
+    int op;
+    long long total;                                        // work items: output pixels x channel chunks (or channels)
+    int H, W, C, R, S, P, Q, sh, sw, ph, pw;
+};
+
+// one work item = one output pixel and EPC consecutive channels (VEC) or one channel
+template <bool IB, bool OB, bool VEC>
+__global__ __launch_bounds__(256) void pool_kernel(PoolParams p)
+{
+    constexpr int EPC = VEC ? Chunk<IB>::EPC : 1;
+    const int cc = p.C / EPC;                               // channel groups per pixel
+    for (long long w = (long long)blockIdx.x * 256 + threadIdx.x; w < p.total; w += (long long)gridDim.x * 256) {
+        const int cg = (int)(w % cc);
+        long long pix = w / cc;
+        const int q = (int)(pix % p.Q);
+        pix /= p.Q;
+        const int op_ = (int)(pix % p.P);
+        const long long n = pix / p.P;
+        float acc[EPC];
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[e] = 0.0f;
+        int inside = 0;
+        for (int r = 0; r < p.R; ++r) {
+            const int h = op_ * p.sh + r - p.ph;
+            if (h < 0 || h >= p.H) continue;
+            for (int s = 0; s < p.S; ++s) {
+                const int x = q * p.sw + s - p.pw;
+                if (x < 0 || x >= p.W) continue;
+                const long long pixel = (n * p.H + h) * p.W + x;
+                float v[EPC];
+                if constexpr (VEC) Chunk<IB>::load(p.x, pixel * cc + cg, v);
+                else v[0] = load1<IB>(p.x, pixel * p.C + cg);
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) {
+                    if (inside == 0) acc[e] = v[e];
+                    else if (p.op == XP_POOL_MAX) acc[e] = fmaxf(acc[e], v[e]);
+                    else if (p.op == XP_POOL_MIN) acc[e] = fminf(acc[e], v[e]);
+                    else acc[e] += v[e];
+                }
+                ++inside;
+            }
+        }
+        if (p.op == XP_POOL_AVG && inside > 0) {
+            const float inv = 1.0f / (float)inside;
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) acc[e] *= inv;
+        }
+        if constexpr (VEC) store_chunk<OB, EPC>(p.y, w * EPC, acc);
+        else store1<OB>(p.y, w, acc[0]);
+    }
+}
+
+}  // namespace
+}  // namespace xp
+
+using namespace xp;
+
+extern "C" {
+
+xp_status xp_softmax(int64_t rows, int64_t cols, const void *x, xp_dtype x_type, int64_t ldx,
+                     void *y, xp_dtype y_type, int64_t ldy, void *stream)
+{
+    return row_entry<SOFTMAX>(rows, cols, x, x_type, ldx, nullptr, nullptr, 0.0f, y, y_type, ldy, stream);
+}
+
+xp_status xp_layernorm(int64_t rows, int64_t cols, const void *x, xp_dtype x_type, int64_t ldx,
+                       const void *gamma, const void *beta, float eps, void *y, xp_dtype y_type, int64_t ldy, void *stream)
+{
+    return row_entry<LAYERNORM>(rows, cols, x, x_type, ldx, gamma, beta, eps, y, y_type, ldy, stream);
+}
+
+xp_status xp_rmsnorm(int64_t rows, int64_t cols, const void *x, xp_dtype x_type, int64_t ldx,
+                     const void *gamma, float eps, void *y, xp_dtype y_type, int64_t ldy, void *stream)
+{
+    return row_entry<RMSNORM>(rows, cols, x, x_type, ldx, gamma, nullptr, eps, y, y_type, ldy, stream);
+}
+
+xp_status xp_unary(xp_unary_op op, int64_t n, const void *x, xp_dtype x_type, void *y, xp_dtype y_type, void *stream)
+{
+    if (op < XP_RELU || op > XP_SIGN) return XP_ERR_UNSUPPORTED;
+    return point_entry((int)op, n, x, nullptr, x_type, y, y_type, stream);
+}
+
+xp_status xp_add(int64_t n, const void *a, const void *b, xp_dtype type, void *y, xp_dtype y_type, void *stream)
+{
+    return point_entry(-1, n, a, b, type, y, y_type, stream);
+}
+
+xp_status xp_pool2d_nhwc(xp_pool_op op, int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S,
+                         int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                         const void *x, xp_dtype x_type, void *y, xp_dtype y_type, void *stream)
+{
+    if (N < 0 || H < 0 || W < 0 || C < 0) return XP_ERR_SHAPE;
+    if (R <= 0 || S <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return XP_ERR_SHAPE;
+    if (op < XP_POOL_MAX || op > XP_POOL_SUM) return XP_ERR_UNSUPPORTED;
+    if ((x_type != XP_F32 && x_type != XP_BF16) || (y_type != XP_F32 && y_type != XP_BF16)) return XP_ERR_UNSUPPORTED;
+    if (H + 2 * pad_h < R || W + 2 * pad_w < S) return XP_OK;                // empty output
+    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1, Q = (W + 2 * pad_w - S) / stride_w + 1;
+    if (N == 0 || C == 0) return XP_OK;
+    if (!x || !y) return XP_ERR_NULL;
+    const int isz = x_type == XP_BF16 ? 2 : 4, osz = y_type == XP_BF16 ? 2 : 4;
+    if (!aligned(x, isz) || !aligned(y, osz)) return XP_ERR_ALIGN;
+    const int64_t lim = 0x7fffffffLL;
+    if (H > lim || W > lim || C > lim || R > lim || S > lim || stride_h > lim || stride_w > lim || pad_h > lim || pad_w > lim)
+        return XP_ERR_SHAPE;
+    const int epc = x_type == XP_BF16 ? 8 : 4;
+    const bool vec = C % epc == 0 && aligned(x, 16) && aligned(y, (uintptr_t)epc * osz);
+    PoolParams p;
+    p.x = x; p.y = y; p.op = (int)op;
+    p.total = N * P * Q * (vec ? C / epc : C);
+    p.H = (int)H; p.W = (int)W; p.C = (int)C; p.R = (int)R; p.S = (int)S; p.P = (int)P; p.Q = (int)Q;
+    p.sh = (int)stride_h; p.sw = (int)stride_w; p.ph = (int)pad_h; p.pw = (int)pad_w;
+    long long blocks = (p.total + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    const dim3 grid((unsigned)blocks), block(256);
+    hipStream_t s = (hipStream_t)stream;
+#define XP_POOL(IB, OB)                                                                             \
+    do {                                                                                            \
+        if (vec) hipLaunchKernelGGL((pool_kernel<IB, OB, true>), grid, block, 0, s, p);             \
+        else hipLaunchKernelGGL((pool_kernel<IB, OB, false>), grid, block, 0, s, p);                \
+    } while (0)
+    if (x_type == XP_BF16) { if (y_type == XP_BF16) XP_POOL(true, true); else XP_POOL(true, false); }
+    else { if (y_type == XP_BF16) XP_POOL(false, true); else XP_POOL(false, false); }
+#undef XP_POOL
+    return hipGetLastError() == hipSuccess ? XP_OK : XP_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -44,6 +44,12 @@ _lib.xp_tune_workspace_bytes.restype = C.c_size_t
 _lib.xp_tune_save.argtypes = [C.c_char_p]
 _lib.xp_tune_load.argtypes = [C.c_char_p]
 _lib.xp_tune_clear.restype = None
+_lib.xp_softmax.argtypes = [_i64, _i64, _vp, _i, _i64, _vp, _i, _i64, _vp]
+_lib.xp_layernorm.argtypes = [_i64, _i64, _vp, _i, _i64, _vp, _vp, _f, _vp, _i, _i64, _vp]
+_lib.xp_rmsnorm.argtypes = [_i64, _i64, _vp, _i, _i64, _vp, _f, _vp, _i, _i64, _vp]
+_lib.xp_unary.argtypes = [_i, _i64, _vp, _i, _vp, _i, _vp]
+_lib.xp_add.argtypes = [_i64, _vp, _vp, _i, _vp, _i, _vp]
+_lib.xp_pool2d_nhwc.argtypes = [_i] + [_i64] * 10 + [_vp, _i, _vp, _i, _vp]
 _lib.xp_num_configs.argtypes = [_i, _i]
 _lib.xp_describe_config.argtypes = [_i, _i, _i, C.c_char_p, C.c_size_t]
 _lib.xp_force_config.argtypes = [_i, _i, _i]
@@ -52,7 +58,8 @@ _lib.xp_status_string.argtypes = [_i]
 _lib.xp_status_string.restype = C.c_char_p
 _lib.xp_version.restype = C.c_char_p
 for _name in ("xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_attention", "xp_tune_gemm", "xp_tune_gemm_batched",
-              "xp_tune_conv2d_nhwc", "xp_tune_save", "xp_tune_load", "xp_tune_count", "xp_num_configs", "xp_describe_config",
+              "xp_tune_conv2d_nhwc", "xp_tune_save", "xp_tune_load", "xp_tune_count", "xp_softmax", "xp_layernorm",
+              "xp_rmsnorm", "xp_unary", "xp_add", "xp_pool2d_nhwc", "xp_num_configs", "xp_describe_config",
               "xp_force_config", "xp_last_config"):
     getattr(_lib, _name).restype = _i
 
@@ -179,6 +186,38 @@ def xp_tune_clear() -> None:
 
 def xp_tune_count() -> int:
     return _lib.xp_tune_count()
+
+
+UNARY = {"relu": 0, "gelu": 1, "sigmoid": 2, "sign": 3}
+POOL = {"max": 0, "avg": 1, "min": 2, "sum": 3}
+
+
+def xp_softmax(rows, cols, x, ldx, y, ldy, stream=None, x_type=None, y_type=None):
+    """Row softmax on the GPU (see include/xp.h: xp_softmax)."""
+    _check(_lib.xp_softmax(rows, cols, _ptr(x), _dt(x, x_type), ldx, _ptr(y), _dt(y, y_type), ldy, _stream(stream)))
+
+
+def xp_layernorm(rows, cols, x, ldx, gamma, beta, eps, y, ldy, stream=None, x_type=None, y_type=None):
+    _check(_lib.xp_layernorm(rows, cols, _ptr(x), _dt(x, x_type), ldx, _ptr(gamma), _ptr(beta), eps,
+                             _ptr(y), _dt(y, y_type), ldy, _stream(stream)))
+
+
+def xp_rmsnorm(rows, cols, x, ldx, gamma, eps, y, ldy, stream=None, x_type=None, y_type=None):
+    _check(_lib.xp_rmsnorm(rows, cols, _ptr(x), _dt(x, x_type), ldx, _ptr(gamma), eps, _ptr(y), _dt(y, y_type), ldy,
+                           _stream(stream)))
+
+
+def xp_unary(op, n, x, y, stream=None, x_type=None, y_type=None):
+    _check(_lib.xp_unary(UNARY.get(op, op), n, _ptr(x), _dt(x, x_type), _ptr(y), _dt(y, y_type), _stream(stream)))
+
+
+def xp_add(n, a, b, y, stream=None, x_type=None, y_type=None):
+    _check(_lib.xp_add(n, _ptr(a), _ptr(b), _dt(a, x_type), _ptr(y), _dt(y, y_type), _stream(stream)))
+
+
+def xp_pool2d_nhwc(op, N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w, x, y, stream=None, x_type=None, y_type=None):
+    _check(_lib.xp_pool2d_nhwc(POOL.get(op, op), N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w,
+                               _ptr(x), _dt(x, x_type), _ptr(y), _dt(y, y_type), _stream(stream)))
 
 
 def xp_num_configs(op: int, in_type) -> int:

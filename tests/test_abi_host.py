@@ -204,6 +204,33 @@ def test_tune_validation(lib):
     assert xp.xp_tune_count() == 0
 
 
+def test_memory_bound_operator_validation(lib):
+    # every call here must be turned away (or be empty) on the host: the pointers are fake
+    def soft(rows=2, cols=8, x=64, xt=0, ldx=8, y=64, yt=0, ldy=8):
+        return lib.xp_softmax(rows, cols, x, xt, ldx, y, yt, ldy, None)
+    assert soft(rows=-1) == 2
+    assert soft(ldx=7) == 3 and soft(ldy=7) == 3
+    assert soft(x=None) == 1 and soft(y=None) == 1
+    assert soft(xt=2) == 5 and soft(yt=3) == 5
+    assert soft(x=66, xt=0) == 4 and soft(x=65, xt=1) == 4
+    assert soft(rows=0, x=None, y=None) == 0 and soft(cols=0, x=None, y=None, ldx=0, ldy=0) == 0
+    assert lib.xp_layernorm(2, 8, 64, 0, 8, None, None, -1.0, 64, 0, 8, None) == 5       # negative eps
+    assert lib.xp_layernorm(2, 8, 64, 0, 8, 66, None, 1e-5, 64, 0, 8, None) == 4        # gamma misaligned
+    assert lib.xp_rmsnorm(2, 8, 64, 0, 8, None, float("inf"), 64, 0, 8, None) == 5
+    assert lib.xp_unary(7, 4, 64, 0, 64, 0, None) == 5
+    assert lib.xp_unary(0, -1, 64, 0, 64, 0, None) == 2
+    assert lib.xp_unary(0, 4, None, 0, 64, 0, None) == 1
+    assert lib.xp_unary(0, 0, None, 0, None, 0, None) == 0
+    assert lib.xp_add(4, 64, None, 0, 64, 0, None) == 1
+    assert lib.xp_add(4, 64, 64, 2, 64, 0, None) == 5
+    def pool(op=0, N=1, H=4, W=4, C=8, R=2, S=2, sh=2, sw=2, ph=0, pw=0, x=64, xt=0, y=64, yt=0):
+        return lib.xp_pool2d_nhwc(op, N, H, W, C, R, S, sh, sw, ph, pw, x, xt, y, yt, None)
+    assert pool(op=4) == 5 and pool(R=0) == 2 and pool(sh=0) == 2 and pool(ph=-1) == 2 and pool(N=-1) == 2
+    assert pool(x=None) == 1 and pool(xt=2) == 5
+    assert pool(H=1, W=1, x=None, y=None) == 0                # window larger than the image: empty
+    assert pool(C=0, x=None, y=None) == 0
+
+
 def test_entry_points_resolve_their_builders():
     # build() compiles for minutes, so it is not run here; what broke once is the lookup of the
     # oracle's build module behind the package attribute of the same name
