@@ -27,9 +27,12 @@ __device__ __forceinline__ unsigned short to_bf16(float v) { return (unsigned sh
 // EPC elements per 16-byte input chunk: 4 fp32 or 8 bf16
 template <bool BF16> struct Chunk {
     static constexpr int EPC = BF16 ? 8 : 4;
+    // STREAM: data that is read exactly once (the operand itself) bypasses the caches' retention;
+    // small vectors that every row needs again (gamma, beta) and pooling windows, which overlap, do not
+    template <bool STREAM = true>
     __device__ static __forceinline__ void load(const void *p, long long chunk, float (&v)[EPC])
     {
-        const u32x4 w = *((const u32x4 *)p + chunk);
+        const u32x4 w = STREAM ? __builtin_nontemporal_load((const u32x4 *)p + chunk) : *((const u32x4 *)p + chunk);
         if constexpr (BF16) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) { v[2 * i] = bf16_lo(w[i]); v[2 * i + 1] = bf16_hi(w[i]); }
@@ -46,13 +49,13 @@ template <bool OUT_BF16, int EPC> __device__ __forceinline__ void store_chunk(vo
         unsigned w[EPC / 2];
 #pragma unroll
         for (int i = 0; i < EPC / 2; ++i) w[i] = pack_bf16(v[2 * i], v[2 * i + 1]);
-        if constexpr (EPC == 8) *(u32x4 *)((unsigned short *)p + e0) = u32x4{w[0], w[1], w[2], w[3]};
-        else *(u32x2 *)((unsigned short *)p + e0) = u32x2{w[0], w[1]};
+        if constexpr (EPC == 8) __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, (u32x4 *)((unsigned short *)p + e0));
+        else __builtin_nontemporal_store(u32x2{w[0], w[1]}, (u32x2 *)((unsigned short *)p + e0));
     } else {
 #pragma unroll
         for (int i = 0; i < EPC; i += 4)
-            *(u32x4 *)((float *)p + e0 + i) = u32x4{__float_as_uint(v[i]), __float_as_uint(v[i + 1]), __float_as_uint(v[i + 2]),
-                                                    __float_as_uint(v[i + 3])};
+            __builtin_nontemporal_store(u32x4{__float_as_uint(v[i]), __float_as_uint(v[i + 1]), __float_as_uint(v[i + 2]),
+                                              __float_as_uint(v[i + 3])}, (u32x4 *)((float *)p + e0 + i));
     }
 }
 template <bool BF16> __device__ __forceinline__ float load1(const void *p, long long i)
@@ -98,13 +101,12 @@ __device__ __forceinline__ float row_reduce(float v, float *scratch, int group, 
     return v;
 }
 
-constexpr int MAXC = 8;                                    // 16-byte chunks of a row that one thread keeps in registers
-
-// TPR threads per row; the workgroup holds BLOCK / TPR rows.  cols is a multiple of EPC, rows start
-// 16-byte aligned, cols / EPC <= TPR * MAXC.
-template <int OP, bool IN_BF16, bool OUT_BF16, int TPR>
+// TPR threads per row, each holding up to NC chunks; the workgroup holds BLOCK / TPR rows.  cols is a
+// multiple of EPC, rows start 16-byte aligned, cols / EPC <= TPR * NC.
+template <int OP, bool IN_BF16, bool OUT_BF16, int TPR, int NC>
 __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void row_kernel(RowParams p)
 {
+    constexpr int MAXC = NC;                               // 16-byte chunks of the row that one thread keeps in registers
     constexpr int BLOCK = TPR < 256 ? 256 : TPR, RPB = BLOCK / TPR, EPC = Chunk<IN_BF16>::EPC;
     __shared__ float scratch[BLOCK / 64];
     const int group = threadIdx.x / TPR, t = threadIdx.x % TPR;
@@ -171,25 +173,34 @@ __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void row_kernel(RowParams p)
         scale = 1.0f / sqrtf(q + p.eps);
     }
     if (!live) return;
+    const float offset = -shift * scale;                   // y = x * scale + offset [* gamma + beta]
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
         const int ch = t + c * TPR;
         if (ch >= nchunks) continue;
         float o[EPC];
 #pragma unroll
-        for (int e = 0; e < EPC; ++e) o[e] = (v[c][e] - shift) * scale;
+        for (int e = 0; e < EPC; ++e) o[e] = OP == LAYERNORM ? __builtin_fmaf(v[c][e], scale, offset) : v[c][e] * scale;
         if constexpr (OP != SOFTMAX) {
-            if (p.gamma) {
-                float g[EPC];
-                Chunk<IN_BF16>::load(p.gamma, ch, g);
+            if (p.gamma && OP == LAYERNORM && p.beta) {
+                float g[EPC], b[EPC];
+                Chunk<IN_BF16>::template load<false>(p.gamma, ch, g);
+                Chunk<IN_BF16>::template load<false>(p.beta, ch, b);
 #pragma unroll
-                for (int e = 0; e < EPC; ++e) o[e] *= g[e];
-            }
-            if (OP == LAYERNORM && p.beta) {
-                float b[EPC];
-                Chunk<IN_BF16>::load(p.beta, ch, b);
+                for (int e = 0; e < EPC; ++e) o[e] = __builtin_fmaf(o[e], g[e], b[e]);
+            } else {
+                if (p.gamma) {
+                    float g[EPC];
+                    Chunk<IN_BF16>::template load<false>(p.gamma, ch, g);
 #pragma unroll
-                for (int e = 0; e < EPC; ++e) o[e] += b[e];
+                    for (int e = 0; e < EPC; ++e) o[e] *= g[e];
+                }
+                if (OP == LAYERNORM && p.beta) {
+                    float b[EPC];
+                    Chunk<IN_BF16>::template load<false>(p.beta, ch, b);
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e) o[e] += b[e];
+                }
             }
         }
         store_chunk<OUT_BF16, EPC>(p.y, row * p.ldy + (long long)ch * EPC, o);
@@ -253,14 +264,17 @@ hipError_t launch_row(const RowParams &p, hipStream_t stream)
                      p.ldy % EPC == 0 && (!p.gamma || aligned(p.gamma, 16)) && (!p.beta || aligned(p.beta, 16)) &&
                      p.rows <= 0x7fffffffLL;
     const int nchunks = p.cols / EPC;
-    if (vec && nchunks <= 64 * MAXC)
-        hipLaunchKernelGGL((row_kernel<OP, IB, OB, 64>), dim3((unsigned)((p.rows + 3) / 4)), dim3(256), 0, stream, p);
-    else if (vec && nchunks <= 256 * MAXC)
-        hipLaunchKernelGGL((row_kernel<OP, IB, OB, 256>), dim3((unsigned)p.rows), dim3(256), 0, stream, p);
-    else if (vec && nchunks <= 1024 * MAXC)
-        hipLaunchKernelGGL((row_kernel<OP, IB, OB, 1024>), dim3((unsigned)p.rows), dim3(1024), 0, stream, p);
-    else
-        hipLaunchKernelGGL((row_general_kernel<OP, IB, OB>), dim3((unsigned)p.rows), dim3(256), 0, stream, p);
+    const dim3 g4((unsigned)((p.rows + 3) / 4)), g1((unsigned)p.rows);
+    // the fewest threads per row that can hold it, and no more register chunks than the row needs
+    if (vec && nchunks <= 64 * 1) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 64, 1>), g4, dim3(256), 0, stream, p);
+    else if (vec && nchunks <= 64 * 2) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 64, 2>), g4, dim3(256), 0, stream, p);
+    else if (vec && nchunks <= 64 * 4) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 64, 4>), g4, dim3(256), 0, stream, p);
+    else if (vec && nchunks <= 64 * 8) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 64, 8>), g4, dim3(256), 0, stream, p);
+    else if (vec && nchunks <= 256 * 4) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 256, 4>), g1, dim3(256), 0, stream, p);
+    else if (vec && nchunks <= 256 * 8) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 256, 8>), g1, dim3(256), 0, stream, p);
+    else if (vec && nchunks <= 1024 * 4) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 1024, 4>), g1, dim3(1024), 0, stream, p);
+    else if (vec && nchunks <= 1024 * 8) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 1024, 8>), g1, dim3(1024), 0, stream, p);
+    else hipLaunchKernelGGL((row_general_kernel<OP, IB, OB>), g1, dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -288,13 +302,36 @@ xp_status row_entry(int64_t rows, int64_t cols, const void *x, xp_dtype x_type, 
 }
 
 // ------------------------------------------------------------------------------ element-wise operators
+// erfc(z) for z >= 0 as t * exp(-z*z + p(t)), t = 1 / (1 + z/2): p is the degree-8 fit printed by
+// fit_erfc.py beside this file (relative error about 1e-6 for z <= 3, 4e-6 for z <= 6, set by the
+// fp32 rounding of the exponent).  A dozen instructions where the library erfcf takes several times
+// that, which is what makes GELU memory-bound rather than ALU-bound.
+__device__ __forceinline__ float erfc_pos(float z)
+{
+    const float t = __builtin_amdgcn_rcpf(1.0f + 0.5f * z);
+    float p = 0.0833144188f;
+    p = __builtin_fmaf(p, t, -0.58055824f);
+    p = __builtin_fmaf(p, t, 1.53260946f);
+    p = __builtin_fmaf(p, t, -1.85293126f);
+    p = __builtin_fmaf(p, t, 0.904557347f);
+    p = __builtin_fmaf(p, t, -0.259300739f);
+    p = __builtin_fmaf(p, t, 0.44532609f);
+    p = __builtin_fmaf(p, t, 0.992125869f);
+    p = __builtin_fmaf(p, t, -1.26514339f);
+    return t * __expf(__builtin_fmaf(-z, z, p));
+}
+
 __device__ __forceinline__ float unary_apply(int op, float v)
 {
     switch (op) {
     case XP_RELU: return fmaxf(v, 0.0f);
-    // 1 + erf(z) cancels for z < 0: the complementary error function keeps the relative accuracy there
-    case XP_GELU: return v >= 0.0f ? 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)) : 0.5f * v * erfcf(-v * 0.70710678118654752f);
-    case XP_SIGMOID: return 1.0f / (1.0f + expf(-v));
+    case XP_GELU: {
+        // x * Phi(x), Phi(x) = erfc(-x / sqrt 2) / 2: for x < 0 directly (1 + erf would cancel there),
+        // for x >= 0 as 1 - Phi(-x)
+        const float h = 0.5f * erfc_pos(fabsf(v) * 0.70710678118654752f);
+        return v * (v < 0.0f ? h : 1.0f - h);
+    }
+    case XP_SIGMOID: return __builtin_amdgcn_rcpf(1.0f + __expf(-v));      // a few ulp; exp overflow gives 1/inf = 0, as it should
     default: return v > 0.0f ? 1.0f : (v < 0.0f ? -1.0f : 0.0f);
     }
 }
@@ -377,8 +414,9 @@ struct PoolParams {
     int H, W, C, R, S, P, Q, sh, sw, ph, pw;
 };
 
-// one work item = one output pixel and EPC consecutive channels (VEC) or one channel
-template <bool IB, bool OB, bool VEC>
+// one work item = one output pixel and EPC consecutive channels (VEC) or one channel.  WIN > 0: the
+// window is WIN x WIN, known at compile time, so that its loads are all issued before the first is used.
+template <bool IB, bool OB, bool VEC, int WIN>
 __global__ __launch_bounds__(256) void pool_kernel(PoolParams p)
 {
     constexpr int EPC = VEC ? Chunk<IB>::EPC : 1;
@@ -394,24 +432,47 @@ __global__ __launch_bounds__(256) void pool_kernel(PoolParams p)
 #pragma unroll
         for (int e = 0; e < EPC; ++e) acc[e] = 0.0f;
         int inside = 0;
-        for (int r = 0; r < p.R; ++r) {
-            const int h = op_ * p.sh + r - p.ph;
-            if (h < 0 || h >= p.H) continue;
-            for (int s = 0; s < p.S; ++s) {
-                const int x = q * p.sw + s - p.pw;
-                if (x < 0 || x >= p.W) continue;
-                const long long pixel = (n * p.H + h) * p.W + x;
-                float v[EPC];
-                if constexpr (VEC) Chunk<IB>::load(p.x, pixel * cc + cg, v);
-                else v[0] = load1<IB>(p.x, pixel * p.C + cg);
+        auto take = [&](const float (&v)[EPC]) {
 #pragma unroll
-                for (int e = 0; e < EPC; ++e) {
-                    if (inside == 0) acc[e] = v[e];
-                    else if (p.op == XP_POOL_MAX) acc[e] = fmaxf(acc[e], v[e]);
-                    else if (p.op == XP_POOL_MIN) acc[e] = fminf(acc[e], v[e]);
-                    else acc[e] += v[e];
+            for (int e = 0; e < EPC; ++e) {
+                if (inside == 0) acc[e] = v[e];
+                else if (p.op == XP_POOL_MAX) acc[e] = fmaxf(acc[e], v[e]);
+                else if (p.op == XP_POOL_MIN) acc[e] = fminf(acc[e], v[e]);
+                else acc[e] += v[e];
+            }
+            ++inside;
+        };
+        auto fetch = [&](int h, int x, float (&v)[EPC]) {
+            const long long pixel = (n * p.H + h) * p.W + x;
+            if constexpr (VEC) Chunk<IB>::template load<false>(p.x, pixel * cc + cg, v);
+            else v[0] = load1<IB>(p.x, pixel * p.C + cg);
+        };
+        if constexpr (WIN > 0) {
+            float v[WIN * WIN][EPC];
+            bool in[WIN * WIN];
+#pragma unroll
+            for (int r = 0; r < WIN; ++r)
+#pragma unroll
+                for (int s = 0; s < WIN; ++s) {
+                    const int h = op_ * p.sh + r - p.ph, x = q * p.sw + s - p.pw;
+                    in[r * WIN + s] = h >= 0 && h < p.H && x >= 0 && x < p.W;
+                    // positions outside the image load the nearest pixel inside (never used): no branch around a load
+                    fetch(min(max(h, 0), p.H - 1), min(max(x, 0), p.W - 1), v[r * WIN + s]);
                 }
-                ++inside;
+#pragma unroll
+            for (int i = 0; i < WIN * WIN; ++i)
+                if (in[i]) take(v[i]);
+        } else {
+            for (int r = 0; r < p.R; ++r) {
+                const int h = op_ * p.sh + r - p.ph;
+                if (h < 0 || h >= p.H) continue;
+                for (int s = 0; s < p.S; ++s) {
+                    const int x = q * p.sw + s - p.pw;
+                    if (x < 0 || x >= p.W) continue;
+                    float v[EPC];
+                    fetch(h, x, v);
+                    take(v);
+                }
             }
         }
         if (p.op == XP_POOL_AVG && inside > 0) {
@@ -488,10 +549,13 @@ xp_status xp_pool2d_nhwc(xp_pool_op op, int64_t N, int64_t H, int64_t W, int64_t
     if (blocks > 256 * 32) blocks = 256 * 32;
     const dim3 grid((unsigned)blocks), block(256);
     hipStream_t s = (hipStream_t)stream;
+    const int win = (R == S && (R == 2 || R == 3) && vec) ? (int)R : 0;
 #define XP_POOL(IB, OB)                                                                             \
     do {                                                                                            \
-        if (vec) hipLaunchKernelGGL((pool_kernel<IB, OB, true>), grid, block, 0, s, p);             \
-        else hipLaunchKernelGGL((pool_kernel<IB, OB, false>), grid, block, 0, s, p);                \
+        if (win == 3) hipLaunchKernelGGL((pool_kernel<IB, OB, true, 3>), grid, block, 0, s, p);     \
+        else if (win == 2) hipLaunchKernelGGL((pool_kernel<IB, OB, true, 2>), grid, block, 0, s, p); \
+        else if (vec) hipLaunchKernelGGL((pool_kernel<IB, OB, true, 0>), grid, block, 0, s, p);     \
+        else hipLaunchKernelGGL((pool_kernel<IB, OB, false, 0>), grid, block, 0, s, p);             \
     } while (0)
     if (x_type == XP_BF16) { if (y_type == XP_BF16) XP_POOL(true, true); else XP_POOL(true, false); }
     else { if (y_type == XP_BF16) XP_POOL(false, true); else XP_POOL(false, false); }
