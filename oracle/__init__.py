@@ -42,6 +42,8 @@ def lib() -> C.CDLL:
         L.oracle_unary.argtypes = [i, i64, vp, i, vp]
         L.oracle_add.argtypes = [i64, vp, vp, i, vp]
         L.oracle_pool2d_nhwc.argtypes = [i] + [i64] * 10 + [vp, i, vp]
+        L.oracle_depthwise_conv2d_nhwc.argtypes = [i64] * 10 + [vp, i, vp, i, i, vp]
+        L.oracle_depthwise_conv2d_nhwc.restype = i
         for f in (L.oracle_gemm_float, L.oracle_gemm_i8, L.oracle_gemm_float_batched,
                   L.oracle_conv2d_nhwc, L.oracle_attention, L.oracle_softmax, L.oracle_layernorm,
                   L.oracle_rmsnorm, L.oracle_unary, L.oracle_add, L.oracle_pool2d_nhwc, L.oracle_num_threads):
@@ -214,4 +216,13 @@ def pool2d_nhwc(op: str, x, *, N, H, W, C, R, S, stride=(1, 1), pad=(0, 0)) -> n
     ref = np.empty((N, P, Q, C), dtype=np.float64)
     _rc(lib().oracle_pool2d_nhwc(POOL[op], N, H, W, C, R, S, stride[0], stride[1], pad[0], pad[1], _ptr(x), _ftype(x),
                                  _ptr(ref)), "oracle_pool2d_nhwc")
+    return ref
+
+
+def depthwise_conv2d_nhwc(x, w, *, N, H, W, C, R, S, stride=(1, 1), pad=(0, 0), filter_layout="rsck") -> np.ndarray:
+    """fp64 reference of the depthwise NHWC convolution, dense N x P x Q x C."""
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    ref = np.empty((N, P, Q, C), dtype=np.float64)
+    _rc(lib().oracle_depthwise_conv2d_nhwc(N, H, W, C, R, S, stride[0], stride[1], pad[0], pad[1], _ptr(x), _ftype(x),
+                                           _ptr(w), _ftype(w), _FILTER[filter_layout], _ptr(ref)), "oracle_depthwise_conv2d_nhwc")
     return ref

@@ -118,6 +118,14 @@ int oracle_pool2d_nhwc(int op, int64_t N, int64_t H, int64_t W, int64_t C, int64
                        int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
                        const void *x, int x_type, double *ref);
 
+/* Depthwise convolution, NHWC (Table 5: Depthwise Conv): out[n,p,q,c] = sum_{r,s} in[n, p*sh + r - ph, q*sw + s - pw, c] * w(c,r,s),
+ * zero padding, no bias.  Filter layouts: ORACLE_KRSC  w(c,r,s) = w[(c*R + r)*S + s]  (channel-major),
+ * ORACLE_RSCK  w(c,r,s) = w[(r*S + s)*C + c]  (channel-minor). */
+int oracle_depthwise_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S,
+                                 int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                 const void *input, int in_type, const void *filter, int w_type, int w_layout,
+                                 double *ref);
+
 /* Number of OpenMP threads the loops above will use. */
 int oracle_num_threads(void);
 

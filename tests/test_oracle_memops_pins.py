@@ -195,3 +195,42 @@ def test_bad_arguments_are_refused(oracle):
     with pytest.raises(ValueError):
         oracle.pool2d_nhwc("max", x, N=1, H=2, W=2, C=2, R=0, S=1)
     assert oracle.softmax(x, rows=0, cols=4).shape == (0, 4)
+
+
+# --------------------------------------------------------------------------------- depthwise conv
+
+def test_depthwise_is_the_full_convolution_with_a_diagonal_filter(oracle):
+    # w_full(k,r,s,c) = w(c,r,s) if k == c else 0 turns the (already pinned) dense convolution into the depthwise one
+    N, H, W, C, R, S = 2, 6, 7, 5, 3, 2
+    x = _rand((N, H, W, C), 1)
+    w_crs = _rand((C, R, S), 2)
+    full = np.zeros((C, R, S, C), np.float32)
+    for c in range(C):
+        full[c, :, :, c] = w_crs[c]
+    kw = dict(stride=(2, 1), pad=(1, 1))
+    expect = oracle.conv2d_nhwc(x, full, N=N, H=H, W=W, Cin=C, Cout=C, R=R, S=S, filter_layout="krsc", **kw)
+    got = oracle.depthwise_conv2d_nhwc(x, w_crs, N=N, H=H, W=W, C=C, R=R, S=S, filter_layout="krsc", **kw)
+    np.testing.assert_allclose(got, expect, rtol=1e-14, atol=1e-15)
+    # the channel-minor filter layout holds the same numbers transposed
+    w_rsc = np.ascontiguousarray(w_crs.transpose(1, 2, 0))
+    np.testing.assert_array_equal(oracle.depthwise_conv2d_nhwc(x, w_rsc, N=N, H=H, W=W, C=C, R=R, S=S, filter_layout="rsck", **kw), got)
+
+
+def test_depthwise_closed_forms(oracle):
+    N, H, W, C = 1, 5, 6, 3
+    x = _rand((N, H, W, C), 1)
+    delta = np.zeros((3, 3, C), np.float32)
+    delta[1, 1, :] = [1.0, 2.0, -1.0]                      # centre tap, a different gain per channel
+    y = oracle.depthwise_conv2d_nhwc(x, delta, N=N, H=H, W=W, C=C, R=3, S=3, pad=(1, 1))
+    np.testing.assert_array_equal(y, x.astype(np.float64) * np.array([1.0, 2.0, -1.0]))
+    ones = np.ones((N, H, W, C), np.float32)
+    y = oracle.depthwise_conv2d_nhwc(ones, np.ones((3, 3, C), np.float32), N=N, H=H, W=W, C=C, R=3, S=3, pad=(1, 1))
+    assert y[0, 0, 0, 0] == 4 and y[0, 0, 3, 1] == 6 and y[0, 2, 2, 2] == 9
+    # channels do not mix: changing channel 0 of the input leaves the other outputs alone
+    x2 = x.copy()
+    x2[..., 0] += 1.0
+    w = _rand((3, 3, C), 2)
+    a = oracle.depthwise_conv2d_nhwc(x, w, N=N, H=H, W=W, C=C, R=3, S=3, pad=(1, 1))
+    b = oracle.depthwise_conv2d_nhwc(x2, w, N=N, H=H, W=W, C=C, R=3, S=3, pad=(1, 1))
+    np.testing.assert_array_equal(a[..., 1:], b[..., 1:])
+    assert not np.allclose(a[..., 0], b[..., 0])
