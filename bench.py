@@ -271,7 +271,13 @@ def main() -> int:
         rate("maxpool_bf16_64x112x112x64_3x3s2", (pn * ph_ * ph_ * pc + pn * 56 * 56 * pc) * 2,
              lambda: (lambda i: xp.xp_pool2d_nhwc("max", pn, ph_, ph_, pc, 3, 3, 2, 2, 1, 1, px[i], py[i]))(nxt4()),
              "4 rotating sets of 128 MB")
-        del px, py
+        dn, dh, dc = 32, 112, 64
+        py2 = [torch.empty(dn, dh, dh, dc, device="cuda", dtype=torch.bfloat16) for _ in range(4)]
+        dwf = (0.3 * torch.randn(3, 3, dc, device="cuda")).bfloat16()
+        rate("depthwise_bf16_32x112x112x64_3x3s1", 2 * dn * dh * dh * dc * 2,
+             lambda: (lambda i: xp.xp_depthwise_conv2d_nhwc(dn, dh, dh, dc, 3, 3, 1, 1, 1, 1, px[i], dwf, "rsck", py2[i]))(nxt4()),
+             "4 rotating sets of 103 MB")
+        del px, py, py2
         side["memory_bound"] = mem
         out["other_workloads"] = side
 

@@ -200,6 +200,18 @@ xp_status xp_pool2d_nhwc(xp_pool_op op, int64_t N, int64_t H, int64_t W, int64_t
                          int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
                          const void *x, xp_dtype x_type, void *y, xp_dtype y_type, void *stream);
 
+/* Depthwise 2-D convolution, NHWC (Table 5, "Depthwise Conv"): every channel has its own R x S filter,
+ *   y[n,p,q,c] = sum_{r<R, s<S} x[n, p*stride_h + r - pad_h, q*stride_w + s - pad_w, c] * w(c,r,s),
+ * zero padding, no bias; P, Q as for xp_conv2d_nhwc.  x is N x H x W x C contiguous, y is N x P x Q x C.
+ * Filter layouts: XP_FILTER_RSCK  w(c,r,s) = w[(r*S + s)*C + c]  (channel-minor: the fast, vectorised form),
+ *                 XP_FILTER_KRSC  w(c,r,s) = w[(c*R + r)*S + s]  (channel-major).
+ * x and w share a type (F32 or BF16); y is F32 or BF16; arithmetic fp32.  Memory-bound: one pass. */
+xp_status xp_depthwise_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S,
+                                   int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                   const void *x, xp_dtype x_type,
+                                   const void *w, xp_dtype w_type, xp_filter_layout w_layout,
+                                   void *y, xp_dtype y_type, void *stream);
+
 /*
  * Run-time parameter search: the brute-force intra-pass auto-tuning of the paper (Section 5.1) with
  * its reward (Eq. 3-4), inside the library.  xp_tune_* takes the arguments of the entry point it is

@@ -1,5 +1,6 @@
 // Memory-bound operators of the paper's benchmark (Table 5: Activation -- ReLU, Softmax, GeLU,
-// Sigmoid; Elementwise -- Add, Sign; Pooling -- Max/Avg/Min/SumPool; LLM -- LayerNorm, RMSNorm).
+// Sigmoid; Elementwise -- Add, Sign; Pooling -- Max/Avg/Min/SumPool; LLM -- LayerNorm, RMSNorm;
+// Convolution -- Depthwise Conv, which reuses nothing either).
 // Each reads its input once and writes its output once: the bound is HBM bandwidth, the matrix
 // cores have nothing to do.  Common shape of the kernels: 16-byte loads and stores, fp32
 // arithmetic whatever the storage type (fp32 or bf16, output rounded to nearest even), and for the
@@ -485,6 +486,82 @@ __global__ __launch_bounds__(256) void pool_kernel(PoolParams p)
     }
 }
 
+// ------------------------------------------------------------------------------- depthwise convolution
+// Same work decomposition as pooling (one output pixel x EPC channels per work item), with a weight
+// per (tap, channel).  WIN > 0: a WIN x WIN window with channel-minor weights, loads issued up front.
+struct DwParams {
+    const void *x, *w;
+    void *y;
+    long long total;
+    int H, W, C, R, S, P, Q, sh, sw, ph, pw;
+    int channel_minor;                                      // w(c,r,s) at (r*S + s)*C + c, else (c*R + r)*S + s
+};
+
+template <bool IB, bool OB, bool VEC, int WIN>
+__global__ __launch_bounds__(256) void depthwise_kernel(DwParams p)
+{
+    constexpr int EPC = VEC ? Chunk<IB>::EPC : 1;
+    const int cc = p.C / EPC;
+    for (long long wi = (long long)blockIdx.x * 256 + threadIdx.x; wi < p.total; wi += (long long)gridDim.x * 256) {
+        const int cg = (int)(wi % cc);
+        long long pix = wi / cc;
+        const int q = (int)(pix % p.Q);
+        pix /= p.Q;
+        const int op_ = (int)(pix % p.P);
+        const long long n = pix / p.P;
+        float acc[EPC];
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[e] = 0.0f;
+        auto fetch = [&](int h, int x, float (&v)[EPC]) {
+            const long long pixel = (n * p.H + h) * p.W + x;
+            if constexpr (VEC) Chunk<IB>::template load<false>(p.x, pixel * cc + cg, v);
+            else v[0] = load1<IB>(p.x, pixel * p.C + cg);
+        };
+        auto weights = [&](int r, int s, float (&g)[EPC]) {
+            if (p.channel_minor) {
+                if constexpr (VEC) Chunk<IB>::template load<false>(p.w, (long long)(r * p.S + s) * cc + cg, g);
+                else g[0] = load1<IB>(p.w, (long long)(r * p.S + s) * p.C + cg);
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) g[e] = load1<IB>(p.w, ((long long)(cg * EPC + e) * p.R + r) * p.S + s);
+            }
+        };
+        if constexpr (WIN > 0) {
+            float v[WIN * WIN][EPC], g[WIN * WIN][EPC];
+            bool in[WIN * WIN];
+#pragma unroll
+            for (int r = 0; r < WIN; ++r)
+#pragma unroll
+                for (int s = 0; s < WIN; ++s) {
+                    const int h = op_ * p.sh + r - p.ph, x = q * p.sw + s - p.pw;
+                    in[r * WIN + s] = h >= 0 && h < p.H && x >= 0 && x < p.W;
+                    fetch(min(max(h, 0), p.H - 1), min(max(x, 0), p.W - 1), v[r * WIN + s]);   // clamped: no branch around a load
+                    Chunk<IB>::template load<false>(p.w, (long long)(r * WIN + s) * cc + cg, g[r * WIN + s]);
+                }
+#pragma unroll
+            for (int i = 0; i < WIN * WIN; ++i)
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) acc[e] = __builtin_fmaf(in[i] ? v[i][e] : 0.0f, g[i][e], acc[e]);
+        } else {
+            for (int r = 0; r < p.R; ++r) {
+                const int h = op_ * p.sh + r - p.ph;
+                if (h < 0 || h >= p.H) continue;
+                for (int s = 0; s < p.S; ++s) {
+                    const int x = q * p.sw + s - p.pw;
+                    if (x < 0 || x >= p.W) continue;
+                    float v[EPC], g[EPC];
+                    fetch(h, x, v);
+                    weights(r, s, g);
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e) acc[e] = __builtin_fmaf(v[e], g[e], acc[e]);
+                }
+            }
+        }
+        if constexpr (VEC) store_chunk<OB, EPC>(p.y, wi * EPC, acc);
+        else store1<OB>(p.y, wi, acc[0]);
+    }
+}
+
 }  // namespace
 }  // namespace xp
 
@@ -560,6 +637,51 @@ xp_status xp_pool2d_nhwc(xp_pool_op op, int64_t N, int64_t H, int64_t W, int64_t
     if (x_type == XP_BF16) { if (y_type == XP_BF16) XP_POOL(true, true); else XP_POOL(true, false); }
     else { if (y_type == XP_BF16) XP_POOL(false, true); else XP_POOL(false, false); }
 #undef XP_POOL
+    return hipGetLastError() == hipSuccess ? XP_OK : XP_ERR_LAUNCH;
+}
+
+xp_status xp_depthwise_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S,
+                                   int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                   const void *x, xp_dtype x_type, const void *w, xp_dtype w_type, xp_filter_layout w_layout,
+                                   void *y, xp_dtype y_type, void *stream)
+{
+    if (N < 0 || H < 0 || W < 0 || C < 0) return XP_ERR_SHAPE;
+    if (R <= 0 || S <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return XP_ERR_SHAPE;
+    if (w_layout != XP_FILTER_KRSC && w_layout != XP_FILTER_RSCK) return XP_ERR_UNSUPPORTED;
+    if ((x_type != XP_F32 && x_type != XP_BF16) || w_type != x_type || (y_type != XP_F32 && y_type != XP_BF16)) return XP_ERR_UNSUPPORTED;
+    if (H + 2 * pad_h < R || W + 2 * pad_w < S) return XP_OK;                // empty output
+    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1, Q = (W + 2 * pad_w - S) / stride_w + 1;
+    if (N == 0 || C == 0) return XP_OK;
+    if (!x || !w || !y) return XP_ERR_NULL;
+    const int isz = x_type == XP_BF16 ? 2 : 4, osz = y_type == XP_BF16 ? 2 : 4;
+    if (!aligned(x, isz) || !aligned(w, isz) || !aligned(y, osz)) return XP_ERR_ALIGN;
+    const int64_t lim = 0x7fffffffLL;
+    if (H > lim || W > lim || C > lim || R > lim || S > lim || stride_h > lim || stride_w > lim || pad_h > lim || pad_w > lim ||
+        R * S > lim)
+        return XP_ERR_SHAPE;
+    const int epc = x_type == XP_BF16 ? 8 : 4;
+    const bool minor = w_layout == XP_FILTER_RSCK;
+    const bool vec = C % epc == 0 && aligned(x, 16) && aligned(y, (uintptr_t)epc * osz) && (!minor || aligned(w, 16));
+    DwParams p;
+    p.x = x; p.w = w; p.y = y;
+    p.total = N * P * Q * (vec ? C / epc : C);
+    p.H = (int)H; p.W = (int)W; p.C = (int)C; p.R = (int)R; p.S = (int)S; p.P = (int)P; p.Q = (int)Q;
+    p.sh = (int)stride_h; p.sw = (int)stride_w; p.ph = (int)pad_h; p.pw = (int)pad_w;
+    p.channel_minor = minor ? 1 : 0;
+    long long blocks = (p.total + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    const dim3 grid((unsigned)blocks), block(256);
+    hipStream_t s = (hipStream_t)stream;
+    const bool win3 = vec && minor && R == 3 && S == 3;
+#define XP_DW(IB, OB)                                                                                  \
+    do {                                                                                               \
+        if (win3) hipLaunchKernelGGL((depthwise_kernel<IB, OB, true, 3>), grid, block, 0, s, p);       \
+        else if (vec) hipLaunchKernelGGL((depthwise_kernel<IB, OB, true, 0>), grid, block, 0, s, p);   \
+        else hipLaunchKernelGGL((depthwise_kernel<IB, OB, false, 0>), grid, block, 0, s, p);           \
+    } while (0)
+    if (x_type == XP_BF16) { if (y_type == XP_BF16) XP_DW(true, true); else XP_DW(true, false); }
+    else { if (y_type == XP_BF16) XP_DW(false, true); else XP_DW(false, false); }
+#undef XP_DW
     return hipGetLastError() == hipSuccess ? XP_OK : XP_ERR_LAUNCH;
 }
 

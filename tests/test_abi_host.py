@@ -229,6 +229,13 @@ def test_memory_bound_operator_validation(lib):
     assert pool(x=None) == 1 and pool(xt=2) == 5
     assert pool(H=1, W=1, x=None, y=None) == 0                # window larger than the image: empty
     assert pool(C=0, x=None, y=None) == 0
+    def dw(N=1, H=4, W=4, C=8, R=3, S=3, sh=1, sw=1, ph=1, pw=1, x=64, xt=0, w=64, wt=0, wl=1, y=64, yt=0):
+        return lib.xp_depthwise_conv2d_nhwc(N, H, W, C, R, S, sh, sw, ph, pw, x, xt, w, wt, wl, y, yt, None)
+    assert dw(R=0) == 2 and dw(N=-1) == 2 and dw(sw=0) == 2
+    assert dw(wl=2) == 5 and dw(xt=1, wt=0) == 5 and dw(xt=2, wt=2) == 5
+    assert dw(x=None) == 1 and dw(w=None) == 1 and dw(y=None) == 1
+    assert dw(w=66) == 4
+    assert dw(H=1, W=1, ph=0, pw=0, x=None, w=None, y=None) == 0
 
 
 def test_entry_points_resolve_their_builders():

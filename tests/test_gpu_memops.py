@@ -216,3 +216,41 @@ def test_layernorm_and_softmax_workloads_full_size(xp, oracle):
     ys = _out("f32", rows * cols, 0.0)
     xp.xp_softmax(rows, cols, dev(s.reshape(-1)), cols, ys, cols)
     check_float(_host(ys).reshape(rows, cols), oracle.softmax(s, rows=rows, cols=cols), "softmax workload")
+
+
+DW_CASES = [  # N, H, W, C, R, S, stride, pad
+    (2, 8, 8, 16, 3, 3, (1, 1), (1, 1)),
+    (1, 9, 7, 8, 3, 3, (2, 2), (1, 1)),
+    (1, 6, 6, 5, 3, 3, (1, 1), (1, 1)),                  # 5 channels: scalar path
+    (2, 10, 12, 32, 5, 3, (2, 1), (2, 1)),               # non-square window: general loop
+    (1, 14, 14, 64, 3, 3, (1, 1), (0, 0)),
+    (1, 3, 3, 8, 1, 1, (1, 1), (0, 0)),                  # 1 x 1: a per-channel scale
+]
+
+
+@pytest.mark.parametrize("layout", ["rsck", "krsc"])
+@pytest.mark.parametrize("kinds", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32")])
+def test_depthwise_conv(xp, oracle, layout, kinds):
+    kin, kout = kinds
+    for (N, H, W, C, R, S, stride, pad) in DW_CASES:
+        x = _gen(kin, (N, H, W, C), 1)
+        w = _gen(kin, (R, S, C) if layout == "rsck" else (C, R, S), 2, sigma=0.3)
+        ref = oracle.depthwise_conv2d_nhwc(x, w, N=N, H=H, W=W, C=C, R=R, S=S, stride=stride, pad=pad, filter_layout=layout)
+        y = _out(kout, ref.size, 7.0)
+        xp.xp_depthwise_conv2d_nhwc(N, H, W, C, R, S, stride[0], stride[1], pad[0], pad[1], dev(x.reshape(-1)),
+                                    dev(w.reshape(-1)), layout, y, x_type=kin, w_type=kin)
+        _check(_host(y).reshape(ref.shape), ref, f"depthwise {layout} {kinds} {(N, H, W, C, R, S, stride, pad)}")
+
+
+def test_depthwise_workload_full_size(xp, oracle):
+    """A MobileNet-like stage: 32 x 112 x 112 x 64, 3 x 3, stride 1, pad 1, bf16 in and out."""
+    N, H, W, C = 32, 112, 112, 64
+    x = _gen("bf16", (N, H, W, C), 1)
+    w = _gen("bf16", (3, 3, C), 2, sigma=0.3)
+    y = _out("bf16", N * H * W * C, 0.0)
+    xp.xp_depthwise_conv2d_nhwc(N, H, W, C, 3, 3, 1, 1, 1, 1, dev(x.reshape(-1)), dev(w.reshape(-1)), "rsck", y,
+                                x_type="bf16", w_type="bf16")
+    got = _host(y).reshape(N, H, W, C)
+    for n in (0, 17, 31):                                # three whole images
+        ref = oracle.depthwise_conv2d_nhwc(np.ascontiguousarray(x[n:n + 1]), w, N=1, H=H, W=W, C=C, R=3, S=3, pad=(1, 1))
+        _check(np.ascontiguousarray(got[n:n + 1]), ref, f"depthwise workload image {n}")
