@@ -44,6 +44,8 @@ def lib() -> C.CDLL:
         L.oracle_pool2d_nhwc.argtypes = [i] + [i64] * 10 + [vp, i, vp]
         L.oracle_depthwise_conv2d_nhwc.argtypes = [i64] * 10 + [vp, i, vp, i, i, vp]
         L.oracle_depthwise_conv2d_nhwc.restype = i
+        L.oracle_conv2d_nchw.argtypes = [i64] * 11 + [vp, i, vp, i, vp]
+        L.oracle_conv2d_nchw.restype = i
         for f in (L.oracle_gemm_float, L.oracle_gemm_i8, L.oracle_gemm_float_batched,
                   L.oracle_conv2d_nhwc, L.oracle_attention, L.oracle_softmax, L.oracle_layernorm,
                   L.oracle_rmsnorm, L.oracle_unary, L.oracle_add, L.oracle_pool2d_nhwc, L.oracle_num_threads):
@@ -225,4 +227,13 @@ def depthwise_conv2d_nhwc(x, w, *, N, H, W, C, R, S, stride=(1, 1), pad=(0, 0), 
     ref = np.empty((N, P, Q, C), dtype=np.float64)
     _rc(lib().oracle_depthwise_conv2d_nhwc(N, H, W, C, R, S, stride[0], stride[1], pad[0], pad[1], _ptr(x), _ftype(x),
                                            _ptr(w), _ftype(w), _FILTER[filter_layout], _ptr(ref)), "oracle_depthwise_conv2d_nhwc")
+    return ref
+
+
+def conv2d_nchw(x, w, *, N, H, W, Cin, Cout, R, S, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    """fp64 reference of the NCHW cross-correlation with a KCRS filter, dense N x Cout x P x Q."""
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    ref = np.empty((N, Cout, P, Q), dtype=np.float64)
+    _rc(lib().oracle_conv2d_nchw(N, H, W, Cin, Cout, R, S, stride[0], stride[1], pad[0], pad[1], _ptr(x), _ftype(x),
+                                 _ptr(w), _ftype(w), _ptr(ref)), "oracle_conv2d_nchw")
     return ref

@@ -401,3 +401,37 @@ int oracle_depthwise_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int
                 }
     return 0;
 }
+
+/* Convolution with NCHW activations and a KCRS filter: the same sum as oracle_conv2d_nhwc, other strides. */
+int oracle_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t R, int64_t S,
+                       int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                       const void *input, int in_type, const void *filter, int w_type, double *ref)
+{
+    if (N < 0 || H < 0 || W < 0 || Cin < 0 || Cout < 0 || R <= 0 || S <= 0) return 1;
+    if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return 1;
+    if (bad_type(in_type) || bad_type(w_type)) return 2;
+    if (H + 2 * pad_h < R || W + 2 * pad_w < S) return 0;
+    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1, Q = (W + 2 * pad_w - S) / stride_w + 1;
+    if (N == 0 || Cout == 0) return 0;
+    if (!ref || (Cin > 0 && (!input || !filter))) return 4;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < Cout; ++k)
+            for (int64_t p = 0; p < P; ++p)
+                for (int64_t q = 0; q < Q; ++q) {
+                    double acc = 0.0;
+                    for (int64_t c = 0; c < Cin; ++c)
+                        for (int64_t r = 0; r < R; ++r) {
+                            const int64_t h = p * stride_h + r - pad_h;
+                            if (h < 0 || h >= H) continue;
+                            for (int64_t s = 0; s < S; ++s) {
+                                const int64_t w = q * stride_w + s - pad_w;
+                                if (w < 0 || w >= W) continue;
+                                acc += widen(input, in_type, ((n * Cin + c) * H + h) * W + w)
+                                     * widen(filter, w_type, ((k * Cin + c) * R + r) * S + s);
+                            }
+                        }
+                    ref[((n * Cout + k) * P + p) * Q + q] = acc;
+                }
+    return 0;
+}

@@ -126,6 +126,12 @@ int oracle_depthwise_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int
                                  const void *input, int in_type, const void *filter, int w_type, int w_layout,
                                  double *ref);
 
+/* Convolution, NCHW (Table 5: Conv2D NCHW): input N x Cin x H x W, filter Cout x Cin x R x S, ref N x Cout x P x Q;
+ * out[n,k,p,q] = sum_{c,r,s} in[n, c, p*sh + r - ph, q*sw + s - pw] * w[k,c,r,s], zero padding, no bias. */
+int oracle_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t R, int64_t S,
+                       int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                       const void *input, int in_type, const void *filter, int w_type, double *ref);
+
 /* Number of OpenMP threads the loops above will use. */
 int oracle_num_threads(void);
 

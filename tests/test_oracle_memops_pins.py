@@ -234,3 +234,36 @@ def test_depthwise_closed_forms(oracle):
     b = oracle.depthwise_conv2d_nhwc(x2, w, N=N, H=H, W=W, C=C, R=3, S=3, pad=(1, 1))
     np.testing.assert_array_equal(a[..., 1:], b[..., 1:])
     assert not np.allclose(a[..., 0], b[..., 0])
+
+
+# ------------------------------------------------------------------------------------- NCHW conv
+
+def test_nchw_convolution_is_the_nhwc_one_on_transposed_data(oracle):
+    N, H, W, Cin, Cout, R, S = 2, 6, 5, 3, 4, 3, 2
+    x = _rand((N, Cin, H, W), 1)
+    w = _rand((Cout, Cin, R, S), 2)
+    kw = dict(stride=(2, 1), pad=(1, 2))
+    got = oracle.conv2d_nchw(x, w, N=N, H=H, W=W, Cin=Cin, Cout=Cout, R=R, S=S, **kw)
+    x_nhwc = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+    w_krsc = np.ascontiguousarray(w.transpose(0, 2, 3, 1))
+    expect = oracle.conv2d_nhwc(x_nhwc, w_krsc, N=N, H=H, W=W, Cin=Cin, Cout=Cout, R=R, S=S, filter_layout="krsc", **kw)
+    np.testing.assert_allclose(got, expect.transpose(0, 3, 1, 2), rtol=1e-13, atol=1e-15)    # the channel sum runs in another order
+
+
+def test_nchw_convolution_closed_forms(oracle):
+    N, H, W, C = 1, 4, 5, 3
+    x = _rand((N, C, H, W), 1)
+    delta = np.zeros((C, C, 3, 3), np.float32)
+    for c in range(C):
+        delta[c, c, 1, 1] = 1.0
+    np.testing.assert_array_equal(oracle.conv2d_nchw(x, delta, N=N, H=H, W=W, Cin=C, Cout=C, R=3, S=3, pad=(1, 1)), x.astype(np.float64))
+    # shifted delta: out[p, q] = in[p - 1, q - 1] with a zero border (correlation, not convolution)
+    shift = np.zeros((C, C, 3, 3), np.float32)
+    for c in range(C):
+        shift[c, c, 0, 0] = 1.0
+    y = oracle.conv2d_nchw(x, shift, N=N, H=H, W=W, Cin=C, Cout=C, R=3, S=3, pad=(1, 1))
+    np.testing.assert_array_equal(y[0, :, 1:, 1:], x[0, :, :-1, :-1].astype(np.float64))
+    assert (y[0, :, 0, :] == 0).all() and (y[0, :, :, 0] == 0).all()
+    ones = oracle.conv2d_nchw(np.ones((1, 2, 4, 4), np.float32), np.ones((1, 2, 3, 3), np.float32), N=1, H=4, W=4, Cin=2, Cout=1,
+                              R=3, S=3, pad=(1, 1))
+    assert ones[0, 0, 0, 0] == 8 and ones[0, 0, 0, 1] == 12 and ones[0, 0, 1, 1] == 18
