@@ -200,6 +200,24 @@ xp_status xp_pool2d_nhwc(xp_pool_op op, int64_t N, int64_t H, int64_t W, int64_t
                          int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
                          const void *x, xp_dtype x_type, void *y, xp_dtype y_type, void *stream);
 
+/*
+ * 2-D convolution, NCHW (Table 5, "Conv2D NCHW"): the sum of xp_conv2d_nhwc with
+ *   input N x Cin x H x W, filter Cout x Cin x R x S (KCRS), output N x Cout x P x Q, all contiguous.
+ * It is computed by a change of layout: activations and filter are transposed to NHWC / KRSC in the
+ * workspace, the NHWC kernels run, the result is transposed back (three extra memory passes; callers
+ * that can keep their tensors in NHWC should call xp_conv2d_nhwc).
+ *   workspace   DEVICE memory owned by the caller, 256-byte aligned, at least
+ *               xp_conv2d_nchw_workspace_bytes(...) bytes (0 is returned for invalid or empty shapes);
+ *               contents are scratch.  XP_ERR_WORKSPACE if missing, misaligned or too small.
+ * Types as for xp_conv2d_nhwc.  N and Cout up to 65535.
+ */
+size_t xp_conv2d_nchw_workspace_bytes(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t R, int64_t S,
+                                      int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w, xp_dtype in_type);
+xp_status xp_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t R, int64_t S,
+                         int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                         const void *input, xp_dtype in_type, const void *filter, xp_dtype w_type,
+                         void *output, xp_dtype out_type, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Depthwise 2-D convolution, NHWC (Table 5, "Depthwise Conv"): every channel has its own R x S filter,
  *   y[n,p,q,c] = sum_{r<R, s<S} x[n, p*stride_h + r - pad_h, q*stride_w + s - pad_w, c] * w(c,r,s),
  * zero padding, no bias; P, Q as for xp_conv2d_nhwc.  x is N x H x W x C contiguous, y is N x P x Q x C.

@@ -1,0 +1,115 @@
+// Conv2D NCHW (Table 5 of the paper) by a change of layout: the activations are transposed to NHWC and
+// the KCRS filter to KRSC in a caller-provided workspace, the NHWC implicit-GEMM kernels do the work,
+// and the NHWC result is transposed back.  The MFMA kernels want the reduction index (channels)
+// contiguous, which is what NHWC is; the three transposes are plain memory passes (LDS-tiled, both
+// sides coalesced) and cost about as much as the operands are large.
+#include "xp_internal.hpp"
+
+namespace xp {
+namespace {
+
+constexpr int TT = 64;                                   // transpose tile edge
+
+struct TrParams {
+    const void *in;
+    void *out;
+    long long rows, cols;                                // of one input matrix; the output is cols x rows
+};
+
+// out[b][c][r] = in[b][r][c]; one 64 x 64 tile per workgroup, through LDS so that both the reads
+// (along c) and the writes (along r) are contiguous
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(TrParams p)
+{
+    __shared__ T tile[TT][TT + 1];
+    const long long b = blockIdx.z;
+    const long long r0 = (long long)blockIdx.y * TT, c0 = (long long)blockIdx.x * TT;
+    const T *in = (const T *)p.in + b * p.rows * p.cols;
+    T *out = (T *)p.out + b * p.rows * p.cols;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < TT; i += 4) {
+        const long long r = r0 + ty + i, c = c0 + tx;
+        if (r < p.rows && c < p.cols) tile[ty + i][tx] = in[r * p.cols + c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TT; i += 4) {
+        const long long c = c0 + ty + i, r = r0 + tx;
+        if (c < p.cols && r < p.rows) out[c * p.rows + r] = tile[tx][ty + i];
+    }
+}
+
+hipError_t transpose(const void *in, void *out, int64_t batch, int64_t rows, int64_t cols, int esz, hipStream_t s)
+{
+    TrParams p;
+    p.in = in; p.out = out; p.rows = rows; p.cols = cols;
+    const dim3 grid((unsigned)((cols + TT - 1) / TT), (unsigned)((rows + TT - 1) / TT), (unsigned)batch);
+    if (esz == 2) hipLaunchKernelGGL(transpose_kernel<unsigned short>, grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(transpose_kernel<unsigned int>, grid, dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+size_t round256(size_t x) { return (x + 255) / 256 * 256; }
+
+}  // namespace
+}  // namespace xp
+
+using namespace xp;
+
+extern "C" {
+
+size_t xp_conv2d_nchw_workspace_bytes(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t R, int64_t S,
+                                      int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w, xp_dtype in_type)
+{
+    if (N < 0 || H < 0 || W < 0 || Cin < 0 || Cout < 0 || R <= 0 || S <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 ||
+        pad_w < 0 || (in_type != XP_F32 && in_type != XP_BF16))
+        return 0;
+    if (H + 2 * pad_h < R || W + 2 * pad_w < S) return 0;
+    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1, Q = (W + 2 * pad_w - S) / stride_w + 1;
+    const size_t esz = (size_t)elem_size(in_type);
+    return round256((size_t)(N * H * W * Cin) * esz) + round256((size_t)(Cout * R * S * Cin) * esz) +
+           round256((size_t)(N * P * Q * Cout) * 4);
+}
+
+xp_status xp_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t R, int64_t S,
+                         int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                         const void *input, xp_dtype in_type, const void *filter, xp_dtype w_type,
+                         void *output, xp_dtype out_type, void *workspace, size_t workspace_bytes, void *stream)
+{
+    // the NHWC entry's own validation, on the pointers it will actually see (checked before anything is launched)
+    if (N < 0 || H < 0 || W < 0 || Cin < 0 || Cout < 0) return XP_ERR_SHAPE;
+    if (R <= 0 || S <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return XP_ERR_SHAPE;
+    if (in_type != w_type || (in_type != XP_F32 && in_type != XP_BF16) || out_type != XP_F32) return XP_ERR_UNSUPPORTED;
+    if (H + 2 * pad_h < R || W + 2 * pad_w < S) return XP_OK;   // empty output
+    if (N == 0 || Cout == 0) return XP_OK;
+    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1, Q = (W + 2 * pad_w - S) / stride_w + 1;
+    const int64_t K = R * S * Cin;
+    if (!output || (K > 0 && (!input || !filter))) return XP_ERR_NULL;
+    const int esz = elem_size(in_type);
+    if (((uintptr_t)output % 4) != 0 || (K > 0 && (((uintptr_t)input % esz) != 0 || ((uintptr_t)filter % esz) != 0))) return XP_ERR_ALIGN;
+    if (H * W > 0x7fffffffLL || P * Q > 0x7fffffffLL || N > 65535 || Cout > 65535) return XP_ERR_SHAPE;   // transpose grids
+    const size_t need = xp_conv2d_nchw_workspace_bytes(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, in_type);
+    if (!workspace || ((uintptr_t)workspace % 256) != 0 || workspace_bytes < need) return XP_ERR_WORKSPACE;
+
+    char *x_nhwc = (char *)workspace;
+    char *w_krsc = x_nhwc + round256((size_t)(N * H * W * Cin) * esz);
+    char *y_nhwc = w_krsc + round256((size_t)(Cout * R * S * Cin) * esz);
+    hipStream_t s = (hipStream_t)stream;
+    if (K > 0) {
+        if (transpose(input, x_nhwc, N, Cin, H * W, esz, s) != hipSuccess) return XP_ERR_LAUNCH;        // [N][C][HW] -> [N][HW][C]
+        if (transpose(filter, w_krsc, Cout, Cin, R * S, esz, s) != hipSuccess) return XP_ERR_LAUNCH;    // [K][C][RS] -> [K][RS][C]
+    }
+    Problem q;
+    bool nothing;
+    const xp_status st = make_conv_problem(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, x_nhwc, in_type,
+                                           w_krsc, w_type, XP_FILTER_KRSC, y_nhwc, XP_F32, stream, &q, &nothing);
+    if (st != XP_OK) return st;
+    if (!nothing) {
+        const xp_status rs = run(q);
+        if (rs != XP_OK) return rs;
+    }
+    return transpose(y_nhwc, output, N, P * Q, Cout, 4, s) == hipSuccess ? XP_OK : XP_ERR_LAUNCH;       // [N][PQ][K] -> [N][K][PQ]
+}
+
+}  // extern "C"

@@ -50,6 +50,9 @@ _lib.xp_rmsnorm.argtypes = [_i64, _i64, _vp, _i, _i64, _vp, _f, _vp, _i, _i64, _
 _lib.xp_unary.argtypes = [_i, _i64, _vp, _i, _vp, _i, _vp]
 _lib.xp_add.argtypes = [_i64, _vp, _vp, _i, _vp, _i, _vp]
 _lib.xp_pool2d_nhwc.argtypes = [_i] + [_i64] * 10 + [_vp, _i, _vp, _i, _vp]
+_lib.xp_conv2d_nchw_workspace_bytes.argtypes = [_i64] * 11 + [_i]
+_lib.xp_conv2d_nchw_workspace_bytes.restype = C.c_size_t
+_lib.xp_conv2d_nchw.argtypes = [_i64] * 11 + [_vp, _i, _vp, _i, _vp, _i, _vp, C.c_size_t, _vp]
 _lib.xp_depthwise_conv2d_nhwc.argtypes = [_i64] * 10 + [_vp, _i, _vp, _i, _i, _vp, _i, _vp]
 _lib.xp_num_configs.argtypes = [_i, _i]
 _lib.xp_describe_config.argtypes = [_i, _i, _i, C.c_char_p, C.c_size_t]
@@ -60,7 +63,7 @@ _lib.xp_status_string.restype = C.c_char_p
 _lib.xp_version.restype = C.c_char_p
 for _name in ("xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_attention", "xp_tune_gemm", "xp_tune_gemm_batched",
               "xp_tune_conv2d_nhwc", "xp_tune_save", "xp_tune_load", "xp_tune_count", "xp_softmax", "xp_layernorm",
-              "xp_rmsnorm", "xp_unary", "xp_add", "xp_pool2d_nhwc", "xp_depthwise_conv2d_nhwc", "xp_num_configs", "xp_describe_config",
+              "xp_rmsnorm", "xp_unary", "xp_add", "xp_pool2d_nhwc", "xp_depthwise_conv2d_nhwc", "xp_conv2d_nchw", "xp_num_configs", "xp_describe_config",
               "xp_force_config", "xp_last_config"):
     getattr(_lib, _name).restype = _i
 
@@ -219,6 +222,19 @@ def xp_add(n, a, b, y, stream=None, x_type=None, y_type=None):
 def xp_pool2d_nhwc(op, N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w, x, y, stream=None, x_type=None, y_type=None):
     _check(_lib.xp_pool2d_nhwc(POOL.get(op, op), N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w,
                                _ptr(x), _dt(x, x_type), _ptr(y), _dt(y, y_type), _stream(stream)))
+
+
+def xp_conv2d_nchw_workspace_bytes(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, in_type) -> int:
+    return _lib.xp_conv2d_nchw_workspace_bytes(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w,
+                                               DTYPE_BY_NAME.get(in_type, in_type))
+
+
+def xp_conv2d_nchw(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, x, w, out, workspace, stream=None,
+                   in_type=None, w_type=None, out_type=None):
+    """NCHW convolution through NHWC in the workspace (see include/xp.h: xp_conv2d_nchw)."""
+    _check(_lib.xp_conv2d_nchw(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, _ptr(x), _dt(x, in_type),
+                               _ptr(w), _dt(w, w_type), _ptr(out), _dt(out, out_type), _ptr(workspace),
+                               workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def xp_depthwise_conv2d_nhwc(N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w, x, w, filter_layout, y, stream=None,

@@ -238,6 +238,23 @@ def test_memory_bound_operator_validation(lib):
     assert dw(H=1, W=1, ph=0, pw=0, x=None, w=None, y=None) == 0
 
 
+def test_conv_nchw_validation(lib):
+    # every call here must be turned away (or be empty) on the host: the pointers are fake
+    def call(N=1, H=4, W=4, Cin=2, Cout=2, R=3, S=3, sh=1, sw=1, ph=1, pw=1, x=256, xt=0, w=256, wt=0, out=256, ot=0,
+             ws=256, wsb=1 << 20):
+        return lib.xp_conv2d_nchw(N, H, W, Cin, Cout, R, S, sh, sw, ph, pw, x, xt, w, wt, out, ot, ws, wsb, None)
+    assert call(N=-1) == 2 and call(R=0) == 2 and call(sh=0) == 2
+    assert call(xt=2, wt=2) == 5 and call(xt=1, wt=0) == 5 and call(ot=1) == 5
+    assert call(x=None) == 1 and call(out=None) == 1
+    assert call(ws=None) == 8 and call(ws=260) == 8 and call(wsb=100) == 8
+    assert call(N=70000) == 2
+    assert call(H=1, W=1, ph=0, pw=0, x=None, w=None, out=None, ws=None) == 0
+    assert call(N=0, x=None, w=None, out=None, ws=None) == 0
+    need = lib.xp_conv2d_nchw_workspace_bytes(1, 4, 4, 2, 2, 3, 3, 1, 1, 1, 1, 0)
+    assert need == 256 + 256 + 256                       # 128 B + 144 B + 128 B, each rounded up to 256
+    assert lib.xp_conv2d_nchw_workspace_bytes(1, 4, 4, 2, 2, 0, 3, 1, 1, 1, 1, 0) == 0
+
+
 def test_entry_points_resolve_their_builders():
     # build() compiles for minutes, so it is not run here; what broke once is the lookup of the
     # oracle's build module behind the package attribute of the same name
