@@ -46,6 +46,8 @@ def lib() -> C.CDLL:
         L.oracle_depthwise_conv2d_nhwc.restype = i
         L.oracle_conv2d_nchw.argtypes = [i64] * 11 + [vp, i, vp, i, vp]
         L.oracle_conv2d_nchw.restype = i
+        L.oracle_deformable_attention.argtypes = [i64] * 6 + [vp, i, vp, vp, vp, vp, vp]
+        L.oracle_deformable_attention.restype = i
         for f in (L.oracle_gemm_float, L.oracle_gemm_i8, L.oracle_gemm_float_batched,
                   L.oracle_conv2d_nhwc, L.oracle_attention, L.oracle_softmax, L.oracle_layernorm,
                   L.oracle_rmsnorm, L.oracle_unary, L.oracle_add, L.oracle_pool2d_nhwc, L.oracle_num_threads):
@@ -236,4 +238,17 @@ def conv2d_nchw(x, w, *, N, H, W, Cin, Cout, R, S, stride=(1, 1), pad=(0, 0)) ->
     ref = np.empty((N, Cout, P, Q), dtype=np.float64)
     _rc(lib().oracle_conv2d_nchw(N, H, W, Cin, Cout, R, S, stride[0], stride[1], pad[0], pad[1], _ptr(x), _ftype(x),
                                  _ptr(w), _ftype(w), _ptr(ref)), "oracle_conv2d_nchw")
+    return ref
+
+
+def deformable_attention(value, level_hw, locations, weights, *, batch, Lq, heads, d, points) -> np.ndarray:
+    """fp64 reference of multi-scale deformable attention, dense batch x Lq x heads x d.
+    level_hw: list of (H, W); locations float32 [batch, Lq, heads, levels, points, 2]; weights float32 without the last axis."""
+    hs = np.array([h for h, _ in level_hw], dtype=np.int64)
+    ws_ = np.array([w for _, w in level_hw], dtype=np.int64)
+    assert locations.dtype == np.float32 and weights.dtype == np.float32
+    ref = np.empty((batch, Lq, heads, d), dtype=np.float64)
+    _rc(lib().oracle_deformable_attention(batch, Lq, heads, d, len(level_hw), points, _ptr(value), _ftype(value),
+                                          _ptr(hs), _ptr(ws_), _ptr(locations), _ptr(weights), _ptr(ref)),
+        "oracle_deformable_attention")
     return ref

@@ -435,3 +435,51 @@ int oracle_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cou
                 }
     return 0;
 }
+
+/* Multi-scale deformable attention: every query samples each feature level at `points` fractional
+ * positions, bilinearly, and adds the samples up with its attention weights. */
+int oracle_deformable_attention(int64_t batch, int64_t Lq, int64_t heads, int64_t d, int64_t levels, int64_t points,
+                                const void *value, int v_type, const int64_t *level_h, const int64_t *level_w,
+                                const float *locations, const float *weights, double *ref)
+{
+    if (batch < 0 || Lq < 0 || heads < 0 || d < 0 || levels < 0 || points < 0) return 1;
+    if (bad_type(v_type)) return 2;
+    if (batch == 0 || Lq == 0 || heads == 0 || d == 0) return 0;
+    if (!ref || (levels > 0 && (!level_h || !level_w))) return 4;
+    int64_t S = 0;
+    for (int64_t l = 0; l < levels; ++l) {
+        if (level_h[l] < 0 || level_w[l] < 0) return 1;
+        S += level_h[l] * level_w[l];
+    }
+    if (levels > 0 && points > 0 && (!locations || !weights || (S > 0 && !value))) return 4;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < batch; ++n)
+        for (int64_t q = 0; q < Lq; ++q)
+            for (int64_t m = 0; m < heads; ++m)
+                for (int64_t c = 0; c < d; ++c) {
+                    double acc = 0.0;
+                    int64_t start = 0;                                  /* first row of this level in `value` */
+                    for (int64_t l = 0; l < levels; ++l) {
+                        const int64_t H = level_h[l], W = level_w[l];
+                        for (int64_t p = 0; p < points; ++p) {
+                            const int64_t at = (((n * Lq + q) * heads + m) * levels + l) * points + p;
+                            /* normalised (x, y) in [0, 1] -> pixel coordinates with pixel centres at i + 0.5 */
+                            const double x = (double)locations[2 * at] * (double)W - 0.5;
+                            const double y = (double)locations[2 * at + 1] * (double)H - 0.5;
+                            const double x0 = floor(x), y0 = floor(y);
+                            double sample = 0.0;
+                            for (int dy = 0; dy < 2; ++dy)
+                                for (int dx = 0; dx < 2; ++dx) {
+                                    const int64_t xi = (int64_t)x0 + dx, yi = (int64_t)y0 + dy;
+                                    if (xi < 0 || xi >= W || yi < 0 || yi >= H) continue;   /* outside: contributes zero */
+                                    const double wx = dx ? x - x0 : 1.0 - (x - x0), wy = dy ? y - y0 : 1.0 - (y - y0);
+                                    sample += wx * wy * widen(value, v_type, ((n * S + start + yi * W + xi) * heads + m) * d + c);
+                                }
+                            acc += (double)weights[at] * sample;
+                        }
+                        start += H * W;
+                    }
+                    ref[((n * Lq + q) * heads + m) * d + c] = acc;
+                }
+    return 0;
+}

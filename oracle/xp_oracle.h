@@ -132,6 +132,17 @@ int oracle_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cou
                        int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
                        const void *input, int in_type, const void *filter, int w_type, double *ref);
 
+/* Multi-scale deformable attention (Table 5: Deformable Attention; the operator of Deformable DETR):
+ *   out[n,q,m,:] = sum_{l<levels, p<points} weights[n,q,m,l,p] * bilinear(value_l[n,:,:,m,:], locations[n,q,m,l,p,:])
+ * value is batch x S x heads x d with S = sum_l H_l*W_l, level l stored row-major (H_l x W_l) after the
+ * levels before it; locations are (x, y) in [0,1] relative to the level (x along the width), mapped to
+ * pixel coordinates x*W - 0.5, y*H - 0.5 (pixel centres at half-integers); the bilinear sample takes the
+ * four surrounding pixels, those outside the level count as zero.  locations: batch x Lq x heads x
+ * levels x points x 2 floats; weights: the same without the last axis; ref: batch x Lq x heads x d. */
+int oracle_deformable_attention(int64_t batch, int64_t Lq, int64_t heads, int64_t d, int64_t levels, int64_t points,
+                                const void *value, int v_type, const int64_t *level_h, const int64_t *level_w,
+                                const float *locations, const float *weights, double *ref);
+
 /* Number of OpenMP threads the loops above will use. */
 int oracle_num_threads(void);
 
