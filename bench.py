@@ -288,6 +288,20 @@ def main() -> int:
              lambda: (lambda i: xp.xp_depthwise_conv2d_nhwc(dn, dh, dh, dc, 3, 3, 1, 1, 1, 1, px[i], dwf, "rsck", py2[i]))(nxt4()),
              "4 rotating sets of 103 MB")
         del px, py, py2
+        dcfg = inputs.DEFORMABLE_WORKLOAD
+        dlev, db, dhd, dd, dpt = dcfg["levels"], dcfg["batch"], dcfg["heads"], dcfg["d"], dcfg["points"]
+        dS = sum(h * w_ for h, w_ in dlev)
+        dv_np, dloc_np, dw_np = inputs.deformable_attention_inputs(db, dS, dhd, dd, dlev, dpt, seed=5)
+        dv = [torch.from_numpy(dv_np.view(np.int16)).cuda().view(torch.bfloat16)]
+        dloc, dwg = [torch.from_numpy(dloc_np).cuda()], [torch.from_numpy(dw_np).cuda()]
+        for _ in range(3):                       # the same values at other addresses
+            dv.append(dv[0].clone()); dloc.append(dloc[0].clone()); dwg.append(dwg[0].clone())
+        dout = [torch.empty(db * dS * dhd * dd, device="cuda") for _ in range(4)]
+        rate("deformable_attention_bf16_8x5440q_8h32_4l4p",
+             dv[0].numel() * 2 + dloc[0].numel() * 4 + dwg[0].numel() * 4 + dout[0].numel() * 4,
+             lambda: (lambda i: xp.xp_deformable_attention(db, dS, dhd, dd, dpt, dv[i], dlev, dloc[i], dwg[i], dout[i]))(nxt4()),
+             "4 rotating sets of 134 MB")
+        del dv, dloc, dwg, dout
         side["memory_bound"] = mem
         out["other_workloads"] = side
 

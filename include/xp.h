@@ -218,6 +218,29 @@ xp_status xp_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t C
                          const void *input, xp_dtype in_type, const void *filter, xp_dtype w_type,
                          void *output, xp_dtype out_type, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Multi-scale deformable attention (Table 5, "Deformable Attention"; Section 6 discusses it as the
+ * hardest operator of the benchmark).  The operator of Deformable DETR's attention layers:
+ *   out[n,q,m,:] = sum_{l<levels, p<points} weights[n,q,m,l,p] * bilinear(value_l[n,:,:,m,:], locations[n,q,m,l,p,:])
+ *   value      DEVICE, batch x S x heads x d contiguous, S = sum_l H_l*W_l; level l is stored row-major
+ *              (H_l x W_l pixels) after the levels before it.  F32 or BF16.
+ *   level_h/w  HOST arrays of `levels` entries (at most 16 levels, each side at most 2^24): read
+ *              during the call, not kept.
+ *   locations  DEVICE, float, batch x Lq x heads x levels x points x 2: (x, y) relative to the level,
+ *              x along the width; the pixel coordinates are x*W - 0.5 and y*H - 0.5 (pixel centres at
+ *              half-integers).  8-byte aligned.
+ *   weights    DEVICE, float, batch x Lq x heads x levels x points (the caller has normalised them).
+ *   out        DEVICE, batch x Lq x heads x d contiguous, F32 or BF16; overwritten.
+ * The bilinear sample takes the four pixels around the position; pixels outside the level count as
+ * zero, so a position a full pixel or more outside (or NaN) contributes nothing.  Positions are
+ * computed in fp32, accumulation is fp32.  levels == 0 or points == 0 writes zeros.  d a multiple of
+ * 4 (F32) or 8 (BF16) with 16-byte aligned value/out takes the vectorised kernel.
+ */
+xp_status xp_deformable_attention(int64_t batch, int64_t Lq, int64_t heads, int64_t d, int64_t levels, int64_t points,
+                                  const void *value, xp_dtype v_type, const int64_t *level_h, const int64_t *level_w,
+                                  const float *locations, const float *weights, void *out, xp_dtype out_type,
+                                  void *stream);
+
 /* Depthwise 2-D convolution, NHWC (Table 5, "Depthwise Conv"): every channel has its own R x S filter,
  *   y[n,p,q,c] = sum_{r<R, s<S} x[n, p*stride_h + r - pad_h, q*stride_w + s - pad_w, c] * w(c,r,s),
  * zero padding, no bias; P, Q as for xp_conv2d_nhwc.  x is N x H x W x C contiguous, y is N x P x Q x C.

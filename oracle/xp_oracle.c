@@ -466,6 +466,9 @@ int oracle_deformable_attention(int64_t batch, int64_t Lq, int64_t heads, int64_
                             /* normalised (x, y) in [0, 1] -> pixel coordinates with pixel centres at i + 0.5 */
                             const double x = (double)locations[2 * at] * (double)W - 0.5;
                             const double y = (double)locations[2 * at + 1] * (double)H - 0.5;
+                            /* a full pixel or more outside (or NaN): all four neighbours are padding; also keeps
+                             * the conversions to integers below inside their range */
+                            if (!(x > -1.0 && x < (double)W && y > -1.0 && y < (double)H)) continue;
                             const double x0 = floor(x), y0 = floor(y);
                             double sample = 0.0;
                             for (int dy = 0; dy < 2; ++dy)

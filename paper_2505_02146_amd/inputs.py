@@ -170,3 +170,26 @@ WORKLOADS = ("gemm_f32_256", "gemm_bf16_4096", "gemm_i8_4096x4096x8192",
              "bgemm_bf16_qk", "bgemm_bf16_pv", "conv_bf16_56")
 # operators beyond the GEMM / convolution set, each served by its own entry point
 EXTRA_WORKLOADS = ("attention_bf16_512", "gemv_bf16_8192")
+
+
+# A detection-encoder layer's deformable attention: the queries are the pixels of the four feature
+# levels themselves (64x64 down to 8x8 for a 512x512 image at strides 8..64), 8 heads of 32 channels.
+DEFORMABLE_WORKLOAD = {"batch": 8, "levels": [(64, 64), (32, 32), (16, 16), (8, 8)], "heads": 8, "d": 32, "points": 4}
+
+
+def deformable_attention_inputs(batch, Lq, heads, d, levels, points, seed: int):
+    """(value as bf16 bits, locations fp32, weights fp32) with the structure of an encoder layer: query i
+    is pixel i of the concatenated levels (wrapping round if Lq is larger), its sampling positions are
+    its own normalised centre plus offsets of about two pixels of the sampled level, the weights of a
+    (query, head) are positive and sum to one."""
+    S = sum(h * w for h, w in levels)
+    value = to_bf16_bits(normal((batch, S, heads, d), seed, 1))
+    centres = np.concatenate([np.stack([(np.tile(np.arange(w), h) + 0.5) / w, (np.repeat(np.arange(h), w) + 0.5) / h], axis=-1)
+                              for h, w in levels]).astype(np.float32)
+    ref = centres[np.arange(Lq) % S]                                            # Lq x 2
+    off = normal((batch, Lq, heads, len(levels), points, 2), seed, 2, 2.0)
+    size = np.array([[w, h] for h, w in levels], dtype=np.float32)              # levels x (W, H)
+    loc = (ref[None, :, None, None, None, :] + off / size[None, None, None, :, None, :]).astype(np.float32)
+    u = np.abs(normal((batch, Lq, heads, len(levels), points), seed, 3)) + np.float32(1e-3)
+    wgt = (u / u.sum(axis=(3, 4), keepdims=True)).astype(np.float32)
+    return value, loc, wgt

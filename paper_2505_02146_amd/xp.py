@@ -54,6 +54,7 @@ _lib.xp_conv2d_nchw_workspace_bytes.argtypes = [_i64] * 11 + [_i]
 _lib.xp_conv2d_nchw_workspace_bytes.restype = C.c_size_t
 _lib.xp_conv2d_nchw.argtypes = [_i64] * 11 + [_vp, _i, _vp, _i, _vp, _i, _vp, C.c_size_t, _vp]
 _lib.xp_depthwise_conv2d_nhwc.argtypes = [_i64] * 10 + [_vp, _i, _vp, _i, _i, _vp, _i, _vp]
+_lib.xp_deformable_attention.argtypes = [_i64] * 6 + [_vp, _i, _vp, _vp, _vp, _vp, _vp, _i, _vp]
 _lib.xp_num_configs.argtypes = [_i, _i]
 _lib.xp_describe_config.argtypes = [_i, _i, _i, C.c_char_p, C.c_size_t]
 _lib.xp_force_config.argtypes = [_i, _i, _i]
@@ -63,7 +64,8 @@ _lib.xp_status_string.restype = C.c_char_p
 _lib.xp_version.restype = C.c_char_p
 for _name in ("xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_attention", "xp_tune_gemm", "xp_tune_gemm_batched",
               "xp_tune_conv2d_nhwc", "xp_tune_save", "xp_tune_load", "xp_tune_count", "xp_softmax", "xp_layernorm",
-              "xp_rmsnorm", "xp_unary", "xp_add", "xp_pool2d_nhwc", "xp_depthwise_conv2d_nhwc", "xp_conv2d_nchw", "xp_num_configs", "xp_describe_config",
+              "xp_rmsnorm", "xp_unary", "xp_add", "xp_pool2d_nhwc", "xp_depthwise_conv2d_nhwc", "xp_conv2d_nchw",
+              "xp_deformable_attention", "xp_num_configs", "xp_describe_config",
               "xp_force_config", "xp_last_config"):
     getattr(_lib, _name).restype = _i
 
@@ -242,6 +244,17 @@ def xp_depthwise_conv2d_nhwc(N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w,
     _check(_lib.xp_depthwise_conv2d_nhwc(N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w, _ptr(x), _dt(x, x_type),
                                          _ptr(w), _dt(w, w_type), _FILTER[filter_layout], _ptr(y), _dt(y, y_type),
                                          _stream(stream)))
+
+
+def xp_deformable_attention(batch, Lq, heads, d, points, value, level_hw, locations, weights, out, stream=None,
+                            v_type=None, out_type=None):
+    """level_hw: sequence of (H, W) per level (host side); locations / weights: float32 device tensors."""
+    n = len(level_hw)
+    hs = (C.c_int64 * max(n, 1))(*[int(h) for h, _ in level_hw])
+    ws = (C.c_int64 * max(n, 1))(*[int(w) for _, w in level_hw])
+    _check(_lib.xp_deformable_attention(batch, Lq, heads, d, n, points, _ptr(value), _dt(value, v_type),
+                                        C.cast(hs, C.c_void_p), C.cast(ws, C.c_void_p), _ptr(locations), _ptr(weights),
+                                        _ptr(out), _dt(out, out_type), _stream(stream)))
 
 
 def xp_num_configs(op: int, in_type) -> int:

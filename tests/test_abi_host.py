@@ -238,6 +238,25 @@ def test_memory_bound_operator_validation(lib):
     assert dw(H=1, W=1, ph=0, pw=0, x=None, w=None, y=None) == 0
 
 
+def test_deformable_attention_validation(lib):
+    # every call here must be turned away (or be empty) on the host: the pointers are fake
+    import ctypes as C
+    hs, ws = (C.c_int64 * 16)(*([4] * 16)), (C.c_int64 * 16)(*([4] * 16))
+    def call(batch=1, Lq=2, heads=2, d=8, levels=2, points=2, v=256, vt=0, h=hs, w=ws, loc=256, wg=256, out=256, ot=0):
+        return lib.xp_deformable_attention(batch, Lq, heads, d, levels, points, v, vt, C.cast(h, C.c_void_p) if h else None,
+                                           C.cast(w, C.c_void_p) if w else None, loc, wg, out, ot, None)
+    assert call(batch=-1) == 2 and call(points=-1) == 2 and call(levels=17) == 2
+    assert call(vt=2) == 5 and call(ot=2) == 5
+    assert call(h=None) == 1 and call(loc=None) == 1 and call(wg=None) == 1 and call(v=None) == 1 and call(out=None) == 1
+    assert call(loc=260) == 4 and call(wg=258) == 4
+    assert call(d=3, v=258) == 4 and call(d=3, out=258) == 4          # scalar path: element alignment
+    bad = (C.c_int64 * 16)(*([-1] * 16))
+    assert call(h=bad) == 2
+    huge = (C.c_int64 * 16)(*([1 << 25] * 16))
+    assert call(w=huge) == 2
+    assert call(Lq=0, v=None, loc=None, wg=None, out=None) == 0 and call(d=0, out=None) == 0
+
+
 def test_conv_nchw_validation(lib):
     # every call here must be turned away (or be empty) on the host: the pointers are fake
     def call(N=1, H=4, W=4, Cin=2, Cout=2, R=3, S=3, sh=1, sw=1, ph=1, pw=1, x=256, xt=0, w=256, wt=0, out=256, ot=0,
