@@ -237,71 +237,14 @@ def main() -> int:
         side["conv_bf16_56_nchw"] = {"ms": round(ms, 5), "TFLOP/s": round(2.0 * 32 * 56 * 56 * 256 * 9 * 256 / (ms * 1e-3) / 1e12, 1),
                                      "note": "NCHW -> NHWC, filter KCRS -> KRSC, NHWC -> NCHW transposes included"}
         del xn, wn, on, wsn
-        # memory-bound operators: achieved bytes/s against the HBM peak.  Timing inputs come from torch's
-        # seeded generator on the device (the values do not matter here; parity is the tests' job).
-        # Working sets are rotated or larger than the 256 MB last-level cache, so the rates are HBM-cold.
-        torch.manual_seed(0)
+        # operators that are not contractions: achieved algorithmic bytes/s against the HBM peak, HBM-cold
+        # (rotating buffer sets larger than the 256 MB last-level cache; workloads in opbench.py)
+        from paper_2505_02146_amd import opbench
         mem = {}
-
-        def rate(name, nbytes, fn, sets):
-            ms, _ = _time_calls(torch, fn, steps2 * 2, warm2)
+        for op in opbench.BENCH_OPS:
+            name, ms, nbytes, note = opbench.time_op(op, steps2 * 2, warm2)
             mem[name] = {"ms": round(ms, 5), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
-                         "pct_hbm_peak": round(100 * nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 2), "buffers": sets}
-
-        rows, cols = 16384, 4096
-        xs = [torch.randn(rows, cols, device="cuda").bfloat16() for _ in range(3)]
-        ys = [torch.empty(rows, cols, device="cuda", dtype=torch.bfloat16) for _ in range(3)]
-        gam, bet = torch.randn(cols, device="cuda").bfloat16(), torch.randn(cols, device="cuda").bfloat16()
-        it = {"i": 0}
-
-        def nxt():
-            it["i"] += 1
-            return it["i"] % 3
-        nb = 2 * rows * cols * 2
-        rate("layernorm_bf16_16384x4096", nb, lambda: (lambda i: xp.xp_layernorm(rows, cols, xs[i], cols, gam, bet, 1e-5, ys[i], cols))(nxt()), "3 rotating sets of 268 MB")
-        rate("rmsnorm_bf16_16384x4096", nb, lambda: (lambda i: xp.xp_rmsnorm(rows, cols, xs[i], cols, gam, 1e-6, ys[i], cols))(nxt()), "3 rotating sets of 268 MB")
-        n = rows * cols
-        rate("gelu_bf16_64M", nb, lambda: (lambda i: xp.xp_unary("gelu", n, xs[i], ys[i]))(nxt()), "3 rotating sets of 268 MB")
-        rate("add_bf16_64M", 3 * n * 2, lambda: (lambda i: xp.xp_add(n, xs[i], xs[(i + 1) % 3], ys[i]))(nxt()), "3 rotating sets")
-        del xs, ys
-        srows, scols = 96 * 512, 512
-        sx = [torch.randn(srows, scols, device="cuda") for _ in range(4)]
-        sy = [torch.empty(srows, scols, device="cuda") for _ in range(4)]
-        it["i"] = 0
-
-        def nxt4():
-            it["i"] += 1
-            return it["i"] % 4
-        rate("softmax_f32_49152x512", 2 * srows * scols * 4, lambda: (lambda i: xp.xp_softmax(srows, scols, sx[i], scols, sy[i], scols))(nxt4()),
-             "4 rotating sets of 201 MB")
-        del sx, sy
-        pn, ph_, pc = 64, 112, 64
-        px = [torch.randn(pn, ph_, ph_, pc, device="cuda").bfloat16() for _ in range(4)]
-        py = [torch.empty(pn, 56, 56, pc, device="cuda", dtype=torch.bfloat16) for _ in range(4)]
-        rate("maxpool_bf16_64x112x112x64_3x3s2", (pn * ph_ * ph_ * pc + pn * 56 * 56 * pc) * 2,
-             lambda: (lambda i: xp.xp_pool2d_nhwc("max", pn, ph_, ph_, pc, 3, 3, 2, 2, 1, 1, px[i], py[i]))(nxt4()),
-             "4 rotating sets of 128 MB")
-        dn, dh, dc = 32, 112, 64
-        py2 = [torch.empty(dn, dh, dh, dc, device="cuda", dtype=torch.bfloat16) for _ in range(4)]
-        dwf = (0.3 * torch.randn(3, 3, dc, device="cuda")).bfloat16()
-        rate("depthwise_bf16_32x112x112x64_3x3s1", 2 * dn * dh * dh * dc * 2,
-             lambda: (lambda i: xp.xp_depthwise_conv2d_nhwc(dn, dh, dh, dc, 3, 3, 1, 1, 1, 1, px[i], dwf, "rsck", py2[i]))(nxt4()),
-             "4 rotating sets of 103 MB")
-        del px, py, py2
-        dcfg = inputs.DEFORMABLE_WORKLOAD
-        dlev, db, dhd, dd, dpt = dcfg["levels"], dcfg["batch"], dcfg["heads"], dcfg["d"], dcfg["points"]
-        dS = sum(h * w_ for h, w_ in dlev)
-        dv_np, dloc_np, dw_np = inputs.deformable_attention_inputs(db, dS, dhd, dd, dlev, dpt, seed=5)
-        dv = [torch.from_numpy(dv_np.view(np.int16)).cuda().view(torch.bfloat16)]
-        dloc, dwg = [torch.from_numpy(dloc_np).cuda()], [torch.from_numpy(dw_np).cuda()]
-        for _ in range(3):                       # the same values at other addresses
-            dv.append(dv[0].clone()); dloc.append(dloc[0].clone()); dwg.append(dwg[0].clone())
-        dout = [torch.empty(db * dS * dhd * dd, device="cuda") for _ in range(4)]
-        rate("deformable_attention_bf16_8x5440q_8h32_4l4p",
-             dv[0].numel() * 2 + dloc[0].numel() * 4 + dwg[0].numel() * 4 + dout[0].numel() * 4,
-             lambda: (lambda i: xp.xp_deformable_attention(db, dS, dhd, dd, dpt, dv[i], dlev, dloc[i], dwg[i], dout[i]))(nxt4()),
-             "4 rotating sets of 134 MB")
-        del dv, dloc, dwg, dout
+                         "pct_hbm_peak": round(100 * nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 2), "buffers": note}
         side["memory_bound"] = mem
         out["other_workloads"] = side
 

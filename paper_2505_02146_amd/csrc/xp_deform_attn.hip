@@ -16,6 +16,8 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int MAX_LEVELS = 16;
 
@@ -73,6 +75,15 @@ template <bool BF16, int EPC> struct Pixel {
 };
 
 constexpr int PU = 4;      // sampling points handled together: 16 corner fetches in flight per lane
+
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Neighbouring work items here
+// share cache lines (the heads of a pixel, the queries of an image), so XCD x (linear id mod 8) takes
+// a contiguous eighth of the items instead of every eighth one.  The grid is a multiple of 8; ids
+// beyond the number of items come out >= that number.
+__device__ __forceinline__ unsigned xcd_chunked(unsigned linear, unsigned grid)
+{
+    return (linear & 7u) * (grid >> 3) + (linear >> 3);
+}
 
 // PU sampling points of one (query, head) on one level.  `map` is the address of this lane's channels
 // in pixel (0,0) of the level (global memory or LDS), `pitch` the bytes from one pixel to the next;
@@ -184,6 +195,10 @@ template <bool BF16, int EPC> struct QuadSampler {
     unsigned own_off[4];
     float own_cw[4];
     unsigned own_ok;
+    // bf16 values: the corner weights as two bf16 terms each (w = hi + lo up to 2^-18 w), packed in
+    // corner pairs {0,1} and {2,3} -- the A operand of the matrix-core sum below
+    unsigned own_hi[2], own_lo[2];
+    unsigned wa[4][2];
     __device__ __forceinline__ void prepare(unsigned pitch, int H, int W, f32x2 xy, float aw)
     {
         float x = __builtin_fmaf(xy[0], (float)W, -0.5f), y = __builtin_fmaf(xy[1], (float)H, -0.5f);
@@ -205,19 +220,61 @@ template <bool BF16, int EPC> struct QuadSampler {
         own_off[2] = (unsigned)(yb * W + xl) * pitch;
         own_off[3] = (unsigned)(yb * W + xr) * pitch;
         own_ok = inside ? 1u : 0u;
+        if constexpr (BF16) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                own_hi[h] = pack_bf16(own_cw[2 * h], own_cw[2 * h + 1]);
+                own_lo[h] = pack_bf16(own_cw[2 * h] - __uint_as_float(own_hi[h] << 16),
+                                      own_cw[2 * h + 1] - __uint_as_float(own_hi[h] & 0xffff0000u));
+            }
+        }
     }
     template <int J> __device__ __forceinline__ void fetch_point(const char *map)
     {
         ok[J] = quad_bcast<J>(own_ok);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            cw[J][k] = quad_bcast<J>(own_cw[k]);
+            if constexpr (!BF16) cw[J][k] = quad_bcast<J>(own_cw[k]);
             px[J][k].fetch(map + quad_bcast<J>(own_off[k]));
+        }
+        if constexpr (BF16) {
+            // odd lanes of the quad carry the low terms, even lanes the high terms (rows 0 and 1 of the
+            // matrix product are used, rows 2 and 3 repeat them and are ignored)
+            const bool low = threadIdx.x & 1;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const unsigned hi = quad_bcast<J>(own_hi[h]), lo = quad_bcast<J>(own_lo[h]);
+                wa[J][h] = low ? lo : hi;
+            }
         }
     }
     __device__ __forceinline__ void fetch(const char *map)
     {
         fetch_point<0>(map); fetch_point<1>(map); fetch_point<2>(map); fetch_point<3>(map);
+    }
+    // bf16 values: the weighted sum of the four corners on the matrix cores.  v_mfma_f32_4x4x4_16B_bf16
+    // multiplies sixteen independent 4x4 blocks, one per lane quad: D[i][j] = sum_k A[i][k] B[k][j] with
+    // row i of A taken from lane i of the quad, column j of B and of D held by lane j.  Here k runs over
+    // the corners, column j is channel e of lane j's chunk, and the rows are the high and the low bf16
+    // terms of the corner weights: rows 0 and 1 of D add up to the fp32-weighted sum.  Per point that is
+    // 8 matrix instructions and 16 byte permutes (which also blank a point outside the map) in place
+    // of 32 widenings and 32 FMAs.
+    __device__ __forceinline__ void accumulate_mfma(f32x4 (&accm)[8]) const
+    {
+        static_assert(BF16 && EPC == 8, "bf16 chunks of eight channels");
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const unsigned sel_even = ok[j] ? 0x05040100u : 0x0c0c0c0cu, sel_odd = ok[j] ? 0x07060302u : 0x0c0c0c0cu;
+            const u32x2 aw = {wa[j][0], wa[j][1]};
+            const s16x4 a = __builtin_bit_cast(s16x4, aw);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const unsigned sel = (e & 1) ? sel_odd : sel_even;
+                const u32x2 bw = {__builtin_amdgcn_perm(px[j][1].w[e >> 1], px[j][0].w[e >> 1], sel),
+                                  __builtin_amdgcn_perm(px[j][3].w[e >> 1], px[j][2].w[e >> 1], sel)};
+                accm[e] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, __builtin_bit_cast(s16x4, bw), accm[e], 0, 0, 0);
+            }
+        }
     }
     __device__ __forceinline__ void accumulate(float (&acc)[EPC]) const
     {
@@ -274,7 +331,7 @@ enum { ANY = 0, FOUR = 1, QUAD = 2 };
 template <bool BF16, bool OUT_BF16, int EPC, int MODE> __global__ __launch_bounds__(256) void deform_kernel(DeformParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
-    const long long unit = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long unit = (long long)xcd_chunked(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
     if (unit >= p.units) return;
     const int chunks = p.d / EPC;
     const long long nqm = unit / chunks;                         // (n * Lq + q) * heads + m
@@ -287,6 +344,9 @@ template <bool BF16, bool OUT_BF16, int EPC, int MODE> __global__ __launch_bound
     float acc[EPC];
 #pragma unroll
     for (int i = 0; i < EPC; ++i) acc[i] = 0.0f;
+    f32x4 accm[8];                                               // QUAD with bf16 values: see accumulate_mfma
+#pragma unroll
+    for (int i = 0; i < 8; ++i) accm[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     const long long at0 = nqm * p.levels * p.points;
     LevelPoints ahead;
@@ -313,7 +373,8 @@ template <bool BF16, bool OUT_BF16, int EPC, int MODE> __global__ __launch_bound
             QuadSampler<BF16, EPC> qs;
             qs.prepare((unsigned)(pixel_stride * ES), H, W, xy, aw);
             qs.fetch(map);
-            qs.accumulate(acc);
+            if constexpr (BF16) qs.accumulate_mfma(accm);
+            else qs.accumulate(acc);
         } else if constexpr (MODE == FOUR) {
             const LevelPoints now = ahead;
             if (l + 1 < p.levels) ahead.load(p.loc + 2 * (at + 4), p.wgt + at + 4);
@@ -323,6 +384,10 @@ template <bool BF16, bool OUT_BF16, int EPC, int MODE> __global__ __launch_bound
             if (H == 0 || W == 0) continue;
             sample_level<BF16, EPC>(map, pixel_stride * ES, H, W, p.loc + 2 * at, p.wgt + at, p.points, acc);
         }
+    }
+    if constexpr (MODE == QUAD && BF16) {
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) acc[i] = accm[i][0] + accm[i][1];
     }
     store_out<OUT_BF16, EPC>(p.out, nqm * p.d + c0, acc);
 }
@@ -337,6 +402,8 @@ template <bool BF16, bool OUT_BF16, int EPC, int MODE> __global__ __launch_bound
 struct LdsPlan {
     int lds_off[MAX_LEVELS];             // byte offset of a staged level, -1: sampled from global memory
     int queries_per_wg;
+    unsigned qblocks, items;             // query blocks per (image, head); workgroups with work
+    int first_global;                    // first non-empty level that is not staged, -1 if there is none
 };
 constexpr int LDS_THREADS = 512;
 
@@ -345,8 +412,11 @@ template <bool BF16, bool OUT_BF16, int MODE> __global__ __launch_bounds__(LDS_T
     constexpr int EPC = BF16 ? 8 : 4, ES = BF16 ? 2 : 4;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x;
-    const int m = blockIdx.y;
-    const long long n = blockIdx.z;
+    const unsigned item = xcd_chunked(blockIdx.x, gridDim.x);    // (image, head, query block), query block fastest
+    if (item >= plan.items) return;
+    const int qblock = item % plan.qblocks;
+    const int m = (item / plan.qblocks) % p.heads;
+    const long long n = item / plan.qblocks / p.heads;
     const int CH = p.d / EPC;                                    // divides LDS_THREADS
     const int PB = p.d * ES;                                     // bytes of one pixel of one head
     const long long pixel_stride = (long long)p.heads * p.d;
@@ -364,8 +434,76 @@ template <bool BF16, bool OUT_BF16, int MODE> __global__ __launch_bounds__(LDS_T
     __syncthreads();
 
     const int c = tid % CH;
-    const int q_first = blockIdx.x * plan.queries_per_wg;
+    const int q_first = qblock * plan.queries_per_wg;
     const int q_end = min(p.Lq, q_first + plan.queries_per_wg);
+    if constexpr (MODE == QUAD) {
+        // At most four levels, four points each, lane c of a head prepares point c.  Loads return in
+        // order, so the sequence of a pass is: the positions and weights of the *next* pass (used only
+        // then), the gathers of the one level that lives in global memory, then -- while those are in
+        // flight -- the staged levels out of LDS, and last the sum over the global level's corners.
+        constexpr int ML = 4;
+        const int stride = LDS_THREADS / CH;
+        const int g = plan.first_global;
+        f32x2 xy_next[ML];
+        float a_next[ML];
+        auto load_points = [&](int q, f32x2 (&xy)[ML], float (&a)[ML]) {
+            const long long at0 = ((n * p.Lq + q) * p.heads + m) * (long long)p.levels * 4 + c;
+#pragma unroll
+            for (int l = 0; l < ML; ++l) {
+                xy[l] = f32x2{0.0f, 0.0f};
+                a[l] = 0.0f;
+                if (l < p.levels) {
+                    xy[l] = __builtin_nontemporal_load((const f32x2 *)(p.loc + 2 * (at0 + 4 * l)));
+                    a[l] = __builtin_nontemporal_load(p.wgt + at0 + 4 * l);
+                }
+            }
+        };
+        int q = q_first + tid / CH;
+        if (q < q_end) load_points(q, xy_next, a_next);
+        for (; q < q_end; q += stride) {
+            f32x2 xy[ML];
+            float a[ML];
+#pragma unroll
+            for (int l = 0; l < ML; ++l) { xy[l] = xy_next[l]; a[l] = a_next[l]; }
+            if (q + stride < q_end) load_points(q + stride, xy_next, a_next);
+            float acc[EPC];
+#pragma unroll
+            for (int i = 0; i < EPC; ++i) acc[i] = 0.0f;
+            f32x4 accm[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) accm[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            QuadSampler<BF16, EPC> qg;
+#pragma unroll
+            for (int l = 0; l < ML; ++l)
+                if (l == g) {
+                    qg.prepare((unsigned)(pixel_stride * ES), p.H[l], p.W[l], xy[l], a[l]);
+                    qg.fetch((const char *)p.value + (head_base + p.start[l] * pixel_stride) * ES + c * 16);
+                }
+#pragma unroll
+            for (int l = 0; l < ML; ++l) {
+                if (l >= p.levels || l == g) continue;
+                const int H = p.H[l], W = p.W[l];
+                if (H == 0 || W == 0) continue;
+                const bool staged = plan.lds_off[l] >= 0;
+                QuadSampler<BF16, EPC> qs;
+                qs.prepare(staged ? (unsigned)PB : (unsigned)(pixel_stride * ES), H, W, xy[l], a[l]);
+                if (staged) qs.fetch(lds + plan.lds_off[l] + c * 16);
+                else qs.fetch((const char *)p.value + (head_base + p.start[l] * pixel_stride) * ES + c * 16);
+                if constexpr (BF16) qs.accumulate_mfma(accm);
+                else qs.accumulate(acc);
+            }
+            if (g >= 0) {
+                if constexpr (BF16) qg.accumulate_mfma(accm);
+                else qg.accumulate(acc);
+            }
+            if constexpr (BF16) {
+#pragma unroll
+                for (int i = 0; i < EPC; ++i) acc[i] = accm[i][0] + accm[i][1];
+            }
+            store_out<OUT_BF16, EPC>(p.out, ((n * p.Lq + q) * p.heads + m) * p.d + c * EPC, acc);
+        }
+        return;
+    }
     for (int q = q_first + tid / CH; q < q_end; q += LDS_THREADS / CH) {
         const long long nqm = (n * p.Lq + q) * p.heads + m;
         float acc[EPC];
@@ -374,32 +512,13 @@ template <bool BF16, bool OUT_BF16, int MODE> __global__ __launch_bounds__(LDS_T
         const long long at0 = nqm * p.levels * p.points;
         LevelPoints ahead;
         if constexpr (MODE == FOUR) ahead.load(p.loc + 2 * at0, p.wgt + at0);
-        f32x2 xy_ahead = {0.0f, 0.0f};
-        float a_ahead = 0.0f;
-        if constexpr (MODE == QUAD) {                            // CH == 4: lane c of a head prepares point c
-            xy_ahead = __builtin_nontemporal_load((const f32x2 *)(p.loc + 2 * (at0 + c)));
-            a_ahead = __builtin_nontemporal_load(p.wgt + at0 + c);
-        }
         for (int l = 0; l < p.levels; ++l) {
             const int H = p.H[l], W = p.W[l];
             const long long at = at0 + (long long)l * p.points;
             const bool staged = plan.lds_off[l] >= 0;
             const char *global_map = (const char *)p.value + (head_base + p.start[l] * pixel_stride) * ES + c * 16;
             const char *lds_map = lds + (staged ? plan.lds_off[l] : 0) + c * 16;
-            if constexpr (MODE == QUAD) {
-                const f32x2 xy = xy_ahead;
-                const float aw = a_ahead;
-                if (l + 1 < p.levels) {
-                    xy_ahead = __builtin_nontemporal_load((const f32x2 *)(p.loc + 2 * (at + 4 + c)));
-                    a_ahead = __builtin_nontemporal_load(p.wgt + at + 4 + c);
-                }
-                if (H == 0 || W == 0) continue;
-                QuadSampler<BF16, EPC> qs;
-                qs.prepare(staged ? (unsigned)PB : (unsigned)(pixel_stride * ES), H, W, xy, aw);
-                if (staged) qs.fetch(lds_map);
-                else qs.fetch(global_map);
-                qs.accumulate(acc);
-            } else if constexpr (MODE == FOUR) {
+            if constexpr (MODE == FOUR) {
                 const LevelPoints now = ahead;
                 if (l + 1 < p.levels) ahead.load(p.loc + 2 * (at + 4), p.wgt + at + 4);
                 if (H == 0 || W == 0) continue;
@@ -431,7 +550,7 @@ int read_mode(const DeformParams &p, int epc, int es)
 
 template <bool BF16, bool OUT_BF16, int EPC> xp_status launch(const DeformParams &p, hipStream_t stream)
 {
-    const long long blocks = (p.units + 255) / 256;
+    const long long blocks = ((p.units + 255) / 256 + 7) / 8 * 8;          // a multiple of 8: see xcd_chunked
     if (blocks > 0x7fffffffLL) return XP_ERR_SHAPE;
     const int mode = EPC == 1 ? ANY : read_mode(p, EPC, BF16 ? 2 : 4);
     if constexpr (EPC > 1) {
@@ -449,7 +568,7 @@ constexpr int NUM_CUS = 256;
 bool plan_lds(const DeformParams &p, long long batch, int es, int epc, LdsPlan &plan, int &lds_bytes, dim3 &grid)
 {
     if (p.d % epc || LDS_THREADS % (p.d / epc) || p.points == 0 || p.levels == 0) return false;
-    if (batch > 65535 || p.heads > 65535 || p.Lq > (1 << 30)) return false;
+    if (p.Lq > (1 << 30)) return false;
     const int PB = p.d * es;
     // levels by size, smallest first, while they fit
     int order[MAX_LEVELS];
@@ -479,16 +598,25 @@ bool plan_lds(const DeformParams &p, long long batch, int es, int epc, LdsPlan &
     const long long qpw = (p.Lq + qblocks - 1) / qblocks;
     const long long gathered = qpw * nstaged * p.points * 4 * PB;
     if (staged * 4 > gathered) return false;
+    plan.first_global = -1;
+    for (int l = p.levels - 1; l >= 0; --l)
+        if (plan.lds_off[l] < 0 && p.H[l] > 0 && p.W[l] > 0) plan.first_global = l;
     plan.queries_per_wg = (int)qpw;
+    plan.qblocks = (unsigned)((p.Lq + qpw - 1) / qpw);
+    const long long items = pairs * plan.qblocks;
+    if (items > 0x7ffffff0LL) return false;
+    plan.items = (unsigned)items;
     lds_bytes = (int)staged;
-    grid = dim3((unsigned)((p.Lq + qpw - 1) / qpw), (unsigned)p.heads, (unsigned)batch);
+    grid = dim3((unsigned)((items + 7) / 8 * 8));
     return true;
 }
 
 template <bool BF16, bool OUT_BF16> xp_status launch_lds(const DeformParams &p, const LdsPlan &plan, int lds_bytes, dim3 grid,
                                                          hipStream_t stream)
 {
-    const int mode = read_mode(p, BF16 ? 8 : 4, BF16 ? 2 : 4);
+    int mode = read_mode(p, BF16 ? 8 : 4, BF16 ? 2 : 4);
+    if (mode == QUAD && p.levels > 4)            // that kernel keeps a pass's positions of all levels in registers
+        mode = (uintptr_t)p.loc % 16 == 0 && (uintptr_t)p.wgt % 16 == 0 ? FOUR : ANY;
     auto kernel = mode == QUAD ? deform_lds_kernel<BF16, OUT_BF16, QUAD>
                 : mode == FOUR ? deform_lds_kernel<BF16, OUT_BF16, FOUR> : deform_lds_kernel<BF16, OUT_BF16, ANY>;
     if (lds_bytes > 48 * 1024 &&
