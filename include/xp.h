@@ -14,7 +14,9 @@
  *     frees or keeps a pointer; there is no hidden workspace.
  *   - Inputs are read-only and may alias each other; the output must not overlap an input.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
- *     on it; the call does not wait for the GPU.
+ *     on it; the call does not wait for the GPU.  A stream under HIP graph capture is fine: the
+ *     compute entry points enqueue kernels only (the xp_tune_* calls synchronise and are not
+ *     capturable).
  *   - Arguments are validated on the host before anything is launched; on error nothing is
  *     launched and a status code is returned.  The library never aborts, throws or prints.
  *   - Supported (A, B -> C) element types: (F32, F32 -> F32), (BF16, BF16 -> F32),

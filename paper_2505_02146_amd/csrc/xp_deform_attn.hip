@@ -76,15 +76,6 @@ template <bool BF16, int EPC> struct Pixel {
 
 constexpr int PU = 4;      // sampling points handled together: 16 corner fetches in flight per lane
 
-// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Neighbouring work items here
-// share cache lines (the heads of a pixel, the queries of an image), so XCD x (linear id mod 8) takes
-// a contiguous eighth of the items instead of every eighth one.  The grid is a multiple of 8; ids
-// beyond the number of items come out >= that number.
-__device__ __forceinline__ unsigned xcd_chunked(unsigned linear, unsigned grid)
-{
-    return (linear & 7u) * (grid >> 3) + (linear >> 3);
-}
-
 // PU sampling points of one (query, head) on one level.  `map` is the address of this lane's channels
 // in pixel (0,0) of the level (global memory or LDS), `pitch` the bytes from one pixel to the next;
 // (lx, ly) the normalised position, a the attention weight, live[j] false for a padding slot.

@@ -129,6 +129,15 @@ __device__ __forceinline__ void xcd_batch_remap(unsigned &x, unsigned &y)
     }
 }
 
+// One-dimensional launches whose neighbouring workgroups share cache lines (window overlap, the heads
+// of a pixel): workgroups are dealt round-robin to the 8 XCDs, so XCD x (linear id mod 8) takes a
+// contiguous eighth of the work instead of every eighth item.  The grid must be a multiple of 8;
+// ids beyond the number of items come out >= that number and the caller skips them.
+__device__ __forceinline__ unsigned xcd_chunked(unsigned linear, unsigned grid)
+{
+    return (linear & 7u) * (grid >> 3) + (linear >> 3);
+}
+
 inline int elem_size(xp_dtype t) { return t == XP_F32 || t == XP_I32 ? 4 : (t == XP_BF16 ? 2 : 1); }
 
 }  // namespace xp

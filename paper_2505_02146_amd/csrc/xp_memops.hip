@@ -422,7 +422,8 @@ __global__ __launch_bounds__(256) void pool_kernel(PoolParams p)
 {
     constexpr int EPC = VEC ? Chunk<IB>::EPC : 1;
     const int cc = p.C / EPC;                               // channel groups per pixel
-    for (long long w = (long long)blockIdx.x * 256 + threadIdx.x; w < p.total; w += (long long)gridDim.x * 256) {
+    // neighbouring outputs share input rows: XCD-contiguous numbering (grid is a multiple of 8)
+    for (long long w = (long long)xcd_chunked(blockIdx.x, gridDim.x) * 256 + threadIdx.x; w < p.total; w += (long long)gridDim.x * 256) {
         const int cg = (int)(w % cc);
         long long pix = w / cc;
         const int q = (int)(pix % p.Q);
@@ -493,6 +494,7 @@ struct DwParams {
     const void *x, *w;
     void *y;
     long long total;
+    long long tiles;                                        // workgroups with work in the tiled kernel
     int H, W, C, R, S, P, Q, sh, sw, ph, pw;
     int channel_minor;                                      // w(c,r,s) at (r*S + s)*C + c, else (c*R + r)*S + s
 };
@@ -502,7 +504,7 @@ __global__ __launch_bounds__(256) void depthwise_kernel(DwParams p)
 {
     constexpr int EPC = VEC ? Chunk<IB>::EPC : 1;
     const int cc = p.C / EPC;
-    for (long long wi = (long long)blockIdx.x * 256 + threadIdx.x; wi < p.total; wi += (long long)gridDim.x * 256) {
+    for (long long wi = (long long)xcd_chunked(blockIdx.x, gridDim.x) * 256 + threadIdx.x; wi < p.total; wi += (long long)gridDim.x * 256) {
         const int cg = (int)(wi % cc);
         long long pix = wi / cc;
         const int q = (int)(pix % p.Q);
@@ -578,7 +580,9 @@ __global__ __launch_bounds__(256) void depthwise3x3_tile_kernel(DwParams p)
     const int cc = p.C / EPC;
     const int t = threadIdx.x;
     const int tiles_w = (p.Q + DW_TW - 1) / DW_TW, tiles_h = (p.P + DW_TH - 1) / DW_TH, cblocks = (cc + DW_CG - 1) / DW_CG;
-    int b = blockIdx.x;
+    // neighbouring tiles share their border rows and columns: XCD-contiguous numbering (grid is a multiple of 8)
+    long long b = xcd_chunked(blockIdx.x, gridDim.x);
+    if (b >= (long long)p.tiles) return;
     const int cb = b % cblocks; b /= cblocks;
     const int tw = b % tiles_w; b /= tiles_w;
     const int th = b % tiles_h;
@@ -703,6 +707,7 @@ xp_status xp_pool2d_nhwc(xp_pool_op op, int64_t N, int64_t H, int64_t W, int64_t
     p.sh = (int)stride_h; p.sw = (int)stride_w; p.ph = (int)pad_h; p.pw = (int)pad_w;
     long long blocks = (p.total + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
+    blocks = (blocks + 7) / 8 * 8;                          // see xcd_chunked
     const dim3 grid((unsigned)blocks), block(256);
     hipStream_t s = (hipStream_t)stream;
     const int win = (R == S && (R == 2 || R == 3) && vec) ? (int)R : 0;
@@ -749,16 +754,18 @@ xp_status xp_depthwise_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, i
     p.channel_minor = minor ? 1 : 0;
     long long blocks = (p.total + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
+    blocks = (blocks + 7) / 8 * 8;
     const dim3 grid((unsigned)blocks), block(256);
     hipStream_t s = (hipStream_t)stream;
     const bool win3 = vec && minor && R == 3 && S == 3;
     // stride 1 and an image of several tiles: the LDS-tiled kernel
     const bool tiled = win3 && stride_h == 1 && stride_w == 1 && P >= DW_TH && Q >= DW_TW;
     const long long tiles = N * ((P + DW_TH - 1) / DW_TH) * ((Q + DW_TW - 1) / DW_TW) * ((C / epc + DW_CG - 1) / DW_CG);
+    p.tiles = tiles;
 #define XP_DW(IB, OB)                                                                                  \
     do {                                                                                               \
-        if (tiled && tiles <= 0x7fffffffLL)                                                            \
-            hipLaunchKernelGGL((depthwise3x3_tile_kernel<IB, OB>), dim3((unsigned)tiles), block, 0, s, p); \
+        if (tiled && tiles <= 0x7ffffff0LL)                                                            \
+            hipLaunchKernelGGL((depthwise3x3_tile_kernel<IB, OB>), dim3((unsigned)((tiles + 7) / 8 * 8)), block, 0, s, p); \
         else if (win3) hipLaunchKernelGGL((depthwise_kernel<IB, OB, true, 3>), grid, block, 0, s, p);  \
         else if (vec) hipLaunchKernelGGL((depthwise_kernel<IB, OB, true, 0>), grid, block, 0, s, p);   \
         else hipLaunchKernelGGL((depthwise_kernel<IB, OB, false, 0>), grid, block, 0, s, p);           \
