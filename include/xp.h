@@ -206,8 +206,8 @@ xp_status xp_pool2d_nhwc(xp_pool_op op, int64_t N, int64_t H, int64_t W, int64_t
  * 2-D convolution, NCHW (Table 5, "Conv2D NCHW"): the sum of xp_conv2d_nhwc with
  *   input N x Cin x H x W, filter Cout x Cin x R x S (KCRS), output N x Cout x P x Q, all contiguous.
  * It is computed by a change of layout: activations and filter are transposed to NHWC / KRSC in the
- * workspace, the NHWC kernels run, the result is transposed back (three extra memory passes; callers
- * that can keep their tensors in NHWC should call xp_conv2d_nhwc).
+ * workspace, the NHWC kernels run and write the N x Cout x P x Q result directly (two extra memory
+ * passes over the inputs; callers that can keep their tensors in NHWC should call xp_conv2d_nhwc).
  *   workspace   DEVICE memory owned by the caller, 256-byte aligned, at least
  *               xp_conv2d_nchw_workspace_bytes(...) bytes (0 is returned for invalid or empty shapes);
  *               contents are scratch.  XP_ERR_WORKSPACE if missing, misaligned or too small.

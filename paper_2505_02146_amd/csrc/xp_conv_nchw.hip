@@ -1,8 +1,8 @@
 // Conv2D NCHW (Table 5 of the paper) by a change of layout: the activations are transposed to NHWC and
-// the KCRS filter to KRSC in a caller-provided workspace, the NHWC implicit-GEMM kernels do the work,
-// and the NHWC result is transposed back.  The MFMA kernels want the reduction index (channels)
-// contiguous, which is what NHWC is; the three transposes are plain memory passes (LDS-tiled, both
-// sides coalesced) and cost about as much as the operands are large.
+// the KCRS filter to KRSC in a caller-provided workspace (LDS-tiled passes, both sides coalesced), the
+// NHWC implicit-GEMM kernels do the work, and their epilogue writes the result straight into the
+// N x Cout x P x Q planes (Problem::c_plane).  The MFMA kernels want the reduction index (channels)
+// contiguous, which is what NHWC is; the output has no such constraint.
 #include "xp_internal.hpp"
 
 namespace xp {
@@ -40,12 +40,56 @@ __global__ __launch_bounds__(256) void transpose_kernel(TrParams p)
     }
 }
 
+// 2-byte elements, rows and cols multiples of 8, both buffers 16-byte aligned: 16-byte global accesses
+// on both sides.  Reading, a lane takes 8 consecutive columns of a row (8 lanes a row of the tile);
+// writing, 8 consecutive rows of a column gathered from LDS (8 lanes a 128-byte output segment).
+// The LDS pitch of 33 words puts the 8 rows of a lane's gather in 8 different banks.
+__global__ __launch_bounds__(256) void transpose16_kernel(TrParams p)
+{
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    constexpr int PITCH = TT + 2;                         // elements: 33 words
+    __shared__ __attribute__((aligned(16))) unsigned short tile[TT * PITCH];
+    const long long b = blockIdx.z;
+    const long long r0 = (long long)blockIdx.y * TT, c0 = (long long)blockIdx.x * TT;
+    const unsigned short *in = (const unsigned short *)p.in + b * p.rows * p.cols;
+    unsigned short *out = (unsigned short *)p.out + b * p.rows * p.cols;
+    const int t = threadIdx.x, chunk = t & 7, line = t >> 3;      // 8 chunks of 8 elements, 32 lines per pass
+    u32x4 v[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const long long r = r0 + line + 32 * i, c = c0 + chunk * 8;
+        v[i] = u32x4{0u, 0u, 0u, 0u};
+        if (r < p.rows && c < p.cols) v[i] = __builtin_nontemporal_load((const u32x4 *)(in + r * p.cols + c));
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        unsigned *dst = (unsigned *)(tile + (line + 32 * i) * PITCH + chunk * 8);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) dst[k] = v[i][k];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int cl = line + 32 * i;                     // column of the tile = output row
+        const long long c = c0 + cl, r = r0 + chunk * 8;
+        if (c < p.cols && r < p.rows) {
+            unsigned w[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                w[k] = (unsigned)tile[(chunk * 8 + 2 * k) * PITCH + cl] | ((unsigned)tile[(chunk * 8 + 2 * k + 1) * PITCH + cl] << 16);
+            __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, (u32x4 *)(out + c * p.rows + r));
+        }
+    }
+}
+
 hipError_t transpose(const void *in, void *out, int64_t batch, int64_t rows, int64_t cols, int esz, hipStream_t s)
 {
     TrParams p;
     p.in = in; p.out = out; p.rows = rows; p.cols = cols;
     const dim3 grid((unsigned)((cols + TT - 1) / TT), (unsigned)((rows + TT - 1) / TT), (unsigned)batch);
-    if (esz == 2) hipLaunchKernelGGL(transpose_kernel<unsigned short>, grid, dim3(256), 0, s, p);
+    if (esz == 2 && rows % 8 == 0 && cols % 8 == 0 && (uintptr_t)in % 16 == 0 && (uintptr_t)out % 16 == 0)
+        hipLaunchKernelGGL(transpose16_kernel, grid, dim3(256), 0, s, p);
+    else if (esz == 2) hipLaunchKernelGGL(transpose_kernel<unsigned short>, grid, dim3(256), 0, s, p);
     else hipLaunchKernelGGL(transpose_kernel<unsigned int>, grid, dim3(256), 0, s, p);
     return hipGetLastError();
 }
@@ -68,8 +112,8 @@ size_t xp_conv2d_nchw_workspace_bytes(int64_t N, int64_t H, int64_t W, int64_t C
     if (H + 2 * pad_h < R || W + 2 * pad_w < S) return 0;
     const int64_t P = (H + 2 * pad_h - R) / stride_h + 1, Q = (W + 2 * pad_w - S) / stride_w + 1;
     const size_t esz = (size_t)elem_size(in_type);
-    return round256((size_t)(N * H * W * Cin) * esz) + round256((size_t)(Cout * R * S * Cin) * esz) +
-           round256((size_t)(N * P * Q * Cout) * 4);
+    (void)P; (void)Q;
+    return round256((size_t)(N * H * W * Cin) * esz) + round256((size_t)(Cout * R * S * Cin) * esz);
 }
 
 xp_status xp_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t R, int64_t S,
@@ -94,7 +138,6 @@ xp_status xp_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t C
 
     char *x_nhwc = (char *)workspace;
     char *w_krsc = x_nhwc + round256((size_t)(N * H * W * Cin) * esz);
-    char *y_nhwc = w_krsc + round256((size_t)(Cout * R * S * Cin) * esz);
     hipStream_t s = (hipStream_t)stream;
     if (K > 0) {
         if (transpose(input, x_nhwc, N, Cin, H * W, esz, s) != hipSuccess) return XP_ERR_LAUNCH;        // [N][C][HW] -> [N][HW][C]
@@ -103,13 +146,11 @@ xp_status xp_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t C
     Problem q;
     bool nothing;
     const xp_status st = make_conv_problem(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, x_nhwc, in_type,
-                                           w_krsc, w_type, XP_FILTER_KRSC, y_nhwc, XP_F32, stream, &q, &nothing);
+                                           w_krsc, w_type, XP_FILTER_KRSC, output, XP_F32, stream, &q, &nothing);
     if (st != XP_OK) return st;
-    if (!nothing) {
-        const xp_status rs = run(q);
-        if (rs != XP_OK) return rs;
-    }
-    return transpose(y_nhwc, output, N, P * Q, Cout, 4, s) == hipSuccess ? XP_OK : XP_ERR_LAUNCH;       // [N][PQ][K] -> [N][K][PQ]
+    if (nothing) return XP_OK;
+    q.c_plane = P * Q;                                    // the kernels' epilogue writes [N][K][PQ] directly
+    return run(q);
 }
 
 }  // extern "C"

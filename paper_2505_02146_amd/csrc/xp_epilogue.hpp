@@ -98,4 +98,21 @@ __device__ __forceinline__ void store_block16t(const AccT &acc, OutT *C, long lo
     }
 }
 
+// The same transposed 16x16 block into a planar output: row i (a pixel) of column j (a channel) lives at
+// ((i / plane) * N + j) * plane + i % plane.  For each of a lane's four columns the 16 lanes l&15
+// write 16 consecutive rows: one 64-byte run of a plane while the rows stay inside one image.
+template <typename AccT, typename OutT>
+__device__ __forceinline__ void store_block16t_planar(const AccT &acc, OutT *C, long long plane, int blk_row0, int blk_col0,
+                                                      int lane, int M, int N, float alpha)
+{
+    const int row = blk_row0 + (lane & 15);
+    const int col0 = blk_col0 + (lane >> 4) * 4;
+    if (row >= M) return;
+    const long long img = row / plane, pix = row - img * plane;
+    OutT *dst = C + (img * N + col0) * plane + pix;
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+        if (col0 + v < N) dst[v * plane] = (OutT)(alpha * acc[v]);
+}
+
 }  // namespace xp

@@ -107,6 +107,7 @@ __global__ __launch_bounds__(ROWS * 64) void gemv_kernel(VParams p)
 template <xp_dtype T>
 bool gemv_can_run(const Problem &q)
 {
+    if (q.c_plane) return false;                          // planar output: the general and direct-to-LDS kernels only
     const int64_t esz = Elem<T>::SIZE;
     if (q.in_type != T || q.conv || q.N != 1 || q.K <= 0) return false;
     if (q.a_sk != 1 || q.b_sk != 1) return false;           // rows of A and the vector contiguous along K

@@ -13,7 +13,7 @@ struct GParams {
     const void *A, *B;
     void *C;
     int64_t M, N, K;
-    int64_t a_sm, a_sk, b_sk, b_sn, ldc;
+    int64_t a_sm, a_sk, b_sk, b_sn, ldc, c_plane;
     int64_t strideA, strideB, strideC;
     float alpha, beta;
     int conv;
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(256) void generic_kernel(GParams p)
         for (int j = 0; j < 4; ++j) {
             const int64_t n = n0 + tx + 16 * j;
             if (n >= p.N) continue;
-            TOut *dst = C + m * p.ldc + n;
+            TOut *dst = p.c_plane ? C + ((m / p.c_plane) * p.N + n) * p.c_plane + m % p.c_plane : C + m * p.ldc + n;
             if constexpr (std::is_floating_point<TAcc>::value) {
                 float v = p.alpha * acc[i][j];
                 if (p.beta != 0.0f) v = __builtin_fmaf(p.beta, *dst, v);
@@ -132,7 +132,7 @@ hipError_t launch_generic(const Problem &q)
     GParams p;
     p.A = q.A; p.B = q.B; p.C = q.C;
     p.M = q.M; p.N = q.N; p.K = q.K;
-    p.a_sm = q.a_sm; p.a_sk = q.a_sk; p.b_sk = q.b_sk; p.b_sn = q.b_sn; p.ldc = q.ldc;
+    p.a_sm = q.a_sm; p.a_sk = q.a_sk; p.b_sk = q.b_sk; p.b_sn = q.b_sn; p.ldc = q.ldc; p.c_plane = q.c_plane;
     p.strideA = q.strideA; p.strideB = q.strideB; p.strideC = q.strideC;
     p.alpha = q.alpha; p.beta = q.beta;
     p.conv = q.conv ? 1 : 0;

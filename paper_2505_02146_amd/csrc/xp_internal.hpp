@@ -21,6 +21,8 @@ struct Problem {
     int64_t a_sm, a_sk;           // A(i,k) = A[i*a_sm + k*a_sk]   (unused for conv)
     int64_t b_sk, b_sn;           // B(k,j) = B[k*b_sk + j*b_sn]
     int64_t ldc;                  // C(i,j) = C[i*ldc + j]
+    int64_t c_plane;              // > 0: planar output instead (NCHW convolution results), C(i,j) =
+                                  // C[((i / c_plane) * N + j) * c_plane + i % c_plane]; ldc unused; beta == 0
     int64_t strideA, strideB, strideC;
     float alpha, beta;
     bool conv;

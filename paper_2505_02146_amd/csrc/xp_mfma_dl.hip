@@ -43,6 +43,7 @@ struct DlParams {
     int KT;                               // number of K steps
     long long lda_b, ldb_b;               // row pitches in bytes
     long long ldc;                        // elements
+    long long c_plane;                    // > 0: planar output (see Problem::c_plane)
     long long strideA_b, strideB_b, strideC;
     float alpha, beta;
     int tiles_m, tiles_n, group_m;
@@ -393,6 +394,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             if constexpr (MF == 32)
                 store_block32<INT8, T::NTSTORE>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 32, n0 + wn * T::WTN + j * 32, lane, m_end,
                                     p.N, p.alpha, p.beta);
+            else if (p.c_plane)
+                store_block16t_planar(acc[i][j], C, p.c_plane, m0 + wm * T::WTM + i * 16, n0 + wn * T::WTN + j * 16, lane, m_end,
+                                      p.N, p.alpha);
             else
                 store_block16t<INT8, T::NTSTORE>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 16, n0 + wn * T::WTN + j * 16, lane, m_end,
                                      p.N, p.alpha, p.beta);
@@ -421,8 +425,10 @@ __global__ __launch_bounds__(T1::NT, 1) void dl_kernel_two_heights(DlParams p)
 // ------------------------------------------------------------------------------------ host side
 
 template <bool INT8>
-bool dl_can_run_common(const Problem &q, int BM, int BN, int RB)
+bool dl_can_run_common(const Problem &q, int BM, int BN, int RB, int MF)
 {
+    // planar output: the 16x16 blocks' lanes hold 16 consecutive rows of a column, a contiguous run of a plane
+    if (q.c_plane && (MF != 16 || q.beta != 0.0f || INT8)) return false;
     const int64_t esz = INT8 ? 1 : 2;
     if (q.in_type != (INT8 ? XP_I8 : XP_BF16)) return false;
     if (q.K <= 0) return false;
@@ -458,6 +464,7 @@ DlParams dl_params(const Problem &q)
     p.KT = (p.Kb + T::RB - 1) / T::RB;
     p.lda_b = q.a_sm * esz; p.ldb_b = q.b_sn * esz;
     p.ldc = q.ldc;
+    p.c_plane = q.c_plane;
     p.strideA_b = q.strideA * esz; p.strideB_b = q.strideB * esz; p.strideC = q.strideC;
     p.alpha = q.alpha; p.beta = q.beta;
     p.tiles_m = (int)((q.M + T::BM - 1) / T::BM);
@@ -522,7 +529,7 @@ double dl_cost(const Problem &q, double eff)
 }
 
 #define XP_DL_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NS, RB, SPREAD, SPREADSTR, OCC, MF, NT, NTSTR, EFF)                                        \
-    bool NAME##_can(const Problem &q) { return dl_can_run_common<INT8>(q, BM, BN, RB); }                       \
+    bool NAME##_can(const Problem &q) { return dl_can_run_common<INT8>(q, BM, BN, RB, MF); }                       \
     hipError_t NAME##_launch(const Problem &q) { return dl_launch<INT8, DlTile<BM, BN, WM, WN, NS, RB, SPREAD, OCC, MF, NT>>(q); }  \
     double NAME##_cost(const Problem &q) { return dl_cost<DlTile<BM, BN, WM, WN, NS, RB, SPREAD, OCC, MF, NT>>(q, EFF); }           \
     const Variant NAME = {TYPESTR " " #BM "x" #BN "x" #RB "B waves " #WM "x" #WN " ring " #NS SPREADSTR " direct-to-lds" NTSTR " mfma" #MF, \
@@ -562,7 +569,7 @@ XP_DL_VARIANT(kI8Dl128x128r64n4s, "i8", true, 128, 128, 2, 2, 4, 64, true, " spr
 
 // one more A buffer than B buffers: three A + two B buffers of 32 KB fill the 160 KB of LDS exactly
 #define XP_DL_ASYM_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, MF, EFF)                                                              \
-    bool NAME##_can(const Problem &q) { return dl_can_run_common<INT8>(q, BM, BN, 128); }                                            \
+    bool NAME##_can(const Problem &q) { return dl_can_run_common<INT8>(q, BM, BN, 128, 16); }                                            \
     hipError_t NAME##_launch(const Problem &q) { return dl_launch<INT8, DlTile<BM, BN, WM, WN, 2, 128, false, 1, MF, false, 3>>(q); } \
     double NAME##_cost(const Problem &q) { return dl_cost<DlTile<BM, BN, WM, WN, 2, 128, false, 1, MF, false, 3>>(q, EFF); }          \
     const Variant NAME = {TYPESTR " " #BM "x" #BN "x128B waves " #WM "x" #WN " ring 3(A)+2(B) direct-to-lds mfma" #MF, NAME##_can, \
@@ -575,7 +582,7 @@ XP_DL_ASYM_VARIANT(kI8Dl256x256a3m16, "i8", true, 256, 256, 2, 4, 16, 0.54)
 // 224-row tiles in whole rounds, a last round of 192-row tiles
 typedef DlTile<224, 256, 2, 4, 2, 128, false, 1, 16, false, 3> TwoHi;
 typedef DlTile<192, 256, 2, 4, 2, 128, false, 1, 16, false, 3> TwoLo;
-bool kBfDlTwoHeights_can(const Problem &q) { return dl_can_run_common<false>(q, 224, 256, 128); }
+bool kBfDlTwoHeights_can(const Problem &q) { return dl_can_run_common<false>(q, 224, 256, 128, 16); }
 hipError_t kBfDlTwoHeights_launch(const Problem &q) { return dl_launch_two_heights<false, TwoHi, TwoLo>(q); }
 double kBfDlTwoHeights_cost(const Problem &q) { return dl_cost<TwoHi>(q, 0.49); }
 const Variant kBfDlTwoHeights = {"bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 3(A)+2(B) direct-to-lds mfma16",

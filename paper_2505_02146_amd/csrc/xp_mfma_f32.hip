@@ -126,6 +126,7 @@ __global__ __launch_bounds__(256) void f32_kernel(FParams p)
 
 bool f32_can_run(const Problem &q)
 {
+    if (q.c_plane) return false;                          // planar output: the general and direct-to-LDS kernels only
     if (q.in_type != XP_F32 || q.conv) return false;
     if (q.M > 0x7fffffffLL || q.N > 0x7fffffffLL || q.K > 0x7fffffffLL) return false;
     return q.batch <= 65535 && ((q.M + 63) / 64) * ((q.N + 63) / 64) <= 0x7fffffffLL;

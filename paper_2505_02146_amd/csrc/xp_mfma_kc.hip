@@ -328,6 +328,7 @@ __global__ __launch_bounds__(T::NT) void kc_kernel(KcParams p)
 template <bool INT8>
 bool kc_can_run_common(const Problem &q, int BM, int BN)
 {
+    if (q.c_plane) return false;                          // planar output: the general and direct-to-LDS kernels only
     const int64_t esz = INT8 ? 1 : 2;
     if (q.in_type != (INT8 ? XP_I8 : XP_BF16)) return false;
     if (q.K <= 0) return false;

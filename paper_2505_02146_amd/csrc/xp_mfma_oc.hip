@@ -282,6 +282,7 @@ bool oc_operand_ok(const void *base, int64_t s_outer, int64_t s_k, int64_t outer
 template <bool INT8, int BM, int BN, int WM, int WN>
 bool oc_can_run(const Problem &q)
 {
+    if (q.c_plane) return false;                          // planar output: the general and direct-to-LDS kernels only
     if (q.in_type != (INT8 ? XP_I8 : XP_BF16) || q.conv) return false;
     if (q.K <= 0 || q.M > 0x7fffffffLL || q.N > 0x7fffffffLL || q.K > 0x3fffffffLL || q.batch > 65535) return false;
     bool a_oc, b_oc;

@@ -264,6 +264,7 @@ __global__ __launch_bounds__(512) void pp_kernel(PpParams p)
 template <bool INT8>
 bool pp_can_run(const Problem &q)
 {
+    if (q.c_plane) return false;                          // planar output: the general and direct-to-LDS kernels only
     const int64_t esz = INT8 ? 1 : 2;
     if (q.in_type != (INT8 ? XP_I8 : XP_BF16) || q.conv) return false;
     if (q.K <= 0 || (q.K * esz) % 16 != 0) return false;

@@ -185,6 +185,7 @@ __global__ __launch_bounds__(320) void sk_kernel(SkParams p)
 template <bool INT8, int BN>
 bool sk_can_run(const Problem &q)
 {
+    if (q.c_plane) return false;                          // planar output: the general and direct-to-LDS kernels only
     const int64_t esz = INT8 ? 1 : 2;
     if (q.in_type != (INT8 ? XP_I8 : XP_BF16) || q.conv) return false;
     if (q.K <= 0 || q.K * esz > RB || (q.K * esz) % 16 != 0) return false;

@@ -270,7 +270,7 @@ def test_conv_nchw_validation(lib):
     assert call(H=1, W=1, ph=0, pw=0, x=None, w=None, out=None, ws=None) == 0
     assert call(N=0, x=None, w=None, out=None, ws=None) == 0
     need = lib.xp_conv2d_nchw_workspace_bytes(1, 4, 4, 2, 2, 3, 3, 1, 1, 1, 1, 0)
-    assert need == 256 + 256 + 256                       # 128 B + 144 B + 128 B, each rounded up to 256
+    assert need == 256 + 256                             # activations 128 B + filter 144 B, each rounded up to 256
     assert lib.xp_conv2d_nchw_workspace_bytes(1, 4, 4, 2, 2, 0, 3, 1, 1, 1, 1, 0) == 0
 
 

@@ -63,3 +63,29 @@ def test_conv_nchw_resnet_stage_sampled(xp, oracle):
     for n in (0, 31):
         ref = oracle.conv2d_nchw(np.ascontiguousarray(x[n:n + 1]), w, N=1, H=H, W=W, Cin=C, Cout=C, R=3, S=3, pad=(1, 1))
         check_float(got[n:n + 1], ref, f"nchw workload image {n}")
+
+
+def test_every_variant_writes_planes_or_declines(xp, oracle):
+    """Forced through each convolution variant: it either declines the planar output or produces it."""
+    import torch
+    N, H, W, Cin, Cout = 3, 13, 10, 64, 80                     # P*Q = 130: 16-row blocks straddle the images
+    x = inputs.to_bf16_bits(inputs.normal((N, Cin, H, W), 9, 1))
+    w = inputs.to_bf16_bits(inputs.normal((Cout, Cin, 3, 3), 9, 2, 1.0 / 24.0))
+    ref = oracle.conv2d_nchw(x, w, N=N, H=H, W=W, Cin=Cin, Cout=Cout, R=3, S=3, pad=(1, 1))
+    ws = torch.empty(xp.xp_conv2d_nchw_workspace_bytes(N, H, W, Cin, Cout, 3, 3, 1, 1, 1, 1, "bf16"), dtype=torch.uint8, device="cuda")
+    ran = []
+    try:
+        for idx in range(xp.xp_num_configs(2, "bf16")):
+            xp.xp_force_config(2, "bf16", idx)
+            out = torch.full(ref.shape, float("nan"), device="cuda")
+            try:
+                xp.xp_conv2d_nchw(N, H, W, Cin, Cout, 3, 3, 1, 1, 1, 1, dev(x.reshape(-1)), dev(w.reshape(-1)), out, ws,
+                                  in_type="bf16", w_type="bf16")
+            except xp.XpError as e:
+                assert e.status == 6, (idx, e.status)                  # XP_ERR_CONFIG: this variant cannot run the call
+                continue
+            check_float(out.cpu().numpy(), ref, f"planar output, variant {idx}: {xp.xp_describe_config(2, 'bf16', idx)}")
+            ran.append(idx)
+    finally:
+        xp.xp_force_config(2, "bf16", -1)
+    assert 0 in ran and len(ran) >= 5, ran                     # the general kernel and the 16x16-block direct-to-LDS kernels
