@@ -265,17 +265,28 @@ hipError_t launch_row(const RowParams &p, hipStream_t stream)
                      p.ldy % EPC == 0 && (!p.gamma || aligned(p.gamma, 16)) && (!p.beta || aligned(p.beta, 16)) &&
                      p.rows <= 0x7fffffffLL;
     const int nchunks = p.cols / EPC;
-    const dim3 g4((unsigned)((p.rows + 3) / 4)), g1((unsigned)p.rows);
-    // the fewest threads per row that can hold it, and no more register chunks than the row needs
-    if (vec && nchunks <= 64 * 1) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 64, 1>), g4, dim3(256), 0, stream, p);
-    else if (vec && nchunks <= 64 * 2) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 64, 2>), g4, dim3(256), 0, stream, p);
-    else if (vec && nchunks <= 64 * 4) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 64, 4>), g4, dim3(256), 0, stream, p);
-    else if (vec && nchunks <= 64 * 8) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 64, 8>), g4, dim3(256), 0, stream, p);
-    else if (vec && nchunks <= 256 * 4) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 256, 4>), g1, dim3(256), 0, stream, p);
-    else if (vec && nchunks <= 256 * 8) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 256, 8>), g1, dim3(256), 0, stream, p);
-    else if (vec && nchunks <= 1024 * 4) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 1024, 4>), g1, dim3(1024), 0, stream, p);
-    else if (vec && nchunks <= 1024 * 8) hipLaunchKernelGGL((row_kernel<OP, IB, OB, 1024, 8>), g1, dim3(1024), 0, stream, p);
-    else hipLaunchKernelGGL((row_general_kernel<OP, IB, OB>), g1, dim3(256), 0, stream, p);
+    const dim3 g1((unsigned)p.rows);
+    // Threads per row: a sweep over row lengths (512 .. 32768 columns, fp32 and bf16, all three
+    // operators) found two 16-byte chunks per thread the best point -- fewer registers, more waves in
+    // flight -- up to 512 threads a row; longer rows take four chunks at 512 threads, then 1024 threads.
+    int tpr = 64;
+    while (tpr < 512 && (nchunks + tpr - 1) / tpr > 2) tpr *= 2;
+    if ((nchunks + tpr - 1) / tpr > 4) tpr = 1024;
+    const int need = (nchunks + tpr - 1) / tpr;
+    const int nc = need <= 1 ? 1 : (need <= 2 ? 2 : (need <= 4 ? 4 : 8));
+    const int block = tpr < 256 ? 256 : tpr;
+    const dim3 grid((unsigned)((p.rows + block / tpr - 1) / (block / tpr)));
+    bool done = false;
+#define XP_ROW(TPR, NC)                                                                                        \
+    if (!done && vec && tpr == TPR && nc == NC && need <= 8) {                                                 \
+        hipLaunchKernelGGL((row_kernel<OP, IB, OB, TPR, NC>), grid, dim3(block), 0, stream, p);                \
+        done = true;                                                                                           \
+    }
+    // the (threads, chunks) pairs that rule can produce
+    XP_ROW(64, 1) XP_ROW(64, 2) XP_ROW(128, 2) XP_ROW(256, 2) XP_ROW(512, 2) XP_ROW(512, 4) XP_ROW(1024, 4) XP_ROW(1024, 8)
+#undef XP_ROW
+    if (done) return hipGetLastError();
+    hipLaunchKernelGGL((row_general_kernel<OP, IB, OB>), g1, dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 
