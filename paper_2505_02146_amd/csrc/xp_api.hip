@@ -7,6 +7,8 @@
 
 #include "xp_internal.hpp"
 
+#include <cmath>
+
 namespace xp {
 
 namespace {
@@ -67,11 +69,16 @@ const Variant *variant(xp_dtype in_type, int idx)
 
 namespace {
 
-// Selection.  Shapes that have been swept on the hardware (sweep.py: every variant forced, gated
-// and timed -- the brute-force parameter search of Section 5.1 of the paper with the reward of
-// Eq. 3-4) are looked up in a table of winners.  Any other shape falls back to a cost estimate
-// that every variant supplies (rounds of workgroups on 256 compute units x tile work / swept
-// efficiency); the cheapest variant that can run the call wins.  Variant 0 always can.
+// Selection.  Shapes that have been swept on the hardware (sweep.py / tune_grid.py: every variant
+// forced, gated and timed -- the brute-force parameter search of Section 5.1 of the paper with the
+// reward of Eq. 3-4) are looked up in a table of winners.  The first entries are the workloads, swept
+// by hand; xp_tuned_table.inc is a grid of common shapes the run-time tuner went through.  A shape
+// that is not in the table takes the winner of its nearest neighbour there -- same operator, type
+// and operand contiguity, distance = sum of |log2| of the ratios of batch, M, N and K, at most
+// kNear -- since the best tile changes slowly with the shape.  Anything farther from every swept
+// shape falls back to a cost estimate that every variant supplies (rounds of workgroups on 256
+// compute units x tile work / swept efficiency); the cheapest variant that can run the call wins.
+// Variant 0 always can.
 struct Tuned {
     xp_op op;
     xp_dtype type;
@@ -87,23 +94,59 @@ const Tuned kTuned[] = {
     {XP_OP_GEMM_BATCHED, XP_BF16, 96, 512, 512, 64, true, true, "bf16 64x128-stream x128B single-k-step producer/consumer nt-stores mfma32"},
     {XP_OP_GEMM_BATCHED, XP_BF16, 96, 512, 64, 512, true, false, "bf16 64x64x128B waves 2x2 k-group-interleaved mfma32"},
     {XP_OP_CONV2D, XP_BF16, 1, 100352, 256, 2304, true, true, "bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 3(A)+2(B) direct-to-lds mfma16"},
+#include "xp_tuned_table.inc"
+};
+constexpr int kNumTuned = (int)(sizeof kTuned / sizeof kTuned[0]);
+constexpr float kNear = 2.0f;
+
+// per entry, resolved once: the variant's index and the logarithms of the extents
+struct TunedIndex {
+    int variant[kNumTuned];
+    float lg[kNumTuned][4];
+    TunedIndex()
+    {
+        for (int i = 0; i < kNumTuned; ++i) {
+            const Tuned &t = kTuned[i];
+            variant[i] = -1;
+            const int n = num_variants(t.type);
+            for (int v = 0; v < n; ++v)
+                if (strcmp(xp::variant(t.type, v)->name, t.variant) == 0) variant[i] = v;
+            lg[i][0] = log2f((float)t.batch); lg[i][1] = log2f((float)t.M); lg[i][2] = log2f((float)t.N); lg[i][3] = log2f((float)t.K);
+        }
+    }
 };
 
 int tuned_variant(const Problem &q)
 {
+    static const TunedIndex index;
     const bool a_kc = q.conv || q.a_sk == 1, b_kc = q.b_sk == 1;
-    for (const Tuned &t : kTuned) {
-        if (t.op != q.op || t.type != q.in_type || t.batch != q.batch || t.M != q.M || t.N != q.N || t.K != q.K ||
-            t.a_kc != a_kc || t.b_kc != b_kc)
-            continue;
-        const int n = num_variants(q.in_type);
-        for (int i = 0; i < n; ++i)
-            if (strcmp(variant(q.in_type, i)->name, t.variant) == 0 && variant(q.in_type, i)->can_run(q)) return i;
+    // an exact entry wins (the first one: the hand-swept workloads precede the grid)
+    for (int i = 0; i < kNumTuned; ++i) {
+        const Tuned &t = kTuned[i];
+        if (t.op == q.op && t.type == q.in_type && t.batch == q.batch && t.M == q.M && t.N == q.N && t.K == q.K && t.a_kc == a_kc &&
+            t.b_kc == b_kc) {
+            const int v = index.variant[i];
+            if (v >= 0 && variant(q.in_type, v)->can_run(q)) return v;
+            break;
+        }
     }
-    return -1;
+    if (q.K <= 0) return -1;
+    const float lq[4] = {log2f((float)q.batch), log2f((float)q.M), log2f((float)q.N), log2f((float)q.K)};
+    int best = -1;
+    // XP_TABLE_NEAR overrides the radius for tuning experiments (0: exact entries only)
+    static const float near = [] { const char *e = getenv("XP_TABLE_NEAR"); return e ? (float)atof(e) : kNear; }();
+    float best_d = near;
+    for (int i = 0; i < kNumTuned; ++i) {
+        const Tuned &t = kTuned[i];
+        if (t.op != q.op || t.type != q.in_type || t.a_kc != a_kc || t.b_kc != b_kc || index.variant[i] < 0) continue;
+        const float d = fabsf(lq[0] - index.lg[i][0]) + fabsf(lq[1] - index.lg[i][1]) + fabsf(lq[2] - index.lg[i][2]) +
+                        fabsf(lq[3] - index.lg[i][3]);
+        if (d <= best_d && variant(q.in_type, index.variant[i])->can_run(q)) { best_d = d; best = index.variant[i]; }
+    }
+    return best;
 }
 
-int select_variant(const Problem &q)
+int select_uncached(const Problem &q)
 {
     const int learned = runtime_tuned_variant(q);        // shapes tuned in this process or loaded from a file
     if (learned >= 0) return learned;
@@ -121,7 +164,47 @@ int select_variant(const Problem &q)
     return best;
 }
 
+// Programs call the same few shapes over and over, and a table walk costs microseconds that a small
+// kernel does not have: each thread remembers its last selections.  A remembered variant is used
+// only if it can still run this call (alignment and pitches are not part of the key); changes of the
+// run-time table invalidate everything through the generation count.
+std::atomic<unsigned> g_generation{1};
+
+struct SelKey {
+    int64_t op, type, kc, batch, M, N, K, planar;
+    bool operator==(const SelKey &o) const { return memcmp(this, &o, sizeof *this) == 0; }
+};
+struct SelSlot {
+    SelKey key;
+    int variant;
+    unsigned generation;                                  // 0: empty
+};
+
+int select_variant(const Problem &q)
+{
+    constexpr int SLOTS = 64;
+    static thread_local SelSlot cache[SLOTS];
+    SelKey k;
+    k.op = q.op; k.type = q.in_type; k.kc = ((q.conv || q.a_sk == 1) ? 1 : 0) | (q.b_sk == 1 ? 2 : 0);
+    k.batch = q.batch; k.M = q.M; k.N = q.N; k.K = q.K; k.planar = q.c_plane != 0;
+    uint64_t h = 1469598103934665603ull;
+    for (const int64_t w : {k.op, k.type, k.kc, k.batch, k.M, k.N, k.K, k.planar}) { h ^= (uint64_t)w; h *= 1099511628211ull; }
+    SelSlot &slot = cache[(h >> 20) % SLOTS];
+    const unsigned gen = g_generation.load(std::memory_order_acquire);
+    if (slot.generation == gen && slot.key == k) {
+        const Variant *v = variant(q.in_type, slot.variant);
+        if (v && v->can_run(q)) return slot.variant;
+    }
+    const int v = select_uncached(q);
+    slot.key = k;
+    slot.variant = v;
+    slot.generation = gen;
+    return v;
+}
+
 }  // namespace
+
+void selection_changed() { g_generation.fetch_add(1, std::memory_order_acq_rel); }
 
 xp_status launch_variant(const Problem &q, int idx)
 {

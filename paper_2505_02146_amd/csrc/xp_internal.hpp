@@ -87,6 +87,7 @@ xp_status launch_variant(const Problem &q, int idx);      // that variant or XP_
 xp_status run(const Problem &q);                          // forced variant, else selection
 // Table of shapes tuned at run time or loaded from a file (xp_tune.hip): index of the recorded
 // variant if the shape is known and the variant can run the call, else -1.
+void selection_changed();                                   // the run-time table changed: forget remembered selections
 int runtime_tuned_variant(const Problem &q);
 
 // Run-time estimate (microseconds) shared by the MFMA variants' cost functions, used only for shapes

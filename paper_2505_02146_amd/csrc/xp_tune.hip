@@ -14,12 +14,67 @@
 #include <map>
 #include <mutex>
 #include <string>
+#include <unordered_map>
 
 namespace xp {
 namespace {
 
 std::mutex g_mutex;
-std::map<std::string, std::string> g_table;     // shape key -> variant name
+std::map<std::string, std::string> g_table;     // shape key -> variant name: what is saved and loaded
+
+// The same table for the launch path, which must not format strings: the key as plain numbers
+// (everything shape_key prints), the variant resolved to its index.
+struct FastKey {
+    int64_t v[16];
+    bool operator==(const FastKey &o) const { return memcmp(v, o.v, sizeof v) == 0; }
+};
+struct FastHash {
+    size_t operator()(const FastKey &k) const
+    {
+        uint64_t h = 1469598103934665603ull;                // FNV-1a over the words
+        for (int64_t w : k.v) { h ^= (uint64_t)w; h *= 1099511628211ull; }
+        return (size_t)h;
+    }
+};
+std::unordered_map<FastKey, int, FastHash> g_fast;
+
+FastKey fast_key(const Problem &q)
+{
+    FastKey k;
+    memset(&k, 0, sizeof k);
+    const int a_kc = (q.conv || q.a_sk == 1) ? 1 : 0, b_kc = q.b_sk == 1 ? 1 : 0;
+    k.v[0] = q.conv ? -1 : (int64_t)q.op;
+    k.v[1] = (int64_t)q.in_type;
+    k.v[2] = b_kc;
+    if (q.conv) {
+        const int64_t c[] = {q.M / (q.P * q.Q), q.H, q.W, q.Cin, q.N, q.R, q.S, q.sh, q.sw, q.ph, q.pw};
+        for (int i = 0; i < 11; ++i) k.v[3 + i] = c[i];
+    } else {
+        k.v[3] = q.batch; k.v[4] = q.M; k.v[5] = q.N; k.v[6] = q.K; k.v[7] = a_kc;
+    }
+    return k;
+}
+
+// the inverse of shape_key, for tables read from a file; false if the text is not a key
+bool parse_key(const char *text, FastKey *k, xp_dtype *type)
+{
+    memset(k, 0, sizeof *k);
+    long long c[12];
+    int t, op, a, b;
+    if (sscanf(text, "conv t%d n%lld h%lld w%lld c%lld k%lld r%lld s%lld sh%lld sw%lld ph%lld pw%lld b%d", &t, &c[0], &c[1], &c[2],
+               &c[3], &c[4], &c[5], &c[6], &c[7], &c[8], &c[9], &c[10], &b) == 13) {
+        k->v[0] = -1; k->v[1] = t; k->v[2] = b;
+        for (int i = 0; i < 11; ++i) k->v[3 + i] = c[i];
+        *type = (xp_dtype)t;
+        return true;
+    }
+    if (sscanf(text, "gemm%d t%d b%lld m%lld n%lld k%lld a%d b%d", &op, &t, &c[0], &c[1], &c[2], &c[3], &a, &b) == 8) {
+        k->v[0] = op; k->v[1] = t; k->v[2] = b; k->v[3] = c[0]; k->v[4] = c[1]; k->v[5] = c[2]; k->v[6] = c[3]; k->v[7] = a;
+        *type = (xp_dtype)t;
+        return true;
+    }
+    return false;
+}
 
 std::string shape_key(const Problem &q)
 {
@@ -177,7 +232,9 @@ xp_status tune(const Problem &q0, void *workspace, size_t workspace_bytes, int r
     {
         std::lock_guard<std::mutex> lock(g_mutex);
         g_table[shape_key(q0)] = variant(q0.in_type, win)->name;
+        g_fast[fast_key(q0)] = win;
     }
+    selection_changed();
     if (best) *best = win;
     if (best_us) *best_us = win_us;
     return launch_variant(q0, win);                                                 // C itself, once, with the winner
@@ -187,16 +244,15 @@ xp_status tune(const Problem &q0, void *workspace, size_t workspace_bytes, int r
 
 int runtime_tuned_variant(const Problem &q)
 {
-    std::string name;
+    int v;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
-        if (g_table.empty()) return -1;
-        auto it = g_table.find(shape_key(q));
-        if (it == g_table.end()) return -1;
-        name = it->second;
+        if (g_fast.empty()) return -1;
+        auto it = g_fast.find(fast_key(q));
+        if (it == g_fast.end()) return -1;
+        v = it->second;
     }
-    const int v = variant_by_name(q.in_type, name);
-    return (v >= 0 && variant(q.in_type, v)->can_run(q)) ? v : -1;
+    return variant(q.in_type, v)->can_run(q) ? v : -1;
 }
 
 }  // namespace xp
@@ -281,9 +337,18 @@ xp_status xp_tune_load(const char *path)
         if (!bar) continue;
         std::string key(line, bar - line), name(bar + 3);
         while (!name.empty() && (name.back() == '\n' || name.back() == '\r' || name.back() == ' ')) name.pop_back();
-        if (!key.empty() && !name.empty()) g_table[key] = name;
+        if (key.empty() || name.empty()) continue;
+        g_table[key] = name;
+        FastKey fk;
+        xp_dtype type;
+        if (parse_key(key.c_str(), &fk, &type)) {
+            const int v = variant_by_name(type, name);       // names this build does not know are kept in the text only
+            if (v >= 0) g_fast[fk] = v;
+            else g_fast.erase(fk);
+        }
     }
     fclose(f);
+    selection_changed();
     return XP_OK;
 }
 
@@ -291,6 +356,8 @@ void xp_tune_clear(void)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     g_table.clear();
+    g_fast.clear();
+    selection_changed();
 }
 
 int xp_tune_count(void)

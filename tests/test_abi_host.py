@@ -1,6 +1,7 @@
 """Host-side checks that need no GPU: the library loads, exports the declared symbols, and
 validates arguments before touching the device."""
 import ctypes
+import os
 import pathlib
 import re
 
@@ -292,3 +293,20 @@ def test_status_strings(lib):
     seen = {xp.status_string(i) for i in range(9)}
     assert len(seen) == 9 and "ok" in seen
     assert "gfx950" in xp.version()
+
+
+def test_built_in_tuned_table_is_the_generators_output():
+    """xp_tuned_table.inc is generated from the tuner's saved text beside it; the two must agree."""
+    import subprocess
+    import sys
+    src = os.path.join(os.path.dirname(__file__), "..", "paper_2505_02146_amd", "csrc")
+    out = subprocess.run([sys.executable, os.path.join(src, "make_tuned_table.py"), os.path.join(src, "xp_tuned_grid.txt")],
+                         check=True, capture_output=True, text=True).stdout
+    assert out == open(os.path.join(src, "xp_tuned_table.inc")).read()
+    names = set(l.split('"')[1] for l in out.splitlines() if l.startswith("{"))
+    from paper_2505_02146_amd import xp
+    known = set()
+    for t in ("f32", "bf16", "i8"):
+        for op in (0,):
+            known |= {xp.xp_describe_config(op, t, i) for i in range(xp.xp_num_configs(op, t))}
+    assert names <= known, names - known                 # every winner names a variant this build has
