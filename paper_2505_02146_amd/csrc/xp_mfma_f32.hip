@@ -7,6 +7,7 @@
 // whichever way the operand lies in memory.  Global loads are scalar, predicated at the edges,
 // and run along the operand's contiguous index.
 #include "xp_internal.hpp"
+#include "xp_epilogue.hpp"
 
 namespace xp {
 namespace {
@@ -124,6 +125,179 @@ __global__ __launch_bounds__(256) void f32_kernel(FParams p)
         }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Pipelined variant.  The fp32 matrix instruction is slow (64 cycles for a 32x32x2 step, 1/16 of the
+// bf16 rate), so one wave's fragment reads are cheap beside it and what the kernel has to avoid is
+// the matrix pipe standing still: around barriers and while a tile is staged.  Here a K step's
+// global loads (16-byte, issued a whole step ahead) sit in registers while the current step is
+// multiplied, go into the other LDS buffer at the end of it, and one barrier a step flips the
+// buffers.  The layouts are template parameters (KA / KB: operand contiguous along K), the
+// staging is K-major as above.  Operands need 16-byte alignment and a multiple of 4 along their
+// contiguous index; anything else takes the kernel above.
+constexpr int PK = 16;                                   // K step of the pipelined kernel
+
+template <int BM, int BN, bool KA, bool KB>
+__global__ __launch_bounds__(256) void f32p_kernel(FParams p)
+{
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
+    constexpr int CA = BM * PK / 4 / 256, CB = BN * PK / 4 / 256;          // 16-byte chunks per thread and step
+    constexpr int PA = BM + 4, PB = BN + 4;
+    __shared__ __attribute__((aligned(16))) float As[2][PK][PA];
+    __shared__ __attribute__((aligned(16))) float Bs[2][PK][PB];
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = (blockIdx.x / p.tiles_n) * BM, n0 = (blockIdx.x % p.tiles_n) * BN;
+    const long long b = blockIdx.y;
+    const float *A = p.A + b * p.strideA;
+    const float *B = p.B + b * p.strideB;
+    float *C = p.C + b * p.strideC;
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // chunk e of an operand tile: K-contiguous -> row e / 4, k offset 4 * (e % 4); else k = e / (rows/4),
+    // rows 4 * (e % (rows/4)) .. +3
+    f32x4 ra[CA], rb[CB];
+    auto load = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < CA; ++i) {
+            const int e = t + 256 * i;
+            ra[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if constexpr (KA) {
+                const int m = m0 + e / (PK / 4), k = k0 + 4 * (e % (PK / 4));
+                if (m < p.M && k < p.K) ra[i] = *(const f32x4 *)(A + (long long)m * p.a_sm + k);
+            } else {
+                const int k = k0 + e / (BM / 4), m = m0 + 4 * (e % (BM / 4));
+                if (m < p.M && k < p.K) ra[i] = *(const f32x4 *)(A + (long long)k * p.a_sk + m);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+            const int e = t + 256 * i;
+            rb[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if constexpr (KB) {
+                const int n = n0 + e / (PK / 4), k = k0 + 4 * (e % (PK / 4));
+                if (n < p.N && k < p.K) rb[i] = *(const f32x4 *)(B + (long long)n * p.b_sn + k);
+            } else {
+                const int k = k0 + e / (BN / 4), n = n0 + 4 * (e % (BN / 4));
+                if (n < p.N && k < p.K) rb[i] = *(const f32x4 *)(B + (long long)k * p.b_sk + n);
+            }
+        }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < CA; ++i) {
+            const int e = t + 256 * i;
+            if constexpr (KA) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) As[buf][4 * (e % (PK / 4)) + c][e / (PK / 4)] = ra[i][c];
+            } else {
+                *(f32x4 *)&As[buf][e / (BM / 4)][4 * (e % (BM / 4))] = ra[i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+            const int e = t + 256 * i;
+            if constexpr (KB) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) Bs[buf][4 * (e % (PK / 4)) + c][e / (PK / 4)] = rb[i][c];
+            } else {
+                *(f32x4 *)&Bs[buf][e / (BN / 4)][4 * (e % (BN / 4))] = rb[i];
+            }
+        }
+    };
+    // lane l supplies A(row l&31, k = l>>5) and B(k = l>>5, column l&31) of each 32x32x2 step
+    auto multiply = [&](int buf, int kk_begin, int kk_end) {
+#pragma unroll
+        for (int kk = kk_begin; kk < kk_end; kk += 2) {
+            float af[MI], bf[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) af[i] = As[buf][kk + (lane >> 5)][wm * WTM + i * 32 + (lane & 31)];
+#pragma unroll
+            for (int j = 0; j < NI; ++j) bf[j] = Bs[buf][kk + (lane >> 5)][wn * WTN + j * 32 + (lane & 31)];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    load(0);
+    stage(0);
+    __syncthreads();
+    int buf = 0;
+    for (int k0 = 0; k0 < p.K; k0 += PK) {
+        const bool more = k0 + PK < p.K;                  // uniform
+        if (more) load(k0 + PK);
+        multiply(buf, 0, PK);
+        if (more) stage(buf ^ 1);                         // the buffer every wave finished reading before the last barrier
+        __syncthreads();
+        buf ^= 1;
+    }
+
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+            store_block32<false>(acc[i][j], C, p.ldc, m0 + wm * WTM + i * 32, n0 + wn * WTN + j * 32, lane, p.M, p.N, p.alpha, p.beta);
+}
+
+template <bool KA, bool KB>
+bool f32p_can_run(const Problem &q)
+{
+    if (q.c_plane) return false;
+    if (q.in_type != XP_F32 || q.conv || q.K <= 0) return false;
+    if (q.M > 0x7fffffffLL || q.N > 0x7fffffffLL || q.K > 0x7fffffffLL || q.batch > 65535) return false;
+    if (((q.M + 63) / 64) * ((q.N + 63) / 64) > 0x7fffffffLL) return false;
+    if (((uintptr_t)q.A | (uintptr_t)q.B) % 16 != 0 || q.strideA % 4 != 0 || q.strideB % 4 != 0) return false;
+    if (KA ? (q.a_sk != 1 || q.a_sm % 4 != 0 || q.K % 4 != 0) : (q.a_sm != 1 || q.a_sk % 4 != 0 || q.M % 4 != 0)) return false;
+    if (KB ? (q.b_sk != 1 || q.b_sn % 4 != 0 || q.K % 4 != 0) : (q.b_sn != 1 || q.b_sk % 4 != 0 || q.N % 4 != 0)) return false;
+    return true;
+}
+
+template <int BM, int BN, bool KA, bool KB>
+hipError_t f32p_launch(const Problem &q)
+{
+    FParams p;
+    p.A = (const float *)q.A; p.B = (const float *)q.B; p.C = (float *)q.C;
+    p.M = (int)q.M; p.N = (int)q.N; p.K = (int)q.K;
+    p.a_sm = q.a_sm; p.a_sk = q.a_sk; p.b_sk = q.b_sk; p.b_sn = q.b_sn; p.ldc = q.ldc;
+    p.strideA = q.strideA; p.strideB = q.strideB; p.strideC = q.strideC;
+    p.alpha = q.alpha; p.beta = q.beta;
+    const int tiles_m = (int)((q.M + BM - 1) / BM);
+    p.tiles_n = (int)((q.N + BN - 1) / BN);
+    hipLaunchKernelGGL((f32p_kernel<BM, BN, KA, KB>), dim3((unsigned)(tiles_m * p.tiles_n), (unsigned)q.batch), dim3(256), 0,
+                       q.stream, p);
+    return hipGetLastError();
+}
+
+template <int BM, int BN>
+double f32p_cost(const Problem &q)
+{
+    return tile_cost_us(q, BM, BN, 2 * (int)sizeof(float) * PK * (BM + BN + 8), 256, (BM == 128 ? 0.8 : 0.5) / 16.0, 4);
+}
+
+#define XP_F32P(NAME, BM, BN, KA, KB, LAY)                                                                      \
+    const Variant NAME = {"f32 " #BM "x" #BN "x16 waves 2x2 pipelined " LAY " mfma32x32x2", f32p_can_run<KA, KB>, \
+                          f32p_launch<BM, BN, KA, KB>, f32p_cost<BM, BN>};
+XP_F32P(kF32P128_kk, 128, 128, true, true, "A,B along K")
+XP_F32P(kF32P128_km, 128, 128, true, false, "A along K, B along N")
+XP_F32P(kF32P128_mk, 128, 128, false, true, "A along M, B along K")
+XP_F32P(kF32P128_mm, 128, 128, false, false, "A along M, B along N")
+XP_F32P(kF32P64_kk, 64, 64, true, true, "A,B along K")
+XP_F32P(kF32P64_km, 64, 64, true, false, "A along K, B along N")
+XP_F32P(kF32P64_mk, 64, 64, false, true, "A along M, B along K")
+XP_F32P(kF32P64_mm, 64, 64, false, false, "A along M, B along N")
+#undef XP_F32P
+
 bool f32_can_run(const Problem &q)
 {
     if (q.c_plane) return false;                          // planar output: the general and direct-to-LDS kernels only
@@ -163,9 +337,10 @@ const Variant kF32_64 = {"f32 64x64x16 waves 2x2 mfma32x32x2", f32_can_run, f32_
 
 int f32_mfma_variants(const Variant **out)
 {
-    out[0] = &kF32_128;
-    out[1] = &kF32_64;
-    return 2;
+    const Variant *all[] = {&kF32_128, &kF32_64, &kF32P128_kk, &kF32P128_km, &kF32P128_mk, &kF32P128_mm,
+                            &kF32P64_kk, &kF32P64_km, &kF32P64_mk, &kF32P64_mm};
+    for (int i = 0; i < 10; ++i) out[i] = all[i];
+    return 10;
 }
 
 }  // namespace xp
