@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void f32_kernel(FParams p)
 constexpr int PK = 16;                                   // K step of the pipelined kernel
 
 template <int BM, int BN, bool KA, bool KB>
-__global__ __launch_bounds__(256) void f32p_kernel(FParams p)
+__global__ __launch_bounds__(256, 4) void f32p_kernel(FParams p)
 {
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
@@ -214,19 +214,26 @@ __global__ __launch_bounds__(256) void f32p_kernel(FParams p)
         }
     };
     // lane l supplies A(row l&31, k = l>>5) and B(k = l>>5, column l&31) of each 32x32x2 step
+    // the fragments of sub-step kk + 2 are read into a second register set before the matrix
+    // instructions of sub-step kk are issued, so that no LDS wait stands between them
     auto multiply = [&](int buf, int kk_begin, int kk_end) {
+        float af[2][MI], bf[2][NI];
+        auto fetch = [&](int set, int kk) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i) af[set][i] = As[buf][kk + (lane >> 5)][wm * WTM + i * 32 + (lane & 31)];
+#pragma unroll
+            for (int j = 0; j < NI; ++j) bf[set][j] = Bs[buf][kk + (lane >> 5)][wn * WTN + j * 32 + (lane & 31)];
+        };
+        fetch(0, kk_begin);
 #pragma unroll
         for (int kk = kk_begin; kk < kk_end; kk += 2) {
-            float af[MI], bf[NI];
-#pragma unroll
-            for (int i = 0; i < MI; ++i) af[i] = As[buf][kk + (lane >> 5)][wm * WTM + i * 32 + (lane & 31)];
-#pragma unroll
-            for (int j = 0; j < NI; ++j) bf[j] = Bs[buf][kk + (lane >> 5)][wn * WTN + j * 32 + (lane & 31)];
+            const int set = ((kk - kk_begin) >> 1) & 1;
+            if (kk + 2 < kk_end) fetch(set ^ 1, kk + 2);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[set][i], bf[set][j], acc[i][j], 0, 0, 0);
         }
     };
 
