@@ -207,6 +207,18 @@ def main() -> int:
                                       "vs_two_batched_gemm_stages_without_softmax": round(unfused / ms, 2),
                                       "kernel": xp.xp_describe_config(3, "bf16", xp.xp_last_config(3, "bf16"))}
         del Qs, Ks, Vs, Os
+        # the same operator at a decoder block's shape: 32 heads of 128 over 2048 positions (compute-bound)
+        w2 = inputs.workload("attention_bf16_2048_d128")
+        b2, L2, d2 = w2["batch"], w2["Lq"], w2["d"]
+        Q2, K2, V2 = dev(w2["Q"].reshape(-1)), dev(w2["K"].reshape(-1)), dev(w2["V"].reshape(-1))
+        O2 = torch.empty((b2 * L2 * d2,), dtype=torch.float32, device="cuda")
+        ms2, _ = _time_calls(torch, lambda: xp.xp_attention(b2, L2, L2, d2, d2, w2["scale"], Q2, d2, L2 * d2, K2, d2, L2 * d2, V2, d2,
+                                                            L2 * d2, O2, d2, L2 * d2, q_type="bf16", k_type="bf16", v_type="bf16"),
+                             steps2, warm2)
+        side["attention_bf16_2048_d128"] = {"ms": round(ms2, 5), "TFLOP/s": round(4.0 * b2 * L2 * L2 * d2 / (ms2 * 1e-3) / 1e12, 1),
+                                            "pct_bf16_mfma_peak": round(100 * 4.0 * b2 * L2 * L2 * d2 / (ms2 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+                                            "kernel": xp.xp_describe_config(3, "bf16", xp.xp_last_config(3, "bf16"))}
+        del Q2, K2, V2, O2
         # matrix-vector product: one pass over a 134 MB matrix, HBM-cold by rotation
         wv = inputs.workload("gemv_bf16_8192")
         mv, kv = wv["M"], wv["K"]

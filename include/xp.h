@@ -123,7 +123,7 @@ xp_status xp_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t C
  * (>= the row length) and the batch stride in elements (>= 0; 0 shares Q, K or V across the
  * batch; the O slices must not overlap).  All four are DEVICE pointers owned by the caller.
  * Supported types: Q, K, V all F32 or all BF16; O is F32.  Products and sums are formed in
- * fp32; on the matrix-core path (BF16, d == dv == 64, 16-byte aligned pointers, pitches and
+ * fp32; on the matrix-core path (BF16, d == dv == 64 or 128, 16-byte aligned pointers, pitches and
  * strides) the probabilities are rounded to bf16 before they multiply V.  Other shapes and
  * alignments run on a slower general kernel under the same definition.
  * scale must be finite (the usual choice is 1/sqrt(d)).

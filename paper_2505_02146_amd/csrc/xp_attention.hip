@@ -157,12 +157,19 @@ constexpr int waitcnt_vm_lgkm0(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0
 // D register sets, which is interleaved into LDS D-1 steps later, at the end of step t+D-1.  Every
 // wave issues exactly 4 loads per step (tiles past the end are out of range: zeros, no memory
 // touched), so "at most 4*(D-1) loads outstanding" means that tile t+1 has landed.
-template <int D>
+//
+// HV = head size / 64.  A head of 128 is handled as two halves of 64 that share everything but their
+// tiles: the K tile of a step is two half-tiles (dimensions 0..63 and 64..127, each in the layout
+// above), S^T sums four k steps instead of two; the V tile is two half-tiles of 64 output columns,
+// O^T has eight column blocks instead of four.
+template <int D, int HV>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
 {
     constexpr int NS = D + 1;
-    __shared__ __attribute__((aligned(1024))) char lds[NS * (K_TILE + V_TILE)];
-    char *const ks = lds, *const vs = lds + NS * K_TILE;
+    constexpr int KT = K_TILE * HV, VT = V_TILE * HV;   // one step's K and V tiles
+    constexpr int LPS = 4 * HV;                          // loads a wave issues per step
+    __shared__ __attribute__((aligned(1024))) char lds[NS * (KT + VT)];
+    char *const ks = lds, *const vs = lds + NS * KT;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -173,14 +180,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
     const long long b = by;
 
     const __amdgpu_buffer_rsrc_t rq = make_rsrc(p.Q + b * p.strideQ + (long long)q0 * p.ldq,
-                                                (unsigned)((long long)(min(p.Lq - q0, BQ) - 1) * p.ldq + KROW));
-    const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.K + b * p.strideK, (unsigned)((long long)(p.Lk - 1) * p.ldk + KROW));
-    const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.V + b * p.strideV, (unsigned)((long long)(p.Lk - 1) * p.ldv + KROW));
+                                                (unsigned)((long long)(min(p.Lq - q0, BQ) - 1) * p.ldq + KROW * HV));
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.K + b * p.strideK, (unsigned)((long long)(p.Lk - 1) * p.ldk + KROW * HV));
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.V + b * p.strideV, (unsigned)((long long)(p.Lk - 1) * p.ldv + KROW * HV));
 
-    // the wave's queries: B operand of S^T, two k steps over the head dimension
-    u32x4 qf[2];
+    // the wave's queries: B operand of S^T, two k steps per 64 head dimensions
+    u32x4 qf[2 * HV];
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+    for (int s = 0; s < 2 * HV; ++s)
         qf[s] = __builtin_amdgcn_raw_buffer_load_b128(rq, (unsigned)((wave * 16 + r) * p.ldq) + (32 * s + 8 * g) * 2, 0, 0);
 
     // K tile: 8 wave-level loads of 8 rows each, two per wave, straight into LDS; lane l lands at
@@ -189,18 +196,23 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
     const int kchunk = ((lane & 7) ^ (krow & 6)) << 4;   // rows of a load start at multiples of 8: the swizzle term is the lane's
     auto issue_k = [&](int j0, int koff) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int blk = wave * 2 + i;
-            const unsigned off = (unsigned)((j0 + blk * 8 + krow) * p.ldk) + kchunk;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void *)(ks + koff + blk * 1024), 16, off, 0, 0, 0);
-        }
+        for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int blk = wave * 2 + i;
+                const unsigned off = (unsigned)((j0 + blk * 8 + krow) * p.ldk) + hv * KROW + kchunk;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void *)(ks + koff + hv * K_TILE + blk * 1024), 16, off, 0, 0, 0);
+            }
     };
     // V tile: thread t takes key pair t/8 (rows 2kp, 2kp+1) and output columns 8*(t%8) .. +8
     const int vkp = tid >> 3, vc = tid & 7;
-    u32x4 vr[D][2];
-    auto load_v = [&](int j0, u32x4 (&v)[2]) {
-        v[0] = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp) * p.ldv) + vc * 16, 0, 0);
-        v[1] = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp + 1) * p.ldv) + vc * 16, 0, 0);
+    u32x4 vr[D][HV][2];
+    auto load_v = [&](int j0, u32x4 (&v)[HV][2]) {
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) {
+            v[hv][0] = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp) * p.ldv) + hv * KROW + vc * 16, 0, 0);
+            v[hv][1] = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp + 1) * p.ldv) + hv * KROW + vc * 16, 0, 0);
+        }
     };
     // where the pair lands inside a column: group (k step, lane group), word slot
     const int vk2 = vkp & 15;
@@ -208,12 +220,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
     // vswz(8*vc + e) is vc for e < 4 and vc ^ 1 for e >= 4
     const int vw0 = 8 * vc * VPITCH + ((vgrp ^ vc) << 4) + vslot * 4;
     const int vw1 = 8 * vc * VPITCH + ((vgrp ^ vc ^ 1) << 4) + vslot * 4;
-    auto store_v = [&](int voff, const u32x4 (&v)[2]) {
+    auto store_v = [&](int voff, const u32x4 (&v)[HV][2]) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {                    // word {V[2kp][x], V[2kp+1][x]} of column x = 8*vc + e
-            const unsigned w = __builtin_amdgcn_perm(v[1][e >> 1], v[0][e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
-            *(unsigned *)(vs + voff + (e < 4 ? vw0 : vw1) + e * VPITCH) = w;
-        }
+        for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {                // word {V[2kp][x], V[2kp+1][x]} of column x = 64*hv + 8*vc + e
+                const unsigned w = __builtin_amdgcn_perm(v[hv][1][e >> 1], v[hv][0][e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
+                *(unsigned *)(vs + voff + hv * V_TILE + (e < 4 ? vw0 : vw1) + e * VPITCH) = w;
+            }
     };
     // fragment of column block x, k step h: column 16x + r, group (4h + g) ^ vswz(16x + r)
     const int vsr = ((r >> 2) ^ (r >> 3)) & 1;
@@ -223,26 +237,26 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
     float top = -INFINITY;
     f32x4 total = {0.0f, 0.0f, 0.0f, 0.0f};              // running sum of the query's probabilities (4 copies)
     const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};   // bf16 1.0 x 8
-    f32x4 acc[4];
+    f32x4 acc[4 * HV];
 #pragma unroll
-    for (int x = 0; x < 4; ++x) acc[x] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int x = 0; x < 4 * HV; ++x) acc[x] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     const int NT = (p.Lk + BK - 1) / BK;
 #pragma unroll
     for (int u = 0; u < D; ++u) {
-        issue_k(u * BK, u * K_TILE);
+        issue_k(u * BK, u * KT);
         load_v(u * BK, vr[u]);
     }
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(4 * (D - 1)));   // tile 0 (and the queries) have landed
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LPS * (D - 1)));   // tile 0 (and the queries) have landed
     store_v(0, vr[0]);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(4 * (D - 1)));
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LPS * (D - 1)));
     wg_barrier();
 
     int cur = 0;                                         // ring slot of the tile being multiplied
-    auto step = [&](int t, u32x4 (&v_in)[2], const u32x4 (&v_out)[2]) {
+    auto step = [&](int t, u32x4 (&v_in)[HV][2], const u32x4 (&v_out)[HV][2]) {
         const int j0 = t * BK;
         const int prev = cur == 0 ? NS - 1 : cur - 1, next = cur == NS - 1 ? 0 : cur + 1;
-        issue_k(j0 + D * BK, prev * K_TILE);             // slot read one barrier ago
+        issue_k(j0 + D * BK, prev * KT);                 // slot read one barrier ago
         load_v(j0 + D * BK, v_in);
         // S^T: 4 blocks of 16 keys
         f32x4 s[4];
@@ -251,8 +265,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
             s[kb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
             const int row = kb * 16 + r;
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const u32x4 kf = *(const u32x4 *)(ks + cur * K_TILE + row * KROW + (((4 * h + g) ^ (row & 6)) << 4));
+            for (int h = 0; h < 2 * HV; ++h) {
+                const u32x4 kf = *(const u32x4 *)(ks + cur * KT + (h >> 1) * K_TILE + row * KROW + (((4 * (h & 1) + g) ^ (row & 6)) << 4));
                 s[kb] = mma(kf, qf[h], s[kb]);
             }
         }
@@ -288,7 +302,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
             top = new_top;
             total *= shrink;
 #pragma unroll
-            for (int x = 0; x < 4; ++x) acc[x] *= shrink;
+            for (int x = 0; x < 4 * HV; ++x) acc[x] *= shrink;
         }
         // probabilities exp2(c*s - top), rounded to bf16 for the second contraction
         u32x4 pf[2];
@@ -304,15 +318,17 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
 #pragma unroll
         for (int h = 0; h < 2; ++h) total = mma(ones, pf[h], total);
 #pragma unroll
-        for (int x = 0; x < 4; ++x)
+        for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int grp_hi = (4 * h) ^ ((2 * x) & 4);
-                const u32x4 vf = *(const u32x4 *)(vs + cur * V_TILE + ((x & 1) ? vf1 : vf0) + 16 * x * VPITCH + grp_hi * 16);
-                acc[x] = mma(vf, pf[h], acc[x]);
-            }
-        store_v(next * V_TILE, v_out);                   // tile t+1, into a slot last read D barriers ago
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(4 * (D - 1)));
+            for (int x = 0; x < 4; ++x)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int grp_hi = (4 * h) ^ ((2 * x) & 4);
+                    const u32x4 vf = *(const u32x4 *)(vs + cur * VT + hv * V_TILE + ((x & 1) ? vf1 : vf0) + 16 * x * VPITCH + grp_hi * 16);
+                    acc[4 * hv + x] = mma(vf, pf[h], acc[4 * hv + x]);
+                }
+        store_v(next * VT, v_out);                       // tile t+1, into a slot last read D barriers ago
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LPS * (D - 1)));
         wg_barrier();
         cur = next;
     };
@@ -330,7 +346,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
     if (q < p.Lq) {
         float *dst = p.O + b * p.strideO + (long long)q * p.ldo + 4 * g;
 #pragma unroll
-        for (int x = 0; x < 4; ++x) *(f32x4 *)(dst + 16 * x) = acc[x] * inv;
+        for (int x = 0; x < 4 * HV; ++x) *(f32x4 *)(dst + 16 * x) = acc[x] * inv;
     }
 }
 
@@ -362,9 +378,10 @@ hipError_t general_launch(const AttnProblem &q)
     return hipGetLastError();
 }
 
+template <int HV>
 bool mfma_can_run(const AttnProblem &q)
 {
-    if (q.in_type != XP_BF16 || q.d != HD || q.dv != HD) return false;
+    if (q.in_type != XP_BF16 || q.d != HD * HV || q.dv != HD * HV) return false;
     if (q.scale == 0.0f) return false;                   // the kernel masks absent keys by an infinite raw score times the scale
     if (q.batch > 65535 || q.Lq > 0x3fffffffLL || q.Lk > 0x3fffffffLL) return false;
     const void *ptrs[3] = {q.Q, q.K, q.V};
@@ -378,29 +395,33 @@ bool mfma_can_run(const AttnProblem &q)
     return true;
 }
 
-template <int D>
+template <int D, int HV>
 hipError_t mfma_launch(const AttnProblem &q)
 {
     AttnParams p = params_elements(q);
     p.ldq *= 2; p.ldk *= 2; p.ldv *= 2;                  // bytes
     p.strideQ *= 2; p.strideK *= 2; p.strideV *= 2;
     const dim3 grid((unsigned)((q.Lq + BQ - 1) / BQ), (unsigned)q.batch);
-    hipLaunchKernelGGL(attn_mfma_kernel<D>, grid, dim3(256), 0, q.stream, p);
+    hipLaunchKernelGGL((attn_mfma_kernel<D, HV>), grid, dim3(256), 0, q.stream, p);
     return hipGetLastError();
 }
 
 const AttnVariant kGeneral = {"general attention one wave per query valu", general_can_run, general_launch};
-const AttnVariant kMfma64d1 = {"bf16 attention head 64, 64 queries x 64-key steps, prefetch 1, waves 4x1 mfma16", mfma_can_run,
-                               mfma_launch<1>};
-const AttnVariant kMfma64d2 = {"bf16 attention head 64, 64 queries x 64-key steps, prefetch 2, waves 4x1 mfma16", mfma_can_run,
-                               mfma_launch<2>};
+const AttnVariant kMfma64d1 = {"bf16 attention head 64, 64 queries x 64-key steps, prefetch 1, waves 4x1 mfma16", mfma_can_run<1>,
+                               mfma_launch<1, 1>};
+const AttnVariant kMfma64d2 = {"bf16 attention head 64, 64 queries x 64-key steps, prefetch 2, waves 4x1 mfma16", mfma_can_run<1>,
+                               mfma_launch<2, 1>};
+const AttnVariant kMfma128d1 = {"bf16 attention head 128, 64 queries x 64-key steps, prefetch 1, waves 4x1 mfma16", mfma_can_run<2>,
+                                mfma_launch<1, 2>};
+const AttnVariant kMfma128d2 = {"bf16 attention head 128, 64 queries x 64-key steps, prefetch 2, waves 4x1 mfma16", mfma_can_run<2>,
+                                mfma_launch<2, 2>};
 // swept on the 96 x 512 x 512 x 64 workload: a prefetch distance of 1 is as fast as 2 (the step is bound
 // by its own dependency chain, not by load latency) and leaves more LDS free; 3 is slower
-const AttnVariant *const kBf16Table[] = {&kGeneral, &kMfma64d2, &kMfma64d1};   // the last that can run is the default
+const AttnVariant *const kBf16Table[] = {&kGeneral, &kMfma64d2, &kMfma64d1, &kMfma128d2, &kMfma128d1};   // the last that can run is the default
 
 }  // namespace
 
-int attn_num_variants(xp_dtype in_type) { return in_type == XP_BF16 ? 3 : (in_type == XP_F32 ? 1 : 0); }
+int attn_num_variants(xp_dtype in_type) { return in_type == XP_BF16 ? 5 : (in_type == XP_F32 ? 1 : 0); }
 
 const AttnVariant *attn_variant(xp_dtype in_type, int idx)
 {

@@ -157,6 +157,13 @@ def workload(name: str, seed: int = 0) -> dict:
                     Q=to_bf16_bits(normal((b, L, d), seed, TID_A)),
                     K=to_bf16_bits(normal((b, L, d), seed, TID_B)),
                     V=to_bf16_bits(normal((b, L, d), seed, TID_C)))
+    if name == "attention_bf16_2048_d128":
+        # a decoder-style block: 32 heads of 128 over 2048 positions
+        b, L, d = 32, 2048, 128
+        return dict(op="attention", dtype="bf16", batch=b, Lq=L, Lk=L, d=d, dv=d, scale=1.0 / np.sqrt(128.0),
+                    Q=to_bf16_bits(normal((b, L, d), seed, TID_A)),
+                    K=to_bf16_bits(normal((b, L, d), seed, TID_B)),
+                    V=to_bf16_bits(normal((b, L, d), seed, TID_C)))
     if name == "gemv_bf16_8192":
         # matrix-vector product: nothing is reused, the 134 MB matrix is read once
         M = K = 8192
@@ -169,7 +176,7 @@ def workload(name: str, seed: int = 0) -> dict:
 WORKLOADS = ("gemm_f32_256", "gemm_bf16_4096", "gemm_i8_4096x4096x8192",
              "bgemm_bf16_qk", "bgemm_bf16_pv", "conv_bf16_56")
 # operators beyond the GEMM / convolution set, each served by its own entry point
-EXTRA_WORKLOADS = ("attention_bf16_512", "gemv_bf16_8192")
+EXTRA_WORKLOADS = ("attention_bf16_512", "attention_bf16_2048_d128", "gemv_bf16_8192")
 
 
 # A detection-encoder layer's deformable attention: the queries are the pixels of the four feature

@@ -15,9 +15,11 @@ from tests.helpers import GATE_ELEM, GATE_FRO, dev
 
 pytestmark = pytest.mark.gpu
 
-TIGHT = {0: 2e-5, 1: 2.5e-3, 2: 2.5e-3}     # variant 0 is the general kernel, the rest are mfma kernels
-MFMA = [1, 2]
-DEFAULT = 2                                             # what the library picks when it can (the last entry)
+TIGHT = {0: 2e-5, 1: 2.5e-3, 2: 2.5e-3, 3: 2.5e-3, 4: 2.5e-3}     # variant 0 is the general kernel, the rest are mfma kernels
+MFMA = [1, 2]                                           # head size 64
+MFMA128 = [3, 4]                                        # head size 128
+DEFAULT = 2                                             # what the library picks for head size 64 when it can
+DEFAULT128 = 4                                          # ... and for head size 128 (the last entry)
 
 
 @pytest.fixture(scope="module")
@@ -102,6 +104,45 @@ def test_head64_bf16_both_kernels(xp, oracle, shape, variant):
     _gate(got, ref, f"{shape} variant {variant}", TIGHT[variant])
 
 
+@pytest.mark.parametrize("variant", [0] + MFMA128)
+@pytest.mark.parametrize("shape", MFMA_SHAPES)
+def test_head128_bf16_both_kernels(xp, oracle, shape, variant):
+    batch, Lq, Lk = shape
+    got, ref, used, _ = _run(xp, oracle, batch=batch, Lq=Lq, Lk=Lk, d=128, dv=128, scale=0.0884, variant=variant)
+    assert used == variant
+    _gate(got, ref, f"head 128 {shape} variant {variant}", TIGHT[variant])
+
+
+@pytest.mark.parametrize("variant", MFMA128)
+def test_head128_padded_shared_peaked_and_single_key(xp, oracle, variant):
+    got, ref, used, _ = _run(xp, oracle, batch=3, Lq=90, Lk=150, d=128, dv=128, scale=0.0884, variant=variant,
+                             pad=(8, 16, 24, 4), gap=64)
+    assert used == variant
+    _gate(got, ref, "head 128 padded", TIGHT[variant])
+    got, ref, used, _ = _run(xp, oracle, batch=4, Lq=80, Lk=100, d=128, dv=128, scale=0.0884, variant=variant, share_kv=True)
+    _gate(got, ref, "head 128 shared K/V", TIGHT[variant])
+    got, ref, _, _ = _run(xp, oracle, batch=2, Lq=66, Lk=200, d=128, dv=128, scale=20.0, variant=variant)
+    _gate(got, ref, "head 128 peaked", 4e-3)
+    got, ref, _, (Q, K, V) = _run(xp, oracle, batch=2, Lq=70, Lk=1, d=128, dv=128, scale=0.7, variant=variant)
+    expect = inputs.bf16_bits_to_f32(V).astype(np.float64)
+    assert np.array_equal(got, np.broadcast_to(expect, got.shape))
+
+
+def test_head128_is_selected_and_head64_variants_decline_it(xp, oracle):
+    got, ref, used, _ = _run(xp, oracle, batch=2, Lq=130, Lk=260, d=128, dv=128, scale=0.0884)
+    assert used == DEFAULT128
+    _gate(got, ref, "selected head 128", TIGHT[DEFAULT128])
+    with pytest.raises(xp.XpError) as e:
+        _run(xp, oracle, batch=2, Lq=33, Lk=47, d=128, dv=128, scale=0.2, variant=1)
+    assert e.value.status == 6
+    with pytest.raises(xp.XpError) as e:
+        _run(xp, oracle, batch=2, Lq=33, Lk=47, d=64, dv=64, scale=0.2, variant=3)
+    assert e.value.status == 6
+    got, ref, used, _ = _run(xp, oracle, batch=2, Lq=33, Lk=47, d=128, dv=64, scale=0.2)     # mixed sizes: the general kernel
+    assert used == 0
+    _gate(got, ref, "d 128 dv 64", TIGHT[0])
+
+
 @pytest.mark.parametrize("variant", [0] + MFMA)
 def test_padded_pitches_and_batch_gaps(xp, oracle, variant):
     got, ref, used, _ = _run(xp, oracle, batch=3, Lq=90, Lk=150, d=64, dv=64, scale=0.125, variant=variant,
@@ -112,7 +153,7 @@ def test_padded_pitches_and_batch_gaps(xp, oracle, variant):
 
 def test_selection_takes_the_mfma_kernel_when_it_can_and_the_general_one_otherwise(xp, oracle):
     got, ref, used, _ = _run(xp, oracle, batch=2, Lq=70, Lk=90, d=64, dv=64, scale=0.125)
-    assert used == DEFAULT and xp.xp_num_configs(xp.XP_OP_ATTENTION, "bf16") == DEFAULT + 1
+    assert used == DEFAULT and xp.xp_num_configs(xp.XP_OP_ATTENTION, "bf16") == DEFAULT128 + 1
     _gate(got, ref, "selected mfma", TIGHT[DEFAULT])
     # row pitch not a multiple of 16 bytes: the matrix-core kernel declines
     got, ref, used, _ = _run(xp, oracle, batch=2, Lq=70, Lk=90, d=64, dv=64, scale=0.125, pad=(3, 0, 0, 0))
@@ -182,3 +223,23 @@ def test_attention_workload_full_size(xp, oracle):
     ref = oracle.attention(w["Q"].reshape(-1), w["K"].reshape(-1), w["V"].reshape(-1), batch=b, Lq=L, Lk=L, d=d, dv=d,
                            scale=w["scale"])
     _gate(O.cpu().numpy(), ref, "attention_bf16_512", TIGHT[DEFAULT])
+
+
+def test_attention_head128_workload_sampled(xp, oracle):
+    """The decoder-block workload (32 x 2048 x 2048 x 128) as the benchmark runs it; three batch indices
+    are checked in full against the oracle."""
+    import torch
+    w = inputs.workload("attention_bf16_2048_d128")
+    b, L, d = w["batch"], w["Lq"], w["d"]
+    xp.xp_force_config(xp.XP_OP_ATTENTION, "bf16", -1)
+    O = torch.full((b, L, d), float("nan"), device="cuda")
+    xp.xp_attention(b, L, L, d, d, w["scale"], dev(w["Q"].reshape(-1)), d, L * d, dev(w["K"].reshape(-1)), d, L * d,
+                    dev(w["V"].reshape(-1)), d, L * d, O, d, L * d, q_type="bf16", k_type="bf16", v_type="bf16")
+    torch.cuda.synchronize()
+    assert xp.xp_last_config(xp.XP_OP_ATTENTION, "bf16") == DEFAULT128
+    got = O.cpu().numpy()
+    assert np.isfinite(got).all()
+    for x in (0, 13, 31):
+        ref = oracle.attention(w["Q"][x].reshape(-1), w["K"][x].reshape(-1), w["V"][x].reshape(-1), batch=1, Lq=L, Lk=L, d=d, dv=d,
+                               scale=w["scale"])
+        _gate(got[x:x + 1], ref, f"attention_bf16_2048_d128 batch index {x}", TIGHT[DEFAULT128])
