@@ -20,6 +20,9 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void lds_void;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr unsigned OOB = 0x80000000u;
 constexpr float LOG2E = 1.4426950408889634f;
@@ -105,23 +108,22 @@ __global__ __launch_bounds__(64) void attn_general_kernel(AttnParams p)
 // and the lane's probabilities of two key blocks are exactly the 8 values the B operand of
 //   O^T = V^T P^T      (A = V^T from LDS, B = P^T from registers)
 // needs, if the 32 keys of one k step are numbered: slot 8*g + e  <->  key 4*g + e (e < 4),
-// key 16 + 4*g + (e - 4) (e >= 4).  V is staged to LDS column-major as words {V[2kp][x], V[2kp+1][x]}
-// (two keys of one output column), the 16 words of a column and k step ordered so that the four
-// words a lane needs (its 8 keys of column x in the numbering above) are one aligned 16-byte group:
-// one 128-bit read per operand.  O^T comes out with the query in l%16 again, so the running
-// rescale factor applies without any exchange, and a lane ends up with 4 consecutive output
-// columns: one 16-byte store.
+// key 16 + 4*g + (e - 4) (e >= 4).  V lies in LDS as it lies in memory, one key per row (it goes there
+// straight from global memory, like K), and the A operand -- 8 keys of ONE output column -- is
+// gathered by the transposing LDS read of this architecture (ds_read_b64_tr_b16): within a block of
+// 16 lanes, lane i receives as value j the element (i & 3) of the 8 bytes addressed by lane
+// 4*j + (i >> 2).  With lane a of a block addressing key row k0 + (a >> 2), columns 16x + 4*(a & 3) ..,
+// lane i obtains V[k0 + j][16x + i], j = 0..3: four consecutive keys of its column.  Two such reads
+// (k0 = 32h + 4g and 32h + 16 + 4g) are the 8 keys of the numbering above.  O^T comes out with the
+// query in l%16 again, so the running rescale factor applies without any exchange, and a lane
+// ends up with 4 consecutive output columns: one 16-byte store.
 constexpr int HD = 64;                                  // head size (Q/K and V)
 constexpr int BQ = 64, BK = 64;                         // queries per workgroup, keys per step
 constexpr int KROW = HD * 2;                            // bytes per K row in LDS (swizzled 16-byte chunks)
 constexpr int K_TILE = BK * KROW;
-// V tile in LDS: column x at x*VPITCH, 8 groups of 16 bytes (k step h, lane group g -> group 4h+g),
-// the group index XORed with vswz(x).  Pitch and swizzle were found by exhaustive search against
-// the measured pass grouping of 128-bit LDS reads: fragment reads and staging writes are both
-// free of bank conflicts.
-constexpr int VPITCH = 144;
-constexpr int V_TILE = HD * VPITCH;
-__device__ __forceinline__ int vswz(int x) { return (((x >> 2) ^ (x >> 3)) & 1) | (((x >> 4) & 3) << 1); }
+// V tile in LDS: the layout of the K tile (128-byte rows, the 16-byte chunk index XORed with row & 6):
+// a transposing read touches 16 rows x 32 bytes, and that swizzle spreads its chunks evenly over the banks
+constexpr int V_TILE = K_TILE;
 constexpr float TAU = 8.0f;                             // the reference maximum may lag by this much (log2 units)
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes)
@@ -204,34 +206,29 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void *)(ks + koff + hv * K_TILE + blk * 1024), 16, off, 0, 0, 0);
             }
     };
-    // V tile: thread t takes key pair t/8 (rows 2kp, 2kp+1) and output columns 8*(t%8) .. +8
-    const int vkp = tid >> 3, vc = tid & 7;
-    u32x4 vr[D][HV][2];
-    auto load_v = [&](int j0, u32x4 (&v)[HV][2]) {
-#pragma unroll
-        for (int hv = 0; hv < HV; ++hv) {
-            v[hv][0] = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp) * p.ldv) + hv * KROW + vc * 16, 0, 0);
-            v[hv][1] = __builtin_amdgcn_raw_buffer_load_b128(rv, (unsigned)((j0 + 2 * vkp + 1) * p.ldv) + hv * KROW + vc * 16, 0, 0);
-        }
-    };
-    // where the pair lands inside a column: group (k step, lane group), word slot
-    const int vk2 = vkp & 15;
-    const int vgrp = (vkp >> 4) * 4 + ((vk2 & 7) >> 1), vslot = (vk2 >> 3) * 2 + (vk2 & 1);
-    // vswz(8*vc + e) is vc for e < 4 and vc ^ 1 for e >= 4
-    const int vw0 = 8 * vc * VPITCH + ((vgrp ^ vc) << 4) + vslot * 4;
-    const int vw1 = 8 * vc * VPITCH + ((vgrp ^ vc ^ 1) << 4) + vslot * 4;
-    auto store_v = [&](int voff, const u32x4 (&v)[HV][2]) {
+    // V tile: the same, from V
+    auto issue_v = [&](int j0, int voff) {
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {                // word {V[2kp][x], V[2kp+1][x]} of column x = 64*hv + 8*vc + e
-                const unsigned w = __builtin_amdgcn_perm(v[hv][1][e >> 1], v[hv][0][e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
-                *(unsigned *)(vs + voff + hv * V_TILE + (e < 4 ? vw0 : vw1) + e * VPITCH) = w;
+            for (int i = 0; i < 2; ++i) {
+                const int blk = wave * 2 + i;
+                const unsigned off = (unsigned)((j0 + blk * 8 + krow) * p.ldv) + hv * KROW + kchunk;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void *)(vs + voff + hv * V_TILE + blk * 1024), 16, off, 0, 0, 0);
             }
     };
-    // fragment of column block x, k step h: column 16x + r, group (4h + g) ^ vswz(16x + r)
-    const int vsr = ((r >> 2) ^ (r >> 3)) & 1;
-    const int vf0 = r * VPITCH + ((g ^ vsr) << 4), vf1 = r * VPITCH + ((g ^ vsr ^ 2) << 4);   // x even / odd
+    // transposing fragment reads: lane a = l%16 of block g addresses key row 4g + (a >> 2) (+ 32h, + 16 for
+    // the second half of the numbering), the 8 bytes at columns 16x + 4*(a & 3) of its half-tile
+    const int va = lane & 15;
+    const int vrow = 4 * g + (va >> 2);
+    const int vbase = vrow * KROW + 8 * (va & 1), vchunk = (va & 3) >> 1, vsw = vrow & 6;
+    auto read_v = [&](int voff, int hv, int x, int h) {
+        const char *at = vs + voff + hv * V_TILE + vbase + 32 * h * KROW + (((2 * x + vchunk) ^ vsw) << 4);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)at);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(at + 16 * KROW));
+        const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+        return u32x4{l2[0], l2[1], h2[0], h2[1]};
+    };
 
     const float c = p.scale * LOG2E;                     // scores are kept in units of log2
     float top = -INFINITY;
@@ -245,19 +242,17 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
 #pragma unroll
     for (int u = 0; u < D; ++u) {
         issue_k(u * BK, u * KT);
-        load_v(u * BK, vr[u]);
+        issue_v(u * BK, u * VT);
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LPS * (D - 1)));   // tile 0 (and the queries) have landed
-    store_v(0, vr[0]);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LPS * (D - 1)));
     wg_barrier();
 
     int cur = 0;                                         // ring slot of the tile being multiplied
-    auto step = [&](int t, u32x4 (&v_in)[HV][2], const u32x4 (&v_out)[HV][2]) {
+    auto step = [&](int t) {
         const int j0 = t * BK;
         const int prev = cur == 0 ? NS - 1 : cur - 1, next = cur == NS - 1 ? 0 : cur + 1;
         issue_k(j0 + D * BK, prev * KT);                 // slot read one barrier ago
-        load_v(j0 + D * BK, v_in);
+        issue_v(j0 + D * BK, prev * VT);
         // S^T: 4 blocks of 16 keys
         f32x4 s[4];
 #pragma unroll
@@ -322,12 +317,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
 #pragma unroll
             for (int x = 0; x < 4; ++x)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int grp_hi = (4 * h) ^ ((2 * x) & 4);
-                    const u32x4 vf = *(const u32x4 *)(vs + cur * VT + hv * V_TILE + ((x & 1) ? vf1 : vf0) + 16 * x * VPITCH + grp_hi * 16);
-                    acc[4 * hv + x] = mma(vf, pf[h], acc[4 * hv + x]);
-                }
-        store_v(next * VT, v_out);                       // tile t+1, into a slot last read D barriers ago
+                for (int h = 0; h < 2; ++h) acc[4 * hv + x] = mma(read_v(cur * VT, hv, x, h), pf[h], acc[4 * hv + x]);
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LPS * (D - 1)));
         wg_barrier();
         cur = next;
@@ -336,7 +326,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             if (t0 + u >= NT) break;                     // uniform over the workgroup
-            step(t0 + u, vr[u], vr[(u + 1) % D]);
+            step(t0 + u);
         }
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
