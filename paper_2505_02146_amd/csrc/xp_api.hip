@@ -465,9 +465,11 @@ xp_status xp_attention(int64_t batch, int64_t Lq, int64_t Lk, int64_t d, int64_t
         if (!v || !v->can_run(q)) return XP_ERR_CONFIG;
         idx = forced;
     } else {
-        // the last variant that can run the call: the table is ordered from general to specialised
-        for (int i = attn_num_variants(q_type) - 1; i > 0; --i)
-            if (attn_variant(q_type, i)->can_run(q)) { idx = i; break; }
+        // the last variant that can run the call and finds it worthwhile: the table is ordered from general to specialised
+        for (int i = attn_num_variants(q_type) - 1; i > 0; --i) {
+            const AttnVariant *v = attn_variant(q_type, i);
+            if (v->can_run(q) && (!v->worthwhile || v->worthwhile(q))) { idx = i; break; }
+        }
     }
     const AttnVariant *v = attn_variant(q_type, idx);
     if (!v || !v->can_run(q)) return XP_ERR_UNSUPPORTED;

@@ -164,12 +164,19 @@ constexpr int waitcnt_vm_lgkm0(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0
 // tiles: the K tile of a step is two half-tiles (dimensions 0..63 and 64..127, each in the layout
 // above), S^T sums four k steps instead of two; the V tile is two half-tiles of 64 output columns,
 // O^T has eight column blocks instead of four.
-template <int D, int HV>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
+//
+// NW = waves per workgroup (4 or 8), 16 queries each.  The K and V tiles are shared by all of them, so
+// eight waves halve the LDS a query needs and let twice as many waves live on a SIMD; matrix and vector
+// instructions of different waves do not overlap on this hardware (a SIMD issues one or the other:
+// measured, the times add), so what more waves hide is the waiting -- barriers, LDS and load latency.
+template <int D, int HV, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_mfma_kernel(AttnParams p)
 {
     constexpr int NS = D + 1;
     constexpr int KT = K_TILE * HV, VT = V_TILE * HV;   // one step's K and V tiles
-    constexpr int LPS = 4 * HV;                          // loads a wave issues per step
+    constexpr int BPW = 8 / NW;                          // 8-row blocks of a half-tile that one wave loads
+    constexpr int LPS = 2 * BPW * HV;                    // loads a wave issues per step
+    constexpr int BQW = 16 * NW;                         // queries per workgroup
     __shared__ __attribute__((aligned(1024))) char lds[NS * (KT + VT)];
     char *const ks = lds, *const vs = lds + NS * KT;
 
@@ -178,11 +185,11 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
     const int r = lane & 15, g = lane >> 4;
     unsigned bx, by;
     xcd_batch_remap(bx, by);                            // the query tiles of one problem share an L2: K, V fetched once
-    const int q0 = bx * BQ;
+    const int q0 = bx * BQW;
     const long long b = by;
 
     const __amdgpu_buffer_rsrc_t rq = make_rsrc(p.Q + b * p.strideQ + (long long)q0 * p.ldq,
-                                                (unsigned)((long long)(min(p.Lq - q0, BQ) - 1) * p.ldq + KROW * HV));
+                                                (unsigned)((long long)(min(p.Lq - q0, BQW) - 1) * p.ldq + KROW * HV));
     const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.K + b * p.strideK, (unsigned)((long long)(p.Lk - 1) * p.ldk + KROW * HV));
     const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.V + b * p.strideV, (unsigned)((long long)(p.Lk - 1) * p.ldv + KROW * HV));
 
@@ -200,8 +207,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int blk = wave * 2 + i;
+            for (int i = 0; i < BPW; ++i) {
+                const int blk = wave * BPW + i;
                 const unsigned off = (unsigned)((j0 + blk * 8 + krow) * p.ldk) + hv * KROW + kchunk;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void *)(ks + koff + hv * K_TILE + blk * 1024), 16, off, 0, 0, 0);
             }
@@ -211,8 +218,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p)
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int blk = wave * 2 + i;
+            for (int i = 0; i < BPW; ++i) {
+                const int blk = wave * BPW + i;
                 const unsigned off = (unsigned)((j0 + blk * 8 + krow) * p.ldv) + hv * KROW + kchunk;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void *)(vs + voff + hv * V_TILE + blk * 1024), 16, off, 0, 0, 0);
             }
@@ -385,33 +392,41 @@ bool mfma_can_run(const AttnProblem &q)
     return true;
 }
 
-template <int D, int HV>
+template <int D, int HV, int NW>
 hipError_t mfma_launch(const AttnProblem &q)
 {
     AttnParams p = params_elements(q);
     p.ldq *= 2; p.ldk *= 2; p.ldv *= 2;                  // bytes
     p.strideQ *= 2; p.strideK *= 2; p.strideV *= 2;
-    const dim3 grid((unsigned)((q.Lq + BQ - 1) / BQ), (unsigned)q.batch);
-    hipLaunchKernelGGL((attn_mfma_kernel<D, HV>), grid, dim3(256), 0, q.stream, p);
+    const dim3 grid((unsigned)((q.Lq + 16 * NW - 1) / (16 * NW)), (unsigned)q.batch);
+    hipLaunchKernelGGL((attn_mfma_kernel<D, HV, NW>), grid, dim3(64 * NW), 0, q.stream, p);
     return hipGetLastError();
 }
 
 const AttnVariant kGeneral = {"general attention one wave per query valu", general_can_run, general_launch};
 const AttnVariant kMfma64d1 = {"bf16 attention head 64, 64 queries x 64-key steps, prefetch 1, waves 4x1 mfma16", mfma_can_run<1>,
-                               mfma_launch<1, 1>};
+                               mfma_launch<1, 1, 4>};
 const AttnVariant kMfma64d2 = {"bf16 attention head 64, 64 queries x 64-key steps, prefetch 2, waves 4x1 mfma16", mfma_can_run<1>,
-                               mfma_launch<2, 1>};
+                               mfma_launch<2, 1, 4>};
 const AttnVariant kMfma128d1 = {"bf16 attention head 128, 64 queries x 64-key steps, prefetch 1, waves 4x1 mfma16", mfma_can_run<2>,
-                                mfma_launch<1, 2>};
+                                mfma_launch<1, 2, 4>};
 const AttnVariant kMfma128d2 = {"bf16 attention head 128, 64 queries x 64-key steps, prefetch 2, waves 4x1 mfma16", mfma_can_run<2>,
-                                mfma_launch<2, 2>};
+                                mfma_launch<2, 2, 4>};
+// Eight waves per workgroup pay when there are at least two such workgroups per compute unit (swept: 32 x 2048^2
+// x 128 660 -> 827 TFLOP/s, 16 x 4096^2 x 128 748 -> 908, 32 x 2048^2 x 64 631 -> 701; the 96 x 512^2 x 64
+// workload, 384 workgroups of 128 queries, is 5 % slower than with 768 workgroups of 64)
+bool w8_worthwhile(const AttnProblem &q) { return q.batch * ((q.Lq + 127) / 128) >= 512; }
+const AttnVariant kMfma64w8 = {"bf16 attention head 64, 128 queries x 64-key steps, prefetch 1, waves 8x1 mfma16", mfma_can_run<1>,
+                               mfma_launch<1, 1, 8>, w8_worthwhile};
+const AttnVariant kMfma128w8 = {"bf16 attention head 128, 128 queries x 64-key steps, prefetch 1, waves 8x1 mfma16", mfma_can_run<2>,
+                                mfma_launch<1, 2, 8>, w8_worthwhile};
 // swept on the 96 x 512 x 512 x 64 workload: a prefetch distance of 1 is as fast as 2 (the step is bound
 // by its own dependency chain, not by load latency) and leaves more LDS free; 3 is slower
-const AttnVariant *const kBf16Table[] = {&kGeneral, &kMfma64d2, &kMfma64d1, &kMfma128d2, &kMfma128d1};   // the last that can run is the default
+const AttnVariant *const kBf16Table[] = {&kGeneral, &kMfma64d2, &kMfma64d1, &kMfma128d2, &kMfma128d1, &kMfma64w8, &kMfma128w8};   // the last that can run is the default
 
 }  // namespace
 
-int attn_num_variants(xp_dtype in_type) { return in_type == XP_BF16 ? 5 : (in_type == XP_F32 ? 1 : 0); }
+int attn_num_variants(xp_dtype in_type) { return in_type == XP_BF16 ? 7 : (in_type == XP_F32 ? 1 : 0); }
 
 const AttnVariant *attn_variant(xp_dtype in_type, int idx)
 {

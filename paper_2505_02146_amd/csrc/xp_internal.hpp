@@ -53,6 +53,7 @@ struct AttnVariant {
     const char *name;
     bool (*can_run)(const AttnProblem &);
     hipError_t (*launch)(const AttnProblem &);
+    bool (*worthwhile)(const AttnProblem &) = nullptr;   // selection skips a variant that can run but would not pay; null: always
 };
 int attn_num_variants(xp_dtype in_type);                    // index 0 is the general kernel
 const AttnVariant *attn_variant(xp_dtype in_type, int idx);

@@ -15,11 +15,13 @@ from tests.helpers import GATE_ELEM, GATE_FRO, dev
 
 pytestmark = pytest.mark.gpu
 
-TIGHT = {0: 2e-5, 1: 2.5e-3, 2: 2.5e-3, 3: 2.5e-3, 4: 2.5e-3}     # variant 0 is the general kernel, the rest are mfma kernels
-MFMA = [1, 2]                                           # head size 64
-MFMA128 = [3, 4]                                        # head size 128
-DEFAULT = 2                                             # what the library picks for head size 64 when it can
-DEFAULT128 = 4                                          # ... and for head size 128 (the last entry)
+TIGHT = {0: 2e-5, 1: 2.5e-3, 2: 2.5e-3, 3: 2.5e-3, 4: 2.5e-3, 5: 2.5e-3, 6: 2.5e-3}     # variant 0 is the general kernel, the rest are mfma kernels
+MFMA = [1, 2, 5]                                        # head size 64 (5: eight waves, 128 queries per workgroup)
+MFMA128 = [3, 4, 6]                                     # head size 128 (6: eight waves)
+DEFAULT = 2                                             # what the library picks for head size 64 when it can (small problems)
+DEFAULT128 = 4                                          # ... and for head size 128
+BIG128 = 6                                              # with at least 512 workgroups of 128 queries: the eight-wave kernels
+NVARIANTS = 7
 
 
 @pytest.fixture(scope="module")
@@ -153,7 +155,7 @@ def test_padded_pitches_and_batch_gaps(xp, oracle, variant):
 
 def test_selection_takes_the_mfma_kernel_when_it_can_and_the_general_one_otherwise(xp, oracle):
     got, ref, used, _ = _run(xp, oracle, batch=2, Lq=70, Lk=90, d=64, dv=64, scale=0.125)
-    assert used == DEFAULT and xp.xp_num_configs(xp.XP_OP_ATTENTION, "bf16") == DEFAULT128 + 1
+    assert used == DEFAULT and xp.xp_num_configs(xp.XP_OP_ATTENTION, "bf16") == NVARIANTS
     _gate(got, ref, "selected mfma", TIGHT[DEFAULT])
     # row pitch not a multiple of 16 bytes: the matrix-core kernel declines
     got, ref, used, _ = _run(xp, oracle, batch=2, Lq=70, Lk=90, d=64, dv=64, scale=0.125, pad=(3, 0, 0, 0))
@@ -236,10 +238,10 @@ def test_attention_head128_workload_sampled(xp, oracle):
     xp.xp_attention(b, L, L, d, d, w["scale"], dev(w["Q"].reshape(-1)), d, L * d, dev(w["K"].reshape(-1)), d, L * d,
                     dev(w["V"].reshape(-1)), d, L * d, O, d, L * d, q_type="bf16", k_type="bf16", v_type="bf16")
     torch.cuda.synchronize()
-    assert xp.xp_last_config(xp.XP_OP_ATTENTION, "bf16") == DEFAULT128
+    assert xp.xp_last_config(xp.XP_OP_ATTENTION, "bf16") == BIG128       # 32 x 16 workgroups of 128 queries
     got = O.cpu().numpy()
     assert np.isfinite(got).all()
     for x in (0, 13, 31):
         ref = oracle.attention(w["Q"][x].reshape(-1), w["K"][x].reshape(-1), w["V"][x].reshape(-1), batch=1, Lq=L, Lk=L, d=d, dv=d,
                                scale=w["scale"])
-        _gate(got[x:x + 1], ref, f"attention_bf16_2048_d128 batch index {x}", TIGHT[DEFAULT128])
+        _gate(got[x:x + 1], ref, f"attention_bf16_2048_d128 batch index {x}", TIGHT[BIG128])
