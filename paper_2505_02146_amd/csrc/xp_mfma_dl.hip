@@ -155,9 +155,13 @@ template <> struct Acc<true, 16> {
 
 // One tile of C.  `bid` numbers the tiles of the row range [m_base, m_end) of the problem, which is
 // tiles_m tile-rows high; lds points at T::LDS bytes of shared memory.
-template <bool INT8, class T, bool CONV>
+// MODE: 0 GEMM, 1 convolution (A addressed through the im2col map), 2 convolution with planar output
+// (a kernel of its own, so that the epilogue branch costs the others nothing: with the branch in
+// every kernel the NHWC convolution lost 2.4 %)
+template <bool INT8, class T, int MODE>
 __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, int m_base, int m_end, int tiles_m)
 {
+    constexpr bool CONV = MODE != 0, PLANAR = MODE == 2;
     using AccT = typename Acc<INT8, T::MF>::type;
     constexpr int RB = T::RB, MF = T::MF;
     constexpr int NACC = MF == 32 ? 16 : 4;           // accumulator registers per lane and block
@@ -394,7 +398,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             if constexpr (MF == 32)
                 store_block32<INT8, T::NTSTORE>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 32, n0 + wn * T::WTN + j * 32, lane, m_end,
                                     p.N, p.alpha, p.beta);
-            else if (p.c_plane)
+            else if constexpr (PLANAR)
                 store_block16t_planar(acc[i][j], C, p.c_plane, m0 + wm * T::WTM + i * 16, n0 + wn * T::WTN + j * 16, lane, m_end,
                                       p.N, p.alpha);
             else
@@ -403,23 +407,23 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         }
 }
 
-template <bool INT8, class T, bool CONV>
+template <bool INT8, class T, int MODE>
 __global__ __launch_bounds__(T::NT, T::OCC) void dl_kernel(DlParams p)
 {
     __shared__ __attribute__((aligned(1024))) char lds[T::LDS];
-    dl_body<INT8, T, CONV>(p, lds, blockIdx.x, 0, p.M, p.tiles_m);
+    dl_body<INT8, T, MODE>(p, lds, blockIdx.x, 0, p.M, p.tiles_m);
 }
 
 // Two tile heights in one launch: full rounds of T1 tiles first, then one last round of the lower
 // T2 tiles, so that a grid that does not fill its last round of compute units wastes less of it
 // (workgroups start in index order: the T1 tiles occupy every compute unit before a T2 tile starts).
-template <bool INT8, class T1, class T2, bool CONV>
+template <bool INT8, class T1, class T2, int MODE>
 __global__ __launch_bounds__(T1::NT, 1) void dl_kernel_two_heights(DlParams p)
 {
     static_assert(T1::NT == T2::NT && T1::BN == T2::BN, "the two tile types share the workgroup shape and the tile width");
     __shared__ __attribute__((aligned(1024))) char lds[T1::LDS > T2::LDS ? T1::LDS : T2::LDS];
-    if ((int)blockIdx.x < p.n1) dl_body<INT8, T1, CONV>(p, lds, blockIdx.x, 0, p.m_split, p.tiles_m);
-    else dl_body<INT8, T2, CONV>(p, lds, blockIdx.x - p.n1, p.m_split, p.M, p.tiles_m2);
+    if ((int)blockIdx.x < p.n1) dl_body<INT8, T1, MODE>(p, lds, blockIdx.x, 0, p.m_split, p.tiles_m);
+    else dl_body<INT8, T2, MODE>(p, lds, blockIdx.x - p.n1, p.m_split, p.M, p.tiles_m2);
 }
 
 // ------------------------------------------------------------------------------------ host side
@@ -488,8 +492,14 @@ hipError_t dl_launch(const Problem &q)
 {
     const DlParams p = dl_params<INT8, T>(q);
     const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)q.batch);
-    if (q.conv) hipLaunchKernelGGL((dl_kernel<INT8, T, true>), grid, dim3(T::NT), 0, q.stream, p);
-    else hipLaunchKernelGGL((dl_kernel<INT8, T, false>), grid, dim3(T::NT), 0, q.stream, p);
+    if constexpr (T::MF == 16 && !INT8) {
+        if (q.conv && q.c_plane) {
+            hipLaunchKernelGGL((dl_kernel<INT8, T, 2>), grid, dim3(T::NT), 0, q.stream, p);
+            return hipGetLastError();
+        }
+    }
+    if (q.conv) hipLaunchKernelGGL((dl_kernel<INT8, T, 1>), grid, dim3(T::NT), 0, q.stream, p);
+    else hipLaunchKernelGGL((dl_kernel<INT8, T, 0>), grid, dim3(T::NT), 0, q.stream, p);
     return hipGetLastError();
 }
 
@@ -517,8 +527,14 @@ hipError_t dl_launch_two_heights(const Problem &q)
     p.tiles_m2 = (int)((q.M - split + T2::BM - 1) / T2::BM);
     p.n1 = p.tiles_m * p.tiles_n;
     const dim3 grid((unsigned)(p.n1 + p.tiles_m2 * p.tiles_n), (unsigned)q.batch);
-    if (q.conv) hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, true>), grid, dim3(T1::NT), 0, q.stream, p);
-    else hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, false>), grid, dim3(T1::NT), 0, q.stream, p);
+    if constexpr (T1::MF == 16 && !INT8) {
+        if (q.conv && q.c_plane) {
+            hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, 2>), grid, dim3(T1::NT), 0, q.stream, p);
+            return hipGetLastError();
+        }
+    }
+    if (q.conv) hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, 1>), grid, dim3(T1::NT), 0, q.stream, p);
+    else hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, 0>), grid, dim3(T1::NT), 0, q.stream, p);
     return hipGetLastError();
 }
 
