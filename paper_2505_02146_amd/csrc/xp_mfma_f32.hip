@@ -7,6 +7,8 @@
 // whichever way the operand lies in memory.  Global loads are scalar, predicated at the edges,
 // and run along the operand's contiguous index.
 #include "xp_internal.hpp"
+
+#include <type_traits>
 #include "xp_epilogue.hpp"
 
 namespace xp {
@@ -163,32 +165,58 @@ __global__ __launch_bounds__(256, 4) void f32p_kernel(FParams p)
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     // chunk e of an operand tile: K-contiguous -> row e / 4, k offset 4 * (e % 4); else k = e / (rows/4),
-    // rows 4 * (e % (rows/4)) .. +3
+    // rows 4 * (e % (rows/4)) .. +3.  The loads are buffer loads: the lane's byte offset inside the
+    // operand is fixed for the whole loop, the K position of the step is a scalar added by the load
+    // itself, and a chunk outside the matrix (a row past M or N, a k past K) has an offset beyond the
+    // buffer's range, which reads as zeros -- the loop spends no vector instruction on addresses or
+    // bounds, and every vector instruction there is time taken from the matrix pipe.
+    constexpr unsigned OUTSIDE = 0x80000000u;            // operands are smaller than 2 GiB
+    const unsigned a_bytes = (unsigned)(((KA ? (long long)(p.M - 1) * p.a_sm + p.K : (long long)(p.K - 1) * p.a_sk + p.M)) * 4);
+    const unsigned b_bytes = (unsigned)(((KB ? (long long)(p.N - 1) * p.b_sn + p.K : (long long)(p.K - 1) * p.b_sk + p.N)) * 4);
+    const __amdgpu_buffer_rsrc_t ra_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(A), 0, a_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rb_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(B), 0, b_bytes, 0x00020000);
+    unsigned offa[CA], offb[CB];
+    int ka[CA], kb[CB];                                   // the chunk's first k inside a step
+#pragma unroll
+    for (int i = 0; i < CA; ++i) {
+        const int e = t + 256 * i;
+        if constexpr (KA) {
+            const int m = m0 + e / (PK / 4);
+            ka[i] = 4 * (e % (PK / 4));
+            offa[i] = m < p.M ? (unsigned)(((long long)m * p.a_sm + ka[i]) * 4) : OUTSIDE;
+        } else {
+            const int m = m0 + 4 * (e % (BM / 4));
+            ka[i] = e / (BM / 4);
+            offa[i] = m < p.M ? (unsigned)(((long long)ka[i] * p.a_sk + m) * 4) : OUTSIDE;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < CB; ++i) {
+        const int e = t + 256 * i;
+        if constexpr (KB) {
+            const int n = n0 + e / (PK / 4);
+            kb[i] = 4 * (e % (PK / 4));
+            offb[i] = n < p.N ? (unsigned)(((long long)n * p.b_sn + kb[i]) * 4) : OUTSIDE;
+        } else {
+            const int n = n0 + 4 * (e % (BN / 4));
+            kb[i] = e / (BN / 4);
+            offb[i] = n < p.N ? (unsigned)(((long long)kb[i] * p.b_sk + n) * 4) : OUTSIDE;
+        }
+    }
+    const unsigned step_a = (unsigned)((KA ? 1LL : p.a_sk) * 4), step_b = (unsigned)((KB ? 1LL : p.b_sk) * 4);   // bytes per unit of k
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     f32x4 ra[CA], rb[CB];
-    auto load = [&](int k0) {
+    // FULL: the whole step lies inside K (every step but possibly the last): nothing to check
+    auto load = [&](int k0, bool full) {
 #pragma unroll
         for (int i = 0; i < CA; ++i) {
-            const int e = t + 256 * i;
-            ra[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            if constexpr (KA) {
-                const int m = m0 + e / (PK / 4), k = k0 + 4 * (e % (PK / 4));
-                if (m < p.M && k < p.K) ra[i] = *(const f32x4 *)(A + (long long)m * p.a_sm + k);
-            } else {
-                const int k = k0 + e / (BM / 4), m = m0 + 4 * (e % (BM / 4));
-                if (m < p.M && k < p.K) ra[i] = *(const f32x4 *)(A + (long long)k * p.a_sk + m);
-            }
+            const unsigned off = full || k0 + ka[i] < p.K ? offa[i] : OUTSIDE;
+            ra[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(ra_rsrc, off, (unsigned)k0 * step_a, 0));
         }
 #pragma unroll
         for (int i = 0; i < CB; ++i) {
-            const int e = t + 256 * i;
-            rb[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            if constexpr (KB) {
-                const int n = n0 + e / (PK / 4), k = k0 + 4 * (e % (PK / 4));
-                if (n < p.N && k < p.K) rb[i] = *(const f32x4 *)(B + (long long)n * p.b_sn + k);
-            } else {
-                const int k = k0 + e / (BN / 4), n = n0 + 4 * (e % (BN / 4));
-                if (n < p.N && k < p.K) rb[i] = *(const f32x4 *)(B + (long long)k * p.b_sk + n);
-            }
+            const unsigned off = full || k0 + kb[i] < p.K ? offb[i] : OUTSIDE;
+            rb[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rb_rsrc, off, (unsigned)k0 * step_b, 0));
         }
     };
     auto stage = [&](int buf) {
@@ -237,18 +265,27 @@ __global__ __launch_bounds__(256, 4) void f32p_kernel(FParams p)
         }
     };
 
-    load(0);
+    load(0, PK <= p.K);
     stage(0);
     __syncthreads();
-    int buf = 0;
-    for (int k0 = 0; k0 < p.K; k0 += PK) {
+    // two steps per trip, so that the buffer index is a constant in every LDS address
+    auto step = [&](int k0, auto buf_c) {
+        constexpr int buf = decltype(buf_c)::value;
         const bool more = k0 + PK < p.K;                  // uniform
-        if (more) load(k0 + PK);
+        if (more) load(k0 + PK, k0 + 2 * PK <= p.K);
         multiply(buf, 0, PK);
         if (more) stage(buf ^ 1);                         // the buffer every wave finished reading before the last barrier
         __syncthreads();
-        buf ^= 1;
+    };
+    // (no step is conditional inside the loop: a branch around one makes the compiler copy the 64
+    // accumulator registers where the paths join)
+    const int nsteps = (p.K + PK - 1) / PK;
+    int k0 = 0;
+    for (int pair = 0; pair < nsteps / 2; ++pair, k0 += 2 * PK) {
+        step(k0, std::integral_constant<int, 0>{});
+        step(k0 + PK, std::integral_constant<int, 1>{});
     }
+    if (nsteps & 1) step(k0, std::integral_constant<int, 0>{});
 
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -265,6 +302,10 @@ bool f32p_can_run(const Problem &q)
     if (q.M > 0x7fffffffLL || q.N > 0x7fffffffLL || q.K > 0x7fffffffLL || q.batch > 65535) return false;
     if (((q.M + 63) / 64) * ((q.N + 63) / 64) > 0x7fffffffLL) return false;
     if (((uintptr_t)q.A | (uintptr_t)q.B) % 16 != 0 || q.strideA % 4 != 0 || q.strideB % 4 != 0) return false;
+    // buffer addressing: byte offsets inside one operand stay below 2^31
+    const int64_t a_ext = KA ? (q.M - 1) * q.a_sm + q.K : (q.K - 1) * q.a_sk + q.M;
+    const int64_t b_ext = KB ? (q.N - 1) * q.b_sn + q.K : (q.K - 1) * q.b_sk + q.N;
+    if (a_ext * 4 >= 0x7fffffffLL || b_ext * 4 >= 0x7fffffffLL) return false;
     if (KA ? (q.a_sk != 1 || q.a_sm % 4 != 0 || q.K % 4 != 0) : (q.a_sm != 1 || q.a_sk % 4 != 0 || q.M % 4 != 0)) return false;
     if (KB ? (q.b_sk != 1 || q.b_sn % 4 != 0 || q.K % 4 != 0) : (q.b_sn != 1 || q.b_sk % 4 != 0 || q.N % 4 != 0)) return false;
     return true;
