@@ -248,7 +248,11 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
 
     // issue A loads [lo, hi) of K step kt into the A buffer at byte offset a_off; likewise for B
     constexpr int IT = T::IA + T::IB;
-    auto issue_a = [&](int kt, int a_off, int lo, int hi) {
+    // CHECK: the step may reach or pass the end of K, so every lane tests its chunk; the main part of
+    // the loop issues whole steps only and spends no vector instruction on that (matrix and vector
+    // instructions do not overlap on a SIMD: vector work in the loop is MFMA time lost)
+    auto issue_a = [&](int kt, int a_off, int lo, int hi, auto check_c) {
+        constexpr bool CHECK = decltype(check_c)::value;
         const int kb = kt * RB;
 #pragma unroll
         for (int i = 0; i < T::IA; ++i) {
@@ -264,7 +268,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 off = a_off_g[i];
                 soff = kb;
             }
-            if (kb + a_cb[i] >= p.Kb) off = OOB;
+            if constexpr (CHECK) {
+                if (kb + a_cb[i] >= p.Kb) off = OOB;
+            }
             lds_void *dst = (lds_void *)(lds + a_off + (wave + i * T::NWAVE) * 1024);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, dst, 16, off, soff, 0, 0);
         }
@@ -278,21 +284,24 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             }
         }
     };
-    auto issue_b = [&](int kt, int b_off, int lo, int hi) {
+    auto issue_b = [&](int kt, int b_off, int lo, int hi, auto check_c) {
+        constexpr bool CHECK = decltype(check_c)::value;
         const int kb = kt * RB;
 #pragma unroll
         for (int i = 0; i < T::IB; ++i) {
             if (i < lo || i >= hi) continue;
             unsigned off = b_off_g[i];
-            if (kb + b_cb[i] >= p.Kb) off = OOB;
+            if constexpr (CHECK) {
+                if (kb + b_cb[i] >= p.Kb) off = OOB;
+            }
             lds_void *dst = (lds_void *)(lds + b_off + (wave + i * T::NWAVE) * 1024);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, dst, 16, off, kb, 0, 0);
         }
     };
     // loads [lo, hi) of the IA + IB that one K step issues when both rings have the same depth
-    auto issue = [&](int kt, int a_off, int b_off, int lo, int hi) {
-        issue_a(kt, a_off, lo, hi < T::IA ? hi : T::IA);
-        issue_b(kt, b_off, lo > T::IA ? lo - T::IA : 0, hi - T::IA);
+    auto issue = [&](int kt, int a_off, int b_off, int lo, int hi, auto check_c) {
+        issue_a(kt, a_off, lo, hi < T::IA ? hi : T::IA, check_c);
+        issue_b(kt, b_off, lo > T::IA ? lo - T::IA : 0, hi - T::IA, check_c);
     };
     auto read_frags = [&](int a_off, int b_off, int kk, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
 #pragma unroll
@@ -321,12 +330,12 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             // step j issues B(j+NS-1) and then A(j+NSA-1); the steps before the first one do the same
 #pragma unroll
             for (int j = -(T::NSA - 1); j < 0; ++j) {
-                if (j + T::NS - 1 >= 0) issue_b(j + T::NS - 1, T::B_BASE + (j + T::NS - 1) * T::B_BYTES, 0, T::IB);
-                issue_a(j + T::NSA - 1, (j + T::NSA - 1) * T::A_BYTES, 0, T::IA);
+                if (j + T::NS - 1 >= 0) issue_b(j + T::NS - 1, T::B_BASE + (j + T::NS - 1) * T::B_BYTES, 0, T::IB, std::true_type{});
+                issue_a(j + T::NSA - 1, (j + T::NSA - 1) * T::A_BYTES, 0, T::IA, std::true_type{});
             }
         } else {
 #pragma unroll
-            for (int s = 0; s < T::NS - 1; ++s) issue(s, s * T::A_BYTES, T::B_BASE + s * T::B_BYTES, 0, IT);
+            for (int s = 0; s < T::NS - 1; ++s) issue(s, s * T::A_BYTES, T::B_BASE + s * T::B_BYTES, 0, IT, std::true_type{});
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
         __builtin_amdgcn_s_barrier();
@@ -335,20 +344,20 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         read_frags(0, T::B_BASE, 0, xa, xb);
         int cur_a = 0, cur_b = T::B_BASE;
         int fill_a = (T::NSA - 1) * T::A_BYTES, fill_b = T::B_BASE + (T::NS - 1) * T::B_BYTES;
-        auto step = [&](int kt, auto odd_in) {
+        auto step = [&](int kt, auto odd_in, auto check_c) {
             constexpr bool ODD = decltype(odd_in)::value;   // set multiplied in sub-step 0: false = X, true = Y
             const int nxt_a = cur_a + T::A_BYTES == A_END ? 0 : cur_a + T::A_BYTES;
             const int nxt_b = cur_b + T::B_BYTES == B_END ? T::B_BASE : cur_b + T::B_BYTES;
             // loads go into the buffers read in step kt-1
             if constexpr (T::ASYM) {
-                issue_b(kt + T::NS - 1, fill_b, 0, T::IB);
-                issue_a(kt + T::NSA - 1, fill_a, 0, T::IA);
+                issue_b(kt + T::NS - 1, fill_b, 0, T::IB, check_c);
+                issue_a(kt + T::NSA - 1, fill_a, 0, T::IA, check_c);
             } else if constexpr (!T::SPREAD) {
-                issue(kt + T::NS - 1, fill_a, fill_b, 0, IT);
+                issue(kt + T::NS - 1, fill_a, fill_b, 0, IT, check_c);
             }
 #pragma unroll
             for (int ph = 0; ph < T::PH - 1; ++ph) {
-                if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill_a, fill_b, ph * IT / T::PH, (ph + 1) * IT / T::PH);
+                if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill_a, fill_b, ph * IT / T::PH, (ph + 1) * IT / T::PH, check_c);
                 const bool cur_is_y = ((ph & 1) != 0) != ODD;
                 if (cur_is_y) read_frags(cur_a, cur_b, ph + 1, xa, xb);
                 else read_frags(cur_a, cur_b, ph + 1, ya, yb);
@@ -361,7 +370,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             constexpr bool LAST_IS_Y = (((T::PH - 1) & 1) != 0) != ODD;
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(T::SPREAD ? PENDING - (IT - (T::PH - 1) * IT / T::PH) : PENDING));
             __builtin_amdgcn_s_barrier();
-            if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill_a, fill_b, (T::PH - 1) * IT / T::PH, IT);
+            if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill_a, fill_b, (T::PH - 1) * IT / T::PH, IT, check_c);
             // sub-step 0 of the next buffers (zeros after the last step, never multiplied)
             if constexpr (LAST_IS_Y) read_frags(nxt_a, nxt_b, 0, xa, xb);
             else read_frags(nxt_a, nxt_b, 0, ya, yb);
@@ -375,15 +384,20 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             cur_b = nxt_b;
         };
         if constexpr (T::PH % 2 == 0) {
-            for (int kt = 0; kt < KT; ++kt) step(kt, std::false_type{});
+            // steps whose loads (for step kt + NS - 1, A possibly one further) are whole steps inside K
+            constexpr int AHEAD = (T::NSA > T::NS ? T::NSA : T::NS) - 1;
+            const int whole = p.Kb / RB - AHEAD;
+            int kt = 0;
+            for (; kt < whole; ++kt) step(kt, std::false_type{}, std::false_type{});
+            for (; kt < KT; ++kt) step(kt, std::false_type{}, std::true_type{});
         } else {
             // an odd number of sub-steps per K step: the roles of the two sets swap every step
             int kt = 0;
             for (; kt + 1 < KT; kt += 2) {
-                step(kt, std::false_type{});
-                step(kt + 1, std::true_type{});
+                step(kt, std::false_type{}, std::true_type{});
+                step(kt + 1, std::true_type{}, std::true_type{});
             }
-            if (kt < KT) step(kt, std::false_type{});
+            if (kt < KT) step(kt, std::false_type{}, std::true_type{});
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
     }
