@@ -48,7 +48,7 @@ struct DlParams {
     float alpha, beta;
     int tiles_m, tiles_n, group_m;
     unsigned in_bytes;                    // convolution view
-    int H, W, Cin_b, S, PQ, Q, sh, sw, ph, pw;
+    int H, W, Cin_b, R, S, PQ, Q, sh, sw, ph, pw;
     // two-height launches: workgroups [0, n1) tile rows [0, m_split) with the first tile type,
     // the rest tile rows [m_split, M) with the second
     int n1, m_split, tiles_m2;
@@ -183,8 +183,13 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
 
     const int rows_a = min(m_end - m0, T::BM), rows_b = min(p.N - n0, T::BN);
     __amdgpu_buffer_rsrc_t ra, rb;
+    // Convolution: a lane's offset for a filter tap is its pixel's offset (fixed) plus the tap's offset
+    // (the same for every lane: a scalar), so the loop only has to decide whether the tap falls inside
+    // the image for that pixel -- one bit of a mask worked out here, once.  Pixel offsets are taken
+    // relative to (-pad_h, -pad_w) so that they are never negative; the buffer starts that much earlier.
+    const int conv_bias = CONV ? (p.ph * p.W + p.pw) * p.Cin_b : 0;
     if constexpr (CONV) {
-        ra = make_rsrc(p.A, p.in_bytes);
+        ra = make_rsrc(p.A - conv_bias, p.in_bytes + (unsigned)conv_bias);
     } else {
         ra = make_rsrc(p.A + batch * p.strideA_b + (long long)m0 * p.lda_b,
                        (unsigned)((long long)(rows_a - 1) * p.lda_b + p.Kb));
@@ -196,23 +201,26 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     // lane l lands at row l/CPR, position l%CPR, and fetches the chunk that belongs there
     unsigned a_off_g[T::IA], b_off_g[T::IB];            // byte offsets of this lane's chunks in global memory
     int a_cb[T::IA], b_cb[T::IB];                       // byte offset of the fetched chunk within the row
-    int a_h0[CONV ? T::IA : 1], a_w0[CONV ? T::IA : 1];
+    int a_outside[CONV ? T::IA : 1];                    // conv: bit r*S + s set <=> tap (r, s) of this lane's pixel is padding
 #pragma unroll
     for (int i = 0; i < T::IA; ++i) {
         const int row = (wave + i * T::NWAVE) * T::RPI + lane / T::CPR;
         a_cb[i] = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
         if constexpr (CONV) {
             const int m = m0 + row;
+            a_outside[i] = -1;                          // a row past the end: every tap is outside
+            a_off_g[i] = 0;
             if (m < m_end && row < T::BM) {
                 const int n = m / p.PQ, pq = m % p.PQ;
                 const int op = pq / p.Q, oq = pq % p.Q;
-                a_h0[i] = op * p.sh - p.ph;
-                a_w0[i] = oq * p.sw - p.pw;
-                a_off_g[i] = (unsigned)n * (unsigned)(p.H * p.W) * (unsigned)p.Cin_b + a_cb[i];
-            } else {
-                a_h0[i] = -0x40000000;                  // never inside the image
-                a_w0[i] = 0;
-                a_off_g[i] = 0;
+                const int h0 = op * p.sh - p.ph, w0 = oq * p.sw - p.pw;
+                a_off_g[i] = (unsigned)n * (unsigned)(p.H * p.W) * (unsigned)p.Cin_b +
+                             (unsigned)((h0 + p.ph) * p.W + w0 + p.pw) * (unsigned)p.Cin_b + a_cb[i];
+                int outside = 0;
+                for (int r = 0, t = 0; r < p.R; ++r)
+                    for (int s2 = 0; s2 < p.S; ++s2, ++t)
+                        if ((unsigned)(h0 + r) >= (unsigned)p.H || (unsigned)(w0 + s2) >= (unsigned)p.W) outside |= 1 << t;
+                a_outside[i] = outside;
             }
         } else {
             a_off_g[i] = (unsigned)(row * p.lda_b) + a_cb[i];
@@ -244,7 +252,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
 #pragma unroll
             for (int v = 0; v < NACC; ++v) acc[i][j][v] = 0;
 
-    int tap_r = 0, tap_s = 0, c0_b = 0;                 // conv: K offset of the next step to load
+    int tap_r = 0, tap_s = 0, tap = 0, tap_off = 0, c0_b = 0;   // conv: filter tap and channel offset of the next step to load
 
     // issue A loads [lo, hi) of K step kt into the A buffer at byte offset a_off; likewise for B
     constexpr int IT = T::IA + T::IB;
@@ -260,10 +268,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             unsigned off;
             int soff;
             if constexpr (CONV) {
-                const int h = a_h0[i] + tap_r, w = a_w0[i] + tap_s;
-                const bool ok = (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W;
-                off = ok ? a_off_g[i] + (unsigned)(h * p.W + w) * (unsigned)p.Cin_b : OOB;
-                soff = c0_b;
+                // bit `tap` of the mask, spread over the word, puts a padding tap beyond the buffer's range
+                off = ((unsigned)__builtin_amdgcn_sbfe(a_outside[i], tap, 1) & OOB) | a_off_g[i];
+                soff = c0_b + tap_off;
             } else {
                 off = a_off_g[i];
                 soff = kb;
@@ -279,7 +286,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 c0_b += RB;
                 if (c0_b >= p.Cin_b) {
                     c0_b = 0;
+                    ++tap;
                     if (++tap_s == p.S) { tap_s = 0; ++tap_r; }
+                    tap_off = (tap_r * p.W + tap_s) * p.Cin_b;
                 }
             }
         }
@@ -459,7 +468,9 @@ bool dl_can_run_common(const Problem &q, int BM, int BN, int RB, int MF)
     if (q.conv) {
         if (INT8) return false;
         const int64_t in_bytes = (q.M / (q.P * q.Q)) * q.H * q.W * q.Cin * esz;
-        if (in_bytes >= 0x7fffffffLL) return false;
+        // offsets are taken from (-pad_h, -pad_w) of the first image; a lane's taps are one bit each of a 32-bit mask
+        if (in_bytes + (q.ph * q.W + q.pw) * q.Cin * esz >= 0x7fffffffLL) return false;
+        if (q.R * q.S > 32) return false;
         if ((q.Cin * esz) % RB != 0) return false;         // a K step never straddles a filter tap
         if (((uintptr_t)q.A % 16) != 0) return false;
     } else {
@@ -490,10 +501,10 @@ DlParams dl_params(const Problem &q)
     // tile-rows per raster group; XP_GROUP_M overrides it for tuning experiments
     static const int env_group_m = [] { const char *e = getenv("XP_GROUP_M"); return e ? atoi(e) : 0; }();
     p.group_m = env_group_m > 0 ? env_group_m : 4;
-    p.in_bytes = 0; p.H = p.W = p.Cin_b = p.S = p.PQ = p.Q = p.sh = p.sw = p.ph = p.pw = 0;
+    p.in_bytes = 0; p.H = p.W = p.Cin_b = p.R = p.S = p.PQ = p.Q = p.sh = p.sw = p.ph = p.pw = 0;
     if (q.conv) {
         p.in_bytes = (unsigned)((q.M / (q.P * q.Q)) * q.H * q.W * q.Cin * esz);
-        p.H = (int)q.H; p.W = (int)q.W; p.Cin_b = (int)(q.Cin * esz); p.S = (int)q.S;
+        p.H = (int)q.H; p.W = (int)q.W; p.Cin_b = (int)(q.Cin * esz); p.R = (int)q.R; p.S = (int)q.S;
         p.PQ = (int)(q.P * q.Q); p.Q = (int)q.Q;
         p.sh = (int)q.sh; p.sw = (int)q.sw; p.ph = (int)q.ph; p.pw = (int)q.pw;
     }
