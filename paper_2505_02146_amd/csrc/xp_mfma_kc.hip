@@ -268,11 +268,16 @@ __global__ __launch_bounds__(T::NT) void kc_kernel(KcParams p)
         __builtin_amdgcn_s_waitcnt(0xc07f);     // lgkmcnt(0): this wave's LDS writes have landed
         __builtin_amdgcn_s_barrier();
         read_frags(0, 0, xa, xb);
-        int cur = 0;
         constexpr int S0 = (NSLOT + 2) / 3, S1 = (2 * NSLOT + 2) / 3;
-        for (int kt = 0; kt < KT; ++kt) {
-            const int nxt = cur ^ T::STAGE;     // two buffers
-            const unsigned km = kmask_of(kt + 2);
+        // One K step.  The buffer that is read (CUR) is a template constant, so every LDS address is a
+        // register plus an immediate; CHECK: the step loaded here (kt + 2) may reach past K, so each
+        // lane masks its chunk.  The main part of the loop needs neither: vector instructions do not
+        // overlap with matrix instructions on a SIMD, so address adds and masks there are MFMA time lost.
+        auto step = [&](int kt, auto cur_c, auto check_c) {
+            constexpr int cur = decltype(cur_c)::value ? T::STAGE : 0, nxt = cur ^ T::STAGE;
+            constexpr bool CHECK = decltype(check_c)::value;
+            unsigned km = 0u;
+            if constexpr (CHECK) km = kmask_of(kt + 2);
             // sub-step 0
             read_frags(cur, 1, ya, yb);
 #pragma unroll
@@ -308,8 +313,18 @@ __global__ __launch_bounds__(T::NT) void kc_kernel(KcParams p)
             __builtin_amdgcn_sched_barrier(0);
             mma_all(ya, yb);
             __builtin_amdgcn_sched_barrier(0);
-            cur = nxt;
+        };
+        const int whole = p.Kb / ROWB - 2;       // steps kt < whole load a step that lies wholly inside K
+        int kt = 0;
+        for (; kt + 1 < whole; kt += 2) {
+            step(kt, std::false_type{}, std::false_type{});
+            step(kt + 1, std::true_type{}, std::false_type{});
         }
+        for (; kt + 1 < KT; kt += 2) {
+            step(kt, std::false_type{}, std::true_type{});
+            step(kt + 1, std::true_type{}, std::true_type{});
+        }
+        if (kt < KT) step(kt, std::false_type{}, std::true_type{});
     }
 
     // ---- epilogue
