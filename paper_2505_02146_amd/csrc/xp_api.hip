@@ -35,6 +35,7 @@ void build_tables()
             n += dl_asym_variants(types[s], g_table[s] + n);
         }
         n += gemv_variants(types[s], g_table[s] + n);
+        n += dl_bnm_variants(types[s], g_table[s] + n);       // newest last: the older variants keep their indices
         g_count[s] = n;
     }
 }

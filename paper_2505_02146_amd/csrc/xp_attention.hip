@@ -10,6 +10,7 @@
 //   mfma      bf16 inputs, head size 64 for Q/K and for V: both contractions on the 16x16x32
 //             matrix-core instruction, laid out so that nothing has to be transposed between them
 #include "xp_internal.hpp"
+#include "xp_lds_tr.hpp"
 
 namespace xp {
 namespace {
@@ -20,9 +21,6 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void lds_void;
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr unsigned OOB = 0x80000000u;
 constexpr float LOG2E = 1.4426950408889634f;
@@ -225,16 +223,19 @@ __global__ __launch_bounds__(64 * NW) void attn_mfma_kernel(AttnParams p)
             }
     };
     // transposing fragment reads: lane a = l%16 of block g addresses key row 4g + (a >> 2) (+ 32h, + 16 for
-    // the second half of the numbering), the 8 bytes at columns 16x + 4*(a & 3) of its half-tile
+    // the second half of the numbering), the 8 bytes at columns 16x + 4*(a & 3) of its half-tile.
+    // vx[x]: the lane's byte offset within a half-tile for column block x (the swizzle makes it a
+    // different register per x); half-tile, k step and second half are instruction offsets
     const int va = lane & 15;
     const int vrow = 4 * g + (va >> 2);
-    const int vbase = vrow * KROW + 8 * (va & 1), vchunk = (va & 3) >> 1, vsw = vrow & 6;
-    auto read_v = [&](int voff, int hv, int x, int h) {
-        const char *at = vs + voff + hv * V_TILE + vbase + 32 * h * KROW + (((2 * x + vchunk) ^ vsw) << 4);
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)at);
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(at + 16 * KROW));
-        const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-        return u32x4{l2[0], l2[1], h2[0], h2[1]};
+    const int vchunk = (va & 3) >> 1, vsw = vrow & 6;
+    unsigned vx[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) vx[x] = lds_address(vs) + vrow * KROW + 8 * (va & 1) + (((2 * x + vchunk) ^ vsw) << 4);
+    auto read_v = [&](unsigned at, auto hv_c, auto h_c) {
+        constexpr int OFF = decltype(hv_c)::value * V_TILE + 32 * decltype(h_c)::value * KROW;
+        const lds_tr_u32x2 lo = lds_read_tr16_b64<OFF>(at), hi = lds_read_tr16_b64<OFF + 16 * KROW>(at);
+        return u32x4{lo[0], lo[1], hi[0], hi[1]};
     };
 
     const float c = p.scale * LOG2E;                     // scores are kept in units of log2
@@ -319,12 +320,29 @@ __global__ __launch_bounds__(64 * NW) void attn_mfma_kernel(AttnParams p)
         // place of V^T yields the row sums of the rounded probabilities, for every lane of the query
 #pragma unroll
         for (int h = 0; h < 2; ++h) total = mma(ones, pf[h], total);
+        // The V fragments come by transposing reads issued as assembly (see xp_lds_tr.hpp), group by group
+        // (one column block: 2 k steps, 4 reads), AHEAD groups in front of the MFMAs that use them; the
+        // wait before a group's MFMAs leaves the reads of the younger groups outstanding.
+        {
+            constexpr int NG = 4 * HV, AHEAD = 3;
+            u32x4 vf[NG][2];
+            auto load_group = [&](auto gi_c) {
+                constexpr int GI = decltype(gi_c)::value;
+                const unsigned at = vx[GI % 4] + cur * VT;
+                vf[GI][0] = read_v(at, std::integral_constant<int, GI / 4>{}, std::integral_constant<int, 0>{});
+                vf[GI][1] = read_v(at, std::integral_constant<int, GI / 4>{}, std::integral_constant<int, 1>{});
+            };
+            static_for<(AHEAD < NG ? AHEAD : NG)>([&](auto gi_c) { load_group(gi_c); });
+            static_for<NG>([&](auto gi_c) {
+                constexpr int GI = decltype(gi_c)::value;
+                constexpr int YOUNGER = (NG - 1 - GI < AHEAD - 1 ? NG - 1 - GI : AHEAD - 1);
+                lds_tr_wait<4 * YOUNGER>(vf[GI][0], vf[GI][1]);
 #pragma unroll
-        for (int hv = 0; hv < HV; ++hv)
-#pragma unroll
-            for (int x = 0; x < 4; ++x)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) acc[4 * hv + x] = mma(read_v(cur * VT, hv, x, h), pf[h], acc[4 * hv + x]);
+                for (int h = 0; h < 2; ++h) acc[GI] = mma(vf[GI][h], pf[h], acc[GI]);
+                __builtin_amdgcn_sched_barrier(0);       // or the scheduler collects the MFMAs behind the last wait
+                if constexpr (GI + AHEAD < NG) load_group(std::integral_constant<int, GI + AHEAD>{});
+            });
+        }
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LPS * (D - 1)));
         wg_barrier();
         cur = next;

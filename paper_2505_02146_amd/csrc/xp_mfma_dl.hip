@@ -18,6 +18,7 @@
 //     LDS and touches no memory, so the pipeline needs no conditionals.
 #include "xp_internal.hpp"
 #include "xp_epilogue.hpp"
+#include "xp_lds_tr.hpp"
 
 #include <cstdlib>
 #include <type_traits>
@@ -82,12 +83,14 @@ struct DlTile {
     static constexpr int B_BASE = NSA * A_BYTES;                   // the B ring follows the A ring
     static constexpr int LDS = NSA * A_BYTES + NS * B_BYTES;
     // loads of this wave that may still be in flight when the loads of the next K step must have landed
-    static constexpr int PENDING = ASYM ? IA + (NS - 2) * (IA + IB) : (NS - 2) * (IA + IB);
+    static constexpr bool B_DEEP = NS_ > NSA_;           // the extra buffer goes to B (whose loads then are the ones issued last)
+    static constexpr int NSMIN = NS_ < NSA_ ? NS_ : NSA_;
+    static constexpr int PENDING = ASYM ? (B_DEEP ? IB : IA) + (NSMIN - 2) * (IA + IB) : (NS - 2) * (IA + IB);
     static_assert(RB == 64 || RB == 128, "row bytes");
     static_assert(MF == 32 || MF == 16, "MFMA shape");
     static_assert(WTM % MF == 0 && WTN % MF == 0, "wave sub-tile must be whole MFMA blocks");
     static_assert(PH >= 1, "a K step must hold at least one MFMA sub-step");
-    static_assert(NS >= 2 && NSA >= NS && NSA <= NS + 1 && PENDING <= 63, "ring depths; vmcnt is a 6-bit counter");
+    static_assert(NSMIN >= 2 && NSA <= NS + 1 && NS <= NSA + 1 && PENDING <= 63, "ring depths; vmcnt is a 6-bit counter");
     static_assert(!ASYM || !SPREAD_, "spread issue is for equal ring depths");
     static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
     static_assert(!SPREAD || NS >= 3, "with two buffers the loads of a step must all be issued at its start");
@@ -101,6 +104,11 @@ struct DlTile {
 // that the 16 fragment reads of every pass fall into 16 different 16-byte bank groups
 // (SQ_LDS_BANK_CONFLICT = 0 in the kernels).  Only row bits 0..3 are used, so the term is the
 // same for every 16-row block of a tile.
+// B along N (MODE 3 of dl_body): chunk swizzle of a k row.  A transposing read touches the 16 rows
+// 8g + q (+4), g, q = 0..3, 32 bytes each; all rows start in the same bank, so the term, even and
+// below 16, takes 8 different values on them (each twice: the 512 bytes of a read need two cycles anyway).
+__device__ __forceinline__ int bnm_swz(int kr) { return ((kr & 3) | (((kr >> 3) & 1) << 2)) << 1; }
+
 template <int RB, int MF> __device__ __forceinline__ int swz(int row)
 {
     if constexpr (RB == 128 && MF == 32) return (row & 7) ^ ((row >> 3) & 1);
@@ -161,7 +169,15 @@ template <> struct Acc<true, 16> {
 template <bool INT8, class T, int MODE>
 __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, int m_base, int m_end, int tiles_m)
 {
-    constexpr bool CONV = MODE != 0, PLANAR = MODE == 2;
+    constexpr bool CONV = MODE == 1 || MODE == 2, PLANAR = MODE == 2;
+    // MODE 3: GEMM whose B is contiguous along N (row-major B, the usual layout of a framework's weights
+    // and activations).  Its tile lies in LDS as it lies in memory -- one k per row of BN columns, filled
+    // by the same direct-to-LDS loads -- and a fragment (8 consecutive k of one column) is gathered by the
+    // transposing LDS read (ds_read_b64_tr_b16: in a block of 16 lanes, lane i receives as value j the
+    // element i&3 of the 8 bytes addressed by lane 4j + (i>>2)); two of them per fragment.
+    constexpr bool BNM = MODE == 3;
+    static_assert(!BNM || (T::MF == 16 && T::RB == 128 && !INT8), "B along N: bf16, 16x16x32 blocks, 64 k per step");
+    constexpr int RBN = T::BN * 2;                        // BNM: bytes of one k row of the B tile
     using AccT = typename Acc<INT8, T::MF>::type;
     constexpr int RB = T::RB, MF = T::MF;
     constexpr int NACC = MF == 32 ? 16 : 4;           // accumulator registers per lane and block
@@ -194,8 +210,11 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         ra = make_rsrc(p.A + batch * p.strideA_b + (long long)m0 * p.lda_b,
                        (unsigned)((long long)(rows_a - 1) * p.lda_b + p.Kb));
     }
-    rb = make_rsrc(p.B + batch * p.strideB_b + (long long)n0 * p.ldb_b,
-                   (unsigned)((long long)(rows_b - 1) * p.ldb_b + p.Kb));
+    if constexpr (BNM)                                    // ldb_b: bytes from one k row to the next
+        rb = make_rsrc(p.B + batch * p.strideB_b + (long long)n0 * 2, (unsigned)((long long)(p.Kb / 2 - 1) * p.ldb_b + (long long)rows_b * 2));
+    else
+        rb = make_rsrc(p.B + batch * p.strideB_b + (long long)n0 * p.ldb_b,
+                       (unsigned)((long long)(rows_b - 1) * p.ldb_b + p.Kb));
 
     // load slots: slot i of this wave fills the 1024 LDS bytes of row block (wave + i*NWAVE);
     // lane l lands at row l/CPR, position l%CPR, and fetches the chunk that belongs there
@@ -228,9 +247,30 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     }
 #pragma unroll
     for (int i = 0; i < T::IB; ++i) {
-        const int row = (wave + i * T::NWAVE) * T::RPI + lane / T::CPR;
-        b_cb[i] = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
-        b_off_g[i] = (unsigned)(row * p.ldb_b) + b_cb[i];
+        if constexpr (BNM) {
+            // a wave-level load fills 1024 LDS bytes = 1024 / RBN k rows; the lane at chunk position pc of
+            // k row kr fetches chunk pc ^ bnm_swz(kr) of that row (a chunk: 8 columns)
+            const int kr = (wave + i * T::NWAVE) * (1024 / RBN) + lane / (RBN / 16);
+            const int chunk = (lane % (RBN / 16)) ^ bnm_swz(kr);
+            b_cb[i] = kr * 2;                              // so that the end-of-K test (kb + b_cb >= Kb) means k >= K
+            b_off_g[i] = n0 + chunk * 8 < p.N ? (unsigned)(kr * p.ldb_b) + (chunk << 4) : OOB;
+        } else {
+            const int row = (wave + i * T::NWAVE) * T::RPI + lane / T::CPR;
+            b_cb[i] = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
+            b_off_g[i] = (unsigned)(row * p.ldb_b) + b_cb[i];
+        }
+    }
+    // BNM fragment reads: lane a = l%16 of block g = l/16 addresses k row 8g + (a >> 2) (+ 32 per sub-step,
+    // + 4 for the second read), the 8 bytes at columns 16j + 4*(a & 3) of the wave's column range
+    const unsigned lds_base = lds_address(lds);
+    int fbn[BNM ? T::NI : 1];
+    if constexpr (BNM) {
+        const int a16 = lane & 15, kr = 8 * (lane >> 4) + (a16 >> 2);
+#pragma unroll
+        for (int j = 0; j < T::NI; ++j) {
+            const int chunk = (wn * T::WTN + 16 * j) / 8 + ((a16 & 3) >> 1);
+            fbn[j] = kr * RBN + ((chunk ^ bnm_swz(kr)) << 4) + 8 * (a16 & 1);
+        }
     }
 
     // fragment reads: lane l reads row l % MF of an MF-row block, chunk (64/MF)*kk + l / MF
@@ -304,7 +344,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 if (kb + b_cb[i] >= p.Kb) off = OOB;
             }
             lds_void *dst = (lds_void *)(lds + b_off + (wave + i * T::NWAVE) * 1024);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, dst, 16, off, kb, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, dst, 16, off, BNM ? (int)((unsigned)kt * (RB / 2) * (unsigned)p.ldb_b) : kb, 0, 0);
         }
     };
     // loads [lo, hi) of the IA + IB that one K step issues when both rings have the same depth
@@ -313,12 +353,39 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         issue_b(kt, b_off, lo > T::IA ? lo - T::IA : 0, hi - T::IA, check_c);
     };
     auto read_frags = [&](int a_off, int b_off, int kk, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
+        if constexpr (BNM) {
+            // every fragment read of this mode is assembly (see xp_lds_tr.hpp): offsets are constants
+            // (a K step has two sub-steps here), the waits are mma_all's
+            const unsigned a_at = lds_base + a_off + fa[kk];
+            static_for<T::MI>([&](auto i_c) {
+                constexpr int I = decltype(i_c)::value;
+                af[I] = lds_read_b128<I * MF * RB>(a_at);
+            });
 #pragma unroll
-        for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(lds + a_off + fa[kk] + i * MF * RB);
+            for (int j = 0; j < T::NI; ++j) {
+                const unsigned at = lds_base + b_off + fbn[j];
+                lds_tr_u32x2 lo, hi;
+                if (kk == 0) { lo = lds_read_tr16_b64<0>(at); hi = lds_read_tr16_b64<4 * RBN>(at); }
+                else { lo = lds_read_tr16_b64<32 * RBN>(at); hi = lds_read_tr16_b64<36 * RBN>(at); }
+                bf[j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            }
+        } else {
 #pragma unroll
-        for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + b_off + fb[kk] + j * MF * RB);
+            for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(lds + a_off + fa[kk] + i * MF * RB);
+#pragma unroll
+            for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + b_off + fb[kk] + j * MF * RB);
+        }
     };
-    auto mma_all = [&](const u32x4 (&af)[T::MI], const u32x4 (&bf)[T::NI]) {
+    auto mma_all = [&](u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
+        // BNM: the newest fragment set (read one sub-step ahead of its use, T::MI + 2 * T::NI reads) may
+        // still be on its way, everything older must have come back
+        if constexpr (BNM) {
+            lds_wait<(T::MI + 2 * T::NI < 15 ? T::MI + 2 * T::NI : 15)>();
+#pragma unroll
+            for (int i = 0; i < T::MI; ++i) lds_tie(af[i]);
+#pragma unroll
+            for (int j = 0; j < T::NI; ++j) lds_tie(bf[j]);
+        }
 #pragma unroll
         for (int i = 0; i < T::MI; ++i)
 #pragma unroll
@@ -336,11 +403,13 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     if (KT > 0) {
         u32x4 xa[T::MI], xb[T::NI], ya[T::MI], yb[T::NI];     // fragment sets of even / odd sub-steps
         if constexpr (T::ASYM) {
-            // step j issues B(j+NS-1) and then A(j+NSA-1); the steps before the first one do the same
+            // step j issues B(j+NS-1) and A(j+NSA-1), the deeper ring's last; the steps before the first one do the same
+            constexpr int DEEP = T::B_DEEP ? T::NS : T::NSA;
 #pragma unroll
-            for (int j = -(T::NSA - 1); j < 0; ++j) {
-                if (j + T::NS - 1 >= 0) issue_b(j + T::NS - 1, T::B_BASE + (j + T::NS - 1) * T::B_BYTES, 0, T::IB, std::true_type{});
-                issue_a(j + T::NSA - 1, (j + T::NSA - 1) * T::A_BYTES, 0, T::IA, std::true_type{});
+            for (int j = -(DEEP - 1); j < 0; ++j) {
+                if (!T::B_DEEP && j + T::NS - 1 >= 0) issue_b(j + T::NS - 1, T::B_BASE + (j + T::NS - 1) * T::B_BYTES, 0, T::IB, std::true_type{});
+                if (j + T::NSA - 1 >= 0) issue_a(j + T::NSA - 1, (j + T::NSA - 1) * T::A_BYTES, 0, T::IA, std::true_type{});
+                if (T::B_DEEP) issue_b(j + T::NS - 1, T::B_BASE + (j + T::NS - 1) * T::B_BYTES, 0, T::IB, std::true_type{});
             }
         } else {
 #pragma unroll
@@ -359,8 +428,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             const int nxt_b = cur_b + T::B_BYTES == B_END ? T::B_BASE : cur_b + T::B_BYTES;
             // loads go into the buffers read in step kt-1
             if constexpr (T::ASYM) {
-                issue_b(kt + T::NS - 1, fill_b, 0, T::IB, check_c);
+                if constexpr (!T::B_DEEP) issue_b(kt + T::NS - 1, fill_b, 0, T::IB, check_c);
                 issue_a(kt + T::NSA - 1, fill_a, 0, T::IA, check_c);
+                if constexpr (T::B_DEEP) issue_b(kt + T::NS - 1, fill_b, 0, T::IB, check_c);
             } else if constexpr (!T::SPREAD) {
                 issue(kt + T::NS - 1, fill_a, fill_b, 0, IT, check_c);
             }
@@ -629,7 +699,52 @@ double kBfDlTwoHeights_cost(const Problem &q) { return dl_cost<TwoHi>(q, 0.49); 
 const Variant kBfDlTwoHeights = {"bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 3(A)+2(B) direct-to-lds mfma16",
                                  kBfDlTwoHeights_can, kBfDlTwoHeights_launch, kBfDlTwoHeights_cost};
 
+// ---- B contiguous along N (MODE 3 of dl_body): bf16 GEMM and batched GEMM with a row-major B
+
+bool dl_bnm_can_run(const Problem &q, int BM)
+{
+    if (q.in_type != XP_BF16 || q.conv || q.c_plane) return false;
+    if (q.K <= 0 || q.K % 8 != 0 || q.N % 8 != 0) return false;          // whole 16-byte chunks of A rows and of B rows
+    if (q.M > 0x7fffffffLL || q.N > 0x7fffffffLL || q.batch > 65535) return false;
+    if (q.b_sn != 1 || (q.b_sk * 2) % 16 != 0 || ((uintptr_t)q.B % 16) != 0 || (q.strideB * 2) % 16 != 0) return false;
+    if ((q.K + 256) * q.b_sk * 2 >= 0x7fffffffLL) return false;          // the K position of a step travels as a 32-bit byte offset
+    if (q.a_sk != 1 || (q.a_sm * 2) % 16 != 0 || ((uintptr_t)q.A % 16) != 0 || (q.strideA * 2) % 16 != 0) return false;
+    if ((BM - 1) * q.a_sm * 2 + q.K * 2 >= 0x7fffffffLL) return false;
+    return true;
+}
+
+template <class T>
+hipError_t dl_bnm_launch(const Problem &q)
+{
+    static_assert(T::BN * 2 <= 1024 && 1024 % (T::BN * 2) == 0 && T::BNP == T::BN, "a wave-level load fills whole k rows of the B tile");
+    DlParams p = dl_params<false, T>(q);
+    p.ldb_b = q.b_sk * 2;                                  // bytes from one k row of B to the next
+    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)q.batch);
+    hipLaunchKernelGGL((dl_kernel<false, T, 3>), grid, dim3(T::NT), 0, q.stream, p);
+    return hipGetLastError();
+}
+
+#define XP_DL_BNM_VARIANT(NAME, BM, BN, WM, WN, NSA, NSB, OCC, EFF)                                                         \
+    typedef DlTile<BM, BN, WM, WN, NSB, 128, false, OCC, 16, false, NSA> NAME##_tile;                                     \
+    bool NAME##_can(const Problem &q) { return dl_bnm_can_run(q, BM); }                                                   \
+    hipError_t NAME##_launch(const Problem &q) { return dl_bnm_launch<NAME##_tile>(q); }                                  \
+    double NAME##_cost(const Problem &q) { return dl_cost<NAME##_tile>(q, EFF); }                                         \
+    const Variant NAME = {"bf16 " #BM "x" #BN "x128B waves " #WM "x" #WN " ring " #NSA "(A)+" #NSB "(B) direct-to-lds, B along N by transposing reads, mfma16", \
+                          NAME##_can, NAME##_launch, NAME##_cost};
+
+XP_DL_BNM_VARIANT(kBfBnm256x256a3, 256, 256, 2, 4, 3, 2, 1, 0.50)
+XP_DL_BNM_VARIANT(kBfBnm256x256, 256, 256, 2, 4, 2, 2, 1, 0.48)
+XP_DL_BNM_VARIANT(kBfBnm256x256b3, 256, 256, 2, 4, 2, 3, 1, 0.50)
+XP_DL_BNM_VARIANT(kBfBnm128x128, 128, 128, 2, 2, 2, 2, 2, 0.32)
+
 }  // namespace
+
+int dl_bnm_variants(xp_dtype in_type, const Variant **out)
+{
+    if (in_type != XP_BF16) return 0;
+    out[0] = &kBfBnm256x256a3; out[1] = &kBfBnm256x256; out[2] = &kBfBnm256x256b3; out[3] = &kBfBnm128x128;
+    return 4;
+}
 
 // Registered after every other family so that the older variants keep their indices.
 int dl_asym_variants(xp_dtype in_type, const Variant **out)

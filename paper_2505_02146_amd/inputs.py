@@ -126,6 +126,12 @@ def workload(name: str, seed: int = 0) -> dict:
         return dict(op="gemm", dtype="bf16", M=M, N=N, K=K, a_layout="row", b_layout="col",
                     A=to_bf16_bits(normal((M, K), seed, TID_A)),
                     B=to_bf16_bits(normal((N, K), seed, TID_B)))
+    if name == "gemm_bf16_4096_rowb":
+        # the same product with B stored row-major (K x N, N contiguous), the layout of C = A @ B in a framework
+        M = N = K = 4096
+        return dict(op="gemm", dtype="bf16", M=M, N=N, K=K, a_layout="row", b_layout="row",
+                    A=to_bf16_bits(normal((M, K), seed, TID_A)),
+                    B=to_bf16_bits(normal((K, N), seed, TID_B)))
     if name == "gemm_i8_4096x4096x8192":
         M, N, K = 4096, 4096, 8192
         return dict(op="gemm", dtype="i8", M=M, N=N, K=K, a_layout="row", b_layout="col",
@@ -176,7 +182,7 @@ def workload(name: str, seed: int = 0) -> dict:
 WORKLOADS = ("gemm_f32_256", "gemm_bf16_4096", "gemm_i8_4096x4096x8192",
              "bgemm_bf16_qk", "bgemm_bf16_pv", "conv_bf16_56")
 # operators beyond the GEMM / convolution set, each served by its own entry point
-EXTRA_WORKLOADS = ("attention_bf16_512", "attention_bf16_2048_d128", "gemv_bf16_8192")
+EXTRA_WORKLOADS = ("attention_bf16_512", "attention_bf16_2048_d128", "gemv_bf16_8192", "gemm_bf16_4096_rowb")
 
 
 # A detection-encoder layer's deformable attention: the queries are the pixels of the four feature
