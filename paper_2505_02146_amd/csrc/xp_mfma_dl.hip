@@ -352,29 +352,42 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         issue_a(kt, a_off, lo, hi < T::IA ? hi : T::IA, check_c);
         issue_b(kt, b_off, lo > T::IA ? lo - T::IA : 0, hi - T::IA, check_c);
     };
-    auto read_frags = [&](int a_off, int b_off, int kk, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
-        if constexpr (BNM) {
-            // every fragment read of this mode is assembly (see xp_lds_tr.hpp): offsets are constants
-            // (a K step has two sub-steps here), the waits are mma_all's
-            const unsigned a_at = lds_base + a_off + fa[kk];
-            static_for<T::MI>([&](auto i_c) {
-                constexpr int I = decltype(i_c)::value;
-                af[I] = lds_read_b128<I * MF * RB>(a_at);
-            });
+    // BNM: every fragment read is assembly (see xp_lds_tr.hpp): offsets are instruction constants, the waits
+    // are mma_all's.  AO / BO: byte offsets of the A / B buffer as constants (the unrolled main loop), or -1:
+    // taken from a_off / b_off at run time (one vector addition per address register).  An offset field holds
+    // 16 bits; buffers further up are reached from a second set of address registers 64 KB higher.
+    constexpr bool A_FAR = BNM && (T::NSA - 1) * T::A_BYTES + (T::MI - 1) * MF * RB >= 65536;
+    constexpr bool B_FAR = BNM && (T::NS - 1) * T::B_BYTES + 36 * RBN >= 65536;
+    unsigned fa_far[A_FAR ? T::PH : 1], fbn_far[B_FAR ? T::NI : 1];
+    if constexpr (A_FAR)
+        for (int kk = 0; kk < T::PH; ++kk) fa_far[kk] = lds_base + fa[kk] + 65536;
+    if constexpr (B_FAR)
+        for (int j = 0; j < T::NI; ++j) fbn_far[j] = lds_base + T::B_BASE + fbn[j] + 65536;
+    auto read_frags_bnm = [&](auto ao_c, auto bo_c, auto kk_c, int a_off, int b_off, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
+        constexpr int AO = decltype(ao_c)::value, BO = decltype(bo_c)::value, KK = decltype(kk_c)::value;
+        constexpr bool AFAR = AO >= 0 && AO + (T::MI - 1) * MF * RB >= 65536;
+        constexpr int AIMM = AO < 0 ? 0 : (AFAR ? AO - 65536 : AO);
+        const unsigned a_at = AO < 0 ? lds_base + a_off + fa[KK] : (AFAR ? fa_far[A_FAR ? KK : 0] : lds_base + fa[KK]);
+        static_for<T::MI>([&](auto i_c) {
+            constexpr int I = decltype(i_c)::value;
+            af[I] = lds_read_b128<AIMM + I * MF * RB>(a_at);
+        });
+        constexpr int BREL = BO < 0 ? 0 : BO - T::B_BASE + KK * 32 * RBN;
+        constexpr bool BFAR = BREL + 4 * RBN >= 65536;
+        constexpr int BIMM = BFAR ? BREL - 65536 : BREL;
 #pragma unroll
-            for (int j = 0; j < T::NI; ++j) {
-                const unsigned at = lds_base + b_off + fbn[j];
-                lds_tr_u32x2 lo, hi;
-                if (kk == 0) { lo = lds_read_tr16_b64<0>(at); hi = lds_read_tr16_b64<4 * RBN>(at); }
-                else { lo = lds_read_tr16_b64<32 * RBN>(at); hi = lds_read_tr16_b64<36 * RBN>(at); }
-                bf[j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(lds + a_off + fa[kk] + i * MF * RB);
-#pragma unroll
-            for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + b_off + fb[kk] + j * MF * RB);
+        for (int j = 0; j < T::NI; ++j) {
+            const unsigned at = BO < 0 ? lds_base + b_off + KK * 32 * RBN + fbn[j]
+                                       : (BFAR ? fbn_far[B_FAR ? j : 0] : lds_base + T::B_BASE + fbn[j]);
+            const lds_tr_u32x2 lo = lds_read_tr16_b64<BIMM>(at), hi = lds_read_tr16_b64<BIMM + 4 * RBN>(at);
+            bf[j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
         }
+    };
+    auto read_frags = [&](int a_off, int b_off, int kk, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
+#pragma unroll
+        for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(lds + a_off + fa[kk] + i * MF * RB);
+#pragma unroll
+        for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + b_off + fb[kk] + j * MF * RB);
     };
     auto mma_all = [&](u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
         // BNM: the newest fragment set (read one sub-step ahead of its use, T::MI + 2 * T::NI reads) may
@@ -419,64 +432,101 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         __builtin_amdgcn_s_barrier();
         // fragment sets alternate between sub-steps; `odd` says which set holds the sub-step that
         // is multiplied next (only for PH == 1 does it change from K step to K step)
-        read_frags(0, T::B_BASE, 0, xa, xb);
+        typedef std::integral_constant<int, -1> RunTime;
+        typedef std::integral_constant<int, 0> Zero;
+        typedef std::integral_constant<int, 1> One;
+        if constexpr (BNM) read_frags_bnm(Zero{}, std::integral_constant<int, T::B_BASE>{}, Zero{}, 0, 0, xa, xb);
+        else read_frags(0, T::B_BASE, 0, xa, xb);
         int cur_a = 0, cur_b = T::B_BASE;
         int fill_a = (T::NSA - 1) * T::A_BYTES, fill_b = T::B_BASE + (T::NS - 1) * T::B_BYTES;
-        auto step = [&](int kt, auto odd_in, auto check_c) {
+        // POS >= 0: the step's position in the rings as a constant (the step runs POS steps after one that
+        // found both rings at their first buffers): every LDS offset becomes an instruction constant and the
+        // run-time ring state is neither read nor advanced.  POS < 0: the state variables above.
+        auto step = [&](int kt, auto odd_in, auto check_c, auto pos_c) {
             constexpr bool ODD = decltype(odd_in)::value;   // set multiplied in sub-step 0: false = X, true = Y
-            const int nxt_a = cur_a + T::A_BYTES == A_END ? 0 : cur_a + T::A_BYTES;
-            const int nxt_b = cur_b + T::B_BYTES == B_END ? T::B_BASE : cur_b + T::B_BYTES;
+            constexpr int POS = decltype(pos_c)::value;
+            constexpr int CA = POS < 0 ? -1 : (POS % T::NSA) * T::A_BYTES, NA = POS < 0 ? -1 : ((POS + 1) % T::NSA) * T::A_BYTES;
+            constexpr int CB = POS < 0 ? -1 : T::B_BASE + (POS % T::NS) * T::B_BYTES;
+            constexpr int NB = POS < 0 ? -1 : T::B_BASE + ((POS + 1) % T::NS) * T::B_BYTES;
+            const int nxt_a = POS >= 0 ? NA : (cur_a + T::A_BYTES == A_END ? 0 : cur_a + T::A_BYTES);
+            const int nxt_b = POS >= 0 ? NB : (cur_b + T::B_BYTES == B_END ? T::B_BASE : cur_b + T::B_BYTES);
+            const int now_a = POS >= 0 ? CA : cur_a, now_b = POS >= 0 ? CB : cur_b;
             // loads go into the buffers read in step kt-1
+            const int into_a = POS >= 0 ? ((POS + T::NSA - 1) % T::NSA) * T::A_BYTES : fill_a;
+            const int into_b = POS >= 0 ? T::B_BASE + ((POS + T::NS - 1) % T::NS) * T::B_BYTES : fill_b;
             if constexpr (T::ASYM) {
-                if constexpr (!T::B_DEEP) issue_b(kt + T::NS - 1, fill_b, 0, T::IB, check_c);
-                issue_a(kt + T::NSA - 1, fill_a, 0, T::IA, check_c);
-                if constexpr (T::B_DEEP) issue_b(kt + T::NS - 1, fill_b, 0, T::IB, check_c);
+                if constexpr (!T::B_DEEP) issue_b(kt + T::NS - 1, into_b, 0, T::IB, check_c);
+                issue_a(kt + T::NSA - 1, into_a, 0, T::IA, check_c);
+                if constexpr (T::B_DEEP) issue_b(kt + T::NS - 1, into_b, 0, T::IB, check_c);
             } else if constexpr (!T::SPREAD) {
-                issue(kt + T::NS - 1, fill_a, fill_b, 0, IT, check_c);
+                issue(kt + T::NS - 1, into_a, into_b, 0, IT, check_c);
             }
-#pragma unroll
-            for (int ph = 0; ph < T::PH - 1; ++ph) {
-                if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill_a, fill_b, ph * IT / T::PH, (ph + 1) * IT / T::PH, check_c);
-                const bool cur_is_y = ((ph & 1) != 0) != ODD;
-                if (cur_is_y) read_frags(cur_a, cur_b, ph + 1, xa, xb);
-                else read_frags(cur_a, cur_b, ph + 1, ya, yb);
+            if constexpr (BNM) {
+                // two sub-steps: the second one's fragments (set Y) are read while the first is multiplied
+                static_assert(T::PH == 2 && !ODD && !T::SPREAD, "B along N: two sub-steps per K step");
+                read_frags_bnm(std::integral_constant<int, CA>{}, std::integral_constant<int, CB>{}, One{}, now_a, now_b, ya, yb);
                 __builtin_amdgcn_sched_barrier(0);
-                if (cur_is_y) mma_all(ya, yb);
+                mma_all(xa, xb);
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
+                __builtin_amdgcn_s_barrier();
+                read_frags_bnm(std::integral_constant<int, NA>{}, std::integral_constant<int, NB>{}, Zero{}, nxt_a, nxt_b, xa, xb);
+                __builtin_amdgcn_sched_barrier(0);
+                mma_all(ya, yb);
+                __builtin_amdgcn_sched_barrier(0);
+            } else {
+#pragma unroll
+                for (int ph = 0; ph < T::PH - 1; ++ph) {
+                    if constexpr (T::SPREAD) issue(kt + T::NS - 1, into_a, into_b, ph * IT / T::PH, (ph + 1) * IT / T::PH, check_c);
+                    const bool cur_is_y = ((ph & 1) != 0) != ODD;
+                    if (cur_is_y) read_frags(now_a, now_b, ph + 1, xa, xb);
+                    else read_frags(now_a, now_b, ph + 1, ya, yb);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (cur_is_y) mma_all(ya, yb);
+                    else mma_all(xa, xb);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // last sub-step: its fragments were read before the barrier, the MFMAs run after it
+                constexpr bool LAST_IS_Y = (((T::PH - 1) & 1) != 0) != ODD;
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(T::SPREAD ? PENDING - (IT - (T::PH - 1) * IT / T::PH) : PENDING));
+                __builtin_amdgcn_s_barrier();
+                if constexpr (T::SPREAD) issue(kt + T::NS - 1, into_a, into_b, (T::PH - 1) * IT / T::PH, IT, check_c);
+                // sub-step 0 of the next buffers (zeros after the last step, never multiplied)
+                if constexpr (LAST_IS_Y) read_frags(nxt_a, nxt_b, 0, xa, xb);
+                else read_frags(nxt_a, nxt_b, 0, ya, yb);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (LAST_IS_Y) mma_all(ya, yb);
                 else mma_all(xa, xb);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // last sub-step: its fragments were read before the barrier, the MFMAs run after it
-            constexpr bool LAST_IS_Y = (((T::PH - 1) & 1) != 0) != ODD;
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(T::SPREAD ? PENDING - (IT - (T::PH - 1) * IT / T::PH) : PENDING));
-            __builtin_amdgcn_s_barrier();
-            if constexpr (T::SPREAD) issue(kt + T::NS - 1, fill_a, fill_b, (T::PH - 1) * IT / T::PH, IT, check_c);
-            // sub-step 0 of the next buffers (zeros after the last step, never multiplied)
-            if constexpr (LAST_IS_Y) read_frags(nxt_a, nxt_b, 0, xa, xb);
-            else read_frags(nxt_a, nxt_b, 0, ya, yb);
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (LAST_IS_Y) mma_all(ya, yb);
-            else mma_all(xa, xb);
-            __builtin_amdgcn_sched_barrier(0);
-            fill_a = cur_a;
-            fill_b = cur_b;
-            cur_a = nxt_a;
-            cur_b = nxt_b;
+            if constexpr (POS < 0) {
+                fill_a = cur_a;
+                fill_b = cur_b;
+                cur_a = nxt_a;
+                cur_b = nxt_b;
+            }
         };
         if constexpr (T::PH % 2 == 0) {
             // steps whose loads (for step kt + NS - 1, A possibly one further) are whole steps inside K
             constexpr int AHEAD = (T::NSA > T::NS ? T::NSA : T::NS) - 1;
             const int whole = p.Kb / RB - AHEAD;
             int kt = 0;
-            for (; kt < whole; ++kt) step(kt, std::false_type{}, std::false_type{});
-            for (; kt < KT; ++kt) step(kt, std::false_type{}, std::true_type{});
+            if constexpr (BNM) {
+                // the main part of the loop in rounds of ROUND steps, after which both rings are where they were
+                constexpr int ROUND = T::NSA == T::NS ? T::NS : T::NSA * T::NS;
+                for (; kt + ROUND <= whole; kt += ROUND)
+                    static_for<ROUND>([&](auto pos_c) { step(kt + decltype(pos_c)::value, std::false_type{}, std::false_type{}, pos_c); });
+            }
+            for (; kt < whole; ++kt) step(kt, std::false_type{}, std::false_type{}, RunTime{});
+            for (; kt < KT; ++kt) step(kt, std::false_type{}, std::true_type{}, RunTime{});
         } else {
             // an odd number of sub-steps per K step: the roles of the two sets swap every step
             int kt = 0;
             for (; kt + 1 < KT; kt += 2) {
-                step(kt, std::false_type{}, std::true_type{});
-                step(kt + 1, std::true_type{}, std::true_type{});
+                step(kt, std::false_type{}, std::true_type{}, RunTime{});
+                step(kt + 1, std::true_type{}, std::true_type{}, RunTime{});
             }
-            if (kt < KT) step(kt, std::false_type{}, std::true_type{});
+            if (kt < KT) step(kt, std::false_type{}, std::true_type{}, RunTime{});
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
     }
