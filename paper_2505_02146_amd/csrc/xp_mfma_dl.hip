@@ -169,15 +169,21 @@ template <> struct Acc<true, 16> {
 template <bool INT8, class T, int MODE>
 __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, int m_base, int m_end, int tiles_m)
 {
-    constexpr bool CONV = MODE == 1 || MODE == 2, PLANAR = MODE == 2;
+    constexpr bool CONV = MODE == 1 || MODE == 2 || MODE == 7 || MODE == 8, PLANAR = MODE == 2 || MODE == 8;
     // MODE 3: GEMM whose B is contiguous along N (row-major B, the usual layout of a framework's weights
     // and activations).  Its tile lies in LDS as it lies in memory -- one k per row of BN columns, filled
     // by the same direct-to-LDS loads -- and a fragment (8 consecutive k of one column) is gathered by the
     // transposing LDS read (ds_read_b64_tr_b16: in a block of 16 lanes, lane i receives as value j the
     // element i&3 of the 8 bytes addressed by lane 4j + (i>>2)); two of them per fragment.
-    constexpr bool BNM = MODE == 3;
-    static_assert(!BNM || (T::MF == 16 && T::RB == 128 && !INT8), "B along N: bf16, 16x16x32 blocks, 64 k per step");
+    // MODE 4: the same for A contiguous along M (a column-major A); MODE 5: both.  ASMR: one of them, all
+    // fragment reads are assembly.
+    // MODE 6, 7, 8: MODE 0, 1, 2 with their (plain) fragment reads as assembly too, which buys the main loop
+    // in rounds with constant ring positions (below).
+    constexpr bool BNM = MODE == 3 || MODE == 5, AMM = MODE == 4 || MODE == 5, ASMR = MODE >= 3;
+    static_assert(!ASMR || (T::MF == 16 && T::RB == 128), "assembly reads: 16x16 blocks, 128 bytes of K per step");
+    static_assert(!(AMM || BNM) || !INT8, "operand along its outer index: bf16");
     constexpr int RBN = T::BN * 2;                        // BNM: bytes of one k row of the B tile
+    constexpr int RAM = T::BM * 2;                        // AMM: bytes of one k row of the A tile
     using AccT = typename Acc<INT8, T::MF>::type;
     constexpr int RB = T::RB, MF = T::MF;
     constexpr int NACC = MF == 32 ? 16 : 4;           // accumulator registers per lane and block
@@ -206,6 +212,8 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     const int conv_bias = CONV ? (p.ph * p.W + p.pw) * p.Cin_b : 0;
     if constexpr (CONV) {
         ra = make_rsrc(p.A - conv_bias, p.in_bytes + (unsigned)conv_bias);
+    } else if constexpr (AMM) {                           // lda_b: bytes from one k row to the next
+        ra = make_rsrc(p.A + batch * p.strideA_b + (long long)m0 * 2, (unsigned)((long long)(p.Kb / 2 - 1) * p.lda_b + (long long)rows_a * 2));
     } else {
         ra = make_rsrc(p.A + batch * p.strideA_b + (long long)m0 * p.lda_b,
                        (unsigned)((long long)(rows_a - 1) * p.lda_b + p.Kb));
@@ -225,7 +233,12 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     for (int i = 0; i < T::IA; ++i) {
         const int row = (wave + i * T::NWAVE) * T::RPI + lane / T::CPR;
         a_cb[i] = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
-        if constexpr (CONV) {
+        if constexpr (AMM) {                            // as for B along N below
+            const int kr = (wave + i * T::NWAVE) * (1024 / RAM) + lane / (RAM / 16);
+            const int chunk = (lane % (RAM / 16)) ^ bnm_swz(kr);
+            a_cb[i] = kr * 2;
+            a_off_g[i] = m0 + chunk * 8 < m_end ? (unsigned)(kr * p.lda_b) + (chunk << 4) : OOB;
+        } else if constexpr (CONV) {
             const int m = m0 + row;
             a_outside[i] = -1;                          // a row past the end: every tap is outside
             a_off_g[i] = 0;
@@ -273,6 +286,16 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         }
     }
 
+    int fam[AMM ? T::MI : 1];
+    if constexpr (AMM) {
+        const int a16 = lane & 15, kr = 8 * (lane >> 4) + (a16 >> 2);
+#pragma unroll
+        for (int i = 0; i < T::MI; ++i) {
+            const int chunk = (wm * T::WTM + 16 * i) / 8 + ((a16 & 3) >> 1);
+            fam[i] = kr * RAM + ((chunk ^ bnm_swz(kr)) << 4) + 8 * (a16 & 1);
+        }
+    }
+
     // fragment reads: lane l reads row l % MF of an MF-row block, chunk (64/MF)*kk + l / MF
     const int frow = lane & (MF - 1), fch = lane / MF;
     const int fsw = swz<RB, T::MF>(frow);                      // blocks start at multiples of 16 rows
@@ -313,7 +336,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 soff = c0_b + tap_off;
             } else {
                 off = a_off_g[i];
-                soff = kb;
+                soff = AMM ? (int)((unsigned)kt * (RB / 2) * (unsigned)p.lda_b) : kb;
             }
             if constexpr (CHECK) {
                 if (kb + a_cb[i] >= p.Kb) off = OOB;
@@ -352,35 +375,58 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         issue_a(kt, a_off, lo, hi < T::IA ? hi : T::IA, check_c);
         issue_b(kt, b_off, lo > T::IA ? lo - T::IA : 0, hi - T::IA, check_c);
     };
-    // BNM: every fragment read is assembly (see xp_lds_tr.hpp): offsets are instruction constants, the waits
+    // ASMR: every fragment read is assembly (see xp_lds_tr.hpp): offsets are instruction constants, the waits
     // are mma_all's.  AO / BO: byte offsets of the A / B buffer as constants (the unrolled main loop), or -1:
     // taken from a_off / b_off at run time (one vector addition per address register).  An offset field holds
     // 16 bits; buffers further up are reached from a second set of address registers 64 KB higher.
-    constexpr bool A_FAR = BNM && (T::NSA - 1) * T::A_BYTES + (T::MI - 1) * MF * RB >= 65536;
-    constexpr bool B_FAR = BNM && (T::NS - 1) * T::B_BYTES + 36 * RBN >= 65536;
-    unsigned fa_far[A_FAR ? T::PH : 1], fbn_far[B_FAR ? T::NI : 1];
+    constexpr int A_TOP = AMM ? 36 * RAM : (T::MI - 1) * MF * RB;        // largest offset within a buffer
+    constexpr int B_TOP = BNM ? 36 * RBN : (T::NI - 1) * MF * RB;
+    constexpr int NFA = AMM ? T::MI : T::PH, NFB = BNM ? T::NI : T::PH;  // address registers per operand
+    constexpr bool A_FAR = ASMR && (T::NSA - 1) * T::A_BYTES + A_TOP >= 65536;
+    constexpr bool B_FAR = ASMR && (T::NS - 1) * T::B_BYTES + B_TOP >= 65536;
+    unsigned fa_far[A_FAR ? NFA : 1], fb_far[B_FAR ? NFB : 1];
     if constexpr (A_FAR)
-        for (int kk = 0; kk < T::PH; ++kk) fa_far[kk] = lds_base + fa[kk] + 65536;
+        for (int x = 0; x < NFA; ++x) fa_far[x] = lds_base + (AMM ? fam[AMM ? x : 0] : fa[AMM ? 0 : x]) + 65536;
     if constexpr (B_FAR)
-        for (int j = 0; j < T::NI; ++j) fbn_far[j] = lds_base + T::B_BASE + fbn[j] + 65536;
-    auto read_frags_bnm = [&](auto ao_c, auto bo_c, auto kk_c, int a_off, int b_off, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
+        for (int x = 0; x < NFB; ++x) fb_far[x] = lds_base + T::B_BASE + (BNM ? fbn[BNM ? x : 0] : fb[BNM ? 0 : x]) + 65536;
+    auto read_frags_asm = [&](auto ao_c, auto bo_c, auto kk_c, int a_off, int b_off, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
         constexpr int AO = decltype(ao_c)::value, BO = decltype(bo_c)::value, KK = decltype(kk_c)::value;
-        constexpr bool AFAR = AO >= 0 && AO + (T::MI - 1) * MF * RB >= 65536;
-        constexpr int AIMM = AO < 0 ? 0 : (AFAR ? AO - 65536 : AO);
-        const unsigned a_at = AO < 0 ? lds_base + a_off + fa[KK] : (AFAR ? fa_far[A_FAR ? KK : 0] : lds_base + fa[KK]);
-        static_for<T::MI>([&](auto i_c) {
-            constexpr int I = decltype(i_c)::value;
-            af[I] = lds_read_b128<AIMM + I * MF * RB>(a_at);
-        });
-        constexpr int BREL = BO < 0 ? 0 : BO - T::B_BASE + KK * 32 * RBN;
-        constexpr bool BFAR = BREL + 4 * RBN >= 65536;
-        constexpr int BIMM = BFAR ? BREL - 65536 : BREL;
-#pragma unroll
-        for (int j = 0; j < T::NI; ++j) {
-            const unsigned at = BO < 0 ? lds_base + b_off + KK * 32 * RBN + fbn[j]
-                                       : (BFAR ? fbn_far[B_FAR ? j : 0] : lds_base + T::B_BASE + fbn[j]);
-            const lds_tr_u32x2 lo = lds_read_tr16_b64<BIMM>(at), hi = lds_read_tr16_b64<BIMM + 4 * RBN>(at);
-            bf[j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+        // operand along K: one address register per sub-step, the blocks are offsets; operand along its
+        // outer index: one address register per block (the swizzle), the sub-step is an offset
+        constexpr int AREL = AO < 0 ? 0 : AO;
+        constexpr bool AFAR = AREL + A_TOP >= 65536;
+        constexpr int AIMM = (AFAR ? AREL - 65536 : AREL) + (AMM ? KK * 32 * RAM : 0);
+        if constexpr (AMM) {
+            static_for<T::MI>([&](auto i_c) {
+                constexpr int I = decltype(i_c)::value;
+                const unsigned at = AO < 0 ? lds_base + a_off + fam[I] : (AFAR ? fa_far[A_FAR ? I : 0] : lds_base + fam[I]);
+                const lds_tr_u32x2 lo = lds_read_tr16_b64<AIMM>(at), hi = lds_read_tr16_b64<AIMM + 4 * RAM>(at);
+                af[I] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            });
+        } else {
+            const unsigned at = AO < 0 ? lds_base + a_off + fa[KK] : (AFAR ? fa_far[A_FAR ? KK : 0] : lds_base + fa[KK]);
+            static_for<T::MI>([&](auto i_c) {
+                constexpr int I = decltype(i_c)::value;
+                af[I] = lds_read_b128<AIMM + I * MF * RB>(at);
+            });
+        }
+        constexpr int BREL = BO < 0 ? 0 : BO - T::B_BASE;
+        constexpr bool BFAR = BREL + B_TOP >= 65536;
+        constexpr int BIMM = (BFAR ? BREL - 65536 : BREL) + (BNM ? KK * 32 * RBN : 0);
+        const unsigned b_rt = lds_base + b_off;          // used with a run-time buffer offset only
+        if constexpr (BNM) {
+            static_for<T::NI>([&](auto j_c) {
+                constexpr int J = decltype(j_c)::value;
+                const unsigned at = BO < 0 ? b_rt + fbn[J] : (BFAR ? fb_far[B_FAR ? J : 0] : lds_base + T::B_BASE + fbn[J]);
+                const lds_tr_u32x2 lo = lds_read_tr16_b64<BIMM>(at), hi = lds_read_tr16_b64<BIMM + 4 * RBN>(at);
+                bf[J] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            });
+        } else {
+            const unsigned at = BO < 0 ? b_rt + fb[KK] : (BFAR ? fb_far[B_FAR ? KK : 0] : lds_base + T::B_BASE + fb[KK]);
+            static_for<T::NI>([&](auto j_c) {
+                constexpr int J = decltype(j_c)::value;
+                bf[J] = lds_read_b128<BIMM + J * MF * RB>(at);
+            });
         }
     };
     auto read_frags = [&](int a_off, int b_off, int kk, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
@@ -390,10 +436,11 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + b_off + fb[kk] + j * MF * RB);
     };
     auto mma_all = [&](u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
-        // BNM: the newest fragment set (read one sub-step ahead of its use, T::MI + 2 * T::NI reads) may
-        // still be on its way, everything older must have come back
-        if constexpr (BNM) {
-            lds_wait<(T::MI + 2 * T::NI < 15 ? T::MI + 2 * T::NI : 15)>();
+        // ASMR: the newest fragment set (read one sub-step ahead of its use) may still be on its way,
+        // everything older must have come back (the counter holds 15: beyond that, part of the newest too)
+        if constexpr (ASMR) {
+            constexpr int READS = (AMM ? 2 : 1) * T::MI + (BNM ? 2 : 1) * T::NI;
+            lds_wait<(READS < 15 ? READS : 15)>();
 #pragma unroll
             for (int i = 0; i < T::MI; ++i) lds_tie(af[i]);
 #pragma unroll
@@ -435,7 +482,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         typedef std::integral_constant<int, -1> RunTime;
         typedef std::integral_constant<int, 0> Zero;
         typedef std::integral_constant<int, 1> One;
-        if constexpr (BNM) read_frags_bnm(Zero{}, std::integral_constant<int, T::B_BASE>{}, Zero{}, 0, 0, xa, xb);
+        if constexpr (ASMR) read_frags_asm(Zero{}, std::integral_constant<int, T::B_BASE>{}, Zero{}, 0, 0, xa, xb);
         else read_frags(0, T::B_BASE, 0, xa, xb);
         int cur_a = 0, cur_b = T::B_BASE;
         int fill_a = (T::NSA - 1) * T::A_BYTES, fill_b = T::B_BASE + (T::NS - 1) * T::B_BYTES;
@@ -461,16 +508,16 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             } else if constexpr (!T::SPREAD) {
                 issue(kt + T::NS - 1, into_a, into_b, 0, IT, check_c);
             }
-            if constexpr (BNM) {
+            if constexpr (ASMR) {
                 // two sub-steps: the second one's fragments (set Y) are read while the first is multiplied
-                static_assert(T::PH == 2 && !ODD && !T::SPREAD, "B along N: two sub-steps per K step");
-                read_frags_bnm(std::integral_constant<int, CA>{}, std::integral_constant<int, CB>{}, One{}, now_a, now_b, ya, yb);
+                static_assert(T::PH == 2 && !ODD && !T::SPREAD, "assembly reads: two sub-steps per K step");
+                read_frags_asm(std::integral_constant<int, CA>{}, std::integral_constant<int, CB>{}, One{}, now_a, now_b, ya, yb);
                 __builtin_amdgcn_sched_barrier(0);
                 mma_all(xa, xb);
                 __builtin_amdgcn_sched_barrier(0);
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
                 __builtin_amdgcn_s_barrier();
-                read_frags_bnm(std::integral_constant<int, NA>{}, std::integral_constant<int, NB>{}, Zero{}, nxt_a, nxt_b, xa, xb);
+                read_frags_asm(std::integral_constant<int, NA>{}, std::integral_constant<int, NB>{}, Zero{}, nxt_a, nxt_b, xa, xb);
                 __builtin_amdgcn_sched_barrier(0);
                 mma_all(ya, yb);
                 __builtin_amdgcn_sched_barrier(0);
@@ -511,7 +558,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             constexpr int AHEAD = (T::NSA > T::NS ? T::NSA : T::NS) - 1;
             const int whole = p.Kb / RB - AHEAD;
             int kt = 0;
-            if constexpr (BNM) {
+            if constexpr (ASMR && !CONV) {
                 // the main part of the loop in rounds of ROUND steps, after which both rings are where they were
                 constexpr int ROUND = T::NSA == T::NS ? T::NS : T::NSA * T::NS;
                 for (; kt + ROUND <= whole; kt += ROUND)
@@ -661,9 +708,10 @@ int64_t two_heights_split(const Problem &q)
     return k * rows1 < q.M ? k * rows1 : q.M;
 }
 
-template <bool INT8, class T1, class T2>
+template <bool INT8, class T1, class T2, bool ASM = false>
 hipError_t dl_launch_two_heights(const Problem &q)
 {
+    constexpr int M0 = ASM ? 6 : 0;                        // the modes with assembly reads follow the plain ones
     DlParams p = dl_params<INT8, T1>(q);
     const int64_t split = two_heights_split<T1, T2>(q);
     p.m_split = (int)split;
@@ -674,12 +722,12 @@ hipError_t dl_launch_two_heights(const Problem &q)
     const dim3 grid((unsigned)(p.n1 + p.tiles_m2 * p.tiles_n), (unsigned)q.batch);
     if constexpr (T1::MF == 16 && !INT8) {
         if (q.conv && q.c_plane) {
-            hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, 2>), grid, dim3(T1::NT), 0, q.stream, p);
+            hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, M0 + 2>), grid, dim3(T1::NT), 0, q.stream, p);
             return hipGetLastError();
         }
     }
-    if (q.conv) hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, 1>), grid, dim3(T1::NT), 0, q.stream, p);
-    else hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, 0>), grid, dim3(T1::NT), 0, q.stream, p);
+    if (q.conv) hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, M0 + 1>), grid, dim3(T1::NT), 0, q.stream, p);
+    else hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, M0>), grid, dim3(T1::NT), 0, q.stream, p);
     return hipGetLastError();
 }
 
@@ -749,51 +797,136 @@ double kBfDlTwoHeights_cost(const Problem &q) { return dl_cost<TwoHi>(q, 0.49); 
 const Variant kBfDlTwoHeights = {"bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 3(A)+2(B) direct-to-lds mfma16",
                                  kBfDlTwoHeights_can, kBfDlTwoHeights_launch, kBfDlTwoHeights_cost};
 
-// ---- B contiguous along N (MODE 3 of dl_body): bf16 GEMM and batched GEMM with a row-major B
+// ---- operands contiguous along their outer index (MODE 3, 4, 5 of dl_body): bf16 GEMM and batched GEMM
+// with a row-major B, a column-major A, or both
 
-bool dl_bnm_can_run(const Problem &q, int BM)
+bool dl_outer_can_run(const Problem &q, int BM, int BN, bool amm, bool bnm)
 {
     if (q.in_type != XP_BF16 || q.conv || q.c_plane) return false;
-    if (q.K <= 0 || q.K % 8 != 0 || q.N % 8 != 0) return false;          // whole 16-byte chunks of A rows and of B rows
-    if (q.M > 0x7fffffffLL || q.N > 0x7fffffffLL || q.batch > 65535) return false;
-    if (q.b_sn != 1 || (q.b_sk * 2) % 16 != 0 || ((uintptr_t)q.B % 16) != 0 || (q.strideB * 2) % 16 != 0) return false;
-    if ((q.K + 256) * q.b_sk * 2 >= 0x7fffffffLL) return false;          // the K position of a step travels as a 32-bit byte offset
-    if (q.a_sk != 1 || (q.a_sm * 2) % 16 != 0 || ((uintptr_t)q.A % 16) != 0 || (q.strideA * 2) % 16 != 0) return false;
-    if ((BM - 1) * q.a_sm * 2 + q.K * 2 >= 0x7fffffffLL) return false;
-    return true;
+    if (q.K <= 0 || q.M > 0x7fffffffLL || q.N > 0x7fffffffLL || q.batch > 65535) return false;
+    if (((uintptr_t)q.A % 16) != 0 || ((uintptr_t)q.B % 16) != 0 || (q.strideA * 2) % 16 != 0 || (q.strideB * 2) % 16 != 0) return false;
+    // along the outer index: whole 16-byte chunks of a k row; the K position of a step travels as a 32-bit byte offset.
+    // along K: whole 16-byte chunks of a row of the operand
+    if (amm) {
+        if (q.a_sm != 1 || (q.a_sk * 2) % 16 != 0 || q.M % 8 != 0 || (q.K + 256) * q.a_sk * 2 >= 0x7fffffffLL) return false;
+    } else {
+        if (q.a_sk != 1 || (q.a_sm * 2) % 16 != 0 || q.K % 8 != 0 || (BM - 1) * q.a_sm * 2 + q.K * 2 >= 0x7fffffffLL) return false;
+    }
+    if (bnm) {
+        if (q.b_sn != 1 || (q.b_sk * 2) % 16 != 0 || q.N % 8 != 0 || (q.K + 256) * q.b_sk * 2 >= 0x7fffffffLL) return false;
+    } else {
+        if (q.b_sk != 1 || (q.b_sn * 2) % 16 != 0 || q.K % 8 != 0 || (BN - 1) * q.b_sn * 2 + q.K * 2 >= 0x7fffffffLL) return false;
+    }
+    return q.K * 2 <= 0x3fffffffLL;
 }
 
-template <class T>
-hipError_t dl_bnm_launch(const Problem &q)
+template <class T, int MODE>
+hipError_t dl_outer_launch(const Problem &q)
 {
-    static_assert(T::BN * 2 <= 1024 && 1024 % (T::BN * 2) == 0 && T::BNP == T::BN, "a wave-level load fills whole k rows of the B tile");
+    constexpr bool AMM = MODE == 4 || MODE == 5, BNM = MODE == 3 || MODE == 5;
+    static_assert(!BNM || (T::BN * 2 <= 1024 && 1024 % (T::BN * 2) == 0 && T::BNP == T::BN), "a wave-level load fills whole k rows of the B tile");
+    static_assert(!AMM || (T::BM * 2 <= 1024 && 1024 % (T::BM * 2) == 0 && T::BMP == T::BM), "a wave-level load fills whole k rows of the A tile");
     DlParams p = dl_params<false, T>(q);
-    p.ldb_b = q.b_sk * 2;                                  // bytes from one k row of B to the next
+    if (AMM) p.lda_b = q.a_sk * 2;                         // bytes from one k row to the next
+    if (BNM) p.ldb_b = q.b_sk * 2;
     const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)q.batch);
-    hipLaunchKernelGGL((dl_kernel<false, T, 3>), grid, dim3(T::NT), 0, q.stream, p);
+    hipLaunchKernelGGL((dl_kernel<false, T, MODE>), grid, dim3(T::NT), 0, q.stream, p);
     return hipGetLastError();
 }
 
-#define XP_DL_BNM_VARIANT(NAME, BM, BN, WM, WN, NSA, NSB, OCC, EFF)                                                         \
+#define XP_DL_OUTER_VARIANT(NAME, MODE, WHAT, BM, BN, WM, WN, NSA, NSB, OCC, EFF)                                          \
     typedef DlTile<BM, BN, WM, WN, NSB, 128, false, OCC, 16, false, NSA> NAME##_tile;                                     \
-    bool NAME##_can(const Problem &q) { return dl_bnm_can_run(q, BM); }                                                   \
-    hipError_t NAME##_launch(const Problem &q) { return dl_bnm_launch<NAME##_tile>(q); }                                  \
+    bool NAME##_can(const Problem &q) { return dl_outer_can_run(q, BM, BN, MODE == 4 || MODE == 5, MODE == 3 || MODE == 5); } \
+    hipError_t NAME##_launch(const Problem &q) { return dl_outer_launch<NAME##_tile, MODE>(q); }                          \
     double NAME##_cost(const Problem &q) { return dl_cost<NAME##_tile>(q, EFF); }                                         \
-    const Variant NAME = {"bf16 " #BM "x" #BN "x128B waves " #WM "x" #WN " ring " #NSA "(A)+" #NSB "(B) direct-to-lds, B along N by transposing reads, mfma16", \
+    const Variant NAME = {"bf16 " #BM "x" #BN "x128B waves " #WM "x" #WN " ring " #NSA "(A)+" #NSB "(B) direct-to-lds, " WHAT " by transposing reads, mfma16", \
                           NAME##_can, NAME##_launch, NAME##_cost};
 
-XP_DL_BNM_VARIANT(kBfBnm256x256a3, 256, 256, 2, 4, 3, 2, 1, 0.50)
-XP_DL_BNM_VARIANT(kBfBnm256x256, 256, 256, 2, 4, 2, 2, 1, 0.48)
-XP_DL_BNM_VARIANT(kBfBnm256x256b3, 256, 256, 2, 4, 2, 3, 1, 0.50)
-XP_DL_BNM_VARIANT(kBfBnm128x128, 128, 128, 2, 2, 2, 2, 2, 0.32)
+XP_DL_OUTER_VARIANT(kBfBnm256x256a3, 3, "B along N", 256, 256, 2, 4, 3, 2, 1, 0.50)
+XP_DL_OUTER_VARIANT(kBfBnm256x256, 3, "B along N", 256, 256, 2, 4, 2, 2, 1, 0.48)
+XP_DL_OUTER_VARIANT(kBfBnm256x256b3, 3, "B along N", 256, 256, 2, 4, 2, 3, 1, 0.50)
+XP_DL_OUTER_VARIANT(kBfBnm128x128, 3, "B along N", 128, 128, 2, 2, 2, 2, 2, 0.32)
+XP_DL_OUTER_VARIANT(kBfAmm256x256, 4, "A along M", 256, 256, 2, 4, 2, 2, 1, 0.48)
+XP_DL_OUTER_VARIANT(kBfAmm128x128, 4, "A along M", 128, 128, 2, 2, 2, 2, 2, 0.32)
+XP_DL_OUTER_VARIANT(kBfAmmBnm256x256, 5, "A along M and B along N", 256, 256, 2, 4, 2, 2, 1, 0.48)
+XP_DL_OUTER_VARIANT(kBfAmmBnm128x128, 5, "A along M and B along N", 128, 128, 2, 2, 2, 2, 2, 0.32)
+// half-size tiles with three buffers per ring, for shapes that 256x256 tiles cut into too few pieces
+XP_DL_OUTER_VARIANT(kBfBnm256x128, 3, "B along N", 256, 128, 4, 2, 3, 3, 1, 0.44)
+XP_DL_OUTER_VARIANT(kBfBnm128x256, 3, "B along N", 128, 256, 2, 4, 3, 3, 1, 0.44)
+XP_DL_OUTER_VARIANT(kBfAmm256x128, 4, "A along M", 256, 128, 4, 2, 3, 3, 1, 0.44)
+XP_DL_OUTER_VARIANT(kBfAmm128x256, 4, "A along M", 128, 256, 2, 4, 3, 3, 1, 0.44)
+XP_DL_OUTER_VARIANT(kBfAmmBnm256x128, 5, "A along M and B along N", 256, 128, 4, 2, 3, 3, 1, 0.44)
+XP_DL_OUTER_VARIANT(kBfAmmBnm128x256, 5, "A along M and B along N", 128, 256, 2, 4, 3, 3, 1, 0.44)
+
+// ---- the K-contiguous GEMM kernels with assembly reads (MODE 6 of dl_body).  The convolution modes 7 and 8
+// compile but spill: the unrolled rounds and the filter-tap state do not fit 256 registers together.
+
+template <bool INT8, class T>
+hipError_t dl_asm_launch(const Problem &q)
+{
+    const DlParams p = dl_params<INT8, T>(q);
+    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)q.batch);
+    if constexpr (!INT8) {
+        if (q.conv) {
+            if (q.c_plane) hipLaunchKernelGGL((dl_kernel<INT8, T, 8>), grid, dim3(T::NT), 0, q.stream, p);
+            else hipLaunchKernelGGL((dl_kernel<INT8, T, 7>), grid, dim3(T::NT), 0, q.stream, p);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((dl_kernel<INT8, T, 6>), grid, dim3(T::NT), 0, q.stream, p);
+    return hipGetLastError();
+}
+
+#define XP_DL_ASM_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NSA, NSB, OCC, EFF)                                          \
+    typedef DlTile<BM, BN, WM, WN, NSB, 128, false, OCC, 16, false, NSA> NAME##_tile;                                     \
+    bool NAME##_can(const Problem &q) { return dl_can_run_common<INT8>(q, BM, BN, 128, 16); }                             \
+    hipError_t NAME##_launch(const Problem &q) { return dl_asm_launch<INT8, NAME##_tile>(q); }                            \
+    double NAME##_cost(const Problem &q) { return dl_cost<NAME##_tile>(q, EFF); }                                         \
+    const Variant NAME = {TYPESTR " " #BM "x" #BN "x128B waves " #WM "x" #WN " ring " #NSA "(A)+" #NSB "(B) direct-to-lds, reads as assembly, mfma16", \
+                          NAME##_can, NAME##_launch, NAME##_cost};
+
+XP_DL_ASM_VARIANT(kBfAsm256x256a3, "bf16", false, 256, 256, 2, 4, 3, 2, 1, 0.55)
+XP_DL_ASM_VARIANT(kBfAsm256x256, "bf16", false, 256, 256, 2, 4, 2, 2, 1, 0.54)
+XP_DL_ASM_VARIANT(kBfAsm224x256a3, "bf16", false, 224, 256, 2, 4, 3, 2, 1, 0.50)
+XP_DL_ASM_VARIANT(kBfAsm128x128, "bf16", false, 128, 128, 2, 2, 2, 2, 2, 0.36)
+XP_DL_ASM_VARIANT(kBfAsm256x128, "bf16", false, 256, 128, 4, 2, 3, 3, 1, 0.46)
+XP_DL_ASM_VARIANT(kBfAsm128x256, "bf16", false, 128, 256, 2, 4, 3, 3, 1, 0.46)
+bool kBfAsmTwoHeights_can(const Problem &q) { return dl_can_run_common<false>(q, 224, 256, 128, 16); }
+hipError_t kBfAsmTwoHeights_launch(const Problem &q) { return dl_launch_two_heights<false, TwoHi, TwoLo, true>(q); }
+double kBfAsmTwoHeights_cost(const Problem &q) { return dl_cost<TwoHi>(q, 0.50); }
+const Variant kBfAsmTwoHeights = {"bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly, mfma16",
+                                  kBfAsmTwoHeights_can, kBfAsmTwoHeights_launch, kBfAsmTwoHeights_cost};
+XP_DL_ASM_VARIANT(kI8Asm256x256a3, "i8", true, 256, 256, 2, 4, 3, 2, 1, 0.55)
+XP_DL_ASM_VARIANT(kI8Asm128x128, "i8", true, 128, 128, 2, 2, 2, 2, 2, 0.36)
+XP_DL_ASM_VARIANT(kI8Asm256x128, "i8", true, 256, 128, 4, 2, 3, 3, 1, 0.46)
+XP_DL_ASM_VARIANT(kI8Asm128x256, "i8", true, 128, 256, 2, 4, 3, 3, 1, 0.46)
+XP_DL_ASM_VARIANT(kI8Asm256x256, "i8", true, 256, 256, 2, 4, 2, 2, 1, 0.54)
 
 }  // namespace
+
+int dl_asm_variants(xp_dtype in_type, const Variant **out)
+{
+    if (in_type == XP_BF16) {
+        const Variant *v[] = {&kBfAsm256x256a3, &kBfAsm256x256, &kBfAsm224x256a3, &kBfAsmTwoHeights, &kBfAsm128x128, &kBfAsm256x128, &kBfAsm128x256};
+        for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
+        return (int)(sizeof v / sizeof *v);
+    }
+    if (in_type == XP_I8) {
+        const Variant *v[] = {&kI8Asm256x256a3, &kI8Asm256x256, &kI8Asm128x128, &kI8Asm256x128, &kI8Asm128x256};
+        for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
+        return (int)(sizeof v / sizeof *v);
+    }
+    return 0;
+}
 
 int dl_bnm_variants(xp_dtype in_type, const Variant **out)
 {
     if (in_type != XP_BF16) return 0;
-    out[0] = &kBfBnm256x256a3; out[1] = &kBfBnm256x256; out[2] = &kBfBnm256x256b3; out[3] = &kBfBnm128x128;
-    return 4;
+    const Variant *v[] = {&kBfBnm256x256a3, &kBfBnm256x256, &kBfBnm256x256b3, &kBfBnm128x128,
+                          &kBfAmm256x256, &kBfAmm128x128, &kBfAmmBnm256x256, &kBfAmmBnm128x128,
+                          &kBfBnm256x128, &kBfBnm128x256, &kBfAmm256x128, &kBfAmm128x256, &kBfAmmBnm256x128, &kBfAmmBnm128x256};
+    for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
+    return (int)(sizeof v / sizeof *v);
 }
 
 // Registered after every other family so that the older variants keep their indices.
