@@ -346,13 +346,16 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         }
         if constexpr (CONV) {
             if (hi >= T::IA && lo < T::IA) {            // the step's A loads are all issued: advance (tap, channel offset)
+                // (scalar selects, no branch: the unrolled rounds stay one basic block)
                 c0_b += RB;
-                if (c0_b >= p.Cin_b) {
-                    c0_b = 0;
-                    ++tap;
-                    if (++tap_s == p.S) { tap_s = 0; ++tap_r; }
-                    tap_off = (tap_r * p.W + tap_s) * p.Cin_b;
-                }
+                const int wrap = c0_b >= p.Cin_b ? 1 : 0;
+                c0_b = wrap ? 0 : c0_b;
+                tap += wrap;
+                tap_s += wrap;
+                const int roll = tap_s == p.S ? 1 : 0;
+                tap_s = roll ? 0 : tap_s;
+                tap_r += roll;
+                tap_off = (tap_r * p.W + tap_s) * p.Cin_b;
             }
         }
     };
@@ -558,7 +561,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             constexpr int AHEAD = (T::NSA > T::NS ? T::NSA : T::NS) - 1;
             const int whole = p.Kb / RB - AHEAD;
             int kt = 0;
-            if constexpr (ASMR && !CONV) {
+            if constexpr (ASMR && (!CONV || T::NSA == T::NS)) {
+                // (convolution: only with equal ring depths -- the six-step round of the 3+2 ring and the filter-tap
+                // state do not fit 256 registers together, the kernel would spill)
                 // the main part of the loop in rounds of ROUND steps, after which both rings are where they were
                 constexpr int ROUND = T::NSA == T::NS ? T::NS : T::NSA * T::NS;
                 for (; kt + ROUND <= whole; kt += ROUND)
@@ -858,8 +863,7 @@ XP_DL_OUTER_VARIANT(kBfAmm128x256, 4, "A along M", 128, 256, 2, 4, 3, 3, 1, 0.44
 XP_DL_OUTER_VARIANT(kBfAmmBnm256x128, 5, "A along M and B along N", 256, 128, 4, 2, 3, 3, 1, 0.44)
 XP_DL_OUTER_VARIANT(kBfAmmBnm128x256, 5, "A along M and B along N", 128, 256, 2, 4, 3, 3, 1, 0.44)
 
-// ---- the K-contiguous GEMM kernels with assembly reads (MODE 6 of dl_body).  The convolution modes 7 and 8
-// compile but spill: the unrolled rounds and the filter-tap state do not fit 256 registers together.
+// ---- the K-contiguous kernels with assembly reads (MODE 6, 7, 8 of dl_body)
 
 template <bool INT8, class T>
 hipError_t dl_asm_launch(const Problem &q)
@@ -891,6 +895,14 @@ XP_DL_ASM_VARIANT(kBfAsm224x256a3, "bf16", false, 224, 256, 2, 4, 3, 2, 1, 0.50)
 XP_DL_ASM_VARIANT(kBfAsm128x128, "bf16", false, 128, 128, 2, 2, 2, 2, 2, 0.36)
 XP_DL_ASM_VARIANT(kBfAsm256x128, "bf16", false, 256, 128, 4, 2, 3, 3, 1, 0.46)
 XP_DL_ASM_VARIANT(kBfAsm128x256, "bf16", false, 128, 256, 2, 4, 3, 3, 1, 0.46)
+XP_DL_ASM_VARIANT(kBfAsm224x256, "bf16", false, 224, 256, 2, 4, 2, 2, 1, 0.50)
+typedef DlTile<224, 256, 2, 4, 2, 128, false, 1, 16, false, 2> TwoHi2;
+typedef DlTile<192, 256, 2, 4, 2, 128, false, 1, 16, false, 2> TwoLo2;
+bool kBfAsmTwoHeights2_can(const Problem &q) { return dl_can_run_common<false>(q, 224, 256, 128, 16); }
+hipError_t kBfAsmTwoHeights2_launch(const Problem &q) { return dl_launch_two_heights<false, TwoHi2, TwoLo2, true>(q); }
+double kBfAsmTwoHeights2_cost(const Problem &q) { return dl_cost<TwoHi2>(q, 0.50); }
+const Variant kBfAsmTwoHeights2 = {"bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 2(A)+2(B) direct-to-lds, reads as assembly, mfma16",
+                                   kBfAsmTwoHeights2_can, kBfAsmTwoHeights2_launch, kBfAsmTwoHeights2_cost};
 bool kBfAsmTwoHeights_can(const Problem &q) { return dl_can_run_common<false>(q, 224, 256, 128, 16); }
 hipError_t kBfAsmTwoHeights_launch(const Problem &q) { return dl_launch_two_heights<false, TwoHi, TwoLo, true>(q); }
 double kBfAsmTwoHeights_cost(const Problem &q) { return dl_cost<TwoHi>(q, 0.50); }
@@ -907,7 +919,8 @@ XP_DL_ASM_VARIANT(kI8Asm256x256, "i8", true, 256, 256, 2, 4, 2, 2, 1, 0.54)
 int dl_asm_variants(xp_dtype in_type, const Variant **out)
 {
     if (in_type == XP_BF16) {
-        const Variant *v[] = {&kBfAsm256x256a3, &kBfAsm256x256, &kBfAsm224x256a3, &kBfAsmTwoHeights, &kBfAsm128x128, &kBfAsm256x128, &kBfAsm128x256};
+        const Variant *v[] = {&kBfAsm256x256a3, &kBfAsm256x256, &kBfAsm224x256a3, &kBfAsmTwoHeights, &kBfAsm128x128, &kBfAsm256x128, &kBfAsm128x256,
+                              &kBfAsm224x256, &kBfAsmTwoHeights2};
         for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
         return (int)(sizeof v / sizeof *v);
     }

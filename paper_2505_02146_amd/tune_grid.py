@@ -28,16 +28,17 @@ def _time(torch, fn, n=20):
 
 
 def gemm_shapes(quick):
-    """(type, B layout, M, N, K): bf16 with both operands contiguous along K on a grid with half steps
-    (tile quantisation shows between powers of two), the other cases on powers of two."""
+    """(type, A layout, B layout, M, N, K): bf16 with both operands contiguous along K on a grid with half
+    steps (tile quantisation shows between powers of two), the other layouts and int8 on powers of two."""
     fine = (512, 2048, 8192) if quick else (256, 384, 512, 768, 1024, 1536, 2048, 3072, 4096, 6144, 8192)
     coarse = (512, 2048, 8192) if quick else (512, 1024, 2048, 4096, 8192)
     for M, N, K in itertools.product(fine, fine, (1024,) if quick else (256, 512, 1024, 2048, 4096, 8192)):
-        yield "bf16", "col", M, N, K
-    for M, N, K in itertools.product(coarse, coarse, (1024,) if quick else (256, 1024, 4096)):
-        yield "bf16", "row", M, N, K
+        yield "bf16", "row", "col", M, N, K
+    for la, lb in (("row", "row"), ("col", "col"), ("col", "row")):
+        for M, N, K in itertools.product(coarse, coarse, (1024,) if quick else (256, 1024, 4096)):
+            yield "bf16", la, lb, M, N, K
     for M, N, K in itertools.product(coarse, coarse, (2048,) if quick else (512, 2048, 8192)):
-        yield "i8", "col", M, N, K
+        yield "i8", "row", "col", M, N, K
 
 
 BATCHED = [  # batch, M, N, K, B layout
@@ -81,20 +82,21 @@ def main(argv=None) -> int:
         print(f"{what}: default v{v0} {us0:8.1f} us -> tuned v{best} {us1:8.1f} us  x{us0 / us1:.2f}  [{xp.xp_describe_config(op, kind, best)}]",
               flush=True)
 
-    for kind, b_layout, M, N, K in gemm_shapes(args.quick):
+    for kind, a_layout, b_layout, M, N, K in gemm_shapes(args.quick):
         if kind == "bf16":
-            A = torch.randn(M, K, device="cuda").bfloat16()
+            A = (torch.randn(M, K, device="cuda") if a_layout == "row" else torch.randn(K, M, device="cuda")).bfloat16()
             B = (torch.randn(N, K, device="cuda") if b_layout == "col" else torch.randn(K, N, device="cuda")).bfloat16()
             C = torch.empty(M, N, device="cuda")
         else:
-            A = torch.randint(-128, 128, (M, K), device="cuda", dtype=torch.int8)
+            A = torch.randint(-128, 128, (M, K) if a_layout == "row" else (K, M), device="cuda", dtype=torch.int8)
             B = torch.randint(-128, 128, (N, K) if b_layout == "col" else (K, N), device="cuda", dtype=torch.int8)
             C = torch.empty(M, N, device="cuda", dtype=torch.int32)
+        lda = K if a_layout == "row" else M
         ldb = K if b_layout == "col" else N
         ws = torch.empty(xp.xp_tune_workspace_bytes(M * N), dtype=torch.uint8, device="cuda")
-        call = lambda: xp.xp_gemm(M, N, K, 1.0, A, "row", K, B, b_layout, ldb, 0.0, C, "row", N)
-        tune = lambda: xp.xp_tune_gemm(M, N, K, 1.0, A, "row", K, B, b_layout, ldb, 0.0, C, "row", N, ws, reps=args.reps)
-        report(f"gemm {kind} B {b_layout} {M}x{N}x{K}", call, tune, 0, kind)
+        call = lambda: xp.xp_gemm(M, N, K, 1.0, A, a_layout, lda, B, b_layout, ldb, 0.0, C, "row", N)
+        tune = lambda: xp.xp_tune_gemm(M, N, K, 1.0, A, a_layout, lda, B, b_layout, ldb, 0.0, C, "row", N, ws, reps=args.reps)
+        report(f"gemm {kind} A {a_layout} B {b_layout} {M}x{N}x{K}", call, tune, 0, kind)
         del A, B, C, ws
     for batch, M, N, K, b_layout in BATCHED:
         A = torch.randn(batch, M, K, device="cuda").bfloat16()
