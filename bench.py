@@ -24,10 +24,12 @@ PEAK_HBM_GBS = 8000.0
 
 # Bytes per launch between the L2s and the memory fabric, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs scaled by a plain 256 MiB copy (factors 2.00 and 1.00), see
-# profiles/dl_kernel_bf16_256x256_ring3a2b_mfma16_gemm_4096.md (and, for the two-buffer variant,
+# profiles/dl_kernel_bf16_256x256_ring3a2b_asm_reads_gemm_4096.md (for the variants with compiler-issued reads
+# profiles/dl_kernel_bf16_256x256_ring3a2b_mfma16_gemm_4096.md and, for the two-buffer variant,
 # profiles/dl_kernel_bf16_256x256_mfma16_gemm_4096.md).  Keyed by kernel variant: a different
 # kernel than the profiled ones reports null.
-TRAFFIC_BYTES = {"bf16 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds mfma16": 268.7e6,
+TRAFFIC_BYTES = {"bf16 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly, mfma16": 268.7e6,
+                 "bf16 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds mfma16": 268.7e6,
                  "bf16 256x256x128B waves 2x4 ring 2 direct-to-lds mfma16": 268.6e6}
 
 
@@ -51,8 +53,8 @@ def _time_calls(torch, fn, steps, warmup):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=500)
     ap.add_argument("--only-main", action="store_true", help="skip the int8 / batched / conv side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--force-variant", type=int, default=-1,
@@ -126,7 +128,7 @@ def main() -> int:
     # ---- side measurements named by the metric
     if not args.only_main:
         side = {}
-        steps2, warm2 = max(20, args.steps // 4), 5
+        steps2, warm2 = max(20, args.steps // 4), max(5, args.warmup // 4)
         del dA, dB, dC
         w8 = inputs.workload("gemm_i8_4096x4096x8192")
         a8, b8 = dev(w8["A"].reshape(-1)), dev(w8["B"].reshape(-1))
