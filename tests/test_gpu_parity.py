@@ -101,6 +101,21 @@ def test_gemm_shapes_all_variants(xp, oracle, kind, la, lb):
         _run_gemm(xp, oracle, kind, M, N, K, la, lb, seed=M + N)
 
 
+@pytest.mark.parametrize("la,lb", [("row", "row"), ("col", "col"), ("col", "row")])
+def test_gemm_operands_along_m_or_n_padding_alpha_beta(xp, oracle, la, lb):
+    """The transposing-read kernels (operands contiguous along M / N) need extents that are multiples of 8:
+    such shapes with padded leading dimensions, alpha and beta, several tiles, a ragged end of K, a K that is
+    no multiple of 8 where no operand is K-contiguous, and a K long enough for the unrolled rounds."""
+    names = [xp.xp_describe_config(0, "bf16", v) for v in range(xp.xp_num_configs(0, "bf16"))]
+    outer = [v for v, n in enumerate(names) if "transposing reads" in n]
+    assert len(outer) >= 6
+    _run_gemm(xp, oracle, "bf16", 136, 72, 96, la, lb, lc="row", pads=(8, 16, 5), alpha=2.0, beta=3.0, integer=True, variants=outer + [-1])
+    _run_gemm(xp, oracle, "bf16", 264, 520, 200, la, lb, lc="col", pads=(24, 8, 3), alpha=-0.5, beta=0.25, variants=outer + [-1])
+    _run_gemm(xp, oracle, "bf16", 392, 136, 1544, la, lb, pads=(8, 8, 0), variants=outer + [-1])
+    if (la, lb) == ("col", "row"):
+        _run_gemm(xp, oracle, "bf16", 128, 256, 203, la, lb, variants=outer + [-1])
+
+
 @pytest.mark.parametrize("kind", ["f32", "bf16"])
 def test_gemm_integer_inputs_bit_exact(xp, oracle, kind):
     # every partial sum is an integer below 2^24: any summation order gives the same fp32 bits
