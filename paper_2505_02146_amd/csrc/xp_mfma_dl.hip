@@ -96,6 +96,18 @@ struct DlTile {
     static_assert(!SPREAD || NS >= 3, "with two buffers the loads of a step must all be issued at its start");
 };
 
+// Operand along its outer index (MODE 3-5 of dl_body): chunk swizzle of a k row of ROWB bytes.  A transposing
+// read touches the 16 rows 8g + q (+4), g, q = 0..3, 32 bytes each.  Rows of 256 bytes or more all start in
+// the same bank: the term, even and below 16, takes 8 different values on them (each twice: the 512 bytes of
+// a read need two cycles anyway).  Rows of 128 bytes alternate between the two halves of the banks and hold
+// only four 32-byte pairs: two bits, from the row bits that the alternation leaves free.
+template <int ROWB> __device__ __forceinline__ int bnm_swz(int kr)
+{
+    static_assert(ROWB == 128 || ROWB == 256 || ROWB == 512, "bytes of one k row of the tile");
+    if constexpr (ROWB == 128) return (((kr >> 1) & 1) | (((kr >> 3) & 1) << 1)) << 1;
+    else return ((kr & 3) | (((kr >> 3) & 1) << 2)) << 1;
+}
+
 // Chunk swizzle: a per-row XOR of the 16-byte chunk index.  A 128-bit LDS read is served in four
 // passes of 16 lanes over 64 four-byte banks; measured with SQ_LDS_BANK_CONFLICT on two-lane
 // probes, a pass holds the lane quads (lane/4) of equal bit parity within one half of the wave
@@ -104,11 +116,6 @@ struct DlTile {
 // that the 16 fragment reads of every pass fall into 16 different 16-byte bank groups
 // (SQ_LDS_BANK_CONFLICT = 0 in the kernels).  Only row bits 0..3 are used, so the term is the
 // same for every 16-row block of a tile.
-// B along N (MODE 3 of dl_body): chunk swizzle of a k row.  A transposing read touches the 16 rows
-// 8g + q (+4), g, q = 0..3, 32 bytes each; all rows start in the same bank, so the term, even and
-// below 16, takes 8 different values on them (each twice: the 512 bytes of a read need two cycles anyway).
-__device__ __forceinline__ int bnm_swz(int kr) { return ((kr & 3) | (((kr >> 3) & 1) << 2)) << 1; }
-
 template <int RB, int MF> __device__ __forceinline__ int swz(int row)
 {
     if constexpr (RB == 128 && MF == 32) return (row & 7) ^ ((row >> 3) & 1);
@@ -195,13 +202,22 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     // workgroup -> tile: one XCD (workgroup id mod 8) owns a run of consecutive tiles, walked in
     // groups of group_m tile-rows, so that the tiles sharing an L2 share A and B panels
     const int nb = tiles_m * p.tiles_n;
-    if ((nb & 7) == 0) bid = (bid & 7) * (nb >> 3) + (bid >> 3);
+    long long batch = blockIdx.y;
+    if ((nb & 7) == 0) {
+        bid = (bid & 7) * (nb >> 3) + (bid >> 3);
+    } else if (gridDim.y > 1 && m_base == 0 && m_end == p.M) {
+        // batched problems of a few tiles each (one tile height per launch): the tiles of a problem would be
+        // dealt to different XCDs and each L2 would fetch the problem's operands again
+        unsigned x, y;
+        xcd_batch_remap(x, y);
+        bid = (int)x;
+        batch = y;
+    }
     const int gsz = p.group_m * p.tiles_n;
     const int g = bid / gsz, first_m = g * p.group_m;
     const int gm = min(tiles_m - first_m, p.group_m);
     const int tm = first_m + (bid % gsz) % gm, tn = (bid % gsz) / gm;
     const int m0 = m_base + tm * T::BM, n0 = tn * T::BN;
-    const long long batch = blockIdx.y;
 
     const int rows_a = min(m_end - m0, T::BM), rows_b = min(p.N - n0, T::BN);
     __amdgpu_buffer_rsrc_t ra, rb;
@@ -235,7 +251,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         a_cb[i] = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
         if constexpr (AMM) {                            // as for B along N below
             const int kr = (wave + i * T::NWAVE) * (1024 / RAM) + lane / (RAM / 16);
-            const int chunk = (lane % (RAM / 16)) ^ bnm_swz(kr);
+            const int chunk = (lane % (RAM / 16)) ^ bnm_swz<RAM>(kr);
             a_cb[i] = kr * 2;
             a_off_g[i] = m0 + chunk * 8 < m_end ? (unsigned)(kr * p.lda_b) + (chunk << 4) : OOB;
         } else if constexpr (CONV) {
@@ -262,9 +278,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     for (int i = 0; i < T::IB; ++i) {
         if constexpr (BNM) {
             // a wave-level load fills 1024 LDS bytes = 1024 / RBN k rows; the lane at chunk position pc of
-            // k row kr fetches chunk pc ^ bnm_swz(kr) of that row (a chunk: 8 columns)
+            // k row kr fetches chunk pc ^ swizzle(kr) of that row (a chunk: 8 columns)
             const int kr = (wave + i * T::NWAVE) * (1024 / RBN) + lane / (RBN / 16);
-            const int chunk = (lane % (RBN / 16)) ^ bnm_swz(kr);
+            const int chunk = (lane % (RBN / 16)) ^ bnm_swz<RBN>(kr);
             b_cb[i] = kr * 2;                              // so that the end-of-K test (kb + b_cb >= Kb) means k >= K
             b_off_g[i] = n0 + chunk * 8 < p.N ? (unsigned)(kr * p.ldb_b) + (chunk << 4) : OOB;
         } else {
@@ -282,7 +298,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
 #pragma unroll
         for (int j = 0; j < T::NI; ++j) {
             const int chunk = (wn * T::WTN + 16 * j) / 8 + ((a16 & 3) >> 1);
-            fbn[j] = kr * RBN + ((chunk ^ bnm_swz(kr)) << 4) + 8 * (a16 & 1);
+            fbn[j] = kr * RBN + ((chunk ^ bnm_swz<RBN>(kr)) << 4) + 8 * (a16 & 1);
         }
     }
 
@@ -292,7 +308,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
 #pragma unroll
         for (int i = 0; i < T::MI; ++i) {
             const int chunk = (wm * T::WTM + 16 * i) / 8 + ((a16 & 3) >> 1);
-            fam[i] = kr * RAM + ((chunk ^ bnm_swz(kr)) << 4) + 8 * (a16 & 1);
+            fam[i] = kr * RAM + ((chunk ^ bnm_swz<RAM>(kr)) << 4) + 8 * (a16 & 1);
         }
     }
 
