@@ -243,16 +243,22 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     // load slots: slot i of this wave fills the 1024 LDS bytes of row block (wave + i*NWAVE);
     // lane l lands at row l/CPR, position l%CPR, and fetches the chunk that belongs there
     unsigned a_off_g[T::IA], b_off_g[T::IB];            // byte offsets of this lane's chunks in global memory
-    int a_cb[T::IA], b_cb[T::IB];                       // byte offset of the fetched chunk within the row
+    // Byte offset of the fetched chunk within the row, for the end-of-K test: a_cb0 + i * A_CB_STEP for load i.
+    // Along K the offset is the same for every load of the lane (a wave's loads are a multiple of 16 rows apart
+    // and the swizzle uses row bits 0..3 only); along the outer index the loads are whole k rows apart.
+    static_assert((T::NWAVE * T::RPI) % 16 == 0, "the loads of a lane differ in row bits above the swizzle's");
+    constexpr int A_CB_STEP = AMM ? 2 * T::NWAVE * (1024 / RAM) : 0, B_CB_STEP = BNM ? 2 * T::NWAVE * (1024 / RBN) : 0;
+    int a_cb0 = 0, b_cb0 = 0;
     int a_outside[CONV ? T::IA : 1];                    // conv: bit r*S + s set <=> tap (r, s) of this lane's pixel is padding
 #pragma unroll
     for (int i = 0; i < T::IA; ++i) {
         const int row = (wave + i * T::NWAVE) * T::RPI + lane / T::CPR;
-        a_cb[i] = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
+        const int a_cb = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
+        if (i == 0) a_cb0 = a_cb;
         if constexpr (AMM) {                            // as for B along N below
             const int kr = (wave + i * T::NWAVE) * (1024 / RAM) + lane / (RAM / 16);
             const int chunk = (lane % (RAM / 16)) ^ bnm_swz<RAM>(kr);
-            a_cb[i] = kr * 2;
+            if (i == 0) a_cb0 = kr * 2;
             a_off_g[i] = m0 + chunk * 8 < m_end ? (unsigned)(kr * p.lda_b) + (chunk << 4) : OOB;
         } else if constexpr (CONV) {
             const int m = m0 + row;
@@ -263,7 +269,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 const int op = pq / p.Q, oq = pq % p.Q;
                 const int h0 = op * p.sh - p.ph, w0 = oq * p.sw - p.pw;
                 a_off_g[i] = (unsigned)n * (unsigned)(p.H * p.W) * (unsigned)p.Cin_b +
-                             (unsigned)((h0 + p.ph) * p.W + w0 + p.pw) * (unsigned)p.Cin_b + a_cb[i];
+                             (unsigned)((h0 + p.ph) * p.W + w0 + p.pw) * (unsigned)p.Cin_b + a_cb;
                 int outside = 0;
                 for (int r = 0, t = 0; r < p.R; ++r)
                     for (int s2 = 0; s2 < p.S; ++s2, ++t)
@@ -271,7 +277,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 a_outside[i] = outside;
             }
         } else {
-            a_off_g[i] = (unsigned)(row * p.lda_b) + a_cb[i];
+            a_off_g[i] = (unsigned)(row * p.lda_b) + a_cb;
         }
     }
 #pragma unroll
@@ -281,12 +287,13 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             // k row kr fetches chunk pc ^ swizzle(kr) of that row (a chunk: 8 columns)
             const int kr = (wave + i * T::NWAVE) * (1024 / RBN) + lane / (RBN / 16);
             const int chunk = (lane % (RBN / 16)) ^ bnm_swz<RBN>(kr);
-            b_cb[i] = kr * 2;                              // so that the end-of-K test (kb + b_cb >= Kb) means k >= K
+            if (i == 0) b_cb0 = kr * 2;                    // so that the end-of-K test (kb + b_cb >= Kb) means k >= K
             b_off_g[i] = n0 + chunk * 8 < p.N ? (unsigned)(kr * p.ldb_b) + (chunk << 4) : OOB;
         } else {
             const int row = (wave + i * T::NWAVE) * T::RPI + lane / T::CPR;
-            b_cb[i] = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
-            b_off_g[i] = (unsigned)(row * p.ldb_b) + b_cb[i];
+            const int b_cb = ((lane % T::CPR) ^ swz<RB, T::MF>(row)) << 4;
+            if (i == 0) b_cb0 = b_cb;
+            b_off_g[i] = (unsigned)(row * p.ldb_b) + b_cb;
         }
     }
     // BNM fragment reads: lane a = l%16 of block g = l/16 addresses k row 8g + (a >> 2) (+ 32 per sub-step,
@@ -355,7 +362,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 soff = AMM ? (int)((unsigned)kt * (RB / 2) * (unsigned)p.lda_b) : kb;
             }
             if constexpr (CHECK) {
-                if (kb + a_cb[i] >= p.Kb) off = OOB;
+                if (kb + a_cb0 + i * A_CB_STEP >= p.Kb) off = OOB;
             }
             lds_void *dst = (lds_void *)(lds + a_off + (wave + i * T::NWAVE) * 1024);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, dst, 16, off, soff, 0, 0);
@@ -383,7 +390,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             if (i < lo || i >= hi) continue;
             unsigned off = b_off_g[i];
             if constexpr (CHECK) {
-                if (kb + b_cb[i] >= p.Kb) off = OOB;
+                if (kb + b_cb0 + i * B_CB_STEP >= p.Kb) off = OOB;
             }
             lds_void *dst = (lds_void *)(lds + b_off + (wave + i * T::NWAVE) * 1024);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, dst, 16, off, BNM ? (int)((unsigned)kt * (RB / 2) * (unsigned)p.ldb_b) : kb, 0, 0);
