@@ -74,6 +74,25 @@ def test_gemm_bf16_4096(xp, oracle):
     _sampled_gemm_check(xp, oracle, w, "bf16", c.cpu().numpy(), np.random.default_rng(0))
 
 
+@pytest.mark.parametrize("la,lb", [("row", "row"), ("col", "col"), ("col", "row")])
+def test_gemm_bf16_4096_other_layouts(xp, oracle, la, lb):
+    """The same 4096^3 product with its operands stored the other way round (row-major B, column-major A, both):
+    the library's own selection -- the transposing-read kernels -- against the same sampled rows, columns
+    and checksums."""
+    import torch
+    w = inputs.workload("gemm_bf16_4096")
+    M, N, K = w["M"], w["N"], w["K"]
+    A, B = w["A"], w["B"]                       # A: M x K, B: N x K
+    a = A if la == "row" else np.ascontiguousarray(A.T)     # col: stored K x M
+    b = B if lb == "col" else np.ascontiguousarray(B.T)     # row: stored K x N
+    c = torch.full((M, N), float("nan"), device="cuda")
+    xp.xp_gemm(M, N, K, 1.0, dev(a.reshape(-1)), la, K if la == "row" else M, dev(b.reshape(-1)), lb, K if lb == "col" else N,
+               0.0, c, "row", N, a_type="bf16", b_type="bf16")
+    name = xp.xp_describe_config(0, "bf16", xp.xp_last_config(0, "bf16"))
+    assert "transposing reads" in name, name
+    _sampled_gemm_check(xp, oracle, w, "bf16", c.cpu().numpy(), np.random.default_rng(1))
+
+
 def test_gemm_i8_4096x4096x8192(xp, oracle):
     import torch
     w = inputs.workload("gemm_i8_4096x4096x8192")
