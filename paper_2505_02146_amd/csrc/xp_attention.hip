@@ -430,14 +430,16 @@ const AttnVariant kMfma128d1 = {"bf16 attention head 128, 64 queries x 64-key st
                                 mfma_launch<1, 2, 4>};
 const AttnVariant kMfma128d2 = {"bf16 attention head 128, 64 queries x 64-key steps, prefetch 2, waves 4x1 mfma16", mfma_can_run<2>,
                                 mfma_launch<2, 2, 4>};
-// Eight waves per workgroup pay when there are at least two such workgroups per compute unit (swept: 32 x 2048^2
-// x 128 660 -> 827 TFLOP/s, 16 x 4096^2 x 128 748 -> 908, 32 x 2048^2 x 64 631 -> 701; the 96 x 512^2 x 64
-// workload, 384 workgroups of 128 queries, is 5 % slower than with 768 workgroups of 64)
-bool w8_worthwhile(const AttnProblem &q) { return q.batch * ((q.Lq + 127) / 128) >= 512; }
+// Eight waves per workgroup pay when there are enough such workgroups: two per compute unit at head size 64, one at
+// head size 128 (swept under sustained load, TFLOP/s with 8 / 4 waves: head 64 -- 32 x 2048^2 732 / 667, 192 x 512^2
+// 550 / 510, but 96 x 512^2 (384 workgroups of 128 queries) 423 / 460 and 48 x 1024^2 528 / 560; head 128 --
+// 32 x 2048^2 891 / 740, 96 x 512^2 (384) 513 / 479, 8 x 4096^2 (256) 856 / 778)
+bool w8_worthwhile_64(const AttnProblem &q) { return q.batch * ((q.Lq + 127) / 128) >= 512; }
+bool w8_worthwhile_128(const AttnProblem &q) { return q.batch * ((q.Lq + 127) / 128) >= 256; }
 const AttnVariant kMfma64w8 = {"bf16 attention head 64, 128 queries x 64-key steps, prefetch 1, waves 8x1 mfma16", mfma_can_run<1>,
-                               mfma_launch<1, 1, 8>, w8_worthwhile};
+                               mfma_launch<1, 1, 8>, w8_worthwhile_64};
 const AttnVariant kMfma128w8 = {"bf16 attention head 128, 128 queries x 64-key steps, prefetch 1, waves 8x1 mfma16", mfma_can_run<2>,
-                                mfma_launch<1, 2, 8>, w8_worthwhile};
+                                mfma_launch<1, 2, 8>, w8_worthwhile_128};
 // swept on the 96 x 512 x 512 x 64 workload: a prefetch distance of 1 is as fast as 2 (the step is bound
 // by its own dependency chain, not by load latency) and leaves more LDS free; 3 is slower
 const AttnVariant *const kBf16Table[] = {&kGeneral, &kMfma64d2, &kMfma64d1, &kMfma128d2, &kMfma128d1, &kMfma64w8, &kMfma128w8};   // the last that can run is the default

@@ -20,7 +20,7 @@ MFMA = [1, 2, 5]                                        # head size 64 (5: eight
 MFMA128 = [3, 4, 6]                                     # head size 128 (6: eight waves)
 DEFAULT = 2                                             # what the library picks for head size 64 when it can (small problems)
 DEFAULT128 = 4                                          # ... and for head size 128
-BIG128 = 6                                              # with at least 512 workgroups of 128 queries: the eight-wave kernels
+BIG128 = 6                                              # with at least 256 workgroups of 128 queries (512 at head size 64): the eight-wave kernels
 NVARIANTS = 7
 
 
