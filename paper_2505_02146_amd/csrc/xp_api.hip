@@ -13,7 +13,7 @@ namespace xp {
 
 namespace {
 
-constexpr int kMaxVariants = 64;
+constexpr int kMaxVariants = 128;                       // 58 bf16 variants at the last count; checked in build_tables
 const Variant *g_table[3][kMaxVariants];
 int g_count[3] = {0, 0, 0};
 std::once_flag g_once;
@@ -37,6 +37,7 @@ void build_tables()
         n += gemv_variants(types[s], g_table[s] + n);
         n += dl_bnm_variants(types[s], g_table[s] + n);       // newest last: the older variants keep their indices
         n += dl_asm_variants(types[s], g_table[s] + n);
+        if (n > kMaxVariants) { fprintf(stderr, "xp: variant table overflow (%d)\n", n); abort(); }
         g_count[s] = n;
     }
 }
