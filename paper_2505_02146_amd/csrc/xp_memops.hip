@@ -428,7 +428,10 @@ struct PoolParams {
 
 // one work item = one output pixel and EPC consecutive channels (VEC) or one channel.  WIN > 0: the
 // window is WIN x WIN, known at compile time, so that its loads are all issued before the first is used.
-template <bool IB, bool OB, bool VEC, int WIN>
+// OP >= 0: the reduction is known at compile time too (the windowed kernels): no selects per element, and an
+// output whose window lies inside the image combines its WIN x WIN values without any test.  The kernel is bound
+// by vector instructions, not by memory, when it tests every element for the operation and for being inside.
+template <bool IB, bool OB, bool VEC, int WIN, int OP = -1>
 __global__ __launch_bounds__(256) void pool_kernel(PoolParams p)
 {
     constexpr int EPC = VEC ? Chunk<IB>::EPC : 1;
@@ -448,9 +451,10 @@ __global__ __launch_bounds__(256) void pool_kernel(PoolParams p)
         auto take = [&](const float (&v)[EPC]) {
 #pragma unroll
             for (int e = 0; e < EPC; ++e) {
+                const int op = OP >= 0 ? OP : p.op;
                 if (inside == 0) acc[e] = v[e];
-                else if (p.op == XP_POOL_MAX) acc[e] = fmaxf(acc[e], v[e]);
-                else if (p.op == XP_POOL_MIN) acc[e] = fminf(acc[e], v[e]);
+                else if (op == XP_POOL_MAX) acc[e] = fmaxf(acc[e], v[e]);
+                else if (op == XP_POOL_MIN) acc[e] = fminf(acc[e], v[e]);
                 else acc[e] += v[e];
             }
             ++inside;
@@ -472,9 +476,28 @@ __global__ __launch_bounds__(256) void pool_kernel(PoolParams p)
                     // positions outside the image load the nearest pixel inside (never used): no branch around a load
                     fetch(min(max(h, 0), p.H - 1), min(max(x, 0), p.W - 1), v[r * WIN + s]);
                 }
+            bool all_in = true;
 #pragma unroll
-            for (int i = 0; i < WIN * WIN; ++i)
-                if (in[i]) take(v[i]);
+            for (int i = 0; i < WIN * WIN; ++i) all_in = all_in && in[i];
+            if (OP >= 0 && all_in) {
+                // the window lies inside the image (all but the border outputs)
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) {
+                    float a = v[0][e];
+#pragma unroll
+                    for (int i = 1; i < WIN * WIN; ++i) {
+                        if (OP == XP_POOL_MAX) a = fmaxf(a, v[i][e]);
+                        else if (OP == XP_POOL_MIN) a = fminf(a, v[i][e]);
+                        else a += v[i][e];
+                    }
+                    acc[e] = a;
+                }
+                inside = WIN * WIN;
+            } else {
+#pragma unroll
+                for (int i = 0; i < WIN * WIN; ++i)
+                    if (in[i]) take(v[i]);
+            }
         } else {
             for (int r = 0; r < p.R; ++r) {
                 const int h = op_ * p.sh + r - p.ph;
@@ -488,7 +511,7 @@ __global__ __launch_bounds__(256) void pool_kernel(PoolParams p)
                 }
             }
         }
-        if (p.op == XP_POOL_AVG && inside > 0) {
+        if ((OP >= 0 ? OP : p.op) == XP_POOL_AVG && inside > 0) {
             const float inv = 1.0f / (float)inside;
 #pragma unroll
             for (int e = 0; e < EPC; ++e) acc[e] *= inv;
@@ -724,7 +747,11 @@ xp_status xp_pool2d_nhwc(xp_pool_op op, int64_t N, int64_t H, int64_t W, int64_t
     const int win = (R == S && (R == 2 || R == 3) && vec) ? (int)R : 0;
 #define XP_POOL(IB, OB)                                                                             \
     do {                                                                                            \
-        if (win == 3) hipLaunchKernelGGL((pool_kernel<IB, OB, true, 3>), grid, block, 0, s, p);     \
+        if (win == 3 && p.op == XP_POOL_MAX) hipLaunchKernelGGL((pool_kernel<IB, OB, true, 3, XP_POOL_MAX>), grid, block, 0, s, p); \
+        else if (win == 3 && p.op == XP_POOL_AVG) hipLaunchKernelGGL((pool_kernel<IB, OB, true, 3, XP_POOL_AVG>), grid, block, 0, s, p); \
+        else if (win == 2 && p.op == XP_POOL_MAX) hipLaunchKernelGGL((pool_kernel<IB, OB, true, 2, XP_POOL_MAX>), grid, block, 0, s, p); \
+        else if (win == 2 && p.op == XP_POOL_AVG) hipLaunchKernelGGL((pool_kernel<IB, OB, true, 2, XP_POOL_AVG>), grid, block, 0, s, p); \
+        else if (win == 3) hipLaunchKernelGGL((pool_kernel<IB, OB, true, 3>), grid, block, 0, s, p);     \
         else if (win == 2) hipLaunchKernelGGL((pool_kernel<IB, OB, true, 2>), grid, block, 0, s, p); \
         else if (vec) hipLaunchKernelGGL((pool_kernel<IB, OB, true, 0>), grid, block, 0, s, p);     \
         else hipLaunchKernelGGL((pool_kernel<IB, OB, false, 0>), grid, block, 0, s, p);             \
