@@ -623,33 +623,32 @@ __global__ __launch_bounds__(256) void depthwise3x3_tile_kernel(DwParams p)
     const long long n = b / tiles_h;
     const int p0 = th * DW_TH, q0 = tw * DW_TW, cg0 = cb * DW_CG;
 
-    // stage the patch: rows p0 - ph .. +DW_PH, columns q0 - pw .. +DW_PW; zeros outside the image or past the last chunk
+    // stage the patch: rows p0 - ph .. +DW_PH, columns q0 - pw .. +DW_PW; zeros outside the image or past the last chunk.
+    // No branch around a load: a position outside loads the nearest chunk inside and is zeroed by a select (with
+    // branches the compiler copied the values already loaded from register to register at every join: a third
+    // of the kernel's vector instructions, and the kernel is bound by those).
     constexpr int PATCH = DW_PH * DW_PW * DW_CG, ROUNDS = (PATCH + 255) / 256;
     u32x4 staged[ROUNDS];
 #pragma unroll
     for (int it = 0; it < ROUNDS; ++it) {                  // all loads first, so that they are in flight together
-        const int i = t + it * 256;
+        const int i = min(t + it * 256, PATCH - 1);
         const int pc = i % DW_CG, col = (i / DW_CG) % DW_PW, row = i / (DW_CG * DW_PW);
         const int h = p0 - p.ph + row, x = q0 - p.pw + col;
-        staged[it] = u32x4{0u, 0u, 0u, 0u};
-        if (i < PATCH && h >= 0 && h < p.H && x >= 0 && x < p.W && cg0 + pc < cc)
-            staged[it] = *((const u32x4 *)p.x + ((n * p.H + h) * p.W + x) * cc + cg0 + pc);
+        const bool valid = h >= 0 && h < p.H && x >= 0 && x < p.W && cg0 + pc < cc;
+        const int hc = min(max(h, 0), p.H - 1), xc = min(max(x, 0), p.W - 1), cgc = min(cg0 + pc, cc - 1);
+        const u32x4 v = *((const u32x4 *)p.x + ((n * p.H + hc) * p.W + xc) * cc + cgc);
+        staged[it] = valid ? v : u32x4{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int it = 0; it < ROUNDS; ++it)
         if (t + it * 256 < PATCH) patch[t + it * 256] = staged[it];
-    // this thread's channel chunk and its 9 weight chunks
+    // this thread's channel chunk and its 9 weight chunks (a chunk past the last one computes with the last
+    // one's weights and is not stored)
     const int cg = t % DW_CG;
     const bool live_c = cg0 + cg < cc;
     float w[9][EPC];
 #pragma unroll
-    for (int k = 0; k < 9; ++k) {
-        if (live_c) Chunk<IB>::template load<false>(p.w, (long long)k * cc + cg0 + cg, w[k]);
-        else {
-#pragma unroll
-            for (int e = 0; e < EPC; ++e) w[k][e] = 0.0f;
-        }
-    }
+    for (int k = 0; k < 9; ++k) Chunk<IB>::template load<false>(p.w, (long long)k * cc + min(cg0 + cg, cc - 1), w[k]);
     __syncthreads();
     // 128 output pixels x 8 chunks over 256 threads: 4 pixels per thread
 #pragma unroll
