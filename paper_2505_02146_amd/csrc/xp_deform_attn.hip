@@ -173,7 +173,9 @@ __device__ __forceinline__ void sample_level4(const char *map, long long pitch, 
 // the fetched words blanked, so that nothing a caller left in that pixel can reach the sum.
 template <int J> __device__ __forceinline__ unsigned quad_bcast(unsigned v)
 {
-    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, J * 0x55, 0xf, 0xf, false);      // quad_perm [J,J,J,J]
+    // (the source as the fallback value too: every lane of a quad permutation has a source, and a constant there
+    // would cost a register initialisation per broadcast)
+    return (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, J * 0x55, 0xf, 0xf, true);      // quad_perm [J,J,J,J]
 }
 template <int J> __device__ __forceinline__ float quad_bcast(float v) { return __uint_as_float(quad_bcast<J>(__float_as_uint(v))); }
 
