@@ -119,12 +119,13 @@ __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void row_kernel(RowParams p)
     float v[MAXC][EPC];
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
+        // no branch around the load (a chunk past the end reads the row's last chunk and is replaced by the
+        // neutral value): at a join the compiler copies the values loaded so far from register to register
         const int ch = t + c * TPR;
-        if (live && ch < nchunks) Chunk<IN_BF16>::load(xr, ch, v[c]);
-        else {
+        const bool in = live && ch < nchunks;
+        Chunk<IN_BF16>::load(xr, min(ch, nchunks - 1), v[c]);
 #pragma unroll
-            for (int e = 0; e < EPC; ++e) v[c][e] = OP == SOFTMAX ? -INFINITY : 0.0f;
-        }
+        for (int e = 0; e < EPC; ++e) v[c][e] = in ? v[c][e] : (OP == SOFTMAX ? -INFINITY : 0.0f);
     }
     const float inv_n = 1.0f / (float)p.cols;
     float shift = 0.0f, scale = 1.0f;                      // y = (x - shift) * scale [* gamma + beta]
