@@ -167,8 +167,9 @@ constexpr int waitcnt_vm_lgkm0(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0
 // eight waves halve the LDS a query needs and let twice as many waves live on a SIMD; matrix and vector
 // instructions of different waves do not overlap on this hardware (a SIMD issues one or the other:
 // measured, the times add), so what more waves hide is the waiting -- barriers, LDS and load latency.
+// (eight waves at head size 128: two workgroups per compute unit, i.e. four waves per SIMD, need the kernel within 128 registers)
 template <int D, int HV, int NW>
-__global__ __launch_bounds__(64 * NW) void attn_mfma_kernel(AttnParams p)
+__global__ __launch_bounds__(64 * NW, (NW == 8 && HV == 2) ? 4 : 1) void attn_mfma_kernel(AttnParams p)
 {
     constexpr int NS = D + 1;
     constexpr int KT = K_TILE * HV, VT = V_TILE * HV;   // one step's K and V tiles
@@ -232,8 +233,8 @@ __global__ __launch_bounds__(64 * NW) void attn_mfma_kernel(AttnParams p)
     unsigned vx[4];
 #pragma unroll
     for (int x = 0; x < 4; ++x) vx[x] = lds_address(vs) + vrow * KROW + 8 * (va & 1) + (((2 * x + vchunk) ^ vsw) << 4);
-    auto read_v = [&](unsigned at, auto hv_c, auto h_c) {
-        constexpr int OFF = decltype(hv_c)::value * V_TILE + 32 * decltype(h_c)::value * KROW;
+    auto read_v = [&](unsigned at, auto slot_c, auto hv_c, auto h_c) {
+        constexpr int OFF = decltype(slot_c)::value * VT + decltype(hv_c)::value * V_TILE + 32 * decltype(h_c)::value * KROW;
         const lds_tr_u32x2 lo = lds_read_tr16_b64<OFF>(at), hi = lds_read_tr16_b64<OFF + 16 * KROW>(at);
         return u32x4{lo[0], lo[1], hi[0], hi[1]};
     };
@@ -255,10 +256,14 @@ __global__ __launch_bounds__(64 * NW) void attn_mfma_kernel(AttnParams p)
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LPS * (D - 1)));   // tile 0 (and the queries) have landed
     wg_barrier();
 
-    int cur = 0;                                         // ring slot of the tile being multiplied
-    auto step = [&](int t) {
+    // One key tile.  CUR: the ring slot of the tile, a constant (the loop below walks the ring in whole turns), so
+    // that every LDS offset is an instruction constant; MASK: the tile may reach past the last key (only the last
+    // tile can).  Both used to be decided at run time in every step: about 60 of its 160 vector instructions,
+    // and vector instructions are time the matrix pipe stands still.
+    auto step = [&](int t, auto mask_c, auto cur_c) {
+        constexpr bool MASK = decltype(mask_c)::value;
+        constexpr int cur = decltype(cur_c)::value, prev = cur == 0 ? NS - 1 : cur - 1;
         const int j0 = t * BK;
-        const int prev = cur == 0 ? NS - 1 : cur - 1, next = cur == NS - 1 ? 0 : cur + 1;
         issue_k(j0 + D * BK, prev * KT);                 // slot read one barrier ago
         issue_v(j0 + D * BK, prev * VT);
         // S^T: 4 blocks of 16 keys
@@ -275,7 +280,7 @@ __global__ __launch_bounds__(64 * NW) void attn_mfma_kernel(AttnParams p)
         }
         // keys past the end count for nothing (only the last tile can hold any): the raw score is set
         // so that its scaled value is minus infinity
-        if (j0 + BK > p.Lk) {
+        if constexpr (MASK) {
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
@@ -328,9 +333,9 @@ __global__ __launch_bounds__(64 * NW) void attn_mfma_kernel(AttnParams p)
             u32x4 vf[NG][2];
             auto load_group = [&](auto gi_c) {
                 constexpr int GI = decltype(gi_c)::value;
-                const unsigned at = vx[GI % 4] + cur * VT;
-                vf[GI][0] = read_v(at, std::integral_constant<int, GI / 4>{}, std::integral_constant<int, 0>{});
-                vf[GI][1] = read_v(at, std::integral_constant<int, GI / 4>{}, std::integral_constant<int, 1>{});
+                const unsigned at = vx[GI % 4];
+                vf[GI][0] = read_v(at, cur_c, std::integral_constant<int, GI / 4>{}, std::integral_constant<int, 0>{});
+                vf[GI][1] = read_v(at, cur_c, std::integral_constant<int, GI / 4>{}, std::integral_constant<int, 1>{});
             };
             static_for<(AHEAD < NG ? AHEAD : NG)>([&](auto gi_c) { load_group(gi_c); });
             static_for<NG>([&](auto gi_c) {
@@ -345,15 +350,18 @@ __global__ __launch_bounds__(64 * NW) void attn_mfma_kernel(AttnParams p)
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LPS * (D - 1)));
         wg_barrier();
-        cur = next;
     };
-    for (int t0 = 0; t0 < NT; t0 += D) {
-#pragma unroll
-        for (int u = 0; u < D; ++u) {
-            if (t0 + u >= NT) break;                     // uniform over the workgroup
-            step(t0 + u);
-        }
-    }
+    // whole turns of the ring over the tiles that lie inside Lk, then what is left: fewer than NS such tiles and,
+    // if Lk is no multiple of the tile, the ragged last one (NS tiles at most; the slots go on from 0)
+    const int NF = p.Lk / BK;
+    int t = 0;
+    for (; t + NS <= NF; t += NS)
+        static_for<NS>([&](auto u_c) { step(t + decltype(u_c)::value, std::false_type{}, u_c); });
+    static_for<NS>([&](auto u_c) {
+        constexpr int U = decltype(u_c)::value;
+        if (t + U < NF) step(t + U, std::false_type{}, u_c);
+        else if (t + U < NT) step(t + U, std::true_type{}, u_c);
+    });
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
 
     const float inv = 1.0f / total[0];
