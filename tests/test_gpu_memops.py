@@ -225,6 +225,11 @@ DW_CASES = [  # N, H, W, C, R, S, stride, pad
     (2, 10, 12, 32, 5, 3, (2, 1), (2, 1)),               # non-square window: general loop
     (1, 14, 14, 64, 3, 3, (1, 1), (0, 0)),
     (1, 3, 3, 8, 1, 1, (1, 1), (0, 0)),                  # 1 x 1: a per-channel scale
+    # the LDS-tiled 3 x 3 stride-1 kernel (channel-minor weights): output tiles cut by the right and bottom
+    # edges, a last block of channel chunks that is partly empty, with and without padding
+    (2, 19, 37, 72, 3, 3, (1, 1), (1, 1)),
+    (1, 20, 40, 64, 3, 3, (1, 1), (0, 0)),
+    (1, 8, 16, 8, 3, 3, (1, 1), (1, 1)),                 # exactly one tile, one chunk
 ]
 
 
