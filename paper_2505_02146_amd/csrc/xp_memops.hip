@@ -13,6 +13,7 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void lds_void;
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
@@ -620,7 +621,7 @@ template <bool IB, bool OB>
 __global__ __launch_bounds__(256) void depthwise3x3_tile_kernel(DwParams p)
 {
     constexpr int EPC = Chunk<IB>::EPC;
-    __shared__ u32x4 patch[DW_PH * DW_PW * DW_CG];          // [patch row][patch column][channel chunk]
+    __shared__ u32x4 patch[(DW_PH * DW_PW * DW_CG + 255) / 256 * 256];   // [patch row][patch column][channel chunk], padded to whole rounds of loads
     const int cc = p.C / EPC;
     const int t = threadIdx.x;
     const int tiles_w = (p.Q + DW_TW - 1) / DW_TW, tiles_h = (p.P + DW_TH - 1) / DW_TH, cblocks = (cc + DW_CG - 1) / DW_CG;
@@ -638,20 +639,22 @@ __global__ __launch_bounds__(256) void depthwise3x3_tile_kernel(DwParams p)
     // branches the compiler copied the values already loaded from register to register at every join: a third
     // of the kernel's vector instructions, and the kernel is bound by those).
     constexpr int PATCH = DW_PH * DW_PW * DW_CG, ROUNDS = (PATCH + 255) / 256;
-    u32x4 staged[ROUNDS];
+    // The loads write LDS directly, 16 bytes per lane at consecutive addresses: lane i of the workgroup's round
+    // `it` fills chunk it * 256 + i of the patch, which is the patch's own order.  A position outside the image,
+    // past the last channel chunk or past the patch gets a byte offset beyond the range of the image's buffer
+    // descriptor, for which the load writes zeros (the patch array is padded to whole rounds for the latter).
+    const __amdgpu_buffer_rsrc_t image = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u32x4 *>((const u32x4 *)p.x + n * p.H * p.W * cc), 0, (unsigned)(p.H * p.W * cc) * 16u, 0x00020000);
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
 #pragma unroll
-    for (int it = 0; it < ROUNDS; ++it) {                  // all loads first, so that they are in flight together
-        const int i = min(t + it * 256, PATCH - 1);
+    for (int it = 0; it < ROUNDS; ++it) {                  // all loads are in flight together
+        const int i = t + it * 256;
         const int pc = i % DW_CG, col = (i / DW_CG) % DW_PW, row = i / (DW_CG * DW_PW);
         const int h = p0 - p.ph + row, x = q0 - p.pw + col;
-        const bool valid = h >= 0 && h < p.H && x >= 0 && x < p.W && cg0 + pc < cc;
-        const int hc = min(max(h, 0), p.H - 1), xc = min(max(x, 0), p.W - 1), cgc = min(cg0 + pc, cc - 1);
-        const u32x4 v = *((const u32x4 *)p.x + ((n * p.H + hc) * p.W + xc) * cc + cgc);
-        staged[it] = valid ? v : u32x4{0u, 0u, 0u, 0u};
+        const bool valid = (h >= 0) & (h < p.H) & (x >= 0) & (x < p.W) & (cg0 + pc < cc) & (i < PATCH);
+        const unsigned off = valid ? ((unsigned)(h * p.W + x) * (unsigned)cc + (unsigned)(cg0 + pc)) * 16u : 0x80000000u;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(image, (lds_void *)(patch + it * 256 + wave * 64), 16, off, 0, 0, 0);
     }
-#pragma unroll
-    for (int it = 0; it < ROUNDS; ++it)
-        if (t + it * 256 < PATCH) patch[t + it * 256] = staged[it];
     // this thread's channel chunk and its 9 weight chunks (a chunk past the last one computes with the last
     // one's weights and is not stored)
     const int cg = t % DW_CG;
@@ -680,6 +683,7 @@ __global__ __launch_bounds__(256) void depthwise3x3_tile_kernel(DwParams p)
             ws[2 * i] = bf16_lo(wr[8][i]);
             ws[2 * i + 1] = bf16_hi(wr[8][i]);
         }
+        __builtin_amdgcn_s_waitcnt(0x0070);              // the patch has arrived in LDS (vmcnt 0, lgkmcnt 0)
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -731,6 +735,7 @@ __global__ __launch_bounds__(256) void depthwise3x3_tile_kernel(DwParams p)
     float w[9][EPC];
 #pragma unroll
     for (int k = 0; k < 9; ++k) Chunk<IB>::template load<false>(p.w, (long long)k * cc + min(cg0 + cg, cc - 1), w[k]);
+    __builtin_amdgcn_s_waitcnt(0x0070);              // the patch has arrived in LDS (vmcnt 0, lgkmcnt 0)
     __syncthreads();
     // 128 output pixels x 8 chunks over 256 threads: 4 pixels per thread, as two pairs of neighbours in a row, so
     // that the 3 x 4 input chunks under a pair are read from LDS and widened to fp32 once (12 instead of 18
@@ -894,7 +899,7 @@ xp_status xp_depthwise_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, i
     hipStream_t s = (hipStream_t)stream;
     const bool win3 = vec && minor && R == 3 && S == 3;
     // stride 1 and an image of several tiles: the LDS-tiled kernel
-    const bool tiled = win3 && stride_h == 1 && stride_w == 1 && P >= DW_TH && Q >= DW_TW;
+    const bool tiled = win3 && stride_h == 1 && stride_w == 1 && P >= DW_TH && Q >= DW_TW && H * W * (C / epc) * 16 <= lim;
     const long long tiles = N * ((P + DW_TH - 1) / DW_TH) * ((Q + DW_TW - 1) / DW_TW) * ((C / epc + DW_CG - 1) / DW_CG);
     p.tiles = tiles;
 #define XP_DW(IB, OB)                                                                                  \
