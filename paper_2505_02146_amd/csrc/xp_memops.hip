@@ -613,7 +613,8 @@ __global__ __launch_bounds__(256) void depthwise_kernel(DwParams p)
 // The one-work-item-per-output kernel above issues 18 loads per output chunk (9 pixels, 9 weights)
 // and is bound by the rate of L1 requests, not by HBM.  Here a workgroup stages the input patch of
 // an 8 x 16 tile of outputs for 8 channel chunks (10 x 18 pixels, 1.4 loads per output chunk, all
-// issued up front) in LDS, keeps its 9 weight chunks unpacked in registers, and reads the taps from LDS.
+// issued up front, written to LDS by the loads themselves) in LDS, keeps its 9 weight chunks in registers,
+// and reads the taps from LDS.
 constexpr int DW_TH = 8, DW_TW = 16, DW_CG = 8;            // output rows, columns and channel chunks per workgroup
 constexpr int DW_PH = DW_TH + 2, DW_PW = DW_TW + 2;
 
@@ -635,9 +636,6 @@ __global__ __launch_bounds__(256) void depthwise3x3_tile_kernel(DwParams p)
     const int p0 = th * DW_TH, q0 = tw * DW_TW, cg0 = cb * DW_CG;
 
     // stage the patch: rows p0 - ph .. +DW_PH, columns q0 - pw .. +DW_PW; zeros outside the image or past the last chunk.
-    // No branch around a load: a position outside loads the nearest chunk inside and is zeroed by a select (with
-    // branches the compiler copied the values already loaded from register to register at every join: a third
-    // of the kernel's vector instructions, and the kernel is bound by those).
     constexpr int PATCH = DW_PH * DW_PW * DW_CG, ROUNDS = (PATCH + 255) / 256;
     // The loads write LDS directly, 16 bytes per lane at consecutive addresses: lane i of the workgroup's round
     // `it` fills chunk it * 256 + i of the patch, which is the patch's own order.  A position outside the image,
