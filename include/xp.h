@@ -221,6 +221,25 @@ xp_status xp_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t C
                          void *output, xp_dtype out_type, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * xp_conv2d_nchw for callers that cannot allocate device memory or pass a workspace of their own: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * result as xp_conv2d_nchw without the workspace: the layout-change passes use a buffer of
+ * xp_conv2d_nchw_static_max_bytes() (64 MiB) that is part of the library's device image, one per GPU,
+ * held until the process ends.  The call allocates and frees nothing (its first call on a device looks
+ * the buffer's address up, once).  A call that needs more than the buffer
+ * (xp_conv2d_nchw_workspace_bytes(...) > xp_conv2d_nchw_static_max_bytes()) returns XP_ERR_SHAPE and
+ * launches nothing: use xp_conv2d_nchw.  All calls on one GPU share the buffer: calls that may overlap
+ * in time there (different streams, or different threads without ordering) race on it and must be
+ * serialised by the caller; calls on one stream are ordered by the stream.  Nothing in the buffer has
+ * to survive from call to call: every call overwrites the part it reads.
+ */
+size_t xp_conv2d_nchw_static_max_bytes(void);
+xp_status xp_conv2d_nchw_static(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t R, int64_t S,
+                                int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                const void *input, xp_dtype in_type, const void *filter, xp_dtype w_type,
+                                void *output, xp_dtype out_type, void *stream);
+
+/*
  * Multi-scale deformable attention (Table 5, "Deformable Attention"; Section 6 discusses it as the
  * hardest operator of the benchmark).  The operator of Deformable DETR's attention layers:
  *   out[n,q,m,:] = sum_{l<levels, p<points} weights[n,q,m,l,p] * bilinear(value_l[n,:,:,m,:], locations[n,q,m,l,p,:])

@@ -5,6 +5,8 @@
 // contiguous, which is what NHWC is; the output has no such constraint.
 #include "xp_internal.hpp"
 
+#include <atomic>
+
 namespace xp {
 namespace {
 
@@ -96,6 +98,69 @@ hipError_t transpose(const void *in, void *out, int64_t batch, int64_t rows, int
 
 size_t round256(size_t x) { return (x + 255) / 256 * 256; }
 
+
+// The library's own layout-change buffer, for callers that cannot hand over a workspace they allocated
+// (xp_conv2d_nchw_static).  One copy per GPU, held from the moment the library is loaded there until the
+// process ends.  In host code the array's name is only a handle: its device address is looked up once per
+// device (static_scratch) and that pointer is what kernels and size checks get.
+constexpr size_t STATIC_BYTES = (size_t)64 << 20;
+__device__ __align__(256) unsigned char scratch[STATIC_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::atomic<void *> scratch_ptr[MAX_DEVICES];
+
+// Device address of `scratch` on the current device (looked up on the first call there; no allocation).
+xp_status static_scratch(void **out)
+{
+    int d = -1;
+    if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= MAX_DEVICES) return XP_ERR_LAUNCH;
+    void *p = scratch_ptr[d].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return XP_ERR_LAUNCH;
+        scratch_ptr[d].store(p, std::memory_order_release);      // every thread finds the same address: a race here is benign
+    }
+    *out = p;
+    return XP_OK;
+}
+
+xp_status conv2d_nchw_in(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t R, int64_t S,
+                         int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                         const void *input, xp_dtype in_type, const void *filter, xp_dtype w_type,
+                         void *output, xp_dtype out_type, void *workspace, size_t workspace_bytes, bool is_static, void *stream)
+{
+    // the NHWC entry's own validation, on the pointers it will actually see (checked before anything is launched)
+    if (N < 0 || H < 0 || W < 0 || Cin < 0 || Cout < 0) return XP_ERR_SHAPE;
+    if (R <= 0 || S <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return XP_ERR_SHAPE;
+    if (in_type != w_type || (in_type != XP_F32 && in_type != XP_BF16) || out_type != XP_F32) return XP_ERR_UNSUPPORTED;
+    if (H + 2 * pad_h < R || W + 2 * pad_w < S) return XP_OK;   // empty output
+    if (N == 0 || Cout == 0) return XP_OK;
+    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1, Q = (W + 2 * pad_w - S) / stride_w + 1;
+    const int64_t K = R * S * Cin;
+    if (!output || (K > 0 && (!input || !filter))) return XP_ERR_NULL;
+    const int esz = elem_size(in_type);
+    if (((uintptr_t)output % 4) != 0 || (K > 0 && (((uintptr_t)input % esz) != 0 || ((uintptr_t)filter % esz) != 0))) return XP_ERR_ALIGN;
+    if (H * W > 0x7fffffffLL || P * Q > 0x7fffffffLL || N > 65535 || Cout > 65535) return XP_ERR_SHAPE;   // transpose grids
+    const size_t need = xp_conv2d_nchw_workspace_bytes(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, in_type);
+    if (is_static && need > workspace_bytes) return XP_ERR_SHAPE;   // beyond the built-in buffer: use the workspace entry point
+    if (!workspace || ((uintptr_t)workspace % 256) != 0 || workspace_bytes < need) return XP_ERR_WORKSPACE;
+
+    char *x_nhwc = (char *)workspace;
+    char *w_krsc = x_nhwc + round256((size_t)(N * H * W * Cin) * esz);
+    hipStream_t s = (hipStream_t)stream;
+    if (K > 0) {
+        if (transpose(input, x_nhwc, N, Cin, H * W, esz, s) != hipSuccess) return XP_ERR_LAUNCH;        // [N][C][HW] -> [N][HW][C]
+        if (transpose(filter, w_krsc, Cout, Cin, R * S, esz, s) != hipSuccess) return XP_ERR_LAUNCH;    // [K][C][RS] -> [K][RS][C]
+    }
+    Problem q;
+    bool nothing;
+    const xp_status st = make_conv_problem(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, x_nhwc, in_type,
+                                           w_krsc, w_type, XP_FILTER_KRSC, output, XP_F32, stream, &q, &nothing);
+    if (st != XP_OK) return st;
+    if (nothing) return XP_OK;
+    q.c_plane = P * Q;                                    // the kernels' epilogue writes [N][K][PQ] directly
+    return run(q);
+}
+
 }  // namespace
 }  // namespace xp
 
@@ -121,36 +186,22 @@ xp_status xp_conv2d_nchw(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t C
                          const void *input, xp_dtype in_type, const void *filter, xp_dtype w_type,
                          void *output, xp_dtype out_type, void *workspace, size_t workspace_bytes, void *stream)
 {
-    // the NHWC entry's own validation, on the pointers it will actually see (checked before anything is launched)
-    if (N < 0 || H < 0 || W < 0 || Cin < 0 || Cout < 0) return XP_ERR_SHAPE;
-    if (R <= 0 || S <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return XP_ERR_SHAPE;
-    if (in_type != w_type || (in_type != XP_F32 && in_type != XP_BF16) || out_type != XP_F32) return XP_ERR_UNSUPPORTED;
-    if (H + 2 * pad_h < R || W + 2 * pad_w < S) return XP_OK;   // empty output
-    if (N == 0 || Cout == 0) return XP_OK;
-    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1, Q = (W + 2 * pad_w - S) / stride_w + 1;
-    const int64_t K = R * S * Cin;
-    if (!output || (K > 0 && (!input || !filter))) return XP_ERR_NULL;
-    const int esz = elem_size(in_type);
-    if (((uintptr_t)output % 4) != 0 || (K > 0 && (((uintptr_t)input % esz) != 0 || ((uintptr_t)filter % esz) != 0))) return XP_ERR_ALIGN;
-    if (H * W > 0x7fffffffLL || P * Q > 0x7fffffffLL || N > 65535 || Cout > 65535) return XP_ERR_SHAPE;   // transpose grids
-    const size_t need = xp_conv2d_nchw_workspace_bytes(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, in_type);
-    if (!workspace || ((uintptr_t)workspace % 256) != 0 || workspace_bytes < need) return XP_ERR_WORKSPACE;
+    return conv2d_nchw_in(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, input, in_type, filter, w_type, output,
+                          out_type, workspace, workspace_bytes, false, stream);
+}
 
-    char *x_nhwc = (char *)workspace;
-    char *w_krsc = x_nhwc + round256((size_t)(N * H * W * Cin) * esz);
-    hipStream_t s = (hipStream_t)stream;
-    if (K > 0) {
-        if (transpose(input, x_nhwc, N, Cin, H * W, esz, s) != hipSuccess) return XP_ERR_LAUNCH;        // [N][C][HW] -> [N][HW][C]
-        if (transpose(filter, w_krsc, Cout, Cin, R * S, esz, s) != hipSuccess) return XP_ERR_LAUNCH;    // [K][C][RS] -> [K][RS][C]
-    }
-    Problem q;
-    bool nothing;
-    const xp_status st = make_conv_problem(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, x_nhwc, in_type,
-                                           w_krsc, w_type, XP_FILTER_KRSC, output, XP_F32, stream, &q, &nothing);
+size_t xp_conv2d_nchw_static_max_bytes(void) { return STATIC_BYTES; }
+
+xp_status xp_conv2d_nchw_static(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t R, int64_t S,
+                                int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                const void *input, xp_dtype in_type, const void *filter, xp_dtype w_type,
+                                void *output, xp_dtype out_type, void *stream)
+{
+    void *ws = nullptr;
+    const xp_status st = static_scratch(&ws);
     if (st != XP_OK) return st;
-    if (nothing) return XP_OK;
-    q.c_plane = P * Q;                                    // the kernels' epilogue writes [N][K][PQ] directly
-    return run(q);
+    return conv2d_nchw_in(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, input, in_type, filter, w_type, output,
+                          out_type, ws, STATIC_BYTES, true, stream);
 }
 
 }  // extern "C"

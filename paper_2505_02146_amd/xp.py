@@ -53,6 +53,9 @@ _lib.xp_pool2d_nhwc.argtypes = [_i] + [_i64] * 10 + [_vp, _i, _vp, _i, _vp]
 _lib.xp_conv2d_nchw_workspace_bytes.argtypes = [_i64] * 11 + [_i]
 _lib.xp_conv2d_nchw_workspace_bytes.restype = C.c_size_t
 _lib.xp_conv2d_nchw.argtypes = [_i64] * 11 + [_vp, _i, _vp, _i, _vp, _i, _vp, C.c_size_t, _vp]
+_lib.xp_conv2d_nchw_static.argtypes = [_i64] * 11 + [_vp, _i, _vp, _i, _vp, _i, _vp]
+_lib.xp_conv2d_nchw_static_max_bytes.argtypes = []
+_lib.xp_conv2d_nchw_static_max_bytes.restype = C.c_size_t
 _lib.xp_depthwise_conv2d_nhwc.argtypes = [_i64] * 10 + [_vp, _i, _vp, _i, _i, _vp, _i, _vp]
 _lib.xp_deformable_attention.argtypes = [_i64] * 6 + [_vp, _i, _vp, _vp, _vp, _vp, _vp, _i, _vp]
 _lib.xp_num_configs.argtypes = [_i, _i]
@@ -65,6 +68,7 @@ _lib.xp_version.restype = C.c_char_p
 for _name in ("xp_gemm", "xp_gemm_batched", "xp_conv2d_nhwc", "xp_attention", "xp_tune_gemm", "xp_tune_gemm_batched",
               "xp_tune_conv2d_nhwc", "xp_tune_save", "xp_tune_load", "xp_tune_count", "xp_softmax", "xp_layernorm",
               "xp_rmsnorm", "xp_unary", "xp_add", "xp_pool2d_nhwc", "xp_depthwise_conv2d_nhwc", "xp_conv2d_nchw",
+              "xp_conv2d_nchw_static",
               "xp_deformable_attention", "xp_num_configs", "xp_describe_config",
               "xp_force_config", "xp_last_config"):
     getattr(_lib, _name).restype = _i
@@ -237,6 +241,17 @@ def xp_conv2d_nchw(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, x
     _check(_lib.xp_conv2d_nchw(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, _ptr(x), _dt(x, in_type),
                                _ptr(w), _dt(w, w_type), _ptr(out), _dt(out, out_type), _ptr(workspace),
                                workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def xp_conv2d_nchw_static_max_bytes() -> int:
+    return _lib.xp_conv2d_nchw_static_max_bytes()
+
+
+def xp_conv2d_nchw_static(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, x, w, out, stream=None,
+                          in_type=None, w_type=None, out_type=None):
+    """xp_conv2d_nchw on the library's built-in layout-change buffer (see include/xp.h: xp_conv2d_nchw_static)."""
+    _check(_lib.xp_conv2d_nchw_static(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, _ptr(x), _dt(x, in_type),
+                                      _ptr(w), _dt(w, w_type), _ptr(out), _dt(out, out_type), _stream(stream)))
 
 
 def xp_depthwise_conv2d_nhwc(N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w, x, w, filter_layout, y, stream=None,
