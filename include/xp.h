@@ -336,6 +336,24 @@ xp_status xp_tune_load(const char *path);
 void xp_tune_clear(void);
 int xp_tune_count(void);
 
+/*
+ * Measurement aid: the rate the matrix cores sustain on this device when nothing else happens.  The
+ * throughput that the paper's parameter search maximises (Section 5.1, Eq. 3-4) is reported against the
+ * chip's nominal MFMA peak; this call provides the measured ceiling beside it.  It launches one kernel:
+ * one workgroup on each of the 256 compute units, `waves` (1 or 2) waves per SIMD, each running `iters`
+ * rounds of 32 independent 16x16 (block == 16; 8 of 32x32 for block == 32) MFMAs of `in_type`
+ * (XP_BF16 or XP_I8) on operands held in registers.  Time it with events on `stream`;
+ * xp_mfma_ceiling_ops(...) is the number of arithmetic operations of one launch (0 for invalid arguments).
+ *   operands   DEVICE, 16-byte aligned, at least 98304 bytes of valid `in_type` values (read once, before the loop;
+ *              their values set the power drawn: use the distribution of the workload)
+ *   sink       DEVICE, at least 256 * 256 * waves * 4 bytes, overwritten (keeps the arithmetic alive)
+ * Errors: XP_ERR_UNSUPPORTED (type, block, waves), XP_ERR_SHAPE (iters < 0 or >= 2^31), XP_ERR_NULL, XP_ERR_ALIGN,
+ * XP_ERR_WORKSPACE (a buffer too small), XP_ERR_LAUNCH.
+ */
+double xp_mfma_ceiling_ops(xp_dtype in_type, int block, int waves, int64_t iters);
+xp_status xp_mfma_ceiling(xp_dtype in_type, int block, int waves, int64_t iters, const void *operands, size_t operand_bytes,
+                          void *sink, size_t sink_bytes, void *stream);
+
 /* Human-readable name of a status code (static storage). */
 const char *xp_status_string(xp_status s);
 

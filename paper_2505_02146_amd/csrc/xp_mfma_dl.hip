@@ -56,8 +56,11 @@ struct DlParams {
 };
 
 template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_, bool SPREAD_ = false, int OCC_ = 1, int MF_ = 32, bool NT_ = false,
-          int NSA_ = NS_>
+          int NSA_ = NS_, bool WEAVE_ = false>
 struct DlTile {
+    // assembly-read modes: the reads of the next fragment set are dealt out between the MFMA block rows of the
+    // current one instead of being issued as one burst in front of them
+    static constexpr bool WEAVE = WEAVE_;
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NS = NS_, RB = RB_;
     // ring depth of the A buffers (NS is that of the B buffers): one more A buffer than B buffers
     // gives the A loads an extra K step to land where LDS cannot hold a third whole stage
@@ -90,7 +93,7 @@ struct DlTile {
     static_assert(MF == 32 || MF == 16, "MFMA shape");
     static_assert(WTM % MF == 0 && WTN % MF == 0, "wave sub-tile must be whole MFMA blocks");
     static_assert(PH >= 1, "a K step must hold at least one MFMA sub-step");
-    static_assert(NSMIN >= 2 && NSA <= NS + 1 && NS <= NSA + 1 && PENDING <= 63, "ring depths; vmcnt is a 6-bit counter");
+    static_assert(NSMIN >= 2 && NSA <= NS + 1 && NS <= NSA + 1 && PENDING + IA + IB <= 63, "ring depths; vmcnt is a 6-bit counter");
     static_assert(!ASYM || !SPREAD_, "spread issue is for equal ring depths");
     static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
     static_assert(!SPREAD || NS >= 3, "with two buffers the loads of a step must all be issued at its start");
@@ -455,6 +458,71 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             });
         }
     };
+    // one fragment of the set: F < NI the B fragment F, else the A fragment F - NI (the B fragments first: every
+    // block row of the next sub-step needs all of them)
+    auto read_frag_asm = [&](auto ao_c, auto bo_c, auto kk_c, auto f_c, int a_off, int b_off, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
+        constexpr int AO = decltype(ao_c)::value, BO = decltype(bo_c)::value, KK = decltype(kk_c)::value, F = decltype(f_c)::value;
+        if constexpr (F >= T::NI) {
+            constexpr int I = F - T::NI;
+            constexpr int AREL = AO < 0 ? 0 : AO;
+            constexpr bool AFAR = AREL + A_TOP >= 65536;
+            constexpr int AIMM = (AFAR ? AREL - 65536 : AREL) + (AMM ? KK * 32 * RAM : 0);
+            if constexpr (AMM) {
+                const unsigned at = AO < 0 ? lds_base + a_off + fam[I] : (AFAR ? fa_far[A_FAR ? I : 0] : lds_base + fam[I]);
+                const lds_tr_u32x2 lo = lds_read_tr16_b64<AIMM>(at), hi = lds_read_tr16_b64<AIMM + 4 * RAM>(at);
+                af[I] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            } else {
+                const unsigned at = AO < 0 ? lds_base + a_off + fa[KK] : (AFAR ? fa_far[A_FAR ? KK : 0] : lds_base + fa[KK]);
+                af[I] = lds_read_b128<AIMM + I * MF * RB>(at);
+            }
+        } else {
+            constexpr int J = F;
+            constexpr int BREL = BO < 0 ? 0 : BO - T::B_BASE;
+            constexpr bool BFAR = BREL + B_TOP >= 65536;
+            constexpr int BIMM = (BFAR ? BREL - 65536 : BREL) + (BNM ? KK * 32 * RBN : 0);
+            const unsigned b_rt = lds_base + b_off;
+            if constexpr (BNM) {
+                const unsigned at = BO < 0 ? b_rt + fbn[J] : (BFAR ? fb_far[B_FAR ? J : 0] : lds_base + T::B_BASE + fbn[J]);
+                const lds_tr_u32x2 lo = lds_read_tr16_b64<BIMM>(at), hi = lds_read_tr16_b64<BIMM + 4 * RBN>(at);
+                bf[J] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            } else {
+                const unsigned at = BO < 0 ? b_rt + fb[KK] : (BFAR ? fb_far[B_FAR ? KK : 0] : lds_base + T::B_BASE + fb[KK]);
+                bf[J] = lds_read_b128<BIMM + J * MF * RB>(at);
+            }
+        }
+    };
+    // WEAVE: one MFMA sub-step on the set (ca, cb) with the reads of the set (na, nb) -- sub-step KK of the buffers at
+    // AO / BO -- dealt out behind its block rows: a wave that issues its reads as one burst keeps the matrix pipe
+    // idle meanwhile when its SIMD neighbour, in step with it, does the same.  The last block rows get no reads, so
+    // that the reads have returned when the step's barrier asks for it.  Columns are walked back and forth: between
+    // two consecutive MFMAs only one operand changes.  after_row(i) is called behind block row i (the second sub-step
+    // of a K step issues the step's global loads there, a share per row).
+    auto weave = [&](auto ao_c, auto bo_c, auto kk_c, int a_off, int b_off, u32x4 (&ca)[T::MI], u32x4 (&cb)[T::NI], u32x4 (&na)[T::MI],
+                     u32x4 (&nb)[T::NI], auto &&after_row) {
+        constexpr int NF = T::MI + T::NI;                               // fragments to read
+        constexpr int ROWS = T::MI > 2 ? T::MI - 2 : 1;                 // block rows that carry reads
+        constexpr int PER = (NF + ROWS - 1) / ROWS;
+        lds_wait<0>();                                                  // (ca, cb) were read during the sub-step before
+#pragma unroll
+        for (int i = 0; i < T::MI; ++i) lds_tie(ca[i]);
+#pragma unroll
+        for (int j = 0; j < T::NI; ++j) lds_tie(cb[j]);
+        static_for<T::MI>([&](auto i_c) {
+            constexpr int I = decltype(i_c)::value;
+#pragma unroll
+            for (int jj = 0; jj < T::NI; ++jj) {
+                const int j = (I & 1) ? T::NI - 1 - jj : jj;
+                if constexpr (MF == 16) acc[I][j] = Acc<INT8, 16>::mma(cb[j], ca[I], acc[I][j]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<PER>([&](auto r_c) {
+                constexpr int F = I * PER + decltype(r_c)::value;
+                if constexpr (F < NF) read_frag_asm(ao_c, bo_c, kk_c, std::integral_constant<int, F>{}, a_off, b_off, na, nb);
+            });
+            after_row(i_c);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
     auto read_frags = [&](int a_off, int b_off, int kk, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
 #pragma unroll
         for (int i = 0; i < T::MI; ++i) af[i] = *(const u32x4 *)(lds + a_off + fa[kk] + i * MF * RB);
@@ -488,7 +556,18 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     constexpr int A_END = T::NSA * T::A_BYTES, B_END = T::B_BASE + T::NS * T::B_BYTES;
     if (KT > 0) {
         u32x4 xa[T::MI], xb[T::NI], ya[T::MI], yb[T::NI];     // fragment sets of even / odd sub-steps
-        if constexpr (T::ASYM) {
+        constexpr bool WV = ASMR && T::WEAVE;
+        if constexpr (WV) {
+            // woven: step j issues B(j+NS) and A(j+NSA), the deeper ring's last, and so do the steps before the first:
+            // every buffer of both rings is filled before the loop
+            constexpr int DEEP = T::NS > T::NSA ? T::NS : T::NSA;
+#pragma unroll
+            for (int j = -DEEP; j < 0; ++j) {
+                if (!T::B_DEEP && j + T::NS >= 0) issue_b(j + T::NS, T::B_BASE + (j + T::NS) * T::B_BYTES, 0, T::IB, std::true_type{});
+                if (j + T::NSA >= 0) issue_a(j + T::NSA, (j + T::NSA) * T::A_BYTES, 0, T::IA, std::true_type{});
+                if (T::B_DEEP && j + T::NS >= 0) issue_b(j + T::NS, T::B_BASE + (j + T::NS) * T::B_BYTES, 0, T::IB, std::true_type{});
+            }
+        } else if constexpr (T::ASYM) {
             // step j issues B(j+NS-1) and A(j+NSA-1), the deeper ring's last; the steps before the first one do the same
             constexpr int DEEP = T::B_DEEP ? T::NS : T::NSA;
 #pragma unroll
@@ -501,7 +580,8 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
 #pragma unroll
             for (int s = 0; s < T::NS - 1; ++s) issue(s, s * T::A_BYTES, T::B_BASE + s * T::B_BYTES, 0, IT, std::true_type{});
         }
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
+        // (woven: one more K step of loads has been issued than the barrier inside a step finds)
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(WV ? PENDING + IT : PENDING));
         __builtin_amdgcn_s_barrier();
         // fragment sets alternate between sub-steps; `odd` says which set holds the sub-step that
         // is multiplied next (only for PH == 1 does it change from K step to K step)
@@ -527,7 +607,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             // loads go into the buffers read in step kt-1
             const int into_a = POS >= 0 ? ((POS + T::NSA - 1) % T::NSA) * T::A_BYTES : fill_a;
             const int into_b = POS >= 0 ? T::B_BASE + ((POS + T::NS - 1) % T::NS) * T::B_BYTES : fill_b;
-            if constexpr (T::ASYM) {
+            if constexpr (ASMR && T::WEAVE) {
+                // (issued in the second sub-step, below)
+            } else if constexpr (T::ASYM) {
                 if constexpr (!T::B_DEEP) issue_b(kt + T::NS - 1, into_b, 0, T::IB, check_c);
                 issue_a(kt + T::NSA - 1, into_a, 0, T::IA, check_c);
                 if constexpr (T::B_DEEP) issue_b(kt + T::NS - 1, into_b, 0, T::IB, check_c);
@@ -537,6 +619,25 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             if constexpr (ASMR) {
                 // two sub-steps: the second one's fragments (set Y) are read while the first is multiplied
                 static_assert(T::PH == 2 && !ODD && !T::SPREAD, "assembly reads: two sub-steps per K step");
+                if constexpr (T::WEAVE) {
+                    // The barrier in the middle of the step is passed when every wave has read the current buffers
+                    // for the last time, so the second sub-step refills them: with the loads for K step kt + NS
+                    // (A: kt + NSA), a share behind each block row.  They have a whole K step to land, not half.
+                    weave(std::integral_constant<int, CA>{}, std::integral_constant<int, CB>{}, One{}, now_a, now_b, xa, xb, ya, yb, [](auto) {});
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
+                    __builtin_amdgcn_s_barrier();
+                    weave(std::integral_constant<int, NA>{}, std::integral_constant<int, NB>{}, Zero{}, nxt_a, nxt_b, ya, yb, xa, xb, [&](auto i_c) {
+                        constexpr int I = decltype(i_c)::value;
+                        constexpr int LO = I * IT / T::MI, HI = (I + 1) * IT / T::MI;
+                        if constexpr (T::ASYM && !T::B_DEEP) {       // B first: the deeper ring's loads are the ones that may stay in flight
+                            issue_b(kt + T::NS, now_b, LO, HI < T::IB ? HI : T::IB, check_c);
+                            issue_a(kt + T::NSA, now_a, LO > T::IB ? LO - T::IB : 0, HI - T::IB, check_c);
+                        } else {
+                            issue_a(kt + T::NSA, now_a, LO, HI < T::IA ? HI : T::IA, check_c);
+                            issue_b(kt + T::NS, now_b, LO > T::IA ? LO - T::IA : 0, HI - T::IA, check_c);
+                        }
+                    });
+                } else {
                 read_frags_asm(std::integral_constant<int, CA>{}, std::integral_constant<int, CB>{}, One{}, now_a, now_b, ya, yb);
                 __builtin_amdgcn_sched_barrier(0);
                 mma_all(xa, xb);
@@ -547,6 +648,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 __builtin_amdgcn_sched_barrier(0);
                 mma_all(ya, yb);
                 __builtin_amdgcn_sched_barrier(0);
+                }
             } else {
 #pragma unroll
                 for (int ph = 0; ph < T::PH - 1; ++ph) {
@@ -581,7 +683,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         };
         if constexpr (T::PH % 2 == 0) {
             // steps whose loads (for step kt + NS - 1, A possibly one further) are whole steps inside K
-            constexpr int AHEAD = (T::NSA > T::NS ? T::NSA : T::NS) - 1;
+            constexpr int AHEAD = (T::NSA > T::NS ? T::NSA : T::NS) - (WV ? 0 : 1);
             const int whole = p.Kb / RB - AHEAD;
             int kt = 0;
             if constexpr (ASMR && (!CONV || T::NSA == T::NS)) {
@@ -904,12 +1006,13 @@ hipError_t dl_asm_launch(const Problem &q)
     return hipGetLastError();
 }
 
-#define XP_DL_ASM_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NSA, NSB, OCC, EFF)                                          \
-    typedef DlTile<BM, BN, WM, WN, NSB, 128, false, OCC, 16, false, NSA> NAME##_tile;                                     \
+#define XP_DL_ASM_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NSA, NSB, OCC, EFF) XP_DL_ASM_VARIANT_W(NAME, TYPESTR, INT8, BM, BN, WM, WN, NSA, NSB, OCC, EFF, false, "")
+#define XP_DL_ASM_VARIANT_W(NAME, TYPESTR, INT8, BM, BN, WM, WN, NSA, NSB, OCC, EFF, WEAVE, WEAVESTR)                      \
+    typedef DlTile<BM, BN, WM, WN, NSB, 128, false, OCC, 16, false, NSA, WEAVE> NAME##_tile;                              \
     bool NAME##_can(const Problem &q) { return dl_can_run_common<INT8>(q, BM, BN, 128, 16); }                             \
     hipError_t NAME##_launch(const Problem &q) { return dl_asm_launch<INT8, NAME##_tile>(q); }                            \
     double NAME##_cost(const Problem &q) { return dl_cost<NAME##_tile>(q, EFF); }                                         \
-    const Variant NAME = {TYPESTR " " #BM "x" #BN "x128B waves " #WM "x" #WN " ring " #NSA "(A)+" #NSB "(B) direct-to-lds, reads as assembly, mfma16", \
+    const Variant NAME = {TYPESTR " " #BM "x" #BN "x128B waves " #WM "x" #WN " ring " #NSA "(A)+" #NSB "(B) direct-to-lds, reads as assembly" WEAVESTR ", mfma16", \
                           NAME##_can, NAME##_launch, NAME##_cost};
 
 XP_DL_ASM_VARIANT(kBfAsm256x256a3, "bf16", false, 256, 256, 2, 4, 3, 2, 1, 0.55)
@@ -936,6 +1039,12 @@ XP_DL_ASM_VARIANT(kI8Asm128x128, "i8", true, 128, 128, 2, 2, 2, 2, 2, 0.36)
 XP_DL_ASM_VARIANT(kI8Asm256x128, "i8", true, 256, 128, 4, 2, 3, 3, 1, 0.46)
 XP_DL_ASM_VARIANT(kI8Asm128x256, "i8", true, 128, 256, 2, 4, 3, 3, 1, 0.46)
 XP_DL_ASM_VARIANT(kI8Asm256x256, "i8", true, 256, 256, 2, 4, 2, 2, 1, 0.54)
+// reads woven between the MFMA block rows
+XP_DL_ASM_VARIANT_W(kBfWv256x256a3, "bf16", false, 256, 256, 2, 4, 3, 2, 1, 0.57, true, " woven")
+XP_DL_ASM_VARIANT_W(kBfWv256x256, "bf16", false, 256, 256, 2, 4, 2, 2, 1, 0.56, true, " woven")
+XP_DL_ASM_VARIANT_W(kBfWv224x256, "bf16", false, 224, 256, 2, 4, 2, 2, 1, 0.51, true, " woven")
+XP_DL_ASM_VARIANT_W(kI8Wv256x256a3, "i8", true, 256, 256, 2, 4, 3, 2, 1, 0.57, true, " woven")
+XP_DL_ASM_VARIANT_W(kI8Wv256x256, "i8", true, 256, 256, 2, 4, 2, 2, 1, 0.56, true, " woven")
 
 }  // namespace
 
@@ -949,6 +1058,44 @@ int dl_asm_variants(xp_dtype in_type, const Variant **out)
     }
     if (in_type == XP_I8) {
         const Variant *v[] = {&kI8Asm256x256a3, &kI8Asm256x256, &kI8Asm128x128, &kI8Asm256x128, &kI8Asm128x256};
+        for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
+        return (int)(sizeof v / sizeof *v);
+    }
+    return 0;
+}
+
+typedef DlTile<224, 256, 2, 4, 2, 128, false, 1, 16, false, 3, true> TwoHiW;
+typedef DlTile<192, 256, 2, 4, 2, 128, false, 1, 16, false, 3, true> TwoLoW;
+typedef DlTile<224, 256, 2, 4, 2, 128, false, 1, 16, false, 2, true> TwoHiW2;
+typedef DlTile<192, 256, 2, 4, 2, 128, false, 1, 16, false, 2, true> TwoLoW2;
+bool kBfWvTwoHeights_can(const Problem &q) { return dl_can_run_common<false>(q, 224, 256, 128, 16); }
+hipError_t kBfWvTwoHeights_launch(const Problem &q) { return dl_launch_two_heights<false, TwoHiW, TwoLoW, true>(q); }
+double kBfWvTwoHeights_cost(const Problem &q) { return dl_cost<TwoHiW>(q, 0.51); }
+const Variant kBfWvTwoHeights = {"bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly woven, mfma16",
+                                 kBfWvTwoHeights_can, kBfWvTwoHeights_launch, kBfWvTwoHeights_cost};
+hipError_t kBfWvTwoHeights2_launch(const Problem &q) { return dl_launch_two_heights<false, TwoHiW2, TwoLoW2, true>(q); }
+double kBfWvTwoHeights2_cost(const Problem &q) { return dl_cost<TwoHiW2>(q, 0.51); }
+const Variant kBfWvTwoHeights2 = {"bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 2(A)+2(B) direct-to-lds, reads as assembly woven, mfma16",
+                                  kBfWvTwoHeights_can, kBfWvTwoHeights2_launch, kBfWvTwoHeights2_cost};
+XP_DL_ASM_VARIANT_W(kBfWv224x256a3, "bf16", false, 224, 256, 2, 4, 3, 2, 1, 0.51, true, " woven")
+XP_DL_ASM_VARIANT_W(kBfWv128x128, "bf16", false, 128, 128, 2, 2, 2, 2, 2, 0.37, true, " woven")
+XP_DL_ASM_VARIANT_W(kBfWv256x128, "bf16", false, 256, 128, 4, 2, 3, 3, 1, 0.47, true, " woven")
+XP_DL_ASM_VARIANT_W(kBfWv128x256, "bf16", false, 128, 256, 2, 4, 3, 3, 1, 0.47, true, " woven")
+XP_DL_ASM_VARIANT_W(kI8Wv128x128, "i8", true, 128, 128, 2, 2, 2, 2, 2, 0.37, true, " woven")
+XP_DL_ASM_VARIANT_W(kI8Wv256x128, "i8", true, 256, 128, 4, 2, 3, 3, 1, 0.47, true, " woven")
+XP_DL_ASM_VARIANT_W(kI8Wv128x256, "i8", true, 128, 256, 2, 4, 3, 3, 1, 0.47, true, " woven")
+
+// Registered last of all: the variants before them keep their indices.
+int dl_weave_variants(xp_dtype in_type, const Variant **out)
+{
+    if (in_type == XP_BF16) {
+        const Variant *v[] = {&kBfWv256x256a3, &kBfWv256x256, &kBfWv224x256, &kBfWvTwoHeights, &kBfWvTwoHeights2, &kBfWv224x256a3,
+                              &kBfWv128x128, &kBfWv256x128, &kBfWv128x256};
+        for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
+        return (int)(sizeof v / sizeof *v);
+    }
+    if (in_type == XP_I8) {
+        const Variant *v[] = {&kI8Wv256x256a3, &kI8Wv256x256, &kI8Wv128x128, &kI8Wv256x128, &kI8Wv128x256};
         for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
         return (int)(sizeof v / sizeof *v);
     }

@@ -58,6 +58,10 @@ _lib.xp_conv2d_nchw_static_max_bytes.argtypes = []
 _lib.xp_conv2d_nchw_static_max_bytes.restype = C.c_size_t
 _lib.xp_depthwise_conv2d_nhwc.argtypes = [_i64] * 10 + [_vp, _i, _vp, _i, _i, _vp, _i, _vp]
 _lib.xp_deformable_attention.argtypes = [_i64] * 6 + [_vp, _i, _vp, _vp, _vp, _vp, _vp, _i, _vp]
+_lib.xp_mfma_ceiling_ops.argtypes = [_i, _i, _i, _i64]
+_lib.xp_mfma_ceiling_ops.restype = C.c_double
+_lib.xp_mfma_ceiling.argtypes = [_i, _i, _i, _i64, _vp, C.c_size_t, _vp, C.c_size_t, _vp]
+_lib.xp_mfma_ceiling.restype = _i
 _lib.xp_num_configs.argtypes = [_i, _i]
 _lib.xp_describe_config.argtypes = [_i, _i, _i, C.c_char_p, C.c_size_t]
 _lib.xp_force_config.argtypes = [_i, _i, _i]
@@ -252,6 +256,17 @@ def xp_conv2d_nchw_static(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, p
     """xp_conv2d_nchw on the library's built-in layout-change buffer (see include/xp.h: xp_conv2d_nchw_static)."""
     _check(_lib.xp_conv2d_nchw_static(N, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, _ptr(x), _dt(x, in_type),
                                       _ptr(w), _dt(w, w_type), _ptr(out), _dt(out, out_type), _stream(stream)))
+
+
+def xp_mfma_ceiling_ops(in_type, block, waves, iters) -> float:
+    return _lib.xp_mfma_ceiling_ops(DTYPE_BY_NAME.get(in_type, in_type), block, waves, iters)
+
+
+def xp_mfma_ceiling(in_type, block, waves, iters, operands, sink, stream=None):
+    """Register-resident MFMA loop (see include/xp.h: xp_mfma_ceiling)."""
+    _check(_lib.xp_mfma_ceiling(DTYPE_BY_NAME.get(in_type, in_type), block, waves, iters, _ptr(operands),
+                                operands.numel() * operands.element_size(), _ptr(sink), sink.numel() * sink.element_size(),
+                                _stream(stream)))
 
 
 def xp_depthwise_conv2d_nhwc(N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w, x, w, filter_layout, y, stream=None,
