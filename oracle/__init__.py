@@ -60,6 +60,14 @@ def num_threads() -> int:
     return lib().oracle_num_threads()
 
 
+def set_num_threads(n: int) -> None:
+    """Caps the OpenMP threads of the loops (n <= 0 restores the default): for timing the oracle on one core."""
+    L = lib()
+    L.oracle_set_num_threads.argtypes = [C.c_int]
+    L.oracle_set_num_threads.restype = None
+    L.oracle_set_num_threads(int(n))
+
+
 def _ftype(a: np.ndarray) -> int:
     if a.dtype == np.float32:
         return 0

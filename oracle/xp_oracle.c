@@ -35,6 +35,14 @@ static inline int64_t at(int layout, int64_t i, int64_t j, int64_t ld)
 static int bad_type(int t) { return t != ORACLE_F32 && t != ORACLE_BF16; }
 static int bad_layout(int l) { return l != ORACLE_ROW && l != ORACLE_COL; }
 
+/* Not arithmetic: caps the threads of the loops below (timing the oracle on one core). n <= 0 restores the default. */
+void oracle_set_num_threads(int n)
+{
+    static int initial = 0;
+    if (initial == 0) initial = omp_get_max_threads();
+    omp_set_num_threads(n > 0 ? n : initial);
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

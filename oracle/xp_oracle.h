@@ -145,6 +145,8 @@ int oracle_deformable_attention(int64_t batch, int64_t Lq, int64_t heads, int64_
 
 /* Number of OpenMP threads the loops above will use. */
 int oracle_num_threads(void);
+/* Caps the threads of those loops (n <= 0: back to the default).  Bookkeeping for timing, no arithmetic. */
+void oracle_set_num_threads(int n);
 
 #ifdef __cplusplus
 }

@@ -4,7 +4,8 @@
 // nominal peak; this kernel gives the second yardstick, the rate the hardware actually holds on random
 // operands under its power limit.
 //
-// One workgroup per compute unit (a padding LDS allocation keeps a second one away), `waves` waves per
+// One workgroup per compute unit (launched with a dynamic LDS allocation of more than half a compute unit's LDS,
+// which keeps a second one away), `waves` waves per
 // SIMD, each with the accumulator footprint of a 256 x 256 GEMM tile: 8 x 4 blocks of 16 x 16 (or 4 x 2 of
 // 32 x 32) fed from 8 A and 4 B fragments (4 and 2), the same reuse pattern as the GEMM kernels' sub-step.
 #include "xp_internal.hpp"
@@ -57,10 +58,8 @@ template <bool INT8, int MF>
 __global__ __launch_bounds__(512) void mfma_ceiling_kernel(const u32x4 *operands, unsigned *sink, int iters)
 {
     constexpr int MI = MF == 16 ? 8 : 4, NI = MF == 16 ? 4 : 2, NACC = MF == 16 ? 4 : 16;
-    __shared__ char pad[PAD_LDS];
     using B = Block<INT8, MF>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (iters < 0) pad[threadIdx.x] = 1;                 // never true: keeps the allocation
     u32x4 a[MI], b[NI];
     const u32x4 *src = operands + ((size_t)(wave & 7) * 12) * 64 + lane;
 #pragma unroll
@@ -121,10 +120,18 @@ xp_status xp_mfma_ceiling(xp_dtype in_type, int block, int waves, int64_t iters,
     const u32x4 *ops = (const u32x4 *)operands;
     unsigned *out = (unsigned *)sink;
     const int n = (int)iters;
-    if (in_type == XP_BF16 && block == 16) hipLaunchKernelGGL((mfma_ceiling_kernel<false, 16>), grid, wg, 0, s, ops, out, n);
-    else if (in_type == XP_BF16) hipLaunchKernelGGL((mfma_ceiling_kernel<false, 32>), grid, wg, 0, s, ops, out, n);
-    else if (block == 16) hipLaunchKernelGGL((mfma_ceiling_kernel<true, 16>), grid, wg, 0, s, ops, out, n);
-    else hipLaunchKernelGGL((mfma_ceiling_kernel<true, 32>), grid, wg, 0, s, ops, out, n);
+    auto launch = [&](auto kernel) {
+        // more than 64 KB of dynamic LDS has to be allowed per kernel (a host-side attribute; no device work)
+        if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, PAD_LDS) != hipSuccess) return false;
+        hipLaunchKernelGGL(kernel, grid, wg, PAD_LDS, s, ops, out, n);
+        return true;
+    };
+    bool ok;
+    if (in_type == XP_BF16 && block == 16) ok = launch(mfma_ceiling_kernel<false, 16>);
+    else if (in_type == XP_BF16) ok = launch(mfma_ceiling_kernel<false, 32>);
+    else if (block == 16) ok = launch(mfma_ceiling_kernel<true, 16>);
+    else ok = launch(mfma_ceiling_kernel<true, 32>);
+    if (!ok) return XP_ERR_LAUNCH;
     return hipGetLastError() == hipSuccess ? XP_OK : XP_ERR_LAUNCH;
 }
 

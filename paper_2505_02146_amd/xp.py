@@ -84,6 +84,14 @@ _DTYPE = {torch.float32: XP_F32, torch.bfloat16: XP_BF16, torch.int16: XP_BF16, 
 DTYPE_BY_NAME = {"f32": XP_F32, "bf16": XP_BF16, "i8": XP_I8, "i32": XP_I32}
 
 
+def to_device(a):
+    """numpy host array -> torch tensor on the current GPU (uint16 bf16 bit patterns travel as int16)."""
+    import numpy as np
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16).copy()).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
 class XpError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
