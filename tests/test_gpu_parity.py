@@ -241,6 +241,10 @@ CONV_CASES = [
     (1, 7, 9, 8, 5, 3, 2, (1, 2), (2, 1)),          # Cin not a multiple of the K step: general kernel
     (3, 6, 6, 192, 300, 2, 3, (1, 1), (0, 2)),
     (1, 20, 20, 64, 16, 5, 5, (3, 1), (2, 2)),
+    # H = 1: one-dimensional convolutions (Table 5, "Conv1D") straight through the NHWC entry point
+    (4, 1, 50, 64, 48, 1, 3, (1, 1), (0, 1)),
+    (2, 1, 333, 128, 32, 1, 7, (1, 2), (0, 3)),
+    (3, 1, 19, 5, 7, 1, 4, (1, 1), (0, 0)),          # few channels: general kernel
 ]
 
 

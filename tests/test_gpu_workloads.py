@@ -1,7 +1,8 @@
 """The five benchmark workloads at full size, in the launch configuration the benchmark times
-(the library's own variant selection), checked against the CPU oracle on sampled full rows,
-full columns and images, and over the whole output by row/column checksums that follow from
-linearity:  1^T C = (1^T A) B  and  C 1 = A (B 1)  (evaluated in fp64 with numpy)."""
+(the library's own variant selection), checked against the CPU oracle over the WHOLE output (the
+oracle finishes each of them in seconds on the host cores), with row/column checksums that follow from
+linearity as a second line of defence:  1^T C = (1^T A) B  and  C 1 = A (B 1)  (fp64, numpy).
+The same product in the other operand layouts is checked on sampled full rows and columns."""
 import numpy as np
 import pytest
 
@@ -37,30 +38,44 @@ def test_gemm_f32_256(xp, oracle):
     assert xp.xp_last_config(0, "f32") > 0, "the MFMA kernel, not the general one, must serve this workload"
 
 
-def _sampled_gemm_check(xp, oracle, w, kind, got, rng):
-    M, N, K = w["M"], w["N"], w["K"]
+def _checksums(w, kind, got):
+    """Whole-output checksums from linearity (independent of the oracle library)."""
+    M, K = w["M"], w["K"]
     A, B = w["A"], w["B"]                       # A: M x K row-major, B: N x K (column-major K x N)
-    rows = np.sort(rng.choice(M, 48, replace=False))
-    cols = np.sort(rng.choice(N, 48, replace=False))
-    rows[0], rows[-1], cols[0], cols[-1] = 0, M - 1, 0, N - 1
-    if kind == "i8":
-        ref_r = oracle.gemm_i8(len(rows), N, K, np.ascontiguousarray(A[rows]).reshape(-1), "row", B.reshape(-1), "col")
-        ref_c = oracle.gemm_i8(M, len(cols), K, A.reshape(-1), "row", np.ascontiguousarray(B[cols]).reshape(-1), "col")
-        assert np.array_equal(got[rows], ref_r)
-        assert np.array_equal(got[:, cols], ref_c)
-        # whole-output checksums, exact in int64
+    if kind == "i8":                            # exact in int64
         assert np.array_equal(got.astype(np.int64).sum(0), A.astype(np.int64).sum(0) @ B.astype(np.int64).T)
         assert np.array_equal(got.astype(np.int64).sum(1), A.astype(np.int64) @ B.astype(np.int64).sum(0))
     else:
-        ref_r = oracle.gemm_float(len(rows), N, K, np.ascontiguousarray(A[rows]).reshape(-1), "row", B.reshape(-1), "col")
-        ref_c = oracle.gemm_float(M, len(cols), K, A.reshape(-1), "row", np.ascontiguousarray(B[cols]).reshape(-1), "col")
-        check_float(got[rows], ref_r, "sampled rows")
-        check_float(got[:, cols], ref_c, "sampled columns")
         Af, Bf = _f64(A), _f64(B)
         scale = np.sqrt(M * K) * float(np.sqrt(np.mean(Af[:64] ** 2) * np.mean(Bf[:64] ** 2)))
         g = got.astype(np.float64)
         assert np.max(np.abs(g.sum(0) - Af.sum(0) @ Bf.T)) <= 1e-3 * scale
         assert np.max(np.abs(g.sum(1) - Af @ Bf.sum(0))) <= 1e-3 * scale
+
+
+def _full_gemm_check(oracle, w, kind, got, what):
+    """Every element of the output against the oracle."""
+    M, N, K = w["M"], w["N"], w["K"]
+    if kind == "i8":
+        ref = oracle.gemm_i8(M, N, K, w["A"].reshape(-1), "row", w["B"].reshape(-1), "col")
+        assert np.array_equal(got, ref), f"{what}: {int(np.count_nonzero(got != ref))} of {ref.size} elements differ"
+    else:
+        ref = oracle.gemm_float(M, N, K, w["A"].reshape(-1), "row", w["B"].reshape(-1), "col")
+        check_float(got, ref, what)
+    _checksums(w, kind, got)
+
+
+def _sampled_gemm_check(xp, oracle, w, kind, got, rng):
+    M, N, K = w["M"], w["N"], w["K"]
+    A, B = w["A"], w["B"]
+    rows = np.sort(rng.choice(M, 48, replace=False))
+    cols = np.sort(rng.choice(N, 48, replace=False))
+    rows[0], rows[-1], cols[0], cols[-1] = 0, M - 1, 0, N - 1
+    ref_r = oracle.gemm_float(len(rows), N, K, np.ascontiguousarray(A[rows]).reshape(-1), "row", B.reshape(-1), "col")
+    ref_c = oracle.gemm_float(M, len(cols), K, A.reshape(-1), "row", np.ascontiguousarray(B[cols]).reshape(-1), "col")
+    check_float(got[rows], ref_r, "sampled rows")
+    check_float(got[:, cols], ref_c, "sampled columns")
+    _checksums(w, kind, got)
 
 
 def test_gemm_bf16_4096(xp, oracle):
@@ -71,7 +86,7 @@ def test_gemm_bf16_4096(xp, oracle):
     xp.xp_gemm(M, N, K, 1.0, dev(w["A"].reshape(-1)), "row", K, dev(w["B"].reshape(-1)), "col", K, 0.0, c, "row", N,
                a_type="bf16", b_type="bf16")
     assert xp.xp_last_config(0, "bf16") > 0
-    _sampled_gemm_check(xp, oracle, w, "bf16", c.cpu().numpy(), np.random.default_rng(0))
+    _full_gemm_check(oracle, w, "bf16", c.cpu().numpy(), "gemm_bf16_4096, all 4096 x 4096 elements")
 
 
 @pytest.mark.parametrize("la,lb", [("row", "row"), ("col", "col"), ("col", "row")])
@@ -100,7 +115,7 @@ def test_gemm_i8_4096x4096x8192(xp, oracle):
     c = torch.full((M, N), -1, dtype=torch.int32, device="cuda")
     xp.xp_gemm(M, N, K, 1.0, dev(w["A"].reshape(-1)), "row", K, dev(w["B"].reshape(-1)), "col", K, 0.0, c, "row", N)
     assert xp.xp_last_config(0, "i8") > 0
-    _sampled_gemm_check(xp, oracle, w, "i8", c.cpu().numpy(), np.random.default_rng(1))
+    _full_gemm_check(oracle, w, "i8", c.cpu().numpy(), "gemm_i8_4096x4096x8192, all 4096 x 4096 elements")
 
 
 @pytest.mark.parametrize("name", ["bgemm_bf16_qk", "bgemm_bf16_pv"])
@@ -129,10 +144,11 @@ def test_conv_bf16_56(xp, oracle):
     assert xp.xp_last_config(2, "bf16") > 0
     got = out.cpu().numpy()
     assert np.all(np.isfinite(got))
-    for n in (0, 13, N - 1):                     # three whole images through the oracle
-        ref = oracle.conv2d_nhwc(np.ascontiguousarray(w["input"][n:n + 1]), w["filter"], N=1, H=H, W=W, Cin=Cin,
-                                 Cout=Cout, R=R, S=S, pad=(1, 1))
-        check_float(got[n:n + 1], ref, f"conv image {n}")
+    # all 32 images through the oracle (a few seconds on the host cores)
+    ref = oracle.conv2d_nhwc(w["input"], w["filter"], N=N, H=H, W=W, Cin=Cin, Cout=Cout, R=R, S=S, pad=(1, 1))
+    check_float(got, ref, "conv_bf16_56, all 32 images")
+    for n in (0, 13, N - 1):                     # and image by image, so that a failure names the image
+        check_float(got[n:n + 1], ref[n:n + 1], f"conv image {n}")
     # whole-output checksum: summing the output over channels k equals convolving with the
     # channel-summed filter; evaluated per image as sum over all positions (fp64, numpy)
     x = _f64(w["input"])
