@@ -13,7 +13,7 @@ namespace xp {
 
 namespace {
 
-constexpr int kMaxVariants = 128;                       // 67 bf16 variants at the last count; checked in build_tables
+constexpr int kMaxVariants = 128;                       // 58 bf16 variants at the last count; checked in build_tables
 const Variant *g_table[3][kMaxVariants];
 int g_count[3] = {0, 0, 0};
 std::once_flag g_once;
@@ -37,7 +37,6 @@ void build_tables()
         n += gemv_variants(types[s], g_table[s] + n);
         n += dl_bnm_variants(types[s], g_table[s] + n);       // newest last: the older variants keep their indices
         n += dl_asm_variants(types[s], g_table[s] + n);
-        n += dl_weave_variants(types[s], g_table[s] + n);
         if (n > kMaxVariants) { fprintf(stderr, "xp: variant table overflow (%d)\n", n); abort(); }
         g_count[s] = n;
     }
@@ -93,11 +92,11 @@ struct Tuned {
 
 const Tuned kTuned[] = {
     {XP_OP_GEMM, XP_F32, 1, 256, 256, 256, true, false, "f32 64x64x16 waves 2x2 mfma32x32x2"},
-    {XP_OP_GEMM, XP_BF16, 1, 4096, 4096, 4096, true, true, "bf16 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly woven, mfma16"},
-    {XP_OP_GEMM, XP_I8, 1, 4096, 4096, 8192, true, true, "i8 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly woven, mfma16"},
+    {XP_OP_GEMM, XP_BF16, 1, 4096, 4096, 4096, true, true, "bf16 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly, mfma16"},
+    {XP_OP_GEMM, XP_I8, 1, 4096, 4096, 8192, true, true, "i8 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly, mfma16"},
     {XP_OP_GEMM_BATCHED, XP_BF16, 96, 512, 512, 64, true, true, "bf16 64x128-stream x128B single-k-step producer/consumer nt-stores mfma32"},
     {XP_OP_GEMM_BATCHED, XP_BF16, 96, 512, 64, 512, true, false, "bf16 64x64x128B waves 2x2 k-group-interleaved mfma32"},
-    {XP_OP_CONV2D, XP_BF16, 1, 100352, 256, 2304, true, true, "bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 2(A)+2(B) direct-to-lds, reads as assembly woven, mfma16"},
+    {XP_OP_CONV2D, XP_BF16, 1, 100352, 256, 2304, true, true, "bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 2(A)+2(B) direct-to-lds, reads as assembly, mfma16"},
 #include "xp_tuned_table.inc"
 };
 constexpr int kNumTuned = (int)(sizeof kTuned / sizeof kTuned[0]);

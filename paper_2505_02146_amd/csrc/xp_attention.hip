@@ -193,6 +193,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 && HV == 2) ? 4 : 1) void attn_mf
     const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.V + b * p.strideV, (unsigned)((long long)(p.Lk - 1) * p.ldv + KROW * HV));
 
     // the wave's queries: B operand of S^T, two k steps per 64 head dimensions
+    // The parameters the key-tile loop uses, as values computed here: a parameter the compiler chose to load again
+    // inside the loop would be a scalar load, which shares its counter with the LDS reads that the loop waits for in
+    // part (s_waitcnt lgkmcnt(n), n > 0, assumes in-order return, which scalar loads do not promise)
+    const int ldk = __builtin_amdgcn_readfirstlane((int)p.ldk), ldv = __builtin_amdgcn_readfirstlane((int)p.ldv);
+    const int Lk = __builtin_amdgcn_readfirstlane(p.Lk);
     u32x4 qf[2 * HV];
 #pragma unroll
     for (int s = 0; s < 2 * HV; ++s)
@@ -208,7 +213,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 && HV == 2) ? 4 : 1) void attn_mf
 #pragma unroll
             for (int i = 0; i < BPW; ++i) {
                 const int blk = wave * BPW + i;
-                const unsigned off = (unsigned)((j0 + blk * 8 + krow) * p.ldk) + hv * KROW + kchunk;
+                const unsigned off = (unsigned)((j0 + blk * 8 + krow) * ldk) + hv * KROW + kchunk;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void *)(ks + koff + hv * K_TILE + blk * 1024), 16, off, 0, 0, 0);
             }
     };
@@ -219,7 +224,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 && HV == 2) ? 4 : 1) void attn_mf
 #pragma unroll
             for (int i = 0; i < BPW; ++i) {
                 const int blk = wave * BPW + i;
-                const unsigned off = (unsigned)((j0 + blk * 8 + krow) * p.ldv) + hv * KROW + kchunk;
+                const unsigned off = (unsigned)((j0 + blk * 8 + krow) * ldv) + hv * KROW + kchunk;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void *)(vs + voff + hv * V_TILE + blk * 1024), 16, off, 0, 0, 0);
             }
     };
@@ -235,8 +240,10 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 && HV == 2) ? 4 : 1) void attn_mf
     for (int x = 0; x < 4; ++x) vx[x] = lds_address(vs) + vrow * KROW + 8 * (va & 1) + (((2 * x + vchunk) ^ vsw) << 4);
     auto read_v = [&](unsigned at, auto slot_c, auto hv_c, auto h_c) {
         constexpr int OFF = decltype(slot_c)::value * VT + decltype(hv_c)::value * V_TILE + 32 * decltype(h_c)::value * KROW;
-        const lds_tr_u32x2 lo = lds_read_tr16_b64<OFF>(at), hi = lds_read_tr16_b64<OFF + 16 * KROW>(at);
-        return u32x4{lo[0], lo[1], hi[0], hi[1]};
+        FragHalves f;                                    // composed into one fragment only after the wait for it
+        f.lo = lds_read_tr16_b64<OFF>(at);
+        f.hi = lds_read_tr16_b64<OFF + 16 * KROW>(at);
+        return f;
     };
 
     const float c = p.scale * LOG2E;                     // scores are kept in units of log2
@@ -247,7 +254,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 && HV == 2) ? 4 : 1) void attn_mf
 #pragma unroll
     for (int x = 0; x < 4 * HV; ++x) acc[x] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-    const int NT = (p.Lk + BK - 1) / BK;
+    const int NT = (Lk + BK - 1) / BK;
 #pragma unroll
     for (int u = 0; u < D; ++u) {
         issue_k(u * BK, u * KT);
@@ -285,7 +292,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 && HV == 2) ? 4 : 1) void attn_mf
             for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    if (j0 + kb * 16 + 4 * g + v >= p.Lk) s[kb][v] = c < 0.0f ? INFINITY : -INFINITY;
+                    if (j0 + kb * 16 + 4 * g + v >= Lk) s[kb][v] = c < 0.0f ? INFINITY : -INFINITY;
         }
         // largest scaled score of the tile: the extreme raw score times c (c may be negative)
         float mx = s[0][0];
@@ -330,7 +337,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 && HV == 2) ? 4 : 1) void attn_mf
         // wait before a group's MFMAs leaves the reads of the younger groups outstanding.
         {
             constexpr int NG = 4 * HV, AHEAD = 3;
-            u32x4 vf[NG][2];
+            FragHalves vf[NG][2];
             auto load_group = [&](auto gi_c) {
                 constexpr int GI = decltype(gi_c)::value;
                 const unsigned at = vx[GI % 4];
@@ -341,9 +348,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 && HV == 2) ? 4 : 1) void attn_mf
             static_for<NG>([&](auto gi_c) {
                 constexpr int GI = decltype(gi_c)::value;
                 constexpr int YOUNGER = (NG - 1 - GI < AHEAD - 1 ? NG - 1 - GI : AHEAD - 1);
-                lds_tr_wait<4 * YOUNGER>(vf[GI][0], vf[GI][1]);
+                lds_wait<4 * YOUNGER>();
+                frag_tie(vf[GI][0]);
+                frag_tie(vf[GI][1]);
 #pragma unroll
-                for (int h = 0; h < 2; ++h) acc[GI] = mma(vf[GI][h], pf[h], acc[GI]);
+                for (int h = 0; h < 2; ++h) acc[GI] = mma(frag_value(vf[GI][h]), pf[h], acc[GI]);
                 __builtin_amdgcn_sched_barrier(0);       // or the scheduler collects the MFMAs behind the last wait
                 if constexpr (GI + AHEAD < NG) load_group(std::integral_constant<int, GI + AHEAD>{});
             });
@@ -353,7 +362,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 && HV == 2) ? 4 : 1) void attn_mf
     };
     // whole turns of the ring over the tiles that lie inside Lk, then what is left: fewer than NS such tiles and,
     // if Lk is no multiple of the tile, the ragged last one (NS tiles at most; the slots go on from 0)
-    const int NF = p.Lk / BK;
+    const int NF = Lk / BK;
     int t = 0;
     for (; t + NS <= NF; t += NS)
         static_for<NS>([&](auto u_c) { step(t + decltype(u_c)::value, std::false_type{}, u_c); });

@@ -83,6 +83,21 @@ __device__ __forceinline__ void lds_tie(V &value)
     asm volatile("" : "+v"(value));
 }
 
+// A 16-byte MFMA fragment gathered by two transposing reads.  The halves are separate values until the wait for
+// them has passed: a fragment composed from the two read results right away could be given registers of its own,
+// and the copies into them would execute before the data has arrived.
+struct FragHalves {
+    lds_tr_u32x2 lo, hi;
+};
+__device__ __forceinline__ void frag_tie(lds_tr_u32x4 &f) { lds_tie(f); }
+__device__ __forceinline__ void frag_tie(FragHalves &f)
+{
+    lds_tie(f.lo);
+    lds_tie(f.hi);
+}
+__device__ __forceinline__ lds_tr_u32x4 frag_value(const lds_tr_u32x4 &f) { return f; }
+__device__ __forceinline__ lds_tr_u32x4 frag_value(const FragHalves &f) { return lds_tr_u32x4{f.lo[0], f.lo[1], f.hi[0], f.hi[1]}; }
+
 // the two together
 template <int N, class... V>
 __device__ __forceinline__ void lds_tr_wait(V &...values)

@@ -56,11 +56,8 @@ struct DlParams {
 };
 
 template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_, bool SPREAD_ = false, int OCC_ = 1, int MF_ = 32, bool NT_ = false,
-          int NSA_ = NS_, bool WEAVE_ = false>
+          int NSA_ = NS_>
 struct DlTile {
-    // assembly-read modes: the reads of the next fragment set are dealt out between the MFMA block rows of the
-    // current one instead of being issued as one burst in front of them
-    static constexpr bool WEAVE = WEAVE_;
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NS = NS_, RB = RB_;
     // ring depth of the A buffers (NS is that of the B buffers): one more A buffer than B buffers
     // gives the A loads an extra K step to land where LDS cannot hold a third whole stage
@@ -404,10 +401,10 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         issue_a(kt, a_off, lo, hi < T::IA ? hi : T::IA, check_c);
         issue_b(kt, b_off, lo > T::IA ? lo - T::IA : 0, hi - T::IA, check_c);
     };
-    // ASMR: every fragment read is assembly (see xp_lds_tr.hpp): offsets are instruction constants, the waits
-    // are mma_all's.  AO / BO: byte offsets of the A / B buffer as constants (the unrolled main loop), or -1:
-    // taken from a_off / b_off at run time (one vector addition per address register).  An offset field holds
-    // 16 bits; buffers further up are reached from a second set of address registers 64 KB higher.
+    // ASMR: every fragment read is assembly (see xp_lds_tr.hpp): offsets are instruction constants, the waits are
+    // explicit.  AO / BO: byte offsets of the A / B buffer as constants (the unrolled main loop), or -1: taken from
+    // a_off / b_off at run time (one vector addition per address register).  An offset field holds 16 bits;
+    // buffers further up are reached from a second set of address registers 64 KB higher.
     constexpr int A_TOP = AMM ? 36 * RAM : (T::MI - 1) * MF * RB;        // largest offset within a buffer
     constexpr int B_TOP = BNM ? 36 * RBN : (T::NI - 1) * MF * RB;
     constexpr int NFA = AMM ? T::MI : T::PH, NFB = BNM ? T::NI : T::PH;  // address registers per operand
@@ -418,49 +415,16 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         for (int x = 0; x < NFA; ++x) fa_far[x] = lds_base + (AMM ? fam[AMM ? x : 0] : fa[AMM ? 0 : x]) + 65536;
     if constexpr (B_FAR)
         for (int x = 0; x < NFB; ++x) fb_far[x] = lds_base + T::B_BASE + (BNM ? fbn[BNM ? x : 0] : fb[BNM ? 0 : x]) + 65536;
-    auto read_frags_asm = [&](auto ao_c, auto bo_c, auto kk_c, int a_off, int b_off, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
-        constexpr int AO = decltype(ao_c)::value, BO = decltype(bo_c)::value, KK = decltype(kk_c)::value;
-        // operand along K: one address register per sub-step, the blocks are offsets; operand along its
-        // outer index: one address register per block (the swizzle), the sub-step is an offset
-        constexpr int AREL = AO < 0 ? 0 : AO;
-        constexpr bool AFAR = AREL + A_TOP >= 65536;
-        constexpr int AIMM = (AFAR ? AREL - 65536 : AREL) + (AMM ? KK * 32 * RAM : 0);
-        if constexpr (AMM) {
-            static_for<T::MI>([&](auto i_c) {
-                constexpr int I = decltype(i_c)::value;
-                const unsigned at = AO < 0 ? lds_base + a_off + fam[I] : (AFAR ? fa_far[A_FAR ? I : 0] : lds_base + fam[I]);
-                const lds_tr_u32x2 lo = lds_read_tr16_b64<AIMM>(at), hi = lds_read_tr16_b64<AIMM + 4 * RAM>(at);
-                af[I] = u32x4{lo[0], lo[1], hi[0], hi[1]};
-            });
-        } else {
-            const unsigned at = AO < 0 ? lds_base + a_off + fa[KK] : (AFAR ? fa_far[A_FAR ? KK : 0] : lds_base + fa[KK]);
-            static_for<T::MI>([&](auto i_c) {
-                constexpr int I = decltype(i_c)::value;
-                af[I] = lds_read_b128<AIMM + I * MF * RB>(at);
-            });
-        }
-        constexpr int BREL = BO < 0 ? 0 : BO - T::B_BASE;
-        constexpr bool BFAR = BREL + B_TOP >= 65536;
-        constexpr int BIMM = (BFAR ? BREL - 65536 : BREL) + (BNM ? KK * 32 * RBN : 0);
-        const unsigned b_rt = lds_base + b_off;          // used with a run-time buffer offset only
-        if constexpr (BNM) {
-            static_for<T::NI>([&](auto j_c) {
-                constexpr int J = decltype(j_c)::value;
-                const unsigned at = BO < 0 ? b_rt + fbn[J] : (BFAR ? fb_far[B_FAR ? J : 0] : lds_base + T::B_BASE + fbn[J]);
-                const lds_tr_u32x2 lo = lds_read_tr16_b64<BIMM>(at), hi = lds_read_tr16_b64<BIMM + 4 * RBN>(at);
-                bf[J] = u32x4{lo[0], lo[1], hi[0], hi[1]};
-            });
-        } else {
-            const unsigned at = BO < 0 ? b_rt + fb[KK] : (BFAR ? fb_far[B_FAR ? KK : 0] : lds_base + T::B_BASE + fb[KK]);
-            static_for<T::NI>([&](auto j_c) {
-                constexpr int J = decltype(j_c)::value;
-                bf[J] = lds_read_b128<BIMM + J * MF * RB>(at);
-            });
-        }
-    };
+    // A fragment as the reads deliver it: one 16-byte read, or the two 8-byte halves of a pair of transposing reads.
+    // The halves stay separate values until the wait for them has passed (frag_tie); composing the four words
+    // earlier would let a register copy run ahead of the data.
+    using AFrag = typename std::conditional<AMM, FragHalves, u32x4>::type;
+    using BFrag = typename std::conditional<BNM, FragHalves, u32x4>::type;
     // one fragment of the set: F < NI the B fragment F, else the A fragment F - NI (the B fragments first: every
-    // block row of the next sub-step needs all of them)
-    auto read_frag_asm = [&](auto ao_c, auto bo_c, auto kk_c, auto f_c, int a_off, int b_off, u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
+    // block row of the next sub-step needs all of them).  Operand along K: one address register per sub-step, the
+    // blocks are offsets; operand along its outer index: one address register per block (the swizzle), the sub-step
+    // is an offset
+    auto read_frag_asm = [&](auto ao_c, auto bo_c, auto kk_c, auto f_c, int a_off, int b_off, AFrag (&af)[T::MI], BFrag (&bf)[T::NI]) {
         constexpr int AO = decltype(ao_c)::value, BO = decltype(bo_c)::value, KK = decltype(kk_c)::value, F = decltype(f_c)::value;
         if constexpr (F >= T::NI) {
             constexpr int I = F - T::NI;
@@ -469,8 +433,8 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             constexpr int AIMM = (AFAR ? AREL - 65536 : AREL) + (AMM ? KK * 32 * RAM : 0);
             if constexpr (AMM) {
                 const unsigned at = AO < 0 ? lds_base + a_off + fam[I] : (AFAR ? fa_far[A_FAR ? I : 0] : lds_base + fam[I]);
-                const lds_tr_u32x2 lo = lds_read_tr16_b64<AIMM>(at), hi = lds_read_tr16_b64<AIMM + 4 * RAM>(at);
-                af[I] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                af[I].lo = lds_read_tr16_b64<AIMM>(at);
+                af[I].hi = lds_read_tr16_b64<AIMM + 4 * RAM>(at);
             } else {
                 const unsigned at = AO < 0 ? lds_base + a_off + fa[KK] : (AFAR ? fa_far[A_FAR ? KK : 0] : lds_base + fa[KK]);
                 af[I] = lds_read_b128<AIMM + I * MF * RB>(at);
@@ -480,39 +444,42 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             constexpr int BREL = BO < 0 ? 0 : BO - T::B_BASE;
             constexpr bool BFAR = BREL + B_TOP >= 65536;
             constexpr int BIMM = (BFAR ? BREL - 65536 : BREL) + (BNM ? KK * 32 * RBN : 0);
-            const unsigned b_rt = lds_base + b_off;
+            const unsigned b_rt = lds_base + b_off;          // used with a run-time buffer offset only
             if constexpr (BNM) {
                 const unsigned at = BO < 0 ? b_rt + fbn[J] : (BFAR ? fb_far[B_FAR ? J : 0] : lds_base + T::B_BASE + fbn[J]);
-                const lds_tr_u32x2 lo = lds_read_tr16_b64<BIMM>(at), hi = lds_read_tr16_b64<BIMM + 4 * RBN>(at);
-                bf[J] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                bf[J].lo = lds_read_tr16_b64<BIMM>(at);
+                bf[J].hi = lds_read_tr16_b64<BIMM + 4 * RBN>(at);
             } else {
                 const unsigned at = BO < 0 ? b_rt + fb[KK] : (BFAR ? fb_far[B_FAR ? KK : 0] : lds_base + T::B_BASE + fb[KK]);
                 bf[J] = lds_read_b128<BIMM + J * MF * RB>(at);
             }
         }
     };
-    // WEAVE: one MFMA sub-step on the set (ca, cb) with the reads of the set (na, nb) -- sub-step KK of the buffers at
+    // One MFMA sub-step on the set (ca, cb) with the reads of the set (na, nb) -- sub-step KK of the buffers at
     // AO / BO -- dealt out behind its block rows: a wave that issues its reads as one burst keeps the matrix pipe
-    // idle meanwhile when its SIMD neighbour, in step with it, does the same.  The last block rows get no reads, so
+    // idle meanwhile when its SIMD neighbour, in step with it, does the same (a cycle counter in the kernel shows
+    // 2430 cycles per K step with bursts, 2140 dealt out; 2048 is the MFMA time).  The last block rows get no reads, so
     // that the reads have returned when the step's barrier asks for it.  Columns are walked back and forth: between
     // two consecutive MFMAs only one operand changes.  after_row(i) is called behind block row i (the second sub-step
-    // of a K step issues the step's global loads there, a share per row).
-    auto weave = [&](auto ao_c, auto bo_c, auto kk_c, int a_off, int b_off, u32x4 (&ca)[T::MI], u32x4 (&cb)[T::NI], u32x4 (&na)[T::MI],
-                     u32x4 (&nb)[T::NI], auto &&after_row) {
+    // of a K step issues the step's global loads there, a share per row).  Every wait is for all LDS operations of the
+    // wave (the counter also counts scalar loads, which may return out of order: no partial waits).
+    auto weave = [&](auto ao_c, auto bo_c, auto kk_c, int a_off, int b_off, AFrag (&ca)[T::MI], BFrag (&cb)[T::NI], AFrag (&na)[T::MI],
+                     BFrag (&nb)[T::NI], auto &&after_row) {
         constexpr int NF = T::MI + T::NI;                               // fragments to read
         constexpr int ROWS = T::MI > 2 ? T::MI - 2 : 1;                 // block rows that carry reads
         constexpr int PER = (NF + ROWS - 1) / ROWS;
         lds_wait<0>();                                                  // (ca, cb) were read during the sub-step before
 #pragma unroll
-        for (int i = 0; i < T::MI; ++i) lds_tie(ca[i]);
+        for (int i = 0; i < T::MI; ++i) frag_tie(ca[i]);
 #pragma unroll
-        for (int j = 0; j < T::NI; ++j) lds_tie(cb[j]);
+        for (int j = 0; j < T::NI; ++j) frag_tie(cb[j]);
         static_for<T::MI>([&](auto i_c) {
             constexpr int I = decltype(i_c)::value;
 #pragma unroll
             for (int jj = 0; jj < T::NI; ++jj) {
                 const int j = (I & 1) ? T::NI - 1 - jj : jj;
-                if constexpr (MF == 16) acc[I][j] = Acc<INT8, 16>::mma(cb[j], ca[I], acc[I][j]);
+                // 16x16 blocks are computed transposed (B fragment as the first operand): see mma_all
+                if constexpr (MF == 16) acc[I][j] = Acc<INT8, 16>::mma(frag_value(cb[j]), frag_value(ca[I]), acc[I][j]);
             }
             __builtin_amdgcn_sched_barrier(0);
             static_for<PER>([&](auto r_c) {
@@ -530,16 +497,6 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         for (int j = 0; j < T::NI; ++j) bf[j] = *(const u32x4 *)(lds + b_off + fb[kk] + j * MF * RB);
     };
     auto mma_all = [&](u32x4 (&af)[T::MI], u32x4 (&bf)[T::NI]) {
-        // ASMR: the newest fragment set (read one sub-step ahead of its use) may still be on its way,
-        // everything older must have come back (the counter holds 15: beyond that, part of the newest too)
-        if constexpr (ASMR) {
-            constexpr int READS = (AMM ? 2 : 1) * T::MI + (BNM ? 2 : 1) * T::NI;
-            lds_wait<(READS < 15 ? READS : 15)>();
-#pragma unroll
-            for (int i = 0; i < T::MI; ++i) lds_tie(af[i]);
-#pragma unroll
-            for (int j = 0; j < T::NI; ++j) lds_tie(bf[j]);
-        }
 #pragma unroll
         for (int i = 0; i < T::MI; ++i)
 #pragma unroll
@@ -555,8 +512,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     constexpr int PENDING = T::PENDING;                  // loads that may still be in flight at a barrier
     constexpr int A_END = T::NSA * T::A_BYTES, B_END = T::B_BASE + T::NS * T::B_BYTES;
     if (KT > 0) {
-        u32x4 xa[T::MI], xb[T::NI], ya[T::MI], yb[T::NI];     // fragment sets of even / odd sub-steps
-        constexpr bool WV = ASMR && T::WEAVE;
+        AFrag xa[T::MI], ya[T::MI];                           // fragment sets of even / odd sub-steps
+        BFrag xb[T::NI], yb[T::NI];
+        constexpr bool WV = ASMR;
         if constexpr (WV) {
             // woven: step j issues B(j+NS) and A(j+NSA), the deeper ring's last, and so do the steps before the first:
             // every buffer of both rings is filled before the loop
@@ -588,8 +546,11 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         typedef std::integral_constant<int, -1> RunTime;
         typedef std::integral_constant<int, 0> Zero;
         typedef std::integral_constant<int, 1> One;
-        if constexpr (ASMR) read_frags_asm(Zero{}, std::integral_constant<int, T::B_BASE>{}, Zero{}, 0, 0, xa, xb);
-        else read_frags(0, T::B_BASE, 0, xa, xb);
+        if constexpr (ASMR) {
+            static_for<T::MI + T::NI>([&](auto f_c) { read_frag_asm(Zero{}, std::integral_constant<int, T::B_BASE>{}, Zero{}, f_c, 0, 0, xa, xb); });
+        } else {
+            read_frags(0, T::B_BASE, 0, xa, xb);
+        }
         int cur_a = 0, cur_b = T::B_BASE;
         int fill_a = (T::NSA - 1) * T::A_BYTES, fill_b = T::B_BASE + (T::NS - 1) * T::B_BYTES;
         // POS >= 0: the step's position in the rings as a constant (the step runs POS steps after one that
@@ -607,7 +568,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             // loads go into the buffers read in step kt-1
             const int into_a = POS >= 0 ? ((POS + T::NSA - 1) % T::NSA) * T::A_BYTES : fill_a;
             const int into_b = POS >= 0 ? T::B_BASE + ((POS + T::NS - 1) % T::NS) * T::B_BYTES : fill_b;
-            if constexpr (ASMR && T::WEAVE) {
+            if constexpr (ASMR) {
                 // (issued in the second sub-step, below)
             } else if constexpr (T::ASYM) {
                 if constexpr (!T::B_DEEP) issue_b(kt + T::NS - 1, into_b, 0, T::IB, check_c);
@@ -619,36 +580,23 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             if constexpr (ASMR) {
                 // two sub-steps: the second one's fragments (set Y) are read while the first is multiplied
                 static_assert(T::PH == 2 && !ODD && !T::SPREAD, "assembly reads: two sub-steps per K step");
-                if constexpr (T::WEAVE) {
-                    // The barrier in the middle of the step is passed when every wave has read the current buffers
-                    // for the last time, so the second sub-step refills them: with the loads for K step kt + NS
-                    // (A: kt + NSA), a share behind each block row.  They have a whole K step to land, not half.
-                    weave(std::integral_constant<int, CA>{}, std::integral_constant<int, CB>{}, One{}, now_a, now_b, xa, xb, ya, yb, [](auto) {});
-                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
-                    __builtin_amdgcn_s_barrier();
-                    weave(std::integral_constant<int, NA>{}, std::integral_constant<int, NB>{}, Zero{}, nxt_a, nxt_b, ya, yb, xa, xb, [&](auto i_c) {
-                        constexpr int I = decltype(i_c)::value;
-                        constexpr int LO = I * IT / T::MI, HI = (I + 1) * IT / T::MI;
-                        if constexpr (T::ASYM && !T::B_DEEP) {       // B first: the deeper ring's loads are the ones that may stay in flight
-                            issue_b(kt + T::NS, now_b, LO, HI < T::IB ? HI : T::IB, check_c);
-                            issue_a(kt + T::NSA, now_a, LO > T::IB ? LO - T::IB : 0, HI - T::IB, check_c);
-                        } else {
-                            issue_a(kt + T::NSA, now_a, LO, HI < T::IA ? HI : T::IA, check_c);
-                            issue_b(kt + T::NS, now_b, LO > T::IA ? LO - T::IA : 0, HI - T::IA, check_c);
-                        }
-                    });
-                } else {
-                read_frags_asm(std::integral_constant<int, CA>{}, std::integral_constant<int, CB>{}, One{}, now_a, now_b, ya, yb);
-                __builtin_amdgcn_sched_barrier(0);
-                mma_all(xa, xb);
-                __builtin_amdgcn_sched_barrier(0);
+                // The barrier in the middle of the step is passed when every wave has read the current buffers
+                // for the last time, so the second sub-step refills them: with the loads for K step kt + NS
+                // (A: kt + NSA), a share behind each block row.  They have a whole K step to land, not half.
+                weave(std::integral_constant<int, CA>{}, std::integral_constant<int, CB>{}, One{}, now_a, now_b, xa, xb, ya, yb, [](auto) {});
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
                 __builtin_amdgcn_s_barrier();
-                read_frags_asm(std::integral_constant<int, NA>{}, std::integral_constant<int, NB>{}, Zero{}, nxt_a, nxt_b, xa, xb);
-                __builtin_amdgcn_sched_barrier(0);
-                mma_all(ya, yb);
-                __builtin_amdgcn_sched_barrier(0);
-                }
+                weave(std::integral_constant<int, NA>{}, std::integral_constant<int, NB>{}, Zero{}, nxt_a, nxt_b, ya, yb, xa, xb, [&](auto i_c) {
+                    constexpr int I = decltype(i_c)::value;
+                    constexpr int LO = I * IT / T::MI, HI = (I + 1) * IT / T::MI;
+                    if constexpr (T::ASYM && !T::B_DEEP) {       // B first: the deeper ring's loads are the ones that may stay in flight
+                        issue_b(kt + T::NS, now_b, LO, HI < T::IB ? HI : T::IB, check_c);
+                        issue_a(kt + T::NSA, now_a, LO > T::IB ? LO - T::IB : 0, HI - T::IB, check_c);
+                    } else {
+                        issue_a(kt + T::NSA, now_a, LO, HI < T::IA ? HI : T::IA, check_c);
+                        issue_b(kt + T::NS, now_b, LO > T::IA ? LO - T::IA : 0, HI - T::IA, check_c);
+                    }
+                });
             } else {
 #pragma unroll
                 for (int ph = 0; ph < T::PH - 1; ++ph) {
@@ -1006,13 +954,12 @@ hipError_t dl_asm_launch(const Problem &q)
     return hipGetLastError();
 }
 
-#define XP_DL_ASM_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NSA, NSB, OCC, EFF) XP_DL_ASM_VARIANT_W(NAME, TYPESTR, INT8, BM, BN, WM, WN, NSA, NSB, OCC, EFF, false, "")
-#define XP_DL_ASM_VARIANT_W(NAME, TYPESTR, INT8, BM, BN, WM, WN, NSA, NSB, OCC, EFF, WEAVE, WEAVESTR)                      \
-    typedef DlTile<BM, BN, WM, WN, NSB, 128, false, OCC, 16, false, NSA, WEAVE> NAME##_tile;                              \
+#define XP_DL_ASM_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, NSA, NSB, OCC, EFF)                                          \
+    typedef DlTile<BM, BN, WM, WN, NSB, 128, false, OCC, 16, false, NSA> NAME##_tile;                                     \
     bool NAME##_can(const Problem &q) { return dl_can_run_common<INT8>(q, BM, BN, 128, 16); }                             \
     hipError_t NAME##_launch(const Problem &q) { return dl_asm_launch<INT8, NAME##_tile>(q); }                            \
     double NAME##_cost(const Problem &q) { return dl_cost<NAME##_tile>(q, EFF); }                                         \
-    const Variant NAME = {TYPESTR " " #BM "x" #BN "x128B waves " #WM "x" #WN " ring " #NSA "(A)+" #NSB "(B) direct-to-lds, reads as assembly" WEAVESTR ", mfma16", \
+    const Variant NAME = {TYPESTR " " #BM "x" #BN "x128B waves " #WM "x" #WN " ring " #NSA "(A)+" #NSB "(B) direct-to-lds, reads as assembly, mfma16", \
                           NAME##_can, NAME##_launch, NAME##_cost};
 
 XP_DL_ASM_VARIANT(kBfAsm256x256a3, "bf16", false, 256, 256, 2, 4, 3, 2, 1, 0.55)
@@ -1039,13 +986,6 @@ XP_DL_ASM_VARIANT(kI8Asm128x128, "i8", true, 128, 128, 2, 2, 2, 2, 2, 0.36)
 XP_DL_ASM_VARIANT(kI8Asm256x128, "i8", true, 256, 128, 4, 2, 3, 3, 1, 0.46)
 XP_DL_ASM_VARIANT(kI8Asm128x256, "i8", true, 128, 256, 2, 4, 3, 3, 1, 0.46)
 XP_DL_ASM_VARIANT(kI8Asm256x256, "i8", true, 256, 256, 2, 4, 2, 2, 1, 0.54)
-// reads woven between the MFMA block rows
-XP_DL_ASM_VARIANT_W(kBfWv256x256a3, "bf16", false, 256, 256, 2, 4, 3, 2, 1, 0.57, true, " woven")
-XP_DL_ASM_VARIANT_W(kBfWv256x256, "bf16", false, 256, 256, 2, 4, 2, 2, 1, 0.56, true, " woven")
-XP_DL_ASM_VARIANT_W(kBfWv224x256, "bf16", false, 224, 256, 2, 4, 2, 2, 1, 0.51, true, " woven")
-XP_DL_ASM_VARIANT_W(kI8Wv256x256a3, "i8", true, 256, 256, 2, 4, 3, 2, 1, 0.57, true, " woven")
-XP_DL_ASM_VARIANT_W(kI8Wv256x256, "i8", true, 256, 256, 2, 4, 2, 2, 1, 0.56, true, " woven")
-
 }  // namespace
 
 int dl_asm_variants(xp_dtype in_type, const Variant **out)
@@ -1058,44 +998,6 @@ int dl_asm_variants(xp_dtype in_type, const Variant **out)
     }
     if (in_type == XP_I8) {
         const Variant *v[] = {&kI8Asm256x256a3, &kI8Asm256x256, &kI8Asm128x128, &kI8Asm256x128, &kI8Asm128x256};
-        for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
-        return (int)(sizeof v / sizeof *v);
-    }
-    return 0;
-}
-
-typedef DlTile<224, 256, 2, 4, 2, 128, false, 1, 16, false, 3, true> TwoHiW;
-typedef DlTile<192, 256, 2, 4, 2, 128, false, 1, 16, false, 3, true> TwoLoW;
-typedef DlTile<224, 256, 2, 4, 2, 128, false, 1, 16, false, 2, true> TwoHiW2;
-typedef DlTile<192, 256, 2, 4, 2, 128, false, 1, 16, false, 2, true> TwoLoW2;
-bool kBfWvTwoHeights_can(const Problem &q) { return dl_can_run_common<false>(q, 224, 256, 128, 16); }
-hipError_t kBfWvTwoHeights_launch(const Problem &q) { return dl_launch_two_heights<false, TwoHiW, TwoLoW, true>(q); }
-double kBfWvTwoHeights_cost(const Problem &q) { return dl_cost<TwoHiW>(q, 0.51); }
-const Variant kBfWvTwoHeights = {"bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly woven, mfma16",
-                                 kBfWvTwoHeights_can, kBfWvTwoHeights_launch, kBfWvTwoHeights_cost};
-hipError_t kBfWvTwoHeights2_launch(const Problem &q) { return dl_launch_two_heights<false, TwoHiW2, TwoLoW2, true>(q); }
-double kBfWvTwoHeights2_cost(const Problem &q) { return dl_cost<TwoHiW2>(q, 0.51); }
-const Variant kBfWvTwoHeights2 = {"bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 2(A)+2(B) direct-to-lds, reads as assembly woven, mfma16",
-                                  kBfWvTwoHeights_can, kBfWvTwoHeights2_launch, kBfWvTwoHeights2_cost};
-XP_DL_ASM_VARIANT_W(kBfWv224x256a3, "bf16", false, 224, 256, 2, 4, 3, 2, 1, 0.51, true, " woven")
-XP_DL_ASM_VARIANT_W(kBfWv128x128, "bf16", false, 128, 128, 2, 2, 2, 2, 2, 0.37, true, " woven")
-XP_DL_ASM_VARIANT_W(kBfWv256x128, "bf16", false, 256, 128, 4, 2, 3, 3, 1, 0.47, true, " woven")
-XP_DL_ASM_VARIANT_W(kBfWv128x256, "bf16", false, 128, 256, 2, 4, 3, 3, 1, 0.47, true, " woven")
-XP_DL_ASM_VARIANT_W(kI8Wv128x128, "i8", true, 128, 128, 2, 2, 2, 2, 2, 0.37, true, " woven")
-XP_DL_ASM_VARIANT_W(kI8Wv256x128, "i8", true, 256, 128, 4, 2, 3, 3, 1, 0.47, true, " woven")
-XP_DL_ASM_VARIANT_W(kI8Wv128x256, "i8", true, 128, 256, 2, 4, 3, 3, 1, 0.47, true, " woven")
-
-// Registered last of all: the variants before them keep their indices.
-int dl_weave_variants(xp_dtype in_type, const Variant **out)
-{
-    if (in_type == XP_BF16) {
-        const Variant *v[] = {&kBfWv256x256a3, &kBfWv256x256, &kBfWv224x256, &kBfWvTwoHeights, &kBfWvTwoHeights2, &kBfWv224x256a3,
-                              &kBfWv128x128, &kBfWv256x128, &kBfWv128x256};
-        for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
-        return (int)(sizeof v / sizeof *v);
-    }
-    if (in_type == XP_I8) {
-        const Variant *v[] = {&kI8Wv256x256a3, &kI8Wv256x256, &kI8Wv128x128, &kI8Wv256x128, &kI8Wv128x256};
         for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
         return (int)(sizeof v / sizeof *v);
     }
