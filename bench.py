@@ -35,8 +35,8 @@ BATCHES = 60                  # event pairs for median / minimum
 # (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, scaled by a plain 256 MiB copy; the profile is named beside the
 # figure).  Not measured by this run; a variant without a profile reports null.
 TRAFFIC = {
-    "bf16 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly woven, mfma16":
-        (None, "profiles/dl_kernel_bf16_256x256_ring3a2b_woven_gemm_4096.md"),
+    "bf16 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly, mfma16":
+        (268.8e6, "profiles/dl_kernel_bf16_256x256_ring3a2b_asm_reads_gemm_4096.md"),
 }
 
 

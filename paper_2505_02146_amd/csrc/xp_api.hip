@@ -37,6 +37,7 @@ void build_tables()
         n += gemv_variants(types[s], g_table[s] + n);
         n += dl_bnm_variants(types[s], g_table[s] + n);       // newest last: the older variants keep their indices
         n += dl_asm_variants(types[s], g_table[s] + n);
+        n += dl_small_variants(types[s], g_table[s] + n);
         if (n > kMaxVariants) { fprintf(stderr, "xp: variant table overflow (%d)\n", n); abort(); }
         g_count[s] = n;
     }

@@ -203,15 +203,16 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     // groups of group_m tile-rows, so that the tiles sharing an L2 share A and B panels
     const int nb = tiles_m * p.tiles_n;
     long long batch = blockIdx.y;
-    if ((nb & 7) == 0) {
-        bid = (bid & 7) * (nb >> 3) + (bid >> 3);
-    } else if (gridDim.y > 1 && m_base == 0 && m_end == p.M) {
+    if (gridDim.y > 1 && m_base == 0 && m_end == p.M && (nb < 64 || (nb & 7) != 0)) {
         // batched problems of a few tiles each (one tile height per launch): the tiles of a problem would be
-        // dealt to different XCDs and each L2 would fetch the problem's operands again
+        // dealt to different XCDs and each L2 would fetch the problem's operands again (with 8 tiles a problem,
+        // tile x of every problem would run on XCD x: the shared operand fetched 8 times)
         unsigned x, y;
         xcd_batch_remap(x, y);
         bid = (int)x;
         batch = y;
+    } else if ((nb & 7) == 0) {
+        bid = (bid & 7) * (nb >> 3) + (bid >> 3);
     }
     const int gsz = p.group_m * p.tiles_n;
     const int g = bid / gsz, first_m = g * p.group_m;
@@ -928,6 +929,11 @@ XP_DL_OUTER_VARIANT(kBfAmm256x256, 4, "A along M", 256, 256, 2, 4, 2, 2, 1, 0.48
 XP_DL_OUTER_VARIANT(kBfAmm128x128, 4, "A along M", 128, 128, 2, 2, 2, 2, 2, 0.32)
 XP_DL_OUTER_VARIANT(kBfAmmBnm256x256, 5, "A along M and B along N", 256, 256, 2, 4, 2, 2, 1, 0.48)
 XP_DL_OUTER_VARIANT(kBfAmmBnm128x128, 5, "A along M and B along N", 128, 128, 2, 2, 2, 2, 2, 0.32)
+// small tiles with deep rings for batched problems that are bound by memory, not by the matrix cores: 48 KB of LDS
+// (three workgroups a compute unit, each with two K steps of loads in flight) or 64 KB (two, with three)
+XP_DL_OUTER_VARIANT(kBfBnm64x64n3, 3, "B along N", 64, 64, 2, 2, 3, 3, 3, 0.20)
+XP_DL_OUTER_VARIANT(kBfBnm64x64n4, 3, "B along N", 64, 64, 2, 2, 4, 4, 2, 0.20)
+XP_DL_OUTER_VARIANT(kBfBnm128x64n3, 3, "B along N", 128, 64, 4, 1, 3, 3, 2, 0.25)
 // half-size tiles with three buffers per ring, for shapes that 256x256 tiles cut into too few pieces
 XP_DL_OUTER_VARIANT(kBfBnm256x128, 3, "B along N", 256, 128, 4, 2, 3, 3, 1, 0.44)
 XP_DL_OUTER_VARIANT(kBfBnm128x256, 3, "B along N", 128, 256, 2, 4, 3, 3, 1, 0.44)
@@ -1012,6 +1018,14 @@ int dl_bnm_variants(xp_dtype in_type, const Variant **out)
                           &kBfBnm256x128, &kBfBnm128x256, &kBfAmm256x128, &kBfAmm128x256, &kBfAmmBnm256x128, &kBfAmmBnm128x256};
     for (size_t i = 0; i < sizeof v / sizeof *v; ++i) out[i] = v[i];
     return (int)(sizeof v / sizeof *v);
+}
+
+// Registered last of all: the variants before them keep their indices.
+int dl_small_variants(xp_dtype in_type, const Variant **out)
+{
+    if (in_type != XP_BF16) return 0;
+    out[0] = &kBfBnm64x64n3; out[1] = &kBfBnm64x64n4; out[2] = &kBfBnm128x64n3;
+    return 3;
 }
 
 // Registered after every other family so that the older variants keep their indices.
