@@ -19,5 +19,15 @@ def build(force: bool = True) -> pathlib.Path:
     return LIB
 
 
+def build_selftest(out_dir) -> pathlib.Path:
+    """The oracle and its closed-form self-test (selftest.c) as one executable under AddressSanitizer and
+    UndefinedBehaviorSanitizer: running it stops at the first access outside an operand buffer."""
+    exe = pathlib.Path(out_dir) / "oracle_selftest"
+    cmd = ["gcc", "-std=c11", "-O1", "-g", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-static-libasan", "-Wall", "-Wextra", "-o", str(exe), str(HERE / "selftest.c"), str(HERE / "xp_oracle.c"), "-lm"]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 if __name__ == "__main__":
     print(build())
