@@ -50,9 +50,14 @@ struct DlParams {
     int tiles_m, tiles_n, group_m;
     unsigned in_bytes;                    // convolution view
     int H, W, Cin_b, R, S, PQ, Q, sh, sw, ph, pw;
+    unsigned pq_magic, q_magic;           // division by PQ and by Q as a multiplication (see fast_div)
+    int pq_shift, q_shift;
     // two-height launches: workgroups [0, n1) tile rows [0, m_split) with the first tile type,
     // the rest tile rows [m_split, M) with the second
     int n1, m_split, tiles_m2;
+#ifdef XP_TRACE
+    long long *trace;                     // diagnostic build: 8 words per workgroup (shader-clock and 100 MHz time stamps)
+#endif
 };
 
 template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_, bool SPREAD_ = false, int OCC_ = 1, int MF_ = 32, bool NT_ = false,
@@ -168,6 +173,14 @@ template <> struct Acc<true, 16> {
     }
 };
 
+// floor(n / d) for 0 <= n < 2^31 as a multiplication: magic = ceil(2^(31 + shift) / d) with shift = ceil(log2 d)
+// (the host works both out once per call); exact for every such n.  A 32-bit division costs some forty vector
+// instructions, and the convolution's set-up has two per load slot.
+__device__ __forceinline__ int fast_div(int n, unsigned magic, int shift)
+{
+    return (int)(((unsigned long long)(unsigned)n * magic) >> (31 + shift));
+}
+
 // One tile of C.  `bid` numbers the tiles of the row range [m_base, m_end) of the problem, which is
 // tiles_m tile-rows high; lds points at T::LDS bytes of shared memory.
 // MODE: 0 GEMM, 1 convolution (A addressed through the im2col map), 2 convolution with planar output
@@ -198,6 +211,12 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / T::WN, wn = wave % T::WN;
+#ifdef XP_TRACE
+    // diagnostic build (-DXP_TRACE): where a workgroup's time goes -- entry, first MFMA, end of the K loop, stores done
+    long long tr_c[4] = {0, 0, 0, 0}, tr_w[4] = {0, 0, 0, 0};
+    const int tr_slot = (int)(blockIdx.y * gridDim.x + blockIdx.x) + (m_base ? (int)(gridDim.x * gridDim.y) : 0);
+    tr_c[0] = clock64(); tr_w[0] = wall_clock64();
+#endif
 
     // workgroup -> tile: one XCD (workgroup id mod 8) owns a run of consecutive tiles, walked in
     // groups of group_m tile-rows, so that the tiles sharing an L2 share A and B panels
@@ -266,16 +285,19 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             a_outside[i] = -1;                          // a row past the end: every tap is outside
             a_off_g[i] = 0;
             if (m < m_end && row < T::BM) {
-                const int n = m / p.PQ, pq = m % p.PQ;
-                const int op = pq / p.Q, oq = pq % p.Q;
+                const int n = fast_div(m, p.pq_magic, p.pq_shift), pq = m - n * p.PQ;
+                const int op = fast_div(pq, p.q_magic, p.q_shift), oq = pq - op * p.Q;
                 const int h0 = op * p.sh - p.ph, w0 = oq * p.sw - p.pw;
                 a_off_g[i] = (unsigned)n * (unsigned)(p.H * p.W) * (unsigned)p.Cin_b +
                              (unsigned)((h0 + p.ph) * p.W + w0 + p.pw) * (unsigned)p.Cin_b + a_cb;
-                int outside = 0;
-                for (int r = 0, t = 0; r < p.R; ++r)
-                    for (int s2 = 0; s2 < p.S; ++s2, ++t)
-                        if ((unsigned)(h0 + r) >= (unsigned)p.H || (unsigned)(w0 + s2) >= (unsigned)p.W) outside |= 1 << t;
-                a_outside[i] = outside;
+                // columns of the window outside the image (one bit each), then row by row: a row outside the image
+                // is outside with all its columns
+                unsigned cols_out = 0;
+                for (int s2 = 0; s2 < p.S; ++s2) cols_out |= ((unsigned)(w0 + s2) >= (unsigned)p.W ? 1u : 0u) << s2;
+                const unsigned row_all = p.S >= 32 ? 0xffffffffu : (1u << p.S) - 1u;
+                unsigned outside = 0;
+                for (int r = 0; r < p.R; ++r) outside |= ((unsigned)(h0 + r) >= (unsigned)p.H ? row_all : cols_out) << (r * p.S);
+                a_outside[i] = (int)outside;
             }
         } else {
             a_off_g[i] = (unsigned)(row * p.lda_b) + a_cb;
@@ -630,6 +652,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 cur_b = nxt_b;
             }
         };
+#ifdef XP_TRACE
+        tr_c[1] = clock64(); tr_w[1] = wall_clock64();
+#endif
         if constexpr (T::PH % 2 == 0) {
             // steps whose loads (for step kt + NS - 1, A possibly one further) are whole steps inside K
             constexpr int AHEAD = (T::NSA > T::NS ? T::NSA : T::NS) - (WV ? 0 : 1);
@@ -656,6 +681,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
     }
+#ifdef XP_TRACE
+    tr_c[2] = clock64(); tr_w[2] = wall_clock64();
+#endif
 
     // epilogue
     using OutT = typename std::conditional<INT8, int, float>::type;
@@ -674,6 +702,14 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 store_block16t<INT8, T::NTSTORE>(acc[i][j], C, p.ldc, m0 + wm * T::WTM + i * 16, n0 + wn * T::WTN + j * 16, lane, m_end,
                                      p.N, p.alpha, p.beta);
         }
+#ifdef XP_TRACE
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));         // the stores have reached L2
+    tr_c[3] = clock64(); tr_w[3] = wall_clock64();
+    if (p.trace && tid == 0) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) { p.trace[tr_slot * 8 + x] = tr_c[x]; p.trace[tr_slot * 8 + 4 + x] = tr_w[x]; }
+    }
+#endif
 }
 
 template <bool INT8, class T, int MODE>
@@ -693,6 +729,23 @@ __global__ __launch_bounds__(T1::NT, 1) void dl_kernel_two_heights(DlParams p)
     __shared__ __attribute__((aligned(1024))) char lds[T1::LDS > T2::LDS ? T1::LDS : T2::LDS];
     if ((int)blockIdx.x < p.n1) dl_body<INT8, T1, MODE>(p, lds, blockIdx.x, 0, p.m_split, p.tiles_m);
     else dl_body<INT8, T2, MODE>(p, lds, blockIdx.x - p.n1, p.m_split, p.M, p.tiles_m2);
+}
+
+// The same two tile heights when one round of each covers the problem (at most one workgroup per compute unit):
+// workgroup i computes T1 tile i and then, without leaving the compute unit, T2 tile i.  Against two workgroups
+// one after the other this saves the hand-over (3.5 us between the last store of the first and the entry of the
+// second, measured with time stamps in the kernel), and the second tile's set-up and first loads run while the
+// first tile's stores drain.
+template <bool INT8, class T1, class T2, int MODE>
+__global__ __launch_bounds__(T1::NT, 1) void dl_kernel_pair(DlParams p)
+{
+    static_assert(T1::NT == T2::NT && T1::BN == T2::BN, "the two tile types share the workgroup shape and the tile width");
+    __shared__ __attribute__((aligned(1024))) char lds[T1::LDS > T2::LDS ? T1::LDS : T2::LDS];
+    dl_body<INT8, T1, MODE>(p, lds, blockIdx.x, 0, p.m_split, p.tiles_m);
+    if ((int)blockIdx.x < p.tiles_m2 * p.tiles_n) {
+        __builtin_amdgcn_s_barrier();                    // every wave has left the first tile's K loop: its LDS buffers may be refilled
+        dl_body<INT8, T2, MODE>(p, lds, blockIdx.x, p.m_split, p.M, p.tiles_m2);
+    }
 }
 
 // ------------------------------------------------------------------------------------ host side
@@ -728,6 +781,10 @@ bool dl_can_run_common(const Problem &q, int BM, int BN, int RB, int MF)
     return tiles <= 0x7fffffffLL;
 }
 
+#ifdef XP_TRACE
+long long *g_dl_trace = nullptr;          // set through xp_debug_set_dl_trace (diagnostic build only)
+#endif
+
 template <bool INT8, class T>
 DlParams dl_params(const Problem &q)
 {
@@ -748,13 +805,24 @@ DlParams dl_params(const Problem &q)
     static const int env_group_m = [] { const char *e = getenv("XP_GROUP_M"); return e ? atoi(e) : 0; }();
     p.group_m = env_group_m > 0 ? env_group_m : 4;
     p.in_bytes = 0; p.H = p.W = p.Cin_b = p.R = p.S = p.PQ = p.Q = p.sh = p.sw = p.ph = p.pw = 0;
+    p.pq_magic = p.q_magic = 0; p.pq_shift = p.q_shift = 0;
     if (q.conv) {
         p.in_bytes = (unsigned)((q.M / (q.P * q.Q)) * q.H * q.W * q.Cin * esz);
         p.H = (int)q.H; p.W = (int)q.W; p.Cin_b = (int)(q.Cin * esz); p.R = (int)q.R; p.S = (int)q.S;
         p.PQ = (int)(q.P * q.Q); p.Q = (int)q.Q;
+        auto magic = [](int d, unsigned &m, int &sh) {
+            sh = 0;
+            while ((1LL << sh) < d) ++sh;
+            m = (unsigned)((((unsigned long long)1 << (31 + sh)) + (unsigned)d - 1) / (unsigned)d);
+        };
+        magic(p.PQ, p.pq_magic, p.pq_shift);
+        magic(p.Q, p.q_magic, p.q_shift);
         p.sh = (int)q.sh; p.sw = (int)q.sw; p.ph = (int)q.ph; p.pw = (int)q.pw;
     }
     p.n1 = 0; p.m_split = 0; p.tiles_m2 = 0;
+#ifdef XP_TRACE
+    p.trace = g_dl_trace;
+#endif
     return p;
 }
 
@@ -798,7 +866,21 @@ hipError_t dl_launch_two_heights(const Problem &q)
     if (split % T1::BM != 0) p.tiles_m += 1;
     p.tiles_m2 = (int)((q.M - split + T2::BM - 1) / T2::BM);
     p.n1 = p.tiles_m * p.tiles_n;
-    const dim3 grid((unsigned)(p.n1 + p.tiles_m2 * p.tiles_n), (unsigned)q.batch);
+    const int n2 = p.tiles_m2 * p.tiles_n;
+    if (q.batch == 1 && p.n1 <= 256 && n2 > 0 && n2 <= p.n1) {
+        // one round of each height: the two tiles of a compute unit in one workgroup
+        const dim3 pgrid((unsigned)p.n1, 1);
+        if constexpr (T1::MF == 16 && !INT8) {
+            if (q.conv && q.c_plane) {
+                hipLaunchKernelGGL((dl_kernel_pair<INT8, T1, T2, M0 + 2>), pgrid, dim3(T1::NT), 0, q.stream, p);
+                return hipGetLastError();
+            }
+        }
+        if (q.conv) hipLaunchKernelGGL((dl_kernel_pair<INT8, T1, T2, M0 + 1>), pgrid, dim3(T1::NT), 0, q.stream, p);
+        else hipLaunchKernelGGL((dl_kernel_pair<INT8, T1, T2, M0>), pgrid, dim3(T1::NT), 0, q.stream, p);
+        return hipGetLastError();
+    }
+    const dim3 grid((unsigned)(p.n1 + n2), (unsigned)q.batch);
     if constexpr (T1::MF == 16 && !INT8) {
         if (q.conv && q.c_plane) {
             hipLaunchKernelGGL((dl_kernel_two_heights<INT8, T1, T2, M0 + 2>), grid, dim3(T1::NT), 0, q.stream, p);
@@ -994,6 +1076,10 @@ XP_DL_ASM_VARIANT(kI8Asm128x256, "i8", true, 128, 256, 2, 4, 3, 3, 1, 0.46)
 XP_DL_ASM_VARIANT(kI8Asm256x256, "i8", true, 256, 256, 2, 4, 2, 2, 1, 0.54)
 }  // namespace
 
+#ifdef XP_TRACE
+void set_dl_trace(long long *p) { g_dl_trace = p; }
+#endif
+
 int dl_asm_variants(xp_dtype in_type, const Variant **out)
 {
     if (in_type == XP_BF16) {
@@ -1052,3 +1138,9 @@ int dl_variants(xp_dtype in_type, const Variant **out)
 }
 
 }  // namespace xp
+
+#ifdef XP_TRACE
+// Diagnostic build only (not declared in include/xp.h): device buffer of 8 x 64-bit words per workgroup that every
+// direct-to-LDS kernel launched afterwards fills with its time stamps; nullptr switches it off.
+extern "C" void xp_debug_set_dl_trace(void *device_buffer) { xp::set_dl_trace((long long *)device_buffer); }
+#endif
