@@ -251,6 +251,22 @@ def main() -> int:
         side["gemm_f32_256"] = dict(m, us=round(m["median_ms"] * 1e3, 2), **{"TFLOP/s": round(f1 / (m["median_ms"] * 1e-3) / 1e12, 3)},
                                     bound="launch latency (33.6 MFLOP, 0.79 MB)",
                                     kernel=xp.xp_describe_config(0, "f32", xp.xp_last_config(0, "f32")))
+        # the same call captured 50 times into a HIP graph: what the kernel costs without the host's share of a launch
+        def call1():
+            xp.xp_gemm(256, 256, 256, 1.0, a1, "row", 256, b1, "row", 256, 0.0, c1, "row", 256)
+        cap_stream = torch.cuda.Stream()
+        cap_stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(cap_stream):
+            call1()
+        torch.cuda.current_stream().wait_stream(cap_stream)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=cap_stream):
+            for _ in range(50):
+                call1()
+        mg = _measure(torch, graph.replay, per_batch=4, preload_ms=30.0)
+        side["gemm_f32_256"]["in_hip_graph_us_per_call"] = round(mg["median_ms"] * 1e3 / 50, 2)
+        side["gemm_f32_256"]["in_hip_graph_TFLOP/s"] = round(f1 / (mg["median_ms"] * 1e-3 / 50) / 1e12, 3)
         if oracle:
             call = lambda: oracle.gemm_float(256, 256, 256, w1["A"].reshape(-1), "row", w1["B"].reshape(-1), "row")
             ref, dt = _timed_oracle(call, 3)
