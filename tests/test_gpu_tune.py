@@ -139,3 +139,43 @@ def test_workspace_too_small_is_refused(xp):
                         b_type="bf16")
     assert e.value.status == 8
     assert xp.xp_tune_count() == 0
+
+
+def test_two_convolutions_with_equal_gemm_extents_keep_their_own_winners(xp, tmp_path):
+    """A 3x3 convolution over 64 channels and a 1x1 convolution over 576 have the same implicit-GEMM extents
+    (M = N*P*Q, N = Cout, K = R*S*Cin).  The table of tuned shapes tells them apart by geometry, and so must the
+    per-thread memory of recent selections: each call gets the variant recorded for its own geometry, in any order."""
+    import torch
+    N, H, W, Cout = 2, 16, 16, 64
+    geo_a = (N, H, W, 64, Cout, 3, 3, 1, 1, 1, 1)
+    geo_b = (N, H, W, 576, Cout, 1, 1, 1, 1, 0, 0)
+    xa, wa = (torch.randn(N, H, W, 64, device="cuda").bfloat16(), (torch.randn(Cout, 3, 3, 64, device="cuda") / 24).bfloat16())
+    xb, wb = (torch.randn(N, H, W, 576, device="cuda").bfloat16(), (torch.randn(Cout, 1, 1, 576, device="cuda") / 24).bfloat16())
+    out = torch.empty(N, H, W, Cout, device="cuda")
+
+    def call(geo, x, w):
+        xp.xp_conv2d_nhwc(*geo, x, w, "krsc", out)
+        return xp.xp_last_config(2, "bf16")
+
+    # record both shapes once (whatever wins), to obtain the table's own spelling of the two keys
+    ws = _ws(xp, N * H * W * Cout)
+    xp.xp_tune_conv2d_nhwc(*geo_a, xa, wa, "krsc", out, ws, reps=3)
+    xp.xp_tune_conv2d_nhwc(*geo_b, xb, wb, "krsc", out, ws, reps=3)
+    path = tmp_path / "two.txt"
+    xp.xp_tune_save(path)
+    lines = [l for l in path.read_text().splitlines() if " | " in l and not l.startswith("#")]
+    assert len(lines) == 2
+    key_a = next(l for l in lines if " c64 " in l).split(" | ")[0]
+    key_b = next(l for l in lines if " c576 " in l).split(" | ")[0]
+    # two different variants that can run both calls: the general kernel and the first register-staged MFMA kernel
+    name_x = xp.xp_describe_config(2, "bf16", 0)
+    idx_y = next(i for i in range(1, xp.xp_num_configs(2, "bf16")) if "direct-to-lds" not in xp.xp_describe_config(2, "bf16", i)
+                 and "mfma" in xp.xp_describe_config(2, "bf16", i))
+    name_y = xp.xp_describe_config(2, "bf16", idx_y)
+    path.write_text(f"{key_a} | {name_x}\n{key_b} | {name_y}\n")
+    xp.xp_tune_clear()
+    xp.xp_tune_load(path)
+    assert call(geo_a, xa, wa) == 0
+    assert call(geo_b, xb, wb) == idx_y
+    assert call(geo_a, xa, wa) == 0
+    assert call(geo_b, xb, wb) == idx_y
