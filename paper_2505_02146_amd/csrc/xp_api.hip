@@ -38,6 +38,7 @@ void build_tables()
         n += dl_bnm_variants(types[s], g_table[s] + n);       // newest last: the older variants keep their indices
         n += dl_asm_variants(types[s], g_table[s] + n);
         n += dl_small_variants(types[s], g_table[s] + n);
+        if (types[s] == XP_F32) n += f32_small_variants(g_table[s] + n);
         if (n > kMaxVariants) { fprintf(stderr, "xp: variant table overflow (%d)\n", n); abort(); }
         g_count[s] = n;
     }
@@ -92,7 +93,7 @@ struct Tuned {
 };
 
 const Tuned kTuned[] = {
-    {XP_OP_GEMM, XP_F32, 1, 256, 256, 256, true, false, "f32 64x64x16 waves 2x2 mfma32x32x2"},
+    {XP_OP_GEMM, XP_F32, 1, 256, 256, 256, true, false, "f32 32x32x256 four waves split k, whole chunk in flight, mfma32x32x2"},
     {XP_OP_GEMM, XP_BF16, 1, 4096, 4096, 4096, true, true, "bf16 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly, mfma16"},
     {XP_OP_GEMM, XP_I8, 1, 4096, 4096, 8192, true, true, "i8 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly, mfma16"},
     {XP_OP_GEMM_BATCHED, XP_BF16, 96, 512, 512, 64, true, true, "bf16 64x128-stream x128B single-k-step producer/consumer nt-stores mfma32"},

@@ -65,6 +65,7 @@ const Variant *variant(xp_dtype in_type, int idx);
 // Registration hooks implemented by the kernel translation units.
 int generic_variants(xp_dtype in_type, const Variant **out);
 int f32_mfma_variants(const Variant **out);
+int f32_small_variants(const Variant **out);
 int kc_variants(xp_dtype in_type, const Variant **out);
 int dl_variants(xp_dtype in_type, const Variant **out);
 int oc_variants(xp_dtype in_type, const Variant **out);

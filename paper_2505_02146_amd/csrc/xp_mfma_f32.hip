@@ -377,6 +377,122 @@ double f32_cost(const Problem &q)
     return tile_cost_us(q, BM, BN, (int)sizeof(float) * FK * (BM + BN + 8), 256, (BM == 128 ? 0.5 : 0.3) / 16.0, 4);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Small problems (a few dozen tiles, K of a few hundred): what such a call costs is latency, not throughput.
+// The tiled kernels above walk K in steps of 16 with the next step's loads one step ahead -- a quarter of a
+// microsecond of MFMA work to cover a load that takes three times as long, sixteen times in a row for K = 256.
+// Here a workgroup owns a 32 x 32 tile of C (many workgroups even for a small C), brings a whole chunk of 256 k
+// of both operands into LDS with every load of the chunk in flight at once (one memory latency per chunk), and
+// its four waves each multiply a quarter of the chunk's k range into their own copy of the tile, which are
+// added up through LDS at the end (wave 0 + wave 1 + wave 2 + wave 3, always in that order).
+constexpr int SK = 256;                                  // k per chunk
+constexpr int ST = 32;                                   // tile edge
+
+__global__ __launch_bounds__(256) void f32s_kernel(FParams p)
+{
+    constexpr int E = ST * SK / 256;                     // elements per thread, operand and chunk
+    __shared__ float As[SK][ST + 4];
+    __shared__ float Bs[SK][ST + 4];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int m0 = (blockIdx.x / p.tiles_n) * ST, n0 = (blockIdx.x % p.tiles_n) * ST;
+    const long long b = blockIdx.y;
+    const float *A = p.A + b * p.strideA;
+    const float *B = p.B + b * p.strideB;
+    float *C = p.C + b * p.strideC;
+    const bool a_kfast = p.a_sk == 1, b_kfast = p.b_sk == 1;
+
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+
+    for (int k0 = 0; k0 < p.K; k0 += SK) {
+        float ra[E], rb[E];
+        // consecutive threads take consecutive elements along the operand's contiguous index
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+            const int e = t + 256 * i;
+            const int r = a_kfast ? e / SK : e % ST, kk = a_kfast ? e % SK : e / ST;
+            const int m = m0 + r, k = k0 + kk;
+            ra[i] = (m < p.M && k < p.K) ? A[m * p.a_sm + k * p.a_sk] : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+            const int e = t + 256 * i;
+            const int c = b_kfast ? e / SK : e % ST, kk = b_kfast ? e % SK : e / ST;
+            const int n = n0 + c, k = k0 + kk;
+            rb[i] = (n < p.N && k < p.K) ? B[k * p.b_sk + n * p.b_sn] : 0.0f;
+        }
+        if (k0 > 0) __syncthreads();                     // the chunk before has been multiplied by every wave
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+            const int e = t + 256 * i;
+            As[a_kfast ? e % SK : e / ST][a_kfast ? e / SK : e % ST] = ra[i];
+            Bs[b_kfast ? e % SK : e / ST][b_kfast ? e / SK : e % ST] = rb[i];
+        }
+        __syncthreads();
+        // this wave's quarter of the chunk; lane l supplies A(row l&31, k = l>>5) and B(k = l>>5, column l&31)
+        const int kq = wave * (SK / 4);
+#pragma unroll 8
+        for (int kk = 0; kk < SK / 4; kk += 2) {
+            const float af = As[kq + kk + (lane >> 5)][lane & 31], bf = Bs[kq + kk + (lane >> 5)][lane & 31];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af, bf, acc, 0, 0, 0);
+        }
+    }
+
+    // the four partial tiles through LDS (As is free after the barrier); thread t then owns 4 accumulator
+    // registers of one lane position: register v of lane l is row (v/4)*8 + (l>>5)*4 + (v&3), column l&31
+    __syncthreads();
+    float *red = &As[0][0];                              // 4 x 16 x 64 floats = 16 KB of the 36 KB
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[(wave * 16 + v) * 64 + lane] = acc[v];
+    __syncthreads();
+    const int col = n0 + (lane & 31);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int v = wave * 4 + x;
+        const float sum = ((red[(0 * 16 + v) * 64 + lane] + red[(1 * 16 + v) * 64 + lane]) + red[(2 * 16 + v) * 64 + lane]) +
+                          red[(3 * 16 + v) * 64 + lane];
+        const int row = m0 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        if (row < p.M && col < p.N) {
+            float *dst = C + (long long)row * p.ldc + col;
+            float r = p.alpha * sum;
+            if (p.beta != 0.0f) r = __builtin_fmaf(p.beta, *dst, r);
+            *dst = r;
+        }
+    }
+}
+
+bool f32s_can_run(const Problem &q)
+{
+    if (q.c_plane || q.in_type != XP_F32 || q.conv || q.K <= 0) return false;
+    if (q.M > 0x7fffffffLL || q.N > 0x7fffffffLL || q.K > 0x7fffffffLL || q.batch > 65535) return false;
+    return ((q.M + ST - 1) / ST) * ((q.N + ST - 1) / ST) <= 0x7fffffffLL;
+}
+
+hipError_t f32s_launch(const Problem &q)
+{
+    FParams p;
+    p.A = (const float *)q.A; p.B = (const float *)q.B; p.C = (float *)q.C;
+    p.M = (int)q.M; p.N = (int)q.N; p.K = (int)q.K;
+    p.a_sm = q.a_sm; p.a_sk = q.a_sk; p.b_sk = q.b_sk; p.b_sn = q.b_sn; p.ldc = q.ldc;
+    p.strideA = q.strideA; p.strideB = q.strideB; p.strideC = q.strideC;
+    p.alpha = q.alpha; p.beta = q.beta;
+    const int tiles_m = (int)((q.M + ST - 1) / ST);
+    p.tiles_n = (int)((q.N + ST - 1) / ST);
+    hipLaunchKernelGGL(f32s_kernel, dim3((unsigned)(tiles_m * p.tiles_n), (unsigned)q.batch), dim3(256), 0, q.stream, p);
+    return hipGetLastError();
+}
+
+// wins the estimate only where it is meant for: at most two workgroups per compute unit and a few chunks of K
+double f32s_cost(const Problem &q)
+{
+    const double tiles = (double)((q.M + ST - 1) / ST) * (double)((q.N + ST - 1) / ST) * (double)q.batch;
+    if (tiles > 512.0 || q.K > 1024) return 1e30;
+    return 3.0 + 1.6 * (double)((q.K + SK - 1) / SK) * (tiles > 256.0 ? 2.0 : 1.0);
+}
+
+const Variant kF32_small = {"f32 32x32x256 four waves split k, whole chunk in flight, mfma32x32x2", f32s_can_run, f32s_launch, f32s_cost};
+
 const Variant kF32_128 = {"f32 128x128x16 waves 2x2 mfma32x32x2", f32_can_run, f32_launch<128, 128>,
                           f32_cost<128, 128>};
 const Variant kF32_64 = {"f32 64x64x16 waves 2x2 mfma32x32x2", f32_can_run, f32_launch<64, 64>, f32_cost<64, 64>};
@@ -389,6 +505,13 @@ int f32_mfma_variants(const Variant **out)
                             &kF32P64_kk, &kF32P64_km, &kF32P64_mk, &kF32P64_mm};
     for (int i = 0; i < 10; ++i) out[i] = all[i];
     return 10;
+}
+
+// Registered after the other fp32 families: their indices stay as they were.
+int f32_small_variants(const Variant **out)
+{
+    out[0] = &kF32_small;
+    return 1;
 }
 
 }  // namespace xp
