@@ -38,6 +38,7 @@ void build_tables()
         n += dl_bnm_variants(types[s], g_table[s] + n);       // newest last: the older variants keep their indices
         n += dl_asm_variants(types[s], g_table[s] + n);
         n += dl_small_variants(types[s], g_table[s] + n);
+        n += rs_variants(types[s], g_table[s] + n);
         if (types[s] == XP_F32) n += f32_small_variants(g_table[s] + n);
         if (n > kMaxVariants) { fprintf(stderr, "xp: variant table overflow (%d)\n", n); abort(); }
         g_count[s] = n;
