@@ -204,7 +204,6 @@ __global__ __launch_bounds__(256, 4) void f32p_kernel(FParams p)
         }
     }
     const unsigned step_a = (unsigned)((KA ? 1LL : p.a_sk) * 4), step_b = (unsigned)((KB ? 1LL : p.b_sk) * 4);   // bytes per unit of k
-    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     f32x4 ra[CA], rb[CB];
     // FULL: the whole step lies inside K (every step but possibly the last): nothing to check
     auto load = [&](int k0, bool full) {
@@ -388,11 +387,65 @@ double f32_cost(const Problem &q)
 constexpr int SK = 256;                                  // k per chunk
 constexpr int ST = 32;                                   // tile edge
 
+// LA, LB: how A and B are brought in. 0: any strides, one element per load. 1: the operand is contiguous along k
+// (row-major A, column-major B), 2: contiguous along its own index (column-major A, row-major B); both with every
+// extent, pitch and pointer that the 16-byte loads touch a multiple of four elements. A k-contiguous operand stays
+// [index][k] in LDS (pitch 260 floats) and a lane reads four consecutive k of its row with one 16-byte read; the
+// other form is [k][index] (pitch 36). The lanes of the lower half of a wave take k = 8q .. 8q+3, those of the upper
+// half 8q+4 .. 8q+7, for A and B alike, so that the four MFMA steps of a group pair equal k (the order of the sum
+// over k is free).
+template <int L>
+struct F32sOperand {
+    static constexpr int E4 = ST * SK / 256 / 4;         // 16-byte groups per thread and chunk
+    static constexpr int PITCH = L == 1 ? SK + 4 : ST + 4;
+    static constexpr int FLOATS = L == 1 ? ST * PITCH : SK * PITCH;
+    typedef float f32x4v __attribute__((ext_vector_type(4)));
+    // group e of the chunk: (index, k) of its first element
+    static __device__ __forceinline__ void where(int e, int &idx, int &kk)
+    {
+        if constexpr (L == 1) { idx = e / (SK / 4); kk = 4 * (e % (SK / 4)); }
+        else { kk = e / (ST / 4); idx = 4 * (e % (ST / 4)); }
+    }
+    // pitch: elements between consecutive values of the slow index (rows for L == 1, k for L == 2)
+    static __device__ __forceinline__ void load(f32x4v (&r)[E4], const float *P, long long pitch, int i0, int I, int k0, int K, int t)
+    {
+#pragma unroll
+        for (int i = 0; i < E4; ++i) {
+            int idx, kk;
+            where(t + 256 * i, idx, kk);
+            const bool ok = i0 + idx < I && k0 + kk < K;                           // I or K is a multiple of 4: a group is whole or absent
+            const long long off = L == 1 ? (long long)(i0 + idx) * pitch + (k0 + kk) : (long long)(k0 + kk) * pitch + (i0 + idx);
+            r[i] = ok ? *(const f32x4v *)(P + off) : f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+    }
+    static __device__ __forceinline__ void store(float *S, const f32x4v (&r)[E4], int t)
+    {
+#pragma unroll
+        for (int i = 0; i < E4; ++i) {
+            int idx, kk;
+            where(t + 256 * i, idx, kk);
+            *(f32x4v *)&S[L == 1 ? idx * PITCH + kk : kk * PITCH + idx] = r[i];
+        }
+    }
+    // the four values k .. k+3 of this lane's row or column
+    static __device__ __forceinline__ f32x4v read(const float *S, int idx, int k)
+    {
+        if constexpr (L == 1) return *(const f32x4v *)&S[idx * PITCH + k];
+        else return f32x4v{S[k * PITCH + idx], S[(k + 1) * PITCH + idx], S[(k + 2) * PITCH + idx], S[(k + 3) * PITCH + idx]};
+    }
+};
+
+template <int LA, int LB>
 __global__ __launch_bounds__(256) void f32s_kernel(FParams p)
 {
+    static_assert((LA == 0) == (LB == 0), "both operands by 16-byte loads, or neither");
+    constexpr bool VEC = LA != 0;
     constexpr int E = ST * SK / 256;                     // elements per thread, operand and chunk
-    __shared__ float As[SK][ST + 4];
-    __shared__ float Bs[SK][ST + 4];
+    constexpr int APITCH = ST + 4;                       // the one-element form keeps both operands [k][index]
+    typedef F32sOperand<VEC ? LA : 2> OA;
+    typedef F32sOperand<VEC ? LB : 2> OB;
+    __shared__ __attribute__((aligned(16))) float As[OA::FLOATS];
+    __shared__ __attribute__((aligned(16))) float Bs[OB::FLOATS];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int m0 = (blockIdx.x / p.tiles_n) * ST, n0 = (blockIdx.x % p.tiles_n) * ST;
     const long long b = blockIdx.y;
@@ -406,6 +459,23 @@ __global__ __launch_bounds__(256) void f32s_kernel(FParams p)
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
     for (int k0 = 0; k0 < p.K; k0 += SK) {
+        if constexpr (VEC) {
+            typename OA::f32x4v ra[OA::E4], rb[OB::E4];
+            OA::load(ra, A, LA == 1 ? p.a_sm : p.a_sk, m0, p.M, k0, p.K, t);
+            OB::load(rb, B, LB == 1 ? p.b_sn : p.b_sk, n0, p.N, k0, p.K, t);
+            if (k0 > 0) __syncthreads();                 // the chunk before has been multiplied by every wave
+            OA::store(As, ra, t);
+            OB::store(Bs, rb, t);
+            __syncthreads();
+            const int kq = wave * (SK / 4) + 4 * (lane >> 5);
+#pragma unroll
+            for (int g = 0; g < SK / 4; g += 8) {
+                const auto a4 = OA::read(As, lane & 31, kq + g);
+                const auto b4 = OB::read(Bs, lane & 31, kq + g);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[u], b4[u], acc, 0, 0, 0);
+            }
+        } else {
         float ra[E], rb[E];
         // consecutive threads take consecutive elements along the operand's contiguous index
 #pragma unroll
@@ -426,23 +496,24 @@ __global__ __launch_bounds__(256) void f32s_kernel(FParams p)
 #pragma unroll
         for (int i = 0; i < E; ++i) {
             const int e = t + 256 * i;
-            As[a_kfast ? e % SK : e / ST][a_kfast ? e / SK : e % ST] = ra[i];
-            Bs[b_kfast ? e % SK : e / ST][b_kfast ? e / SK : e % ST] = rb[i];
+            As[(a_kfast ? e % SK : e / ST) * APITCH + (a_kfast ? e / SK : e % ST)] = ra[i];
+            Bs[(b_kfast ? e % SK : e / ST) * APITCH + (b_kfast ? e / SK : e % ST)] = rb[i];
         }
         __syncthreads();
         // this wave's quarter of the chunk; lane l supplies A(row l&31, k = l>>5) and B(k = l>>5, column l&31)
         const int kq = wave * (SK / 4);
 #pragma unroll 8
         for (int kk = 0; kk < SK / 4; kk += 2) {
-            const float af = As[kq + kk + (lane >> 5)][lane & 31], bf = Bs[kq + kk + (lane >> 5)][lane & 31];
+            const float af = As[(kq + kk + (lane >> 5)) * APITCH + (lane & 31)], bf = Bs[(kq + kk + (lane >> 5)) * APITCH + (lane & 31)];
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af, bf, acc, 0, 0, 0);
+        }
         }
     }
 
     // the four partial tiles through LDS (As is free after the barrier); thread t then owns 4 accumulator
     // registers of one lane position: register v of lane l is row (v/4)*8 + (l>>5)*4 + (v&3), column l&31
     __syncthreads();
-    float *red = &As[0][0];                              // 4 x 16 x 64 floats = 16 KB of the 36 KB
+    float *red = &As[0];                                 // 4 x 16 x 64 floats = 16 KB of the 33 KB or more
 #pragma unroll
     for (int v = 0; v < 16; ++v) red[(wave * 16 + v) * 64 + lane] = acc[v];
     __syncthreads();
@@ -469,6 +540,18 @@ bool f32s_can_run(const Problem &q)
     return ((q.M + ST - 1) / ST) * ((q.N + ST - 1) / ST) <= 0x7fffffffLL;
 }
 
+// 1: 16-byte loads along k, 2: 16-byte loads along the operand's own index, 0: neither is possible
+int f32s_form(const Problem &q, bool is_a)
+{
+    const long long s_idx = is_a ? q.a_sm : q.b_sn, s_k = is_a ? q.a_sk : q.b_sk, ext = is_a ? q.M : q.N;
+    const long long stride = is_a ? q.strideA : q.strideB;
+    const uintptr_t ptr = (uintptr_t)(is_a ? q.A : q.B);
+    if (ptr % 16 != 0 || stride % 4 != 0) return 0;
+    if (s_k == 1 && s_idx % 4 == 0 && q.K % 4 == 0) return 1;
+    if (s_idx == 1 && s_k % 4 == 0 && ext % 4 == 0) return 2;
+    return 0;
+}
+
 hipError_t f32s_launch(const Problem &q)
 {
     FParams p;
@@ -479,18 +562,26 @@ hipError_t f32s_launch(const Problem &q)
     p.alpha = q.alpha; p.beta = q.beta;
     const int tiles_m = (int)((q.M + ST - 1) / ST);
     p.tiles_n = (int)((q.N + ST - 1) / ST);
-    hipLaunchKernelGGL(f32s_kernel, dim3((unsigned)(tiles_m * p.tiles_n), (unsigned)q.batch), dim3(256), 0, q.stream, p);
+    const dim3 grid((unsigned)(tiles_m * p.tiles_n), (unsigned)q.batch);
+    const int la = f32s_form(q, true), lb = f32s_form(q, false);
+    if (la == 1 && lb == 1) hipLaunchKernelGGL((f32s_kernel<1, 1>), grid, dim3(256), 0, q.stream, p);
+    else if (la == 1 && lb == 2) hipLaunchKernelGGL((f32s_kernel<1, 2>), grid, dim3(256), 0, q.stream, p);
+    else if (la == 2 && lb == 1) hipLaunchKernelGGL((f32s_kernel<2, 1>), grid, dim3(256), 0, q.stream, p);
+    else if (la == 2 && lb == 2) hipLaunchKernelGGL((f32s_kernel<2, 2>), grid, dim3(256), 0, q.stream, p);
+    else hipLaunchKernelGGL((f32s_kernel<0, 0>), grid, dim3(256), 0, q.stream, p);
     return hipGetLastError();
 }
 
-// Calibrated on the device (calls replayed from a HIP graph): about 3 us per launch and 4.5 us per chunk of 256 k
-// (256^3 7.7 us, 512 x 512 x 1024 20.3 us, 64 x 64 x 4096 68 us, each ahead of the tiled kernels: 8.3, 26.6, 97);
-// with more than one workgroup per compute unit the tiled kernels win (1024^2 x 256: 27.9 against 9.6)
+// Calibrated on the device (calls replayed from a HIP graph). With 16-byte loads: about 2.4 us per launch and 2 us
+// per chunk of 256 k (256^3 4.4 us, 512 x 512 x 1024 11.2 us, 64 x 64 x 4096 33 us, each ahead of the tiled kernels:
+// 8.4, 26.5, 97). One element per load: 3 us and 4.5 us per chunk. With more than one workgroup per compute unit the
+// tiled kernels win (1024^2 x 256: 11.0 against 9.3)
 double f32s_cost(const Problem &q)
 {
     const double tiles = (double)((q.M + ST - 1) / ST) * (double)((q.N + ST - 1) / ST) * (double)q.batch;
     if (tiles > 256.0 || q.K > 8192) return 1e30;
-    return 3.0 + 4.5 * (double)((q.K + SK - 1) / SK);
+    const double chunks = (double)((q.K + SK - 1) / SK);
+    return f32s_form(q, true) && f32s_form(q, false) ? 2.4 + 2.0 * chunks : 3.0 + 4.5 * chunks;
 }
 
 const Variant kF32_small = {"f32 32x32x256 four waves split k, whole chunk in flight, mfma32x32x2", f32s_can_run, f32s_launch, f32s_cost};
