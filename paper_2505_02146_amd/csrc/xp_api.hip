@@ -13,7 +13,7 @@ namespace xp {
 
 namespace {
 
-constexpr int kMaxVariants = 128;                       // 62 bf16 variants at the last count; checked in build_tables
+constexpr int kMaxVariants = 128;                       // 67 bf16 variants at the last count; checked in build_tables
 const Variant *g_table[3][kMaxVariants];
 int g_count[3] = {0, 0, 0};
 std::once_flag g_once;
@@ -40,6 +40,7 @@ void build_tables()
         n += dl_small_variants(types[s], g_table[s] + n);
         n += rs_variants(types[s], g_table[s] + n);
         if (types[s] == XP_F32) n += f32_small_variants(g_table[s] + n);
+        n += dl_pair_variants(types[s], g_table[s] + n);
         if (n > kMaxVariants) { fprintf(stderr, "xp: variant table overflow (%d)\n", n); abort(); }
         g_count[s] = n;
     }
@@ -95,8 +96,8 @@ struct Tuned {
 
 const Tuned kTuned[] = {
     {XP_OP_GEMM, XP_F32, 1, 256, 256, 256, true, false, "f32 32x32x256 four waves split k, whole chunk in flight, mfma32x32x2"},
-    {XP_OP_GEMM, XP_BF16, 1, 4096, 4096, 4096, true, true, "bf16 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly, mfma16"},
-    {XP_OP_GEMM, XP_I8, 1, 4096, 4096, 8192, true, true, "i8 256x256x128B waves 2x4 ring 3(A)+2(B) direct-to-lds, reads as assembly, mfma16"},
+    {XP_OP_GEMM, XP_BF16, 1, 4096, 4096, 4096, true, true, "bf16 256x256x128B waves 2x2 ring 3(A)+2(B) direct-to-lds, reads as assembly, sub-steps paired, mfma16"},
+    {XP_OP_GEMM, XP_I8, 1, 4096, 4096, 8192, true, true, "i8 256x256x128B waves 2x2 ring 3(A)+2(B) direct-to-lds, reads as assembly, sub-steps paired, mfma16"},
     {XP_OP_GEMM_BATCHED, XP_BF16, 96, 512, 512, 64, true, true, "bf16 64x128-stream x128B single-k-step producer/consumer nt-stores mfma32"},
     {XP_OP_GEMM_BATCHED, XP_BF16, 96, 512, 64, 512, true, false, "bf16 64x64x128B waves 2x2 k-group-interleaved mfma32"},
     {XP_OP_CONV2D, XP_BF16, 1, 100352, 256, 2304, true, true, "bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 2(A)+2(B) direct-to-lds, reads as assembly, mfma16"},

@@ -76,6 +76,7 @@ int dl_bnm_variants(xp_dtype in_type, const Variant **out);
 int dl_asm_variants(xp_dtype in_type, const Variant **out);
 int dl_small_variants(xp_dtype in_type, const Variant **out);
 int rs_variants(xp_dtype in_type, const Variant **out);
+int dl_pair_variants(xp_dtype in_type, const Variant **out);
 int gemv_variants(xp_dtype in_type, const Variant **out);
 
 // Pieces of the dispatcher that the run-time tuner uses (xp_api.hip).

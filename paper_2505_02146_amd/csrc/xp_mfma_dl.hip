@@ -56,13 +56,15 @@ struct DlParams {
     // the rest tile rows [m_split, M) with the second
     int n1, m_split, tiles_m2;
 #ifdef XP_TRACE
-    long long *trace;                     // diagnostic build: 8 words per workgroup (shader-clock and 100 MHz time stamps)
+    long long *trace;                     // diagnostic build: 16 words per workgroup (shader-clock and 100 MHz time stamps)
 #endif
 };
 
 template <int BM_, int BN_, int WM_, int WN_, int NS_, int RB_, bool SPREAD_ = false, int OCC_ = 1, int MF_ = 32, bool NT_ = false,
-          int NSA_ = NS_>
+          int NSA_ = NS_, int PAIR_ = 0>
 struct DlTile {
+    // the two k sub-steps of a block back to back on its accumulator (see pair_loop in dl_body)
+    static constexpr int PAIR = PAIR_;
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NS = NS_, RB = RB_;
     // ring depth of the A buffers (NS is that of the B buffers): one more A buffer than B buffers
     // gives the A loads an extra K step to land where LDS cannot hold a third whole stage
@@ -99,6 +101,8 @@ struct DlTile {
     static_assert(!ASYM || !SPREAD_, "spread issue is for equal ring depths");
     static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
     static_assert(!SPREAD || NS >= 3, "with two buffers the loads of a step must all be issued at its start");
+    static_assert(!PAIR || (NSA == 3 && NS == 2 && MF == 16 && RB == 128 && MI % 4 == 0 && MI >= 4),
+                  "paired sub-steps: three A and two B buffers, block rows in sets of four");
 };
 
 // Operand along its outer index (MODE 3-5 of dl_body): chunk swizzle of a k row of ROWB bytes.  A transposing
@@ -136,6 +140,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, un
 
 // s_waitcnt immediate for "vmcnt <= n and lgkmcnt == 0" (gfx9 encoding, expcnt left open)
 constexpr int waitcnt_vm_lgkm0(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4); }
+// "vmcnt <= n", the other counters left open
+constexpr int waitcnt_vm_only(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -172,6 +178,15 @@ template <> struct Acc<true, 16> {
                                                      c, 0, 0, 0);
     }
 };
+
+// The 16x16 MFMA as assembly with its accumulator held in the accumulation registers.  A wave that owns a 128 x 128
+// tile has 256 accumulator registers, the whole accumulation file; left to the register allocator, which moves values
+// between the two files as it sees fit, its loop is mostly copies.
+template <bool INT8> __device__ __forceinline__ void mma16_acc(typename Acc<INT8, 16>::type &c, u32x4 a, u32x4 b)
+{
+    if constexpr (INT8) asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
 
 // floor(n / d) for 0 <= n < 2^31 as a multiplication: magic = ceil(2^(31 + shift) / d) with shift = ceil(log2 d)
 // (the host works both out once per call); exact for every such n.  A 32-bit division costs some forty vector
@@ -214,6 +229,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
 #ifdef XP_TRACE
     // diagnostic build (-DXP_TRACE): where a workgroup's time goes -- entry, first MFMA, end of the K loop, stores done
     long long tr_c[4] = {0, 0, 0, 0}, tr_w[4] = {0, 0, 0, 0};
+    long long tr_wait[3] = {0, 0, 0};                   // paired loop: cycles waiting for global loads, in the barrier, for LDS reads
     const int tr_slot = (int)(blockIdx.y * gridDim.x + blockIdx.x) + (m_base ? (int)(gridDim.x * gridDim.y) : 0);
     tr_c[0] = clock64(); tr_w[0] = wall_clock64();
 #endif
@@ -447,36 +463,39 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     // block row of the next sub-step needs all of them).  Operand along K: one address register per sub-step, the
     // blocks are offsets; operand along its outer index: one address register per block (the swizzle), the sub-step
     // is an offset
-    auto read_frag_asm = [&](auto ao_c, auto bo_c, auto kk_c, auto f_c, int a_off, int b_off, AFrag (&af)[T::MI], BFrag (&bf)[T::NI]) {
-        constexpr int AO = decltype(ao_c)::value, BO = decltype(bo_c)::value, KK = decltype(kk_c)::value, F = decltype(f_c)::value;
-        if constexpr (F >= T::NI) {
-            constexpr int I = F - T::NI;
-            constexpr int AREL = AO < 0 ? 0 : AO;
-            constexpr bool AFAR = AREL + A_TOP >= 65536;
-            constexpr int AIMM = (AFAR ? AREL - 65536 : AREL) + (AMM ? KK * 32 * RAM : 0);
-            if constexpr (AMM) {
-                const unsigned at = AO < 0 ? lds_base + a_off + fam[I] : (AFAR ? fa_far[A_FAR ? I : 0] : lds_base + fam[I]);
-                af[I].lo = lds_read_tr16_b64<AIMM>(at);
-                af[I].hi = lds_read_tr16_b64<AIMM + 4 * RAM>(at);
-            } else {
-                const unsigned at = AO < 0 ? lds_base + a_off + fa[KK] : (AFAR ? fa_far[A_FAR ? KK : 0] : lds_base + fa[KK]);
-                af[I] = lds_read_b128<AIMM + I * MF * RB>(at);
-            }
+    auto read_a_asm = [&](auto ao_c, auto kk_c, auto i_c, int a_off, AFrag &dst) {
+        constexpr int AO = decltype(ao_c)::value, KK = decltype(kk_c)::value, I = decltype(i_c)::value;
+        constexpr int AREL = AO < 0 ? 0 : AO;
+        constexpr bool AFAR = AREL + A_TOP >= 65536;
+        constexpr int AIMM = (AFAR ? AREL - 65536 : AREL) + (AMM ? KK * 32 * RAM : 0);
+        if constexpr (AMM) {
+            const unsigned at = AO < 0 ? lds_base + a_off + fam[I] : (AFAR ? fa_far[A_FAR ? I : 0] : lds_base + fam[I]);
+            dst.lo = lds_read_tr16_b64<AIMM>(at);
+            dst.hi = lds_read_tr16_b64<AIMM + 4 * RAM>(at);
         } else {
-            constexpr int J = F;
-            constexpr int BREL = BO < 0 ? 0 : BO - T::B_BASE;
-            constexpr bool BFAR = BREL + B_TOP >= 65536;
-            constexpr int BIMM = (BFAR ? BREL - 65536 : BREL) + (BNM ? KK * 32 * RBN : 0);
-            const unsigned b_rt = lds_base + b_off;          // used with a run-time buffer offset only
-            if constexpr (BNM) {
-                const unsigned at = BO < 0 ? b_rt + fbn[J] : (BFAR ? fb_far[B_FAR ? J : 0] : lds_base + T::B_BASE + fbn[J]);
-                bf[J].lo = lds_read_tr16_b64<BIMM>(at);
-                bf[J].hi = lds_read_tr16_b64<BIMM + 4 * RBN>(at);
-            } else {
-                const unsigned at = BO < 0 ? b_rt + fb[KK] : (BFAR ? fb_far[B_FAR ? KK : 0] : lds_base + T::B_BASE + fb[KK]);
-                bf[J] = lds_read_b128<BIMM + J * MF * RB>(at);
-            }
+            const unsigned at = AO < 0 ? lds_base + a_off + fa[KK] : (AFAR ? fa_far[A_FAR ? KK : 0] : lds_base + fa[KK]);
+            dst = lds_read_b128<AIMM + I * MF * RB>(at);
         }
+    };
+    auto read_b_asm = [&](auto bo_c, auto kk_c, auto j_c, int b_off, BFrag &dst) {
+        constexpr int BO = decltype(bo_c)::value, KK = decltype(kk_c)::value, J = decltype(j_c)::value;
+        constexpr int BREL = BO < 0 ? 0 : BO - T::B_BASE;
+        constexpr bool BFAR = BREL + B_TOP >= 65536;
+        constexpr int BIMM = (BFAR ? BREL - 65536 : BREL) + (BNM ? KK * 32 * RBN : 0);
+        const unsigned b_rt = lds_base + b_off;          // used with a run-time buffer offset only
+        if constexpr (BNM) {
+            const unsigned at = BO < 0 ? b_rt + fbn[J] : (BFAR ? fb_far[B_FAR ? J : 0] : lds_base + T::B_BASE + fbn[J]);
+            dst.lo = lds_read_tr16_b64<BIMM>(at);
+            dst.hi = lds_read_tr16_b64<BIMM + 4 * RBN>(at);
+        } else {
+            const unsigned at = BO < 0 ? b_rt + fb[KK] : (BFAR ? fb_far[B_FAR ? KK : 0] : lds_base + T::B_BASE + fb[KK]);
+            dst = lds_read_b128<BIMM + J * MF * RB>(at);
+        }
+    };
+    auto read_frag_asm = [&](auto ao_c, auto bo_c, auto kk_c, auto f_c, int a_off, int b_off, AFrag (&af)[T::MI], BFrag (&bf)[T::NI]) {
+        constexpr int F = decltype(f_c)::value;
+        if constexpr (F >= T::NI) read_a_asm(ao_c, kk_c, std::integral_constant<int, F - T::NI>{}, a_off, af[F - T::NI]);
+        else read_b_asm(bo_c, kk_c, f_c, b_off, bf[F]);
     };
     // One MFMA sub-step on the set (ca, cb) with the reads of the set (na, nb) -- sub-step KK of the buffers at
     // AO / BO -- dealt out behind its block rows: a wave that issues its reads as one burst keeps the matrix pipe
@@ -534,6 +553,172 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     const int KT = p.KT;
     constexpr int PENDING = T::PENDING;                  // loads that may still be in flight at a barrier
     constexpr int A_END = T::NSA * T::A_BYTES, B_END = T::B_BASE + T::NS * T::B_BYTES;
+    if constexpr (T::PAIR != 0) {
+        // Paired sub-steps.  Two MFMAs in a row on the same accumulator draw less power than the same two with other
+        // blocks between them (a loop of nothing but MFMAs on N(0,1) operands at the power limit: 2180 against 2040
+        // TFLOP/s; chains of four are no better, and walking the sub-steps back and forth is not either), and power is
+        // what bounds this loop.  So a block takes both k sub-steps of a K step at once, which needs both sub-steps'
+        // fragments of its row and column in registers: all of the step's B fragments are held (2 NI of them) and A
+        // streams through four sets of two fragments, a set per block row, in groups of two rows.  Behind the first
+        // row of a group go the reads for the next group and the second row covers their latency; every wait is for
+        // all LDS operations.
+        //   groups 0 .. MI/2-2 | barrier | group MI/2-1
+        // The one barrier of step kt precedes its last group: behind it K step kt+1 is in LDS for every wave -- the last
+        // group reads all of its B fragments and its first two A rows -- and every wave has finished with the buffers
+        // of step kt.  The B buffer is refilled at once, by the last group, with step kt+2, which must have landed at
+        // the next barrier; the A buffer by the groups before the next barrier, with step kt+3: those loads are the
+        // youngest at that barrier and stay in flight across it (three A buffers, two B buffers).
+        static_assert(ASMR && T::PH == 2 && !CONV, "paired sub-steps: GEMM with assembly reads");
+        typedef std::integral_constant<int, -1> RunTime;
+        typedef std::integral_constant<int, 0> Zero;
+        typedef std::integral_constant<int, 1> One;
+        constexpr int NG = T::MI / 2;                                   // groups of two block rows
+        constexpr int NBF = 2 * T::NI;                                  // B fragments of a step
+        constexpr int LAST = NG - 1;                                    // the group behind the barrier
+        constexpr bool ACC_FILE = T::NWAVE == 4;                        // one wave per SIMD: accumulators in the accumulation registers
+        if (KT > 0) {
+            AFrag ar[4][2];                                             // block row i % 4, sub-steps 0 and 1
+            BFrag bx[2][T::NI], by[2][T::NI];                           // the B fragments of even / odd K steps
+            issue_a(0, 0, 0, T::IA, std::true_type{});
+            issue_b(0, T::B_BASE, 0, T::IB, std::true_type{});
+            issue_a(1, T::A_BYTES, 0, T::IA, std::true_type{});
+            issue_b(1, T::B_BASE + T::B_BYTES, 0, T::IB, std::true_type{});
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(IT));           // K step 0 has landed
+            __builtin_amdgcn_s_barrier();
+            static_for<NBF>([&](auto f_c) {
+                constexpr int F = decltype(f_c)::value;
+                read_b_asm(std::integral_constant<int, T::B_BASE>{}, std::integral_constant<int, F / T::NI>{},
+                           std::integral_constant<int, F % T::NI>{}, 0, bx[F / T::NI][F % T::NI]);
+            });
+            static_for<4>([&](auto f_c) {
+                constexpr int F = decltype(f_c)::value;
+                read_a_asm(Zero{}, std::integral_constant<int, F % 2>{}, std::integral_constant<int, F / 2>{}, 0, ar[F / 2][F % 2]);
+            });
+            // ring state of the run-time steps: the A buffers of steps kt, kt+1, kt+2 and the B buffers of kt+1, kt (= kt+2)
+            int cur_a = 0, nxt_a = T::A_BYTES, fill_a = 2 * T::A_BYTES, nxt_b = T::B_BASE + T::B_BYTES, fill_b = T::B_BASE;
+            auto step = [&](int kt, auto odd_c, auto check_c, auto pos_c) {
+                constexpr bool ODD = decltype(odd_c)::value;
+                constexpr int POS = decltype(pos_c)::value;
+                constexpr int CA = POS < 0 ? -1 : (POS % 3) * T::A_BYTES, NA = POS < 0 ? -1 : ((POS + 1) % 3) * T::A_BYTES;
+                constexpr int NB = POS < 0 ? -1 : T::B_BASE + ((POS + 1) % 2) * T::B_BYTES;
+                const int now_a = POS >= 0 ? CA : cur_a, next_a = POS >= 0 ? NA : nxt_a, next_b = POS >= 0 ? NB : nxt_b;
+                const int into_a = POS >= 0 ? ((POS + 2) % 3) * T::A_BYTES : fill_a;
+                const int into_b = POS >= 0 ? T::B_BASE + (POS % 2) * T::B_BYTES : fill_b;
+                BFrag (&bc)[2][T::NI] = ODD ? by : bx;
+                BFrag (&bn)[2][T::NI] = ODD ? bx : by;
+                static_for<NG>([&](auto g_c) {
+                    constexpr int G = decltype(g_c)::value, R0 = 2 * G, R1 = 2 * G + 1;
+                    if constexpr (G != LAST || NG == 1) lds_wait<0>();  // (the last group follows the barrier's wait)
+                    if constexpr (G == 0) {
+#pragma unroll
+                        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                            for (int j = 0; j < T::NI; ++j) frag_tie(bc[kk][j]);
+                    }
+                    frag_tie(ar[R0 % 4][0]); frag_tie(ar[R0 % 4][1]); frag_tie(ar[R1 % 4][0]); frag_tie(ar[R1 % 4][1]);
+                    // What the group issues besides its MFMAs, in this order: the four A fragments of the next group's
+                    // rows (of this K step, or rows 0 and 1 of the next one); the last group: the next step's B
+                    // fragments and the B loads of step kt+2; the others: their share of the A loads of step kt+2
+                    // (into the buffer that the barrier of the step before has freed)
+                    constexpr int NRB = G == LAST ? NBF : 0;
+                    constexpr int L_LO = G == LAST ? 0 : G * T::IA / LAST, L_HI = G == LAST ? T::IB : (G + 1) * T::IA / LAST;
+                    constexpr int NITEMS = 4 + NRB + (L_HI - L_LO);
+                    auto item = [&](auto k_c) {
+                        constexpr int K = decltype(k_c)::value;
+                        if constexpr (K < 4) {
+                            constexpr int RN = R0 + 2 + K / 2, KK = K % 2;
+                            if constexpr (RN < T::MI)
+                                read_a_asm(std::integral_constant<int, CA>{}, std::integral_constant<int, KK>{}, std::integral_constant<int, RN>{}, now_a,
+                                           ar[RN % 4][KK]);
+                            else
+                                read_a_asm(std::integral_constant<int, NA>{}, std::integral_constant<int, KK>{}, std::integral_constant<int, RN - T::MI>{},
+                                           next_a, ar[RN % 4][KK]);
+                        } else if constexpr (K < 4 + NRB) {
+                            constexpr int F = K - 4;
+                            read_b_asm(std::integral_constant<int, NB>{}, std::integral_constant<int, F / T::NI>{},
+                                       std::integral_constant<int, F % T::NI>{}, next_b, bn[F / T::NI][F % T::NI]);
+                        } else if constexpr (K < NITEMS) {
+                            constexpr int L = L_LO + K - 4 - NRB;
+                            if constexpr (G == LAST) issue_b(kt + 2, into_b, L, L + 1, check_c);
+                            else issue_a(kt + 2, into_a, L, L + 1, check_c);
+                        }
+                    };
+                    // One wave per SIMD: an item behind every MFMA, so that the matrix pipe never waits for the wave to
+                    // get through a run of other instructions (nobody else issues on this SIMD).  Two waves per SIMD:
+                    // the reads behind the first row (the second covers their latency), the loads split over both rows.
+                    constexpr int PER_ROW = 2 * T::NI;                                          // MFMAs of a block row
+                    static_assert(!ACC_FILE || (4 + NRB <= 2 * PER_ROW - 8 && NITEMS <= 2 * PER_ROW), "the last MFMAs of a group cover the reads' latency");
+                    auto row = [&](auto r_c, auto first_c) {
+                        constexpr int I = decltype(r_c)::value, FIRST = decltype(first_c)::value;
+                        static_for<T::NI>([&](auto jj_c) {
+                            constexpr int JJ = decltype(jj_c)::value, J = (I & 1) ? T::NI - 1 - JJ : JJ;
+                            if constexpr (ACC_FILE) {
+                                mma16_acc<INT8>(acc[I][J], frag_value(bc[0][J]), frag_value(ar[I % 4][0]));
+                                item(std::integral_constant<int, FIRST + 2 * JJ>{});
+                                mma16_acc<INT8>(acc[I][J], frag_value(bc[1][J]), frag_value(ar[I % 4][1]));
+                                item(std::integral_constant<int, FIRST + 2 * JJ + 1>{});
+                            } else {
+                                acc[I][J] = Acc<INT8, 16>::mma(frag_value(bc[0][J]), frag_value(ar[I % 4][0]), acc[I][J]);
+                                acc[I][J] = Acc<INT8, 16>::mma(frag_value(bc[1][J]), frag_value(ar[I % 4][1]), acc[I][J]);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        });
+                    };
+                    row(std::integral_constant<int, R0>{}, Zero{});
+                    if constexpr (!ACC_FILE) {
+                        constexpr int HALF = 4 + NRB + (L_HI - L_LO + 1) / 2;
+                        static_for<HALF>([&](auto k_c) { item(k_c); });
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    row(std::integral_constant<int, R1>{}, std::integral_constant<int, PER_ROW>{});
+                    if constexpr (!ACC_FILE) {
+                        constexpr int HALF = 4 + NRB + (L_HI - L_LO + 1) / 2;
+                        static_for<NITEMS - HALF>([&](auto k_c) { item(std::integral_constant<int, HALF + decltype(k_c)::value>{}); });
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if constexpr (G == LAST - 1 || NG == 1) {
+                        // K step kt+1 has landed; this step's A loads (for step kt+2) may stay in flight
+#ifdef XP_TRACE
+                        const long long tb0 = clock64();
+                        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(T::IA));
+                        const long long tb1 = clock64();
+                        __builtin_amdgcn_s_barrier();
+                        tr_wait[0] += tb1 - tb0;
+                        tr_wait[1] += clock64() - tb1;
+#else
+                        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(T::IA));
+                        __builtin_amdgcn_s_barrier();
+#endif
+                    }
+                });
+                if constexpr (POS < 0) {
+                    const int a = cur_a, b = nxt_b;
+                    cur_a = nxt_a; nxt_a = fill_a; fill_a = a;
+                    nxt_b = fill_b; fill_b = b;
+                }
+            };
+#ifdef XP_TRACE
+            tr_c[1] = clock64(); tr_w[1] = wall_clock64();
+#endif
+            // steps whose loads (K step kt + 2) are whole steps inside K, in rounds after which both rings and the
+            // B fragment sets are where they were: every LDS offset an instruction constant
+            const int whole = p.Kb / RB - 2;
+            int kt = 0;
+            for (; kt + 6 <= whole; kt += 6)
+                static_for<6>([&](auto pos_c) {
+                    step(kt + decltype(pos_c)::value, std::integral_constant<bool, (decltype(pos_c)::value & 1) != 0>{}, std::false_type{}, pos_c);
+                });
+            while (kt < KT) {
+                step(kt, std::false_type{}, std::true_type{}, RunTime{});
+                if (++kt < KT) step(kt, std::true_type{}, std::true_type{}, RunTime{});
+                ++kt;
+            }
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
+            // (the compiler does not know that the statements above are matrix instructions and leaves no room
+            // between the last of them and the first read of its result)
+            if constexpr (ACC_FILE) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        }
+    } else
     if (KT > 0) {
         AFrag xa[T::MI], ya[T::MI];                           // fragment sets of even / odd sub-steps
         BFrag xb[T::NI], yb[T::NI];
@@ -688,6 +873,44 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     // epilogue
     using OutT = typename std::conditional<INT8, int, float>::type;
     OutT *C = (OutT *)p.C + batch * p.strideC;
+    if constexpr (MF == 16 && !PLANAR) {
+        // A tile that lies inside the matrix, beta == 0, 16-byte aligned rows: one address per lane for the whole wave
+        // tile (the block row adds a multiple of the pitch, the block column is an instruction constant), no test per
+        // block, and with alpha == 1 (or integers) the accumulators are stored as they are
+        const bool whole = m0 + T::BM <= m_end && n0 + T::BN <= p.N && (INT8 || p.beta == 0.0f) &&
+                           (((unsigned long long)C | (unsigned long long)(p.ldc * (long long)sizeof(OutT))) & 15) == 0;
+        if (whole) {
+            typedef OutT out4 __attribute__((ext_vector_type(4)));
+            OutT *base = C + (long long)(m0 + wm * T::WTM + (lane & 15)) * p.ldc + (n0 + wn * T::WTN + (lane >> 4) * 4);
+            const long long step16 = 16 * p.ldc;
+            if (INT8 || p.alpha == 1.0f) {
+#pragma unroll
+                for (int i = 0; i < T::MI; ++i, base += step16)
+#pragma unroll
+                    for (int j = 0; j < T::NI; ++j)
+                        put<T::NTSTORE>((out4 *)(base + 16 * j), out4{(OutT)acc[i][j][0], (OutT)acc[i][j][1], (OutT)acc[i][j][2], (OutT)acc[i][j][3]});
+            } else {
+                if constexpr (!INT8) {
+#pragma unroll
+                    for (int i = 0; i < T::MI; ++i, base += step16)
+#pragma unroll
+                        for (int j = 0; j < T::NI; ++j)
+                            put<T::NTSTORE>((out4 *)(base + 16 * j),
+                                            out4{p.alpha * acc[i][j][0], p.alpha * acc[i][j][1], p.alpha * acc[i][j][2], p.alpha * acc[i][j][3]});
+                }
+            }
+#ifdef XP_TRACE
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+            tr_c[3] = clock64(); tr_w[3] = wall_clock64();
+            if (p.trace && tid == 0) {
+#pragma unroll
+                for (int x = 0; x < 4; ++x) { p.trace[tr_slot * 16 + x] = tr_c[x]; p.trace[tr_slot * 16 + 4 + x] = tr_w[x]; }
+                for (int x = 0; x < 3; ++x) p.trace[tr_slot * 16 + 8 + x] = tr_wait[x];
+            }
+#endif
+            return;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < T::MI; ++i)
 #pragma unroll
@@ -707,7 +930,8 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     tr_c[3] = clock64(); tr_w[3] = wall_clock64();
     if (p.trace && tid == 0) {
 #pragma unroll
-        for (int x = 0; x < 4; ++x) { p.trace[tr_slot * 8 + x] = tr_c[x]; p.trace[tr_slot * 8 + 4 + x] = tr_w[x]; }
+        for (int x = 0; x < 4; ++x) { p.trace[tr_slot * 16 + x] = tr_c[x]; p.trace[tr_slot * 16 + 4 + x] = tr_w[x]; }
+        for (int x = 0; x < 3; ++x) p.trace[tr_slot * 16 + 8 + x] = tr_wait[x];
     }
 #endif
 }
@@ -1074,6 +1298,40 @@ XP_DL_ASM_VARIANT(kI8Asm128x128, "i8", true, 128, 128, 2, 2, 2, 2, 2, 0.36)
 XP_DL_ASM_VARIANT(kI8Asm256x128, "i8", true, 256, 128, 4, 2, 3, 3, 1, 0.46)
 XP_DL_ASM_VARIANT(kI8Asm128x256, "i8", true, 128, 256, 2, 4, 3, 3, 1, 0.46)
 XP_DL_ASM_VARIANT(kI8Asm256x256, "i8", true, 256, 256, 2, 4, 2, 2, 1, 0.54)
+
+// ---- the two k sub-steps of a block back to back (DlTile::PAIR): GEMM and batched GEMM
+template <bool INT8, class T>
+hipError_t dl_pair_launch(const Problem &q)
+{
+    const DlParams p = dl_params<INT8, T>(q);
+    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)q.batch);
+    hipLaunchKernelGGL((dl_kernel<INT8, T, 6>), grid, dim3(T::NT), 0, q.stream, p);
+    return hipGetLastError();
+}
+
+#define XP_DL_PAIR_VARIANT(NAME, TYPESTR, INT8, BM, BN, WM, WN, PAIR, PAIRSTR, EFF)                                       \
+    typedef DlTile<BM, BN, WM, WN, 2, 128, false, 1, 16, false, 3, PAIR> NAME##_tile;                                     \
+    bool NAME##_can(const Problem &q) { return !q.conv && dl_can_run_common<INT8>(q, BM, BN, 128, 16); }                  \
+    hipError_t NAME##_launch(const Problem &q) { return dl_pair_launch<INT8, NAME##_tile>(q); }                           \
+    double NAME##_cost(const Problem &q) { return dl_cost<NAME##_tile>(q, EFF); }                                         \
+    const Variant NAME = {TYPESTR " " #BM "x" #BN "x128B waves " #WM "x" #WN " ring 3(A)+2(B) direct-to-lds, reads as assembly, sub-steps paired" PAIRSTR ", mfma16", \
+                          NAME##_can, NAME##_launch, NAME##_cost};
+
+#define XP_DL_PAIR_OUTER_VARIANT(NAME, MODE, WHAT, EFF)                                                                    \
+    typedef DlTile<256, 256, 2, 2, 2, 128, false, 1, 16, false, 3, 1> NAME##_tile;                                        \
+    bool NAME##_can(const Problem &q) { return dl_outer_can_run(q, 256, 256, MODE == 4 || MODE == 5, MODE == 3 || MODE == 5); } \
+    hipError_t NAME##_launch(const Problem &q) { return dl_outer_launch<NAME##_tile, MODE>(q); }                          \
+    double NAME##_cost(const Problem &q) { return dl_cost<NAME##_tile>(q, EFF); }                                         \
+    const Variant NAME = {"bf16 256x256x128B waves 2x2 ring 3(A)+2(B) direct-to-lds, " WHAT " by transposing reads, sub-steps paired, mfma16", \
+                          NAME##_can, NAME##_launch, NAME##_cost};
+
+XP_DL_PAIR_OUTER_VARIANT(kBfPairBnm, 3, "B along N", 0.54)
+XP_DL_PAIR_OUTER_VARIANT(kBfPairAmm, 4, "A along M", 0.52)
+XP_DL_PAIR_OUTER_VARIANT(kBfPairAmmBnm, 5, "A along M and B along N", 0.52)
+XP_DL_PAIR_VARIANT(kBfPair256x256, "bf16", false, 256, 256, 2, 4, 1, "", 0.56)
+XP_DL_PAIR_VARIANT(kI8Pair256x256, "i8", true, 256, 256, 2, 4, 1, "", 0.56)
+XP_DL_PAIR_VARIANT(kI8PairW4, "i8", true, 256, 256, 2, 2, 1, "", 0.58)
+XP_DL_PAIR_VARIANT(kBfPairW4, "bf16", false, 256, 256, 2, 2, 1, "", 0.58)
 }  // namespace
 
 #ifdef XP_TRACE
@@ -1112,6 +1370,14 @@ int dl_small_variants(xp_dtype in_type, const Variant **out)
     if (in_type != XP_BF16) return 0;
     out[0] = &kBfBnm64x64n3; out[1] = &kBfBnm64x64n4; out[2] = &kBfBnm128x64n3;
     return 3;
+}
+
+// Registered after the small ones.
+int dl_pair_variants(xp_dtype in_type, const Variant **out)
+{
+    if (in_type == XP_BF16) { out[0] = &kBfPair256x256; out[1] = &kBfPairW4; out[2] = &kBfPairBnm; out[3] = &kBfPairAmm; out[4] = &kBfPairAmmBnm; return 5; }
+    if (in_type == XP_I8) { out[0] = &kI8Pair256x256; out[1] = &kI8PairW4; return 2; }
+    return 0;
 }
 
 // Registered after every other family so that the older variants keep their indices.
