@@ -13,7 +13,7 @@ namespace xp {
 
 namespace {
 
-constexpr int kMaxVariants = 128;                       // 67 bf16 variants at the last count; checked in build_tables
+constexpr int kMaxVariants = 128;                       // 68 bf16 variants at the last count; checked in build_tables
 const Variant *g_table[3][kMaxVariants];
 int g_count[3] = {0, 0, 0};
 std::once_flag g_once;

@@ -101,8 +101,7 @@ struct DlTile {
     static_assert(!ASYM || !SPREAD_, "spread issue is for equal ring depths");
     static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
     static_assert(!SPREAD || NS >= 3, "with two buffers the loads of a step must all be issued at its start");
-    static_assert(!PAIR || (NSA == 3 && NS == 2 && MF == 16 && RB == 128 && MI % 4 == 0 && MI >= 4),
-                  "paired sub-steps: three A and two B buffers, block rows in sets of four");
+    static_assert(!PAIR || (NSA == 3 && NS == 2 && MF == 16 && RB == 128 && MI >= 3), "paired sub-steps: three A and two B buffers");
 };
 
 // Operand along its outer index (MODE 3-5 of dl_body): chunk swizzle of a k row of ROWB bytes.  A transposing
@@ -463,33 +462,40 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
     // block row of the next sub-step needs all of them).  Operand along K: one address register per sub-step, the
     // blocks are offsets; operand along its outer index: one address register per block (the swizzle), the sub-step
     // is an offset
+    // (each read picks the near or the far address register by its own constant offset: a buffer may straddle 64 KB)
     auto read_a_asm = [&](auto ao_c, auto kk_c, auto i_c, int a_off, AFrag &dst) {
         constexpr int AO = decltype(ao_c)::value, KK = decltype(kk_c)::value, I = decltype(i_c)::value;
         constexpr int AREL = AO < 0 ? 0 : AO;
-        constexpr bool AFAR = AREL + A_TOP >= 65536;
-        constexpr int AIMM = (AFAR ? AREL - 65536 : AREL) + (AMM ? KK * 32 * RAM : 0);
         if constexpr (AMM) {
-            const unsigned at = AO < 0 ? lds_base + a_off + fam[I] : (AFAR ? fa_far[A_FAR ? I : 0] : lds_base + fam[I]);
-            dst.lo = lds_read_tr16_b64<AIMM>(at);
-            dst.hi = lds_read_tr16_b64<AIMM + 4 * RAM>(at);
+            constexpr int LO = AREL + KK * 32 * RAM, HI = LO + 4 * RAM;
+            constexpr bool FAR_LO = LO >= 65536, FAR_HI = HI >= 65536;
+            const unsigned near = AO < 0 ? lds_base + a_off + fam[I] : lds_base + fam[I];
+            const unsigned far = fa_far[A_FAR ? I : 0];
+            dst.lo = lds_read_tr16_b64<FAR_LO ? LO - 65536 : LO>(FAR_LO ? far : near);
+            dst.hi = lds_read_tr16_b64<FAR_HI ? HI - 65536 : HI>(FAR_HI ? far : near);
         } else {
-            const unsigned at = AO < 0 ? lds_base + a_off + fa[KK] : (AFAR ? fa_far[A_FAR ? KK : 0] : lds_base + fa[KK]);
-            dst = lds_read_b128<AIMM + I * MF * RB>(at);
+            constexpr int OFFS = AREL + I * MF * RB;
+            constexpr bool FAR = OFFS >= 65536;
+            const unsigned at = AO < 0 ? lds_base + a_off + fa[KK] : (FAR ? fa_far[A_FAR ? KK : 0] : lds_base + fa[KK]);
+            dst = lds_read_b128<FAR ? OFFS - 65536 : OFFS>(at);
         }
     };
     auto read_b_asm = [&](auto bo_c, auto kk_c, auto j_c, int b_off, BFrag &dst) {
         constexpr int BO = decltype(bo_c)::value, KK = decltype(kk_c)::value, J = decltype(j_c)::value;
         constexpr int BREL = BO < 0 ? 0 : BO - T::B_BASE;
-        constexpr bool BFAR = BREL + B_TOP >= 65536;
-        constexpr int BIMM = (BFAR ? BREL - 65536 : BREL) + (BNM ? KK * 32 * RBN : 0);
         const unsigned b_rt = lds_base + b_off;          // used with a run-time buffer offset only
         if constexpr (BNM) {
-            const unsigned at = BO < 0 ? b_rt + fbn[J] : (BFAR ? fb_far[B_FAR ? J : 0] : lds_base + T::B_BASE + fbn[J]);
-            dst.lo = lds_read_tr16_b64<BIMM>(at);
-            dst.hi = lds_read_tr16_b64<BIMM + 4 * RBN>(at);
+            constexpr int LO = BREL + KK * 32 * RBN, HI = LO + 4 * RBN;
+            constexpr bool FAR_LO = LO >= 65536, FAR_HI = HI >= 65536;
+            const unsigned near = BO < 0 ? b_rt + fbn[J] : lds_base + T::B_BASE + fbn[J];
+            const unsigned far = fb_far[B_FAR ? J : 0];
+            dst.lo = lds_read_tr16_b64<FAR_LO ? LO - 65536 : LO>(FAR_LO ? far : near);
+            dst.hi = lds_read_tr16_b64<FAR_HI ? HI - 65536 : HI>(FAR_HI ? far : near);
         } else {
-            const unsigned at = BO < 0 ? b_rt + fb[KK] : (BFAR ? fb_far[B_FAR ? KK : 0] : lds_base + T::B_BASE + fb[KK]);
-            dst = lds_read_b128<BIMM + J * MF * RB>(at);
+            constexpr int OFFS = BREL + J * MF * RB;
+            constexpr bool FAR = OFFS >= 65536;
+            const unsigned at = BO < 0 ? b_rt + fb[KK] : (FAR ? fb_far[B_FAR ? KK : 0] : lds_base + T::B_BASE + fb[KK]);
+            dst = lds_read_b128<FAR ? OFFS - 65536 : OFFS>(at);
         }
     };
     auto read_frag_asm = [&](auto ao_c, auto bo_c, auto kk_c, auto f_c, int a_off, int b_off, AFrag (&af)[T::MI], BFrag (&bf)[T::NI]) {
@@ -568,16 +574,22 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         // of step kt.  The B buffer is refilled at once, by the last group, with step kt+2, which must have landed at
         // the next barrier; the A buffer by the groups before the next barrier, with step kt+3: those loads are the
         // youngest at that barrier and stay in flight across it (three A buffers, two B buffers).
-        static_assert(ASMR && T::PH == 2 && !CONV, "paired sub-steps: GEMM with assembly reads");
+        static_assert(ASMR && T::PH == 2, "paired sub-steps: with assembly reads");
         typedef std::integral_constant<int, -1> RunTime;
         typedef std::integral_constant<int, 0> Zero;
         typedef std::integral_constant<int, 1> One;
-        constexpr int NG = T::MI / 2;                                   // groups of two block rows
+        // Block rows are counted from OFF: an odd number of rows gets a row 0 that does not exist, so that the groups
+        // stay pairs and the last group, which carries the most reads, has both its rows.  Row v uses fragment set
+        // v % 4; when the (even) row count is no multiple of four the sets of odd K steps are the other two.
+        constexpr int OFF = T::MI & 1, MV = T::MI + OFF;
+        constexpr bool ROT = MV % 4 == 2;
+        constexpr int NG = MV / 2;                                      // groups of two block rows
         constexpr int NBF = 2 * T::NI;                                  // B fragments of a step
         constexpr int LAST = NG - 1;                                    // the group behind the barrier
         constexpr bool ACC_FILE = T::NWAVE == 4;                        // one wave per SIMD: accumulators in the accumulation registers
+        static_assert(NG >= 2, "at least three block rows");
         if (KT > 0) {
-            AFrag ar[4][2];                                             // block row i % 4, sub-steps 0 and 1
+            AFrag ar[4][2];                                             // fragment sets: sub-steps 0 and 1 of a block row
             BFrag bx[2][T::NI], by[2][T::NI];                           // the B fragments of even / odd K steps
             issue_a(0, 0, 0, T::IA, std::true_type{});
             issue_b(0, T::B_BASE, 0, T::IB, std::true_type{});
@@ -591,8 +603,8 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                            std::integral_constant<int, F % T::NI>{}, 0, bx[F / T::NI][F % T::NI]);
             });
             static_for<4>([&](auto f_c) {
-                constexpr int F = decltype(f_c)::value;
-                read_a_asm(Zero{}, std::integral_constant<int, F % 2>{}, std::integral_constant<int, F / 2>{}, 0, ar[F / 2][F % 2]);
+                constexpr int F = decltype(f_c)::value, V = F / 2;
+                if constexpr (V >= OFF) read_a_asm(Zero{}, std::integral_constant<int, F % 2>{}, std::integral_constant<int, V - OFF>{}, 0, ar[V][F % 2]);
             });
             // ring state of the run-time steps: the A buffers of steps kt, kt+1, kt+2 and the B buffers of kt+1, kt (= kt+2)
             int cur_a = 0, nxt_a = T::A_BYTES, fill_a = 2 * T::A_BYTES, nxt_b = T::B_BASE + T::B_BYTES, fill_b = T::B_BASE;
@@ -604,20 +616,23 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 const int now_a = POS >= 0 ? CA : cur_a, next_a = POS >= 0 ? NA : nxt_a, next_b = POS >= 0 ? NB : nxt_b;
                 const int into_a = POS >= 0 ? ((POS + 2) % 3) * T::A_BYTES : fill_a;
                 const int into_b = POS >= 0 ? T::B_BASE + (POS % 2) * T::B_BYTES : fill_b;
+                constexpr int SO = ROT && ODD ? 2 : 0, SN = ROT && !ODD ? 2 : 0;    // set offsets of this step's rows and of the next step's
                 BFrag (&bc)[2][T::NI] = ODD ? by : bx;
                 BFrag (&bn)[2][T::NI] = ODD ? bx : by;
                 static_for<NG>([&](auto g_c) {
-                    constexpr int G = decltype(g_c)::value, R0 = 2 * G, R1 = 2 * G + 1;
-                    if constexpr (G != LAST || NG == 1) lds_wait<0>();  // (the last group follows the barrier's wait)
+                    constexpr int G = decltype(g_c)::value, R0 = 2 * G, R1 = 2 * G + 1;     // (counted from OFF)
+                    constexpr bool REAL0 = R0 >= OFF;
+                    if constexpr (G != LAST) lds_wait<0>();             // (the last group follows the barrier's wait)
                     if constexpr (G == 0) {
 #pragma unroll
                         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
                             for (int j = 0; j < T::NI; ++j) frag_tie(bc[kk][j]);
                     }
-                    frag_tie(ar[R0 % 4][0]); frag_tie(ar[R0 % 4][1]); frag_tie(ar[R1 % 4][0]); frag_tie(ar[R1 % 4][1]);
+                    if constexpr (REAL0) { frag_tie(ar[(R0 + SO) % 4][0]); frag_tie(ar[(R0 + SO) % 4][1]); }
+                    frag_tie(ar[(R1 + SO) % 4][0]); frag_tie(ar[(R1 + SO) % 4][1]);
                     // What the group issues besides its MFMAs, in this order: the four A fragments of the next group's
-                    // rows (of this K step, or rows 0 and 1 of the next one); the last group: the next step's B
+                    // rows (of this K step, or the first two rows of the next one); the last group: the next step's B
                     // fragments and the B loads of step kt+2; the others: their share of the A loads of step kt+2
                     // (into the buffer that the barrier of the step before has freed)
                     constexpr int NRB = G == LAST ? NBF : 0;
@@ -627,12 +642,12 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                         constexpr int K = decltype(k_c)::value;
                         if constexpr (K < 4) {
                             constexpr int RN = R0 + 2 + K / 2, KK = K % 2;
-                            if constexpr (RN < T::MI)
-                                read_a_asm(std::integral_constant<int, CA>{}, std::integral_constant<int, KK>{}, std::integral_constant<int, RN>{}, now_a,
-                                           ar[RN % 4][KK]);
-                            else
-                                read_a_asm(std::integral_constant<int, NA>{}, std::integral_constant<int, KK>{}, std::integral_constant<int, RN - T::MI>{},
-                                           next_a, ar[RN % 4][KK]);
+                            if constexpr (RN < MV)
+                                read_a_asm(std::integral_constant<int, CA>{}, std::integral_constant<int, KK>{}, std::integral_constant<int, RN - OFF>{}, now_a,
+                                           ar[(RN + SO) % 4][KK]);
+                            else if constexpr (RN - MV >= OFF)
+                                read_a_asm(std::integral_constant<int, NA>{}, std::integral_constant<int, KK>{}, std::integral_constant<int, RN - MV - OFF>{},
+                                           next_a, ar[(RN - MV + SN) % 4][KK]);
                         } else if constexpr (K < 4 + NRB) {
                             constexpr int F = K - 4;
                             read_b_asm(std::integral_constant<int, NB>{}, std::integral_constant<int, F / T::NI>{},
@@ -647,36 +662,36 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                     // get through a run of other instructions (nobody else issues on this SIMD).  Two waves per SIMD:
                     // the reads behind the first row (the second covers their latency), the loads split over both rows.
                     constexpr int PER_ROW = 2 * T::NI;                                          // MFMAs of a block row
-                    static_assert(!ACC_FILE || (4 + NRB <= 2 * PER_ROW - 8 && NITEMS <= 2 * PER_ROW), "the last MFMAs of a group cover the reads' latency");
+                    constexpr int SLOTS = (REAL0 ? 2 : 1) * PER_ROW;
+                    static_assert(!ACC_FILE || (4 + NRB <= SLOTS - 8 && NITEMS <= SLOTS), "the last MFMAs of a group cover the reads' latency");
                     auto row = [&](auto r_c, auto first_c) {
-                        constexpr int I = decltype(r_c)::value, FIRST = decltype(first_c)::value;
+                        constexpr int I = decltype(r_c)::value - OFF, S = (decltype(r_c)::value + SO) % 4, FIRST = decltype(first_c)::value;
                         static_for<T::NI>([&](auto jj_c) {
                             constexpr int JJ = decltype(jj_c)::value, J = (I & 1) ? T::NI - 1 - JJ : JJ;
                             if constexpr (ACC_FILE) {
-                                mma16_acc<INT8>(acc[I][J], frag_value(bc[0][J]), frag_value(ar[I % 4][0]));
+                                mma16_acc<INT8>(acc[I][J], frag_value(bc[0][J]), frag_value(ar[S][0]));
                                 item(std::integral_constant<int, FIRST + 2 * JJ>{});
-                                mma16_acc<INT8>(acc[I][J], frag_value(bc[1][J]), frag_value(ar[I % 4][1]));
+                                mma16_acc<INT8>(acc[I][J], frag_value(bc[1][J]), frag_value(ar[S][1]));
                                 item(std::integral_constant<int, FIRST + 2 * JJ + 1>{});
                             } else {
-                                acc[I][J] = Acc<INT8, 16>::mma(frag_value(bc[0][J]), frag_value(ar[I % 4][0]), acc[I][J]);
-                                acc[I][J] = Acc<INT8, 16>::mma(frag_value(bc[1][J]), frag_value(ar[I % 4][1]), acc[I][J]);
+                                acc[I][J] = Acc<INT8, 16>::mma(frag_value(bc[0][J]), frag_value(ar[S][0]), acc[I][J]);
+                                acc[I][J] = Acc<INT8, 16>::mma(frag_value(bc[1][J]), frag_value(ar[S][1]), acc[I][J]);
                             }
                             __builtin_amdgcn_sched_barrier(0);
                         });
                     };
-                    row(std::integral_constant<int, R0>{}, Zero{});
+                    constexpr int HALF = 4 + NRB + (L_HI - L_LO + 1) / 2;
+                    if constexpr (REAL0) row(std::integral_constant<int, R0>{}, Zero{});
                     if constexpr (!ACC_FILE) {
-                        constexpr int HALF = 4 + NRB + (L_HI - L_LO + 1) / 2;
                         static_for<HALF>([&](auto k_c) { item(k_c); });
                         __builtin_amdgcn_sched_barrier(0);
                     }
-                    row(std::integral_constant<int, R1>{}, std::integral_constant<int, PER_ROW>{});
+                    row(std::integral_constant<int, R1>{}, std::integral_constant<int, REAL0 ? PER_ROW : 0>{});
                     if constexpr (!ACC_FILE) {
-                        constexpr int HALF = 4 + NRB + (L_HI - L_LO + 1) / 2;
                         static_for<NITEMS - HALF>([&](auto k_c) { item(std::integral_constant<int, HALF + decltype(k_c)::value>{}); });
                         __builtin_amdgcn_sched_barrier(0);
                     }
-                    if constexpr (G == LAST - 1 || NG == 1) {
+                    if constexpr (G == LAST - 1) {
                         // K step kt+1 has landed; this step's A loads (for step kt+2) may stay in flight
 #ifdef XP_TRACE
                         const long long tb0 = clock64();
@@ -1331,6 +1346,14 @@ XP_DL_PAIR_OUTER_VARIANT(kBfPairAmmBnm, 5, "A along M and B along N", 0.52)
 XP_DL_PAIR_VARIANT(kBfPair256x256, "bf16", false, 256, 256, 2, 4, 1, "", 0.56)
 XP_DL_PAIR_VARIANT(kI8Pair256x256, "i8", true, 256, 256, 2, 4, 1, "", 0.56)
 XP_DL_PAIR_VARIANT(kI8PairW4, "i8", true, 256, 256, 2, 2, 1, "", 0.58)
+// the two tile heights of the convolution (and of tall GEMMs) with paired sub-steps: 7 and 6 block rows per wave
+typedef DlTile<224, 256, 2, 2, 2, 128, false, 1, 16, false, 3, 1> TwoHiP;
+typedef DlTile<192, 256, 2, 2, 2, 128, false, 1, 16, false, 3, 1> TwoLoP;
+bool kBfPairTwoHeights_can(const Problem &q) { return dl_can_run_common<false>(q, 224, 256, 128, 16); }
+hipError_t kBfPairTwoHeights_launch(const Problem &q) { return dl_launch_two_heights<false, TwoHiP, TwoLoP, true>(q); }
+double kBfPairTwoHeights_cost(const Problem &q) { return dl_cost<TwoHiP>(q, 0.51); }
+const Variant kBfPairTwoHeights = {"bf16 224x256x128B then 192x256 in the last round, waves 2x2 ring 3(A)+2(B) direct-to-lds, reads as assembly, sub-steps paired, mfma16",
+                                   kBfPairTwoHeights_can, kBfPairTwoHeights_launch, kBfPairTwoHeights_cost};
 XP_DL_PAIR_VARIANT(kBfPairW4, "bf16", false, 256, 256, 2, 2, 1, "", 0.58)
 }  // namespace
 
@@ -1375,7 +1398,7 @@ int dl_small_variants(xp_dtype in_type, const Variant **out)
 // Registered after the small ones.
 int dl_pair_variants(xp_dtype in_type, const Variant **out)
 {
-    if (in_type == XP_BF16) { out[0] = &kBfPair256x256; out[1] = &kBfPairW4; out[2] = &kBfPairBnm; out[3] = &kBfPairAmm; out[4] = &kBfPairAmmBnm; return 5; }
+    if (in_type == XP_BF16) { out[0] = &kBfPair256x256; out[1] = &kBfPairW4; out[2] = &kBfPairBnm; out[3] = &kBfPairAmm; out[4] = &kBfPairAmmBnm; out[5] = &kBfPairTwoHeights; return 6; }
     if (in_type == XP_I8) { out[0] = &kI8Pair256x256; out[1] = &kI8PairW4; return 2; }
     return 0;
 }
