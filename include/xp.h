@@ -341,10 +341,11 @@ int xp_tune_count(void);
  * throughput that the paper's parameter search maximises (Section 5.1, Eq. 3-4) is reported against the
  * chip's nominal MFMA peak; this call provides the measured ceiling beside it.  It launches one kernel:
  * one workgroup on each of the 256 compute units, `waves` (1 or 2) waves per SIMD, each running `iters`
- * rounds of 32 independent 16x16 (block == 16; 8 of 32x32 for block == 32) MFMAs of `in_type`
+ * rounds of 64 16x16 MFMAs (block == 16: 32 blocks, each taking two operand sets back to back on its accumulator,
+ * the order that draws the least power; block == 32: 8 independent 32x32 MFMAs) of `in_type`
  * (XP_BF16 or XP_I8) on operands held in registers.  Time it with events on `stream`;
  * xp_mfma_ceiling_ops(...) is the number of arithmetic operations of one launch (0 for invalid arguments).
- *   operands   DEVICE, 16-byte aligned, at least 98304 bytes of valid `in_type` values (read once, before the loop;
+ *   operands   DEVICE, 16-byte aligned, at least 196608 bytes (block == 32: 98304) of valid `in_type` values (read once, before the loop;
  *              their values set the power drawn: use the distribution of the workload)
  *   sink       DEVICE, at least 256 * 256 * waves * 4 bytes, overwritten (keeps the arithmetic alive)
  * Errors: XP_ERR_UNSUPPORTED (type, block, waves), XP_ERR_SHAPE (iters < 0 or >= 2^31), XP_ERR_NULL, XP_ERR_ALIGN,

@@ -52,20 +52,25 @@ template <> struct Block<true, 32> {
     }
 };
 
-// operands: 12 fragments of 64 lanes x 16 bytes per wave slot (at least 8 waves' worth: 96 KB);
-// sink: one 32-bit word per thread of the grid
+// operands: per set 12 fragments of 64 lanes x 16 bytes per wave slot (8 wave slots: 96 KB), SETS sets;
+// sink: one 32-bit word per thread of the grid.
+// 16x16 blocks: two operand sets (the two k sub-steps of a K step), each block takes both back to back on its
+// accumulator -- the order that draws the least power of those tried, and the one the GEMM kernel uses.
 template <bool INT8, int MF>
 __global__ __launch_bounds__(512) void mfma_ceiling_kernel(const u32x4 *operands, unsigned *sink, int iters)
 {
-    constexpr int MI = MF == 16 ? 8 : 4, NI = MF == 16 ? 4 : 2, NACC = MF == 16 ? 4 : 16;
+    constexpr int MI = MF == 16 ? 8 : 4, NI = MF == 16 ? 4 : 2, NACC = MF == 16 ? 4 : 16, SETS = MF == 16 ? 2 : 1;
     using B = Block<INT8, MF>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    u32x4 a[MI], b[NI];
-    const u32x4 *src = operands + ((size_t)(wave & 7) * 12) * 64 + lane;
+    u32x4 a[SETS][MI], b[SETS][NI];
 #pragma unroll
-    for (int i = 0; i < MI; ++i) a[i] = src[i * 64];
+    for (int s = 0; s < SETS; ++s) {
+        const u32x4 *src = operands + ((size_t)(s * 8 + (wave & 7)) * 12) * 64 + lane;
 #pragma unroll
-    for (int j = 0; j < NI; ++j) b[j] = src[(8 + j) * 64];
+        for (int i = 0; i < MI; ++i) a[s][i] = src[i * 64];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) b[s][j] = src[(8 + j) * 64];
+    }
     typename B::acc acc[MI][NI];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -77,7 +82,12 @@ __global__ __launch_bounds__(512) void mfma_ceiling_kernel(const u32x4 *operands
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < NI; ++j) acc[i][j] = B::mma(b[j], a[i], acc[i][j]);
+            for (int jj = 0; jj < NI; ++jj) {
+                const int j = (i & 1) ? NI - 1 - jj : jj;
+#pragma unroll
+                for (int s = 0; s < SETS; ++s) acc[i][j] = B::mma(b[s][j], a[s][i], acc[i][j]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
     }
     unsigned x = 0;
 #pragma unroll
@@ -103,7 +113,7 @@ double xp_mfma_ceiling_ops(xp_dtype in_type, int block, int waves, int64_t iters
 {
     if ((in_type != XP_BF16 && in_type != XP_I8) || (block != 16 && block != 32) || (waves != 1 && waves != 2) || iters < 0) return 0.0;
     const double per_mfma = 2.0 * block * block * (block == 16 ? 32 : 16) * (in_type == XP_I8 ? 2 : 1);
-    return 256.0 * 4 * waves * (double)iters * 32.0 / (block == 16 ? 1 : 4) * per_mfma;
+    return 256.0 * 4 * waves * (double)iters * (block == 16 ? 64.0 : 8.0) * per_mfma;
 }
 
 xp_status xp_mfma_ceiling(xp_dtype in_type, int block, int waves, int64_t iters, const void *operands, size_t operand_bytes,
@@ -114,7 +124,7 @@ xp_status xp_mfma_ceiling(xp_dtype in_type, int block, int waves, int64_t iters,
     if (!operands || !sink) return XP_ERR_NULL;
     if (((uintptr_t)operands % 16) != 0 || ((uintptr_t)sink % 4) != 0) return XP_ERR_ALIGN;
     const unsigned threads = 256u * (unsigned)waves;
-    if (operand_bytes < (size_t)8 * 12 * 64 * 16 || sink_bytes < (size_t)256 * threads * 4) return XP_ERR_WORKSPACE;
+    if (operand_bytes < (size_t)(block == 16 ? 2 : 1) * 8 * 12 * 64 * 16 || sink_bytes < (size_t)256 * threads * 4) return XP_ERR_WORKSPACE;
     const dim3 grid(256), wg(threads);
     hipStream_t s = (hipStream_t)stream;
     const u32x4 *ops = (const u32x4 *)operands;
