@@ -11,7 +11,7 @@ INCLUDE = HERE.parent / "include"
 LIB = HERE / "libxp.so"
 OBJ = HERE / "_build"
 
-SOURCES = ["xp_api.hip", "xp_generic.hip", "xp_mfma_f32.hip", "xp_mfma_kc.hip", "xp_mfma_dl.hip", "xp_mfma_oc.hip", "xp_mfma_sk.hip", "xp_mfma_pp.hip", "xp_attention.hip", "xp_gemv.hip", "xp_tune.hip", "xp_memops.hip", "xp_conv_nchw.hip", "xp_deform_attn.hip", "xp_probe.hip", "xp_mfma_rs.hip"]
+SOURCES = ["xp_api.hip", "xp_generic.hip", "xp_mfma_f32.hip", "xp_mfma_kc.hip", "xp_mfma_dl.hip", "xp_mfma_dl_asm.hip", "xp_mfma_dl_pair.hip", "xp_mfma_oc.hip", "xp_mfma_sk.hip", "xp_mfma_pp.hip", "xp_attention.hip", "xp_gemv.hip", "xp_tune.hip", "xp_memops.hip", "xp_conv_nchw.hip", "xp_deform_attn.hip", "xp_probe.hip", "xp_mfma_rs.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", str(INCLUDE), "-I", str(CSRC),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 # The attention kernel rescales its MFMA accumulators with vector arithmetic in every step: keep
@@ -31,7 +31,7 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = False) -> pathlib.Path:
     OBJ.mkdir(exist_ok=True)
-    with cf.ThreadPoolExecutor(max_workers=4) as ex:
+    with cf.ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(LIB), *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
