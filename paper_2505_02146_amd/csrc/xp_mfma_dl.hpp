@@ -809,8 +809,19 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 // for the last time, so the second sub-step refills them: with the loads for K step kt + NS
                 // (A: kt + NSA), a share behind each block row.  They have a whole K step to land, not half.
                 weave(std::integral_constant<int, CA>{}, std::integral_constant<int, CB>{}, One{}, now_a, now_b, xa, xb, ya, yb, [](auto) {});
+#ifdef XP_TRACE
+                {
+                    const long long tb0 = clock64();
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
+                    const long long tb1 = clock64();
+                    __builtin_amdgcn_s_barrier();
+                    tr_wait[0] += tb1 - tb0;
+                    tr_wait[1] += clock64() - tb1;
+                }
+#else
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
                 __builtin_amdgcn_s_barrier();
+#endif
                 weave(std::integral_constant<int, NA>{}, std::integral_constant<int, NB>{}, Zero{}, nxt_a, nxt_b, ya, yb, xa, xb, [&](auto i_c) {
                     constexpr int I = decltype(i_c)::value;
                     constexpr int LO = I * IT / T::MI, HI = (I + 1) * IT / T::MI;
