@@ -132,6 +132,17 @@ def test_gemm_alpha_beta_ld_padding_and_col_major_c(xp, oracle, kind):
     _run_gemm(xp, oracle, kind, 70, 300, 40, "row", "col", lc="row", pads=(3, 5, 1))       # unaligned ld
 
 
+@pytest.mark.parametrize("kind", ["bf16", "i8"])
+def test_gemm_whole_tiles_with_alpha(xp, oracle, kind):
+    """Tiles that lie inside the matrix take the epilogue's whole-tile path: with alpha != 1 (beta = 0), with alpha = 1,
+    with a padded leading dimension of C, and with beta != 0 (which must fall back to the general path)."""
+    _run_gemm(xp, oracle, kind, 512, 768, 136, "row", "col", alpha=1.0 if kind == "i8" else 0.75, beta=0.0, integer=True)   # (int8: no scaling)
+    _run_gemm(xp, oracle, kind, 512, 512, 200, "row", "col", pads=(0, 0, 12), alpha=1.0, beta=0.0)
+    if kind != "i8":
+        _run_gemm(xp, oracle, kind, 512, 512, 72, "row", "col", pads=(0, 0, 3), alpha=-1.5, beta=0.0)      # rows of C not 16-byte aligned
+        _run_gemm(xp, oracle, kind, 512, 256, 72, "row", "col", alpha=0.5, beta=2.0, integer=True)
+
+
 def test_gemm_int8_padding_and_col_major_c(xp, oracle):
     _run_gemm(xp, oracle, "i8", 130, 70, 96, "row", "col", lc="col", pads=(16, 32, 3))
     _run_gemm(xp, oracle, "i8", 70, 300, 40, "row", "col", lc="row", pads=(3, 5, 1))
