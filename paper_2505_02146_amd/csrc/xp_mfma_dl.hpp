@@ -666,15 +666,23 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                     constexpr int PER_ROW = 2 * T::NI;                                          // MFMAs of a block row
                     constexpr int SLOTS = (REAL0 ? 2 : 1) * PER_ROW;
                     static_assert(!ACC_FILE || (4 + NRB <= SLOTS - 8 && NITEMS <= SLOTS), "the last MFMAs of a group cover the reads' latency");
+                    // (one wave per SIMD) what follows MFMA number S of the group: the reads one behind each of the
+                    // first MFMAs; the loads behind every second MFMA where the group has room for that
+                    constexpr int LSTEP = 4 + NRB + 2 * (L_HI - L_LO) <= SLOTS ? 2 : 1;
+                    auto slot = [&](auto s_c) {
+                        constexpr int S = decltype(s_c)::value;
+                        if constexpr (S < 4 + NRB) item(s_c);
+                        else if constexpr ((S - 4 - NRB) % LSTEP == 0) item(std::integral_constant<int, 4 + NRB + (S - 4 - NRB) / LSTEP>{});
+                    };
                     auto row = [&](auto r_c, auto first_c) {
                         constexpr int I = decltype(r_c)::value - OFF, S = (decltype(r_c)::value + SO) % 4, FIRST = decltype(first_c)::value;
                         static_for<T::NI>([&](auto jj_c) {
                             constexpr int JJ = decltype(jj_c)::value, J = (I & 1) ? T::NI - 1 - JJ : JJ;
                             if constexpr (ACC_FILE) {
                                 mma16_acc<INT8>(acc[I][J], frag_value(bc[0][J]), frag_value(ar[S][0]));
-                                item(std::integral_constant<int, FIRST + 2 * JJ>{});
+                                slot(std::integral_constant<int, FIRST + 2 * JJ>{});
                                 mma16_acc<INT8>(acc[I][J], frag_value(bc[1][J]), frag_value(ar[S][1]));
-                                item(std::integral_constant<int, FIRST + 2 * JJ + 1>{});
+                                slot(std::integral_constant<int, FIRST + 2 * JJ + 1>{});
                             } else {
                                 acc[I][J] = Acc<INT8, 16>::mma(frag_value(bc[0][J]), frag_value(ar[S][0]), acc[I][J]);
                                 acc[I][J] = Acc<INT8, 16>::mma(frag_value(bc[1][J]), frag_value(ar[S][1]), acc[I][J]);
