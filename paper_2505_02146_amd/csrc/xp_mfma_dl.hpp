@@ -190,6 +190,13 @@ template <bool INT8> __device__ __forceinline__ void mma16_acc(typename Acc<INT8
     else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
+// 16 bytes per lane from the accumulation registers to dst + OFFSET bytes
+template <int OFFSET, typename AccT, typename OutT> __device__ __forceinline__ void store_from_acc(OutT *dst, const AccT &c)
+{
+    static_assert(OFFSET >= 0 && OFFSET < 4096, "the instruction's offset field");
+    asm volatile("global_store_dwordx4 %0, %1, off offset:%2" : : "v"(dst), "a"(c), "n"(OFFSET) : "memory");
+}
+
 // floor(n / d) for 0 <= n < 2^31 as a multiplication: magic = ceil(2^(31 + shift) / d) with shift = ceil(log2 d)
 // (the host works both out once per call); exact for every such n.  A 32-bit division costs some forty vector
 // instructions, and the convolution's set-up has two per load slot.
@@ -920,11 +927,21 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             OutT *base = C + (long long)(m0 + wm * T::WTM + (lane & 15)) * p.ldc + (n0 + wn * T::WTN + (lane >> 4) * 4);
             const long long step16 = 16 * p.ldc;
             if (INT8 || p.alpha == 1.0f) {
+                if constexpr (T::PAIR != 0 && T::NWAVE == 4 && !T::NTSTORE) {
+                    // accumulators that live in the accumulation registers go to memory from there (the compiler would
+                    // first copy all 256 of them to vector registers: a thousand cycles before the first store)
+                    static_for<T::MI * T::NI>([&](auto b_c) {
+                        constexpr int I = decltype(b_c)::value / T::NI, J = decltype(b_c)::value % T::NI;
+                        store_from_acc<64 * J>(base, acc[I][J]);
+                        if constexpr (J == T::NI - 1) base += step16;
+                    });
+                } else {
 #pragma unroll
-                for (int i = 0; i < T::MI; ++i, base += step16)
+                    for (int i = 0; i < T::MI; ++i, base += step16)
 #pragma unroll
-                    for (int j = 0; j < T::NI; ++j)
-                        put<T::NTSTORE>((out4 *)(base + 16 * j), out4{(OutT)acc[i][j][0], (OutT)acc[i][j][1], (OutT)acc[i][j][2], (OutT)acc[i][j][3]});
+                        for (int j = 0; j < T::NI; ++j)
+                            put<T::NTSTORE>((out4 *)(base + 16 * j), out4{(OutT)acc[i][j][0], (OutT)acc[i][j][1], (OutT)acc[i][j][2], (OutT)acc[i][j][3]});
+                }
             } else {
                 if constexpr (!INT8) {
 #pragma unroll
