@@ -386,7 +386,8 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
 #pragma unroll
             for (int v = 0; v < NACC; ++v) acc[i][j][v] = 0;
 
-    int tap_r = 0, tap_s = 0, tap = 0, tap_off = 0, c0_b = 0;   // conv: filter tap and channel offset of the next step to load
+    int tap_s = 0, tap = 0, tap_off = 0, c0_b = 0;      // conv: filter tap and channel offset of the next step to load
+    const int roll_step = CONV ? (p.W - p.S) * p.Cin_b : 0;
 
     // issue A loads [lo, hi) of K step kt into the A buffer at byte offset a_off; likewise for B
     constexpr int IT = T::IA + T::IB;
@@ -417,16 +418,16 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         }
         if constexpr (CONV) {
             if (hi >= T::IA && lo < T::IA) {            // the step's A loads are all issued: advance (tap, channel offset)
-                // (scalar selects, no branch: the unrolled rounds stay one basic block)
+                // (arithmetic on 0 / -1 masks, neither selects nor branches: the compiler turns selects into branches
+                // here, which cuts the unrolled rounds into pieces and costs it some thirty registers)
                 c0_b += RB;
-                const int wrap = c0_b >= p.Cin_b ? 1 : 0;
-                c0_b = wrap ? 0 : c0_b;
-                tap += wrap;
-                tap_s += wrap;
-                const int roll = tap_s == p.S ? 1 : 0;
-                tap_s = roll ? 0 : tap_s;
-                tap_r += roll;
-                tap_off = (tap_r * p.W + tap_s) * p.Cin_b;
+                const int wrap = (p.Cin_b - 1 - c0_b) >> 31;             // -1 when the channels of the tap are used up
+                c0_b &= ~wrap;
+                tap -= wrap;
+                tap_s -= wrap;
+                const int roll = (p.S - 1 - tap_s) >> 31;                // -1 when the tap row is used up
+                tap_s &= ~roll;
+                tap_off += (p.Cin_b & wrap) + (roll_step & roll);          // next tap: one pixel on; next tap row: W - S more
             }
         }
     };
@@ -888,9 +889,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             constexpr int AHEAD = (T::NSA > T::NS ? T::NSA : T::NS) - (WV ? 0 : 1);
             const int whole = p.Kb / RB - AHEAD;
             int kt = 0;
-            if constexpr (ASMR && (!CONV || T::NSA == T::NS)) {
-                // (convolution: only with equal ring depths -- the six-step round of the 3+2 ring and the filter-tap
-                // state do not fit 256 registers together, the kernel would spill)
+            if constexpr (ASMR) {
                 // the main part of the loop in rounds of ROUND steps, after which both rings are where they were
                 constexpr int ROUND = T::NSA == T::NS ? T::NS : T::NSA * T::NS;
                 for (; kt + ROUND <= whole; kt += ROUND)
