@@ -101,6 +101,8 @@ const Tuned kTuned[] = {
     {XP_OP_GEMM_BATCHED, XP_BF16, 96, 512, 512, 64, true, true, "bf16 64x128-stream x128B single-k-step producer/consumer nt-stores mfma32"},
     {XP_OP_GEMM_BATCHED, XP_BF16, 96, 512, 64, 512, true, false, "bf16 64x64x128B waves 2x2 k-group-interleaved mfma32"},
     {XP_OP_CONV2D, XP_BF16, 1, 100352, 256, 2304, true, true, "bf16 224x256x128B then 192x256 in the last round, waves 2x2 ring 3(A)+2(B) direct-to-lds, reads as assembly, sub-steps paired, mfma16"},
+    // (the same stage with a planar, NCHW, output: the variant above declines it)
+    {XP_OP_CONV2D, XP_BF16, 1, 100352, 256, 2304, true, true, "bf16 224x256x128B then 192x256 in the last round, waves 2x4 ring 2(A)+2(B) direct-to-lds, reads as assembly, mfma16"},
 #include "xp_tuned_table.inc"
 };
 constexpr int kNumTuned = (int)(sizeof kTuned / sizeof kTuned[0]);
@@ -134,7 +136,7 @@ int tuned_variant(const Problem &q)
             t.b_kc == b_kc) {
             const int v = index.variant[i];
             if (v >= 0 && variant(q.in_type, v)->can_run(q)) return v;
-            break;
+            // (an entry whose variant declines this call -- a planar output, say -- leaves it to a later entry for the shape)
         }
     }
     if (q.K <= 0) return -1;
