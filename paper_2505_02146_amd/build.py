@@ -42,5 +42,33 @@ def build(verbose: bool = False) -> pathlib.Path:
     return LIB
 
 
+def build_poison(verbose: bool = False) -> pathlib.Path:
+    """libxp_poison.so: the library with -DXP_LDS_POISON in the direct-to-LDS kernels (see lds_poison in
+    csrc/xp_mfma_dl.hpp); the other objects are those of build(), which must have run."""
+    out = OBJ / "poison"
+    out.mkdir(parents=True, exist_ok=True)
+    dl = [s for s in SOURCES if s.startswith("xp_mfma_dl")]
+
+    def one(src: str) -> str:
+        obj = out / (src + ".o")
+        cmd = ["hipcc", *FLAGS, "-DXP_LDS_POISON", "-c", str(CSRC / src), "-o", str(obj)]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src} (poison build):\n" + "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l))
+        return str(obj)
+
+    with cf.ThreadPoolExecutor(max_workers=3) as ex:
+        objs = list(ex.map(one, dl))
+    objs += [str(OBJ / (s + ".o")) for s in SOURCES if s not in dl]
+    lib = HERE / "libxp_poison.so"
+    r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(lib), *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed (poison build):\n" + r.stderr)
+    if verbose:
+        print("built", lib)
+    return lib
+
+
 if __name__ == "__main__":
     build(verbose=True)
+    build_poison(verbose=True)

@@ -197,6 +197,20 @@ template <int OFFSET, typename AccT, typename OutT> __device__ __forceinline__ v
     asm volatile("global_store_dwordx4 %0, %1, off offset:%2" : : "v"(dst), "a"(c), "n"(OFFSET) : "memory");
 }
 
+// Debug build (-DXP_LDS_POISON, libxp_poison.so): the 16 bytes of an LDS slot that a direct-to-LDS load is about to
+// overwrite are filled with NaNs first (bf16 0x7fc0; as int8 -64 and 127), and the write has completed before the load
+// is issued.  A wave that still reads the slot while the load is in flight -- a ring that is refilled too early -- then
+// sees NaNs every time instead of, almost always, the old and still correct data.
+__device__ __forceinline__ void lds_poison(unsigned lds_byte_address)
+{
+#ifdef XP_LDS_POISON
+    const u32x4 nan = {0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u};
+    asm volatile("ds_write_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : : "v"(lds_byte_address), "v"(nan) : "memory");
+#else
+    (void)lds_byte_address;
+#endif
+}
+
 // floor(n / d) for 0 <= n < 2^31 as a multiplication: magic = ceil(2^(31 + shift) / d) with shift = ceil(log2 d)
 // (the host works both out once per call); exact for every such n.  A 32-bit division costs some forty vector
 // instructions, and the convolution's set-up has two per load slot.
@@ -414,6 +428,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 if (kb + a_cb0 + i * A_CB_STEP >= p.Kb) off = OOB;
             }
             lds_void *dst = (lds_void *)(lds + a_off + (wave + i * T::NWAVE) * 1024);
+            lds_poison(lds_base + a_off + (wave + i * T::NWAVE) * 1024 + lane * 16);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, dst, 16, off, soff, 0, 0);
         }
         if constexpr (CONV) {
@@ -442,6 +457,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 if (kb + b_cb0 + i * B_CB_STEP >= p.Kb) off = OOB;
             }
             lds_void *dst = (lds_void *)(lds + b_off + (wave + i * T::NWAVE) * 1024);
+            lds_poison(lds_base + b_off + (wave + i * T::NWAVE) * 1024 + lane * 16);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, dst, 16, off, BNM ? (int)((unsigned)kt * (RB / 2) * (unsigned)p.ldb_b) : kb, 0, 0);
         }
     };

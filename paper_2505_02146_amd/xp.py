@@ -14,7 +14,10 @@ import pathlib
 import torch
 
 _HERE = pathlib.Path(__file__).resolve().parent
-LIB_PATH = _HERE / "libxp.so"
+import os
+
+# XP_LIBRARY selects another build of the same library (the LDS-poison debug build, say)
+LIB_PATH = pathlib.Path(os.environ["XP_LIBRARY"]) if os.environ.get("XP_LIBRARY") else _HERE / "libxp.so"
 
 if not LIB_PATH.exists():
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2505_02146_amd.build` "

@@ -30,6 +30,14 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, n), n
 
 
+def test_lds_poison_build_exports_the_same_symbols():
+    path = ROOT / "paper_2505_02146_amd" / "libxp_poison.so"
+    assert path.exists(), "run paper_2505_02146_amd/build.py"
+    debug = ctypes.CDLL(str(path))
+    for n in _declared_symbols():
+        assert hasattr(debug, n), n
+
+
 def test_oracle_and_library_share_no_code():
     # neither side includes or imports the other
     for f in (ROOT / "paper_2505_02146_amd").rglob("*"):
