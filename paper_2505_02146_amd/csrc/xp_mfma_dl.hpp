@@ -190,11 +190,25 @@ template <bool INT8> __device__ __forceinline__ void mma16_acc(typename Acc<INT8
     else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
-// 16 bytes per lane from the accumulation registers to dst + OFFSET bytes
+// 16 bytes per lane from the accumulation registers to dst + OFFSET bytes.  The store is written through (sc0 sc1): the
+// lines leave the L2 while the other stores are still being issued, instead of staying dirty until the write-back at
+// the end of the kernel (4096^3 bf16: -1.4 us of 95.5; marking them non-temporal instead costs 6 us).
 template <int OFFSET, typename AccT, typename OutT> __device__ __forceinline__ void store_from_acc(OutT *dst, const AccT &c)
 {
     static_assert(OFFSET >= 0 && OFFSET < 4096, "the instruction's offset field");
-    asm volatile("global_store_dwordx4 %0, %1, off offset:%2" : : "v"(dst), "a"(c), "n"(OFFSET) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off offset:%2 sc0 sc1" : : "v"(dst), "a"(c), "n"(OFFSET) : "memory");
+}
+
+// the same from vector registers (the convolution's two tiles per compute unit: -1.5 to -2.4 us of 100); STREAM keeps
+// the non-temporal stores of the variants that ask for them
+template <bool STREAM, typename V4> __device__ __forceinline__ void put_tile(V4 *dst, V4 v)
+{
+    static_assert(sizeof(V4) == 16, "16 bytes per lane");
+    if constexpr (STREAM) __builtin_nontemporal_store(v, dst);
+    // (a store of more than 8 bytes reads its data a little after it is issued; the compiler keeps the next write of those
+    // registers away from its own stores, for this one the wait states are spelt out: the four-wave kernels without
+    // pinned accumulators copy block after block from the accumulation registers through the same four registers)
+    else asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(dst), "v"(v) : "memory");
 }
 
 // Debug build (-DXP_LDS_POISON, libxp_poison.so): the 16 bytes of an LDS slot that a direct-to-LDS load is about to
@@ -634,8 +648,25 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             });
             // ring state of the run-time steps: the A buffers of steps kt, kt+1, kt+2 and the B buffers of kt+1, kt (= kt+2)
             int cur_a = 0, nxt_a = T::A_BYTES, fill_a = 2 * T::A_BYTES, nxt_b = T::B_BASE + T::B_BYTES, fill_b = T::B_BASE;
-            auto step = [&](int kt, auto odd_c, auto check_c, auto pos_c) {
+            // The last K step of a tile that the whole-tile epilogue will store as it is (one wave per SIMD): a block
+            // row is final when the step has passed it, so its stores go out behind the MFMAs of the row after it, one
+            // behind each pair -- all but the last row's output is on its way when the loop ends.  That step issues no
+            // load and reads nothing of a next step, so it needs no barrier either.
+            using OutT = typename std::conditional<INT8, int, float>::type;
+            constexpr bool EARLY = ACC_FILE && MF == 16 && !PLANAR && !T::NTSTORE;
+            OutT *early = nullptr;                                      // where the block row that is stored next begins
+            long long early_step = 0;
+            if constexpr (EARLY) {
+                OutT *C = (OutT *)p.C + batch * p.strideC;
+                if (m0 + T::BM <= m_end && n0 + T::BN <= p.N && (INT8 || (p.beta == 0.0f && p.alpha == 1.0f)) &&
+                    (((unsigned long long)C | (unsigned long long)(p.ldc * (long long)sizeof(OutT))) & 15) == 0) {
+                    early = C + (long long)(m0 + wm * T::WTM + (lane & 15)) * p.ldc + (n0 + wn * T::WTN + (lane >> 4) * 4);
+                    early_step = 16 * p.ldc;
+                }
+            }
+            auto step = [&](int kt, auto odd_c, auto check_c, auto pos_c, auto final_c) {
                 constexpr bool ODD = decltype(odd_c)::value;
+                constexpr bool FINAL = decltype(final_c)::value;
                 constexpr int POS = decltype(pos_c)::value;
                 constexpr int CA = POS < 0 ? -1 : (POS % 3) * T::A_BYTES, NA = POS < 0 ? -1 : ((POS + 1) % 3) * T::A_BYTES;
                 constexpr int NB = POS < 0 ? -1 : T::B_BASE + ((POS + 1) % 2) * T::B_BYTES;
@@ -648,7 +679,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 static_for<NG>([&](auto g_c) {
                     constexpr int G = decltype(g_c)::value, R0 = 2 * G, R1 = 2 * G + 1;     // (counted from OFF)
                     constexpr bool REAL0 = R0 >= OFF;
-                    if constexpr (G != LAST) lds_wait<0>();             // (the last group follows the barrier's wait)
+                    if constexpr (G != LAST || FINAL) lds_wait<0>();    // (the last group follows the barrier's wait)
                     if constexpr (G == 0) {
 #pragma unroll
                         for (int kk = 0; kk < 2; ++kk)
@@ -671,9 +702,13 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                             if constexpr (RN < MV)
                                 read_a_asm(std::integral_constant<int, CA>{}, std::integral_constant<int, KK>{}, std::integral_constant<int, RN - OFF>{}, now_a,
                                            ar[(RN + SO) % 4][KK]);
+                            else if constexpr (FINAL)
+                                ;
                             else if constexpr (RN - MV >= OFF)
                                 read_a_asm(std::integral_constant<int, NA>{}, std::integral_constant<int, KK>{}, std::integral_constant<int, RN - MV - OFF>{},
                                            next_a, ar[(RN - MV + SN) % 4][KK]);
+                        } else if constexpr (FINAL) {
+                            ;
                         } else if constexpr (K < 4 + NRB) {
                             constexpr int F = K - 4;
                             read_b_asm(std::integral_constant<int, NB>{}, std::integral_constant<int, F / T::NI>{},
@@ -707,6 +742,16 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                                 slot(std::integral_constant<int, FIRST + 2 * JJ>{});
                                 mma16_acc<INT8>(acc[I][J], frag_value(bc[1][J]), frag_value(ar[S][1]));
                                 slot(std::integral_constant<int, FIRST + 2 * JJ + 1>{});
+                                if constexpr (FINAL && I > 0) {
+                                    // the block of the row before that was computed at this place in its row: 2 NI
+                                    // matrix instructions ago, its result has long been written
+                                    constexpr int JP = ((I - 1) & 1) ? T::NI - 1 - JJ : JJ;
+                                    // (the loads that the step before issued, all beyond the end of K, are the last
+                                    // to write LDS: nothing but stores is in flight when the wave ends)
+                                    if constexpr (I == 1 && JJ == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                                    store_from_acc<64 * JP>(early, acc[I - 1][JP]);
+                                    if constexpr (JJ == T::NI - 1) early += early_step;
+                                }
                             } else {
                                 acc[I][J] = Acc<INT8, 16>::mma(frag_value(bc[0][J]), frag_value(ar[S][0]), acc[I][J]);
                                 acc[I][J] = Acc<INT8, 16>::mma(frag_value(bc[1][J]), frag_value(ar[S][1]), acc[I][J]);
@@ -725,7 +770,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                         static_for<NITEMS - HALF>([&](auto k_c) { item(std::integral_constant<int, HALF + decltype(k_c)::value>{}); });
                         __builtin_amdgcn_sched_barrier(0);
                     }
-                    if constexpr (G == LAST - 1) {
+                    if constexpr (G == LAST - 1 && !FINAL) {
                         // K step kt+1 has landed; this step's A loads (for step kt+2) may stay in flight
 #ifdef XP_TRACE
                         const long long tb0 = clock64();
@@ -755,17 +800,45 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             int kt = 0;
             for (; kt + 6 <= whole; kt += 6)
                 static_for<6>([&](auto pos_c) {
-                    step(kt + decltype(pos_c)::value, std::integral_constant<bool, (decltype(pos_c)::value & 1) != 0>{}, std::false_type{}, pos_c);
+                    step(kt + decltype(pos_c)::value, std::integral_constant<bool, (decltype(pos_c)::value & 1) != 0>{}, std::false_type{}, pos_c,
+                         std::false_type{});
                 });
+            bool stored = false;
+            auto tail_step = [&](int k, auto odd_c) {
+                if constexpr (EARLY) {
+                    if (k == KT - 1 && early != nullptr) {
+                        step(k, odd_c, std::true_type{}, RunTime{}, std::true_type{});
+                        stored = true;
+                        return;
+                    }
+                }
+                step(k, odd_c, std::true_type{}, RunTime{}, std::false_type{});
+            };
             while (kt < KT) {
-                step(kt, std::false_type{}, std::true_type{}, RunTime{});
-                if (++kt < KT) step(kt, std::true_type{}, std::true_type{}, RunTime{});
+                tail_step(kt, std::false_type{});
+                if (++kt < KT) tail_step(kt, std::true_type{});
                 ++kt;
             }
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
             // (the compiler does not know that the statements above are matrix instructions and leaves no room
             // between the last of them and the first read of its result)
             if constexpr (ACC_FILE) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+            if constexpr (EARLY) {
+                if (stored) {
+                    static_for<T::NI>([&](auto j_c) { store_from_acc<64 * decltype(j_c)::value>(early, acc[T::MI - 1][decltype(j_c)::value]); });
+#ifdef XP_TRACE
+                    tr_c[2] = clock64(); tr_w[2] = wall_clock64();
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+                    tr_c[3] = clock64(); tr_w[3] = wall_clock64();
+                    if (p.trace && tid == 0) {
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) { p.trace[tr_slot * 16 + x] = tr_c[x]; p.trace[tr_slot * 16 + 4 + x] = tr_w[x]; }
+                        for (int x = 0; x < 3; ++x) p.trace[tr_slot * 16 + 8 + x] = tr_wait[x];
+                    }
+#endif
+                    return;
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));     // no load may outlive the wave
         }
     } else
     if (KT > 0) {
@@ -941,6 +1014,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
             typedef OutT out4 __attribute__((ext_vector_type(4)));
             OutT *base = C + (long long)(m0 + wm * T::WTM + (lane & 15)) * p.ldc + (n0 + wn * T::WTN + (lane >> 4) * 4);
             const long long step16 = 16 * p.ldc;
+            // (the stores below are assembly text to the compiler: it does not see that they read what the last matrix
+            // instructions write, and a tile of one or two blocks per wave has nothing else in between)
+            if constexpr (!T::NTSTORE) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
             if (INT8 || p.alpha == 1.0f) {
                 if constexpr (T::PAIR != 0 && T::NWAVE == 4 && !T::NTSTORE) {
                     // accumulators that live in the accumulation registers go to memory from there (the compiler would
@@ -955,7 +1031,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                     for (int i = 0; i < T::MI; ++i, base += step16)
 #pragma unroll
                         for (int j = 0; j < T::NI; ++j)
-                            put<T::NTSTORE>((out4 *)(base + 16 * j), out4{(OutT)acc[i][j][0], (OutT)acc[i][j][1], (OutT)acc[i][j][2], (OutT)acc[i][j][3]});
+                            put_tile<T::NTSTORE>((out4 *)(base + 16 * j), out4{(OutT)acc[i][j][0], (OutT)acc[i][j][1], (OutT)acc[i][j][2], (OutT)acc[i][j][3]});
                 }
             } else {
                 if constexpr (!INT8) {
@@ -963,8 +1039,8 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                     for (int i = 0; i < T::MI; ++i, base += step16)
 #pragma unroll
                         for (int j = 0; j < T::NI; ++j)
-                            put<T::NTSTORE>((out4 *)(base + 16 * j),
-                                            out4{p.alpha * acc[i][j][0], p.alpha * acc[i][j][1], p.alpha * acc[i][j][2], p.alpha * acc[i][j][3]});
+                            put_tile<T::NTSTORE>((out4 *)(base + 16 * j),
+                                                 out4{p.alpha * acc[i][j][0], p.alpha * acc[i][j][1], p.alpha * acc[i][j][2], p.alpha * acc[i][j][3]});
                 }
             }
 #ifdef XP_TRACE

@@ -138,6 +138,10 @@ def test_gemm_whole_tiles_with_alpha(xp, oracle, kind):
     with a padded leading dimension of C, and with beta != 0 (which must fall back to the general path)."""
     _run_gemm(xp, oracle, kind, 512, 768, 136, "row", "col", alpha=1.0 if kind == "i8" else 0.75, beta=0.0, integer=True)   # (int8: no scaling)
     _run_gemm(xp, oracle, kind, 512, 512, 200, "row", "col", pads=(0, 0, 12), alpha=1.0, beta=0.0)
+    # alpha = 1: the four-wave kernels store a block row behind the next one's MFMAs in the last K step -- that step as
+    # the only one, as an even and as an odd one behind the unrolled rounds, with a partial step at the end
+    for K in (64, 192, 512, 576, 1000):
+        _run_gemm(xp, oracle, kind, 256, 512, K, "row", "col", alpha=1.0, beta=0.0, integer=(K == 512), seed=K)
     if kind != "i8":
         _run_gemm(xp, oracle, kind, 512, 512, 72, "row", "col", pads=(0, 0, 3), alpha=-1.5, beta=0.0)      # rows of C not 16-byte aligned
         _run_gemm(xp, oracle, kind, 512, 256, 72, "row", "col", alpha=0.5, beta=2.0, integer=True)
