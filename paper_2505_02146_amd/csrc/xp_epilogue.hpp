@@ -108,8 +108,9 @@ __device__ __forceinline__ void store_block16t_planar(const AccT &acc, OutT *C, 
     const int row = blk_row0 + (lane & 15);
     const int col0 = blk_col0 + (lane >> 4) * 4;
     if (row >= M) return;
-    const long long img = row / plane, pix = row - img * plane;
-    OutT *dst = C + (img * N + col0) * plane + pix;
+    // (rows and planes are below 2^31 here: a 32-bit division, a quarter of the instructions of a 64-bit one)
+    const unsigned img = (unsigned)row / (unsigned)plane, pix = (unsigned)row - img * (unsigned)plane;
+    OutT *dst = C + ((long long)img * N + col0) * plane + pix;
 #pragma unroll
     for (int v = 0; v < 4; ++v)
         if (col0 + v < N) dst[v * plane] = (OutT)(alpha * acc[v]);

@@ -56,6 +56,7 @@ struct DlParams {
     unsigned in_bytes;                    // convolution view
     int H, W, Cin_b, R, S, PQ, Q, sh, sw, ph, pw;
     unsigned pq_magic, q_magic;           // division by PQ and by Q as a multiplication (see fast_div)
+    unsigned tap_rep;                     // conv: bit r*S set for every filter row r (a row's S mask bits times this: in every row)
     int pq_shift, q_shift;
     // two-height launches: workgroups [0, n1) tile rows [0, m_split) with the first tile type,
     // the rest tile rows [m_split, M) with the second
@@ -266,7 +267,7 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
 #ifdef XP_TRACE
     // diagnostic build (-DXP_TRACE): where a workgroup's time goes -- entry, first MFMA, end of the K loop, stores done
     long long tr_c[4] = {0, 0, 0, 0}, tr_w[4] = {0, 0, 0, 0};
-    long long tr_wait[3] = {0, 0, 0};                   // paired loop, wave 0: cycles waiting for global loads and in the barrier (third word unused)
+    long long tr_wait[3] = {0, 0, 0};                   // paired loop, wave 0: cycles waiting for global loads, in the barrier, and from entry to the first load
     const int tr_slot = (int)(blockIdx.y * gridDim.x + blockIdx.x) + (m_base ? (int)(gridDim.x * gridDim.y) : 0);
     tr_c[0] = clock64(); tr_w[0] = wall_clock64();
 #endif
@@ -343,14 +344,16 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
                 const int h0 = op * p.sh - p.ph, w0 = oq * p.sw - p.pw;
                 a_off_g[i] = (unsigned)n * (unsigned)(p.H * p.W) * (unsigned)p.Cin_b +
                              (unsigned)((h0 + p.ph) * p.W + w0 + p.pw) * (unsigned)p.Cin_b + a_cb;
-                // columns of the window outside the image (one bit each), then row by row: a row outside the image
-                // is outside with all its columns
-                unsigned cols_out = 0;
-                for (int s2 = 0; s2 < p.S; ++s2) cols_out |= ((unsigned)(w0 + s2) >= (unsigned)p.W ? 1u : 0u) << s2;
-                const unsigned row_all = p.S >= 32 ? 0xffffffffu : (1u << p.S) - 1u;
-                unsigned outside = 0;
-                for (int r = 0; r < p.R; ++r) outside |= ((unsigned)(h0 + r) >= (unsigned)p.H ? row_all : cols_out) << (r * p.S);
-                a_outside[i] = (int)outside;
+                // Without loops (a wave issues one instruction every few cycles and nothing else runs on its SIMD: the
+                // set-up's instruction count is the time before the first load).  Columns s of the window inside the
+                // image: [max(-w0, 0), min(W - w0, S)); rows likewise; a row outside the image is outside with all
+                // its columns, the others share the columns' bits (their S bits times tap_rep: in every row)
+                auto low_bits = [](int n) { return n >= 32 ? 0xffffffffu : (1u << n) - 1u; };     // 0 <= n
+                const int c_lo = min(max(-w0, 0), p.S), c_hi = min(max(p.W - w0, 0), p.S);
+                const int r_lo = min(max(-h0, 0), p.R), r_hi = min(max(p.H - h0, 0), p.R);
+                const unsigned cols_out = low_bits(c_lo) | (low_bits(p.S) & ~low_bits(c_hi));
+                const unsigned rows_in = r_hi > r_lo ? low_bits(r_hi * p.S) & ~low_bits(r_lo * p.S) : 0u;
+                a_outside[i] = (int)((low_bits(p.R * p.S) & ~rows_in) | ((cols_out * p.tap_rep) & rows_in));
             }
         } else {
             a_off_g[i] = (unsigned)(row * p.lda_b) + a_cb;
@@ -631,6 +634,9 @@ __device__ __forceinline__ void dl_body(const DlParams &p, char *lds, int bid, i
         if (KT > 0) {
             AFrag ar[4][2];                                             // fragment sets: sub-steps 0 and 1 of a block row
             BFrag bx[2][T::NI], by[2][T::NI];                           // the B fragments of even / odd K steps
+#ifdef XP_TRACE
+            tr_wait[2] = clock64() - tr_c[0];                           // (set-up: entry to the first load)
+#endif
             issue_a(0, 0, 0, T::IA, std::true_type{});
             issue_b(0, T::B_BASE, 0, T::IB, std::true_type{});
             issue_a(1, T::A_BYTES, 0, T::IA, std::true_type{});
@@ -1170,7 +1176,7 @@ DlParams dl_params(const Problem &q)
     static const int env_group_m = [] { const char *e = getenv("XP_GROUP_M"); return e ? atoi(e) : 0; }();
     p.group_m = env_group_m > 0 ? env_group_m : 4;
     p.in_bytes = 0; p.H = p.W = p.Cin_b = p.R = p.S = p.PQ = p.Q = p.sh = p.sw = p.ph = p.pw = 0;
-    p.pq_magic = p.q_magic = 0; p.pq_shift = p.q_shift = 0;
+    p.pq_magic = p.q_magic = 0; p.pq_shift = p.q_shift = 0; p.tap_rep = 0;
     if (q.conv) {
         p.in_bytes = (unsigned)((q.M / (q.P * q.Q)) * q.H * q.W * q.Cin * esz);
         p.H = (int)q.H; p.W = (int)q.W; p.Cin_b = (int)(q.Cin * esz); p.R = (int)q.R; p.S = (int)q.S;
@@ -1182,6 +1188,7 @@ DlParams dl_params(const Problem &q)
         };
         magic(p.PQ, p.pq_magic, p.pq_shift);
         magic(p.Q, p.q_magic, p.q_shift);
+        for (int r = 0; r < p.R; ++r) p.tap_rep |= 1u << (r * p.S);
         p.sh = (int)q.sh; p.sw = (int)q.sw; p.ph = (int)q.ph; p.pw = (int)q.pw;
     }
     p.n1 = 0; p.m_split = 0; p.tiles_m2 = 0;
