@@ -73,13 +73,37 @@ def main(argv=None) -> int:
     t_start = time.time()
     gain = []
 
+    chosen = {}                                     # shape key -> variant name, in the order of the grid
+    tmp = args.out + ".tmp"
+
+    def saved_keys():
+        xp.xp_tune_save(tmp)
+        with open(tmp) as f:
+            return [line.split(" | ", 1)[0] for line in f if " | " in line and not line.startswith("#")]
+
     def report(what, fn, tune, op, kind):
         us0 = _time(torch, fn)
         v0 = xp.xp_last_config(op, kind)
         best, _ = tune()
-        us1 = _time(torch, fn)
+        key = [k for k in saved_keys() if k not in chosen]
+        assert len(key) == 1, (what, key)
+        keep, us1 = best, _time(torch, fn)
+        if best != v0:
+            # A second look before the built-in choice is displaced: the tuner times each candidate once, and on a
+            # power-limited part the clock that a candidate meets depends on what ran before it.  Both variants
+            # in turns, three times; the newcomer has to win by 2 %.
+            t = {v0: [], best: []}
+            for _ in range(3):
+                for v in (v0, best):
+                    xp.xp_force_config(op, kind, v)
+                    t[v].append(_time(torch, fn))
+            xp.xp_force_config(op, kind, -1)
+            us0, us1 = min(t[v0]), min(t[best])
+            if us1 > 0.98 * us0:
+                keep, us1 = v0, us0
+        chosen[key[0]] = xp.xp_describe_config(op, kind, keep)
         gain.append(us0 / us1)
-        print(f"{what}: default v{v0} {us0:8.1f} us -> tuned v{best} {us1:8.1f} us  x{us0 / us1:.2f}  [{xp.xp_describe_config(op, kind, best)}]",
+        print(f"{what}: default v{v0} {us0:8.1f} us -> tuned v{best} {us1:8.1f} us  x{us0 / us1:.2f}  kept v{keep} [{chosen[key[0]]}]",
               flush=True)
 
     for kind, a_layout, b_layout, M, N, K in gemm_shapes(args.quick):
@@ -119,7 +143,13 @@ def main(argv=None) -> int:
         tune = lambda: xp.xp_tune_conv2d_nhwc(n, H, W, Cin, Cout, R, S, stride, stride, pad, pad, x, w, "krsc", out, ws, reps=args.reps)
         report(f"conv bf16 {n}x{H}x{W}x{Cin}->{Cout} {R}x{S} s{stride} p{pad}", call, tune, 2, "bf16")
         del x, w, out, ws
-    xp.xp_tune_save(args.out)
+    with open(tmp) as f:
+        header = [line for line in f if line.startswith("#")]
+    with open(args.out, "w") as f:                  # the format of xp_tune_save, shapes sorted by key as it writes them
+        f.writelines(header)
+        for k in sorted(chosen):
+            f.write(f"{k} | {chosen[k]}\n")
+    __import__("os").remove(tmp)
     g = sorted(gain)
     print(f"{len(g)} shapes tuned in {time.time() - t_start:.0f} s; default/tuned time: median x{g[len(g) // 2]:.2f}, "
           f"worst x{g[-1]:.2f}, geometric mean x{(__import__('math').prod(g)) ** (1 / len(g)):.3f}; saved to {args.out}")
