@@ -260,6 +260,11 @@ CONV_CASES = [
     (4, 1, 50, 64, 48, 1, 3, (1, 1), (0, 1)),
     (2, 1, 333, 128, 32, 1, 7, (1, 2), (0, 3)),
     (3, 1, 19, 5, 7, 1, 4, (1, 1), (0, 0)),          # few channels: general kernel
+    # windows that stick out on both sides at once (image narrower than the filter), a tall one-column filter with
+    # more padding than image rows at the stride, 32 taps (the whole padding mask): the MFMA kernels' mask arithmetic
+    (2, 2, 3, 64, 32, 3, 5, (1, 1), (1, 2)),
+    (1, 9, 4, 128, 16, 7, 1, (2, 1), (3, 0)),
+    (1, 5, 11, 64, 24, 4, 8, (1, 3), (3, 7)),
 ]
 
 
